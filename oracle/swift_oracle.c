@@ -1,0 +1,589 @@
+/*
+ * swift_oracle.c -- CPU oracle for layer-skipping self-speculative greedy decoding.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP library is checked against.  Nothing in the product path may link, load
+ * or call it; only the tests, the smoke check and the benchmark's CPU-baseline
+ * leg do.  It shares no code with the HIP library.
+ *
+ * What it computes
+ *   - The target model M_T: a LLaMA-style decoder (the paper names LLaMA-2 as
+ *     its backbone, Section 5.1): token embedding, L layers of
+ *     [pre-RMSNorm -> rotary multi-head / grouped-query causal attention ->
+ *     residual add] and [pre-RMSNorm -> SwiGLU MLP -> residual add], a final
+ *     RMSNorm and an untied LM head.  No biases.
+ *   - The draft model M_D: the same network with the sublayers named by the
+ *     skipped-layer set z bypassed (Section 3.1: z in {0,1}^L with L counting
+ *     attention and MLP sublayers separately).  A skipped sublayer leaves the
+ *     residual stream untouched and writes no key/value.
+ *   - One decoding step of the acceleration phase (Section 4.2): greedy
+ *     autoregressive drafting (Eq. 5) with confidence p_j = max softmax and
+ *     early stop when p_j < eps, verification of [pending, y'_1..y'_k] by the
+ *     full model in one causal block, acceptance of the longest matching
+ *     prefix plus the target's own next token, and roll-back of the cache
+ *     length.
+ *   - Plain greedy autoregressive decoding (the definition the method must
+ *     reproduce token for token), a brute-force forward without any cache,
+ *     and the expected-speedup closed form (Appendix B.3, Eq. 6).
+ *
+ * Arithmetic
+ *   Every floating-point step is carried out in fp64.  Rounding happens only
+ *   where the data format fixes it: weights arrive already rounded to their
+ *   storage type (fp32 or bf16); keys (after the rotation) and values are
+ *   rounded to the cache's storage type when they are written, taking that
+ *   decision the way an fp32 kernel would (fp64 -> fp32 -> storage type);
+ *   rotary cos/sin are rounded to fp32; logits are rounded to fp32 before the
+ *   arg-max so that ties are decided in the precision the logits are reported
+ *   in.  Each dot product runs over its index in increasing order with one
+ *   accumulator, attention runs over cache slots in increasing order, and a
+ *   block of rows is simply the single-row forward called once per row, so a
+ *   token's logits are bit-identical whether it is computed alone or inside a
+ *   verify block.  Threads split output rows only, never a reduction, so the
+ *   result does not depend on the thread count.
+ *
+ * Parity pins (tests/test_oracle_*.py): speculative output == autoregressive
+ * output for many masks / draft lengths / thresholds; cached forward ==
+ * brute-force forward; closed forms for the all-skipped draft, single-slot
+ * and equal-key attention, uniform logits; RoPE worked example and
+ * relative-position property; RMSNorm invariances; Eq. 6 against the values
+ * printed in the paper's Table 4.
+ * Parity unpinned: behaviour on trained weights (acceptance rates, M, the
+ * measured speedups) -- needs checkpoints and datasets that are not available.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORA_OK 0
+#define ORA_EINVAL -1
+#define ORA_ECAPACITY -2
+#define ORA_ESTATE -3
+
+#define ORA_F32 0
+#define ORA_BF16 1
+#define ORA_MAX_BLOCK 64
+
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, max_seq;
+    double rms_eps, rope_theta;
+    int32_t kv_dtype; /* ORA_F32 or ORA_BF16: storage type of the key/value cache */
+} ora_config;
+
+typedef struct {
+    const void *p; /* borrowed, row-major [out][in] */
+    int dtype;
+    int64_t n;
+} ora_tensor;
+
+typedef struct {
+    ora_tensor attn_norm, wq, wk, wv, wo, mlp_norm, wg, wu, wd;
+} ora_layer;
+
+typedef struct ora_model {
+    ora_config c;
+    ora_tensor embed, final_norm, lm_head;
+    ora_layer *layers;
+    float *kcache, *vcache; /* [L][max_seq][n_kv*d]; values already rounded to kv_dtype */
+    int threads;
+    /* decoding state */
+    int n;        /* cache length: slots [0,n) hold committed target keys/values */
+    int pending;  /* last emitted token, not yet in the cache; -1 before prefill */
+    int k_draft;  /* draft tokens of the current step (-1: none drafted) */
+    int32_t draft[ORA_MAX_BLOCK];
+    int k_verify; /* k of the last verify (-1: none) */
+    int32_t vtokens[ORA_MAX_BLOCK + 1];
+    int32_t target[ORA_MAX_BLOCK + 1];
+    /* counters (Appendix B.3) */
+    int64_t n_draft_passes, n_verify_passes, n_accepted, n_emitted;
+} ora_model;
+
+/* ---------------------------------------------------------------- helpers */
+
+static inline float bf16_bits_to_float(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* fp32 -> bf16 by round-to-nearest-even, returned as the fp32 it represents */
+static inline float round_to_bf16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return f; /* NaN stays NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+static inline double tget(const ora_tensor *t, int64_t i) {
+    if (t->dtype == ORA_F32) return (double)((const float *)t->p)[i];
+    return (double)bf16_bits_to_float(((const uint16_t *)t->p)[i]);
+}
+
+/* y[o] = sum_{i=0..K-1} W[o][i] * x[i], i increasing, one fp64 accumulator */
+static void matvec(const ora_model *m, const ora_tensor *W, int O, int K, const double *x, double *y) {
+    (void)m;
+#pragma omp parallel for schedule(static) num_threads(m->threads)
+    for (int o = 0; o < O; ++o) {
+        double acc = 0.0;
+        if (W->dtype == ORA_F32) {
+            const float *w = (const float *)W->p + (int64_t)o * K;
+            for (int i = 0; i < K; ++i) acc += (double)w[i] * x[i];
+        } else {
+            const uint16_t *w = (const uint16_t *)W->p + (int64_t)o * K;
+            for (int i = 0; i < K; ++i) acc += (double)bf16_bits_to_float(w[i]) * x[i];
+        }
+        y[o] = acc;
+    }
+}
+
+/* RMSNorm: out_i = x_i * g_i / sqrt(mean_j x_j^2 + eps) */
+void ora_rmsnorm(const double *x, const double *g, int n, double eps, double *out) {
+    double ss = 0.0;
+    for (int i = 0; i < n; ++i) ss += x[i] * x[i];
+    double r = 1.0 / sqrt(ss / (double)n + eps);
+    for (int i = 0; i < n; ++i) out[i] = x[i] * r * g[i];
+}
+
+static void rmsnorm_t(const double *x, const ora_tensor *g, int n, double eps, double *out) {
+    double ss = 0.0;
+    for (int i = 0; i < n; ++i) ss += x[i] * x[i];
+    double r = 1.0 / sqrt(ss / (double)n + eps);
+    for (int i = 0; i < n; ++i) out[i] = x[i] * r * tget(g, i);
+}
+
+/* Rotary embedding of one head vector at absolute position pos, in place.
+ * Pairs (i, i + d/2); frequency theta^(-2i/d); angle pos * frequency;
+ * (a, b) -> (a cos - b sin, b cos + a sin).  cos/sin are rounded to fp32. */
+void ora_rope(double *v, int d, int pos, double theta) {
+    int half = d / 2;
+    for (int i = 0; i < half; ++i) {
+        double freq = pow(theta, -2.0 * (double)i / (double)d);
+        double ang = (double)pos * freq;
+        double c = (double)(float)cos(ang), s = (double)(float)sin(ang);
+        double a = v[i], b = v[i + half];
+        v[i] = a * c - b * s;
+        v[i + half] = b * c + a * s;
+    }
+}
+
+static inline float round_kv(const ora_config *c, double x) {
+    float f = (float)x;
+    return c->kv_dtype == ORA_BF16 ? round_to_bf16(f) : f;
+}
+
+/* One query head against n_ctx cached slots: softmax(q.k_u / sqrt(d)) . v_u.
+ * kc / vc point at slot 0 of the right KV head; consecutive slots are `stride` apart. */
+void ora_attend(const double *q, const float *kc, const float *vc, int64_t stride, int n_ctx, int d,
+                double *out) {
+    double *s = (double *)malloc(sizeof(double) * (size_t)n_ctx);
+    double scale = 1.0 / sqrt((double)d), mx = -INFINITY;
+    for (int u = 0; u < n_ctx; ++u) {
+        double acc = 0.0;
+        const float *kr = kc + (int64_t)u * stride;
+        for (int i = 0; i < d; ++i) acc += q[i] * (double)kr[i];
+        s[u] = acc * scale;
+        if (s[u] > mx) mx = s[u];
+    }
+    double den = 0.0;
+    for (int u = 0; u < n_ctx; ++u) {
+        s[u] = exp(s[u] - mx);
+        den += s[u];
+    }
+    for (int i = 0; i < d; ++i) out[i] = 0.0;
+    for (int u = 0; u < n_ctx; ++u) {
+        double a = s[u] / den;
+        const float *vr = vc + (int64_t)u * stride;
+        for (int i = 0; i < d; ++i) out[i] += a * (double)vr[i];
+    }
+    free(s);
+}
+
+/* SwiGLU gate: silu(g) * u with silu(z) = z / (1 + exp(-z)) */
+double ora_swiglu(double g, double u) { return g / (1.0 + exp(-g)) * u; }
+
+/* Greedy choice and confidence from a logits row.
+ * token = lowest index attaining the maximum of the fp32-rounded logits;
+ * conf  = max softmax = 1 / sum_i exp(l_i - l_max)  (temperature 1). */
+void ora_argmax_conf(const double *logits, int n, int32_t *token, double *conf) {
+    int best = 0;
+    float bv = (float)logits[0];
+    for (int i = 1; i < n; ++i) {
+        float v = (float)logits[i];
+        if (v > bv) {
+            bv = v;
+            best = i;
+        }
+    }
+    double den = 0.0;
+    for (int i = 0; i < n; ++i) den += exp((double)(float)logits[i] - (double)bv);
+    *token = best;
+    if (conf) *conf = 1.0 / den;
+}
+
+/* Expected wall-time speedup of the acceleration phase (Appendix B.3, Eq. 6):
+ * M tokens per target pass cost one target pass plus (M-1)/alpha draft passes
+ * of relative cost c each. */
+double ora_expected_speedup(double M, double alpha, double c) { return M * alpha / ((M - 1.0) * c + alpha); }
+
+/* Longest accepted prefix: largest m <= k with draft[r] == target[r] for all r < m
+ * (draft[r] is y'_{r+1}; target[r] is the full model's greedy token after row r). */
+int ora_match_prefix(const int32_t *draft, const int32_t *target, int k) {
+    int m = 0;
+    while (m < k && draft[m] == target[m]) ++m;
+    return m;
+}
+
+/* ---------------------------------------------------------------- model */
+
+int ora_create(const ora_config *c, ora_model **out) {
+    if (!c || !out) return ORA_EINVAL;
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        (c->head_dim & 1) || c->ffn <= 0 || c->vocab <= 0 || c->max_seq <= 0 ||
+        c->n_q_heads % c->n_kv_heads != 0 || (c->kv_dtype != ORA_F32 && c->kv_dtype != ORA_BF16))
+        return ORA_EINVAL;
+    ora_model *m = (ora_model *)calloc(1, sizeof(ora_model));
+    m->c = *c;
+    m->layers = (ora_layer *)calloc((size_t)c->n_layers, sizeof(ora_layer));
+    size_t kvn = (size_t)c->n_layers * c->max_seq * c->n_kv_heads * c->head_dim;
+    m->kcache = (float *)calloc(kvn, sizeof(float));
+    m->vcache = (float *)calloc(kvn, sizeof(float));
+    m->threads = 1;
+    m->pending = -1;
+    m->k_draft = -1;
+    m->k_verify = -1;
+    *out = m;
+    return ORA_OK;
+}
+
+void ora_destroy(ora_model *m) {
+    if (!m) return;
+    free(m->layers);
+    free(m->kcache);
+    free(m->vcache);
+    free(m);
+}
+
+void ora_set_threads(ora_model *m, int t) { m->threads = t < 1 ? 1 : t; }
+
+int ora_threads_available(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Borrow a tensor.  name: "embed", "final_norm", "lm_head",
+ * "l<i>.{attn_norm,wq,wk,wv,wo,mlp_norm,wg,wu,wd}"; row-major [out][in]. */
+int ora_set_tensor(ora_model *m, const char *name, const void *data, int dtype, int64_t n) {
+    if (!m || !name || !data || (dtype != ORA_F32 && dtype != ORA_BF16)) return ORA_EINVAL;
+    const ora_config *c = &m->c;
+    int64_t H = c->hidden, Q = (int64_t)c->n_q_heads * c->head_dim, KV = (int64_t)c->n_kv_heads * c->head_dim,
+            F = c->ffn, V = c->vocab;
+    ora_tensor t = {data, dtype, n};
+    ora_tensor *dst = NULL;
+    int64_t want = -1;
+    if (!strcmp(name, "embed")) dst = &m->embed, want = V * H;
+    else if (!strcmp(name, "final_norm")) dst = &m->final_norm, want = H;
+    else if (!strcmp(name, "lm_head")) dst = &m->lm_head, want = V * H;
+    else if (name[0] == 'l') {
+        char *end;
+        long l = strtol(name + 1, &end, 10);
+        if (end == name + 1 || *end != '.' || l < 0 || l >= c->n_layers) return ORA_EINVAL;
+        const char *f = end + 1;
+        ora_layer *y = &m->layers[l];
+        if (!strcmp(f, "attn_norm")) dst = &y->attn_norm, want = H;
+        else if (!strcmp(f, "wq")) dst = &y->wq, want = Q * H;
+        else if (!strcmp(f, "wk")) dst = &y->wk, want = KV * H;
+        else if (!strcmp(f, "wv")) dst = &y->wv, want = KV * H;
+        else if (!strcmp(f, "wo")) dst = &y->wo, want = H * Q;
+        else if (!strcmp(f, "mlp_norm")) dst = &y->mlp_norm, want = H;
+        else if (!strcmp(f, "wg")) dst = &y->wg, want = F * H;
+        else if (!strcmp(f, "wu")) dst = &y->wu, want = F * H;
+        else if (!strcmp(f, "wd")) dst = &y->wd, want = H * F;
+    }
+    if (!dst || n != want) return ORA_EINVAL;
+    *dst = t;
+    return ORA_OK;
+}
+
+static float *kslot(const ora_model *m, int l, int pos) {
+    const ora_config *c = &m->c;
+    return m->kcache + ((int64_t)l * c->max_seq + pos) * c->n_kv_heads * c->head_dim;
+}
+static float *vslot(const ora_model *m, int l, int pos) {
+    const ora_config *c = &m->c;
+    return m->vcache + ((int64_t)l * c->max_seq + pos) * c->n_kv_heads * c->head_dim;
+}
+
+/* Forward of ONE token at absolute position pos through the network with the
+ * sublayers in `skip` bypassed (skip == NULL: the full target model).
+ * Reads cache slots [0,pos) and writes slot pos in every non-skipped attention
+ * sublayer.  logits: fp64 [vocab]. */
+int ora_forward_row(ora_model *m, int32_t token, int pos, const uint8_t *skip, double *logits) {
+    const ora_config *c = &m->c;
+    if (token < 0 || token >= c->vocab) return ORA_EINVAL;
+    if (pos < 0 || pos >= c->max_seq) return ORA_ECAPACITY;
+    const int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, F = c->ffn;
+    const int Q = nq * d, KV = nkv * d, group = nq / nkv;
+    double *x = (double *)malloc(sizeof(double) * (size_t)H);
+    double *xh = (double *)malloc(sizeof(double) * (size_t)H);
+    double *q = (double *)malloc(sizeof(double) * (size_t)Q);
+    double *k = (double *)malloc(sizeof(double) * (size_t)KV);
+    double *v = (double *)malloc(sizeof(double) * (size_t)KV);
+    double *att = (double *)malloc(sizeof(double) * (size_t)Q);
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)H);
+    double *hg = (double *)malloc(sizeof(double) * (size_t)F);
+    double *hu = (double *)malloc(sizeof(double) * (size_t)F);
+
+    for (int i = 0; i < H; ++i) x[i] = tget(&m->embed, (int64_t)token * H + i);
+
+    for (int l = 0; l < c->n_layers; ++l) {
+        const ora_layer *y = &m->layers[l];
+        if (!(skip && skip[2 * l])) {
+            rmsnorm_t(x, &y->attn_norm, H, c->rms_eps, xh);
+            matvec(m, &y->wq, Q, H, xh, q);
+            matvec(m, &y->wk, KV, H, xh, k);
+            matvec(m, &y->wv, KV, H, xh, v);
+            for (int h = 0; h < nq; ++h) ora_rope(q + h * d, d, pos, c->rope_theta);
+            for (int h = 0; h < nkv; ++h) ora_rope(k + h * d, d, pos, c->rope_theta);
+            float *ks = kslot(m, l, pos), *vs = vslot(m, l, pos);
+            for (int i = 0; i < KV; ++i) {
+                ks[i] = round_kv(c, k[i]);
+                vs[i] = round_kv(c, v[i]);
+            }
+#pragma omp parallel for schedule(static) num_threads(m->threads)
+            for (int h = 0; h < nq; ++h) {
+                int g = h / group;
+                ora_attend(q + h * d, kslot(m, l, 0) + g * d, vslot(m, l, 0) + g * d, KV, pos + 1, d, att + h * d);
+            }
+            matvec(m, &y->wo, H, Q, att, tmp);
+            for (int i = 0; i < H; ++i) x[i] += tmp[i];
+        }
+        if (!(skip && skip[2 * l + 1])) {
+            rmsnorm_t(x, &y->mlp_norm, H, c->rms_eps, xh);
+            matvec(m, &y->wg, F, H, xh, hg);
+            matvec(m, &y->wu, F, H, xh, hu);
+            for (int i = 0; i < F; ++i) hg[i] = ora_swiglu(hg[i], hu[i]);
+            matvec(m, &y->wd, H, F, hg, tmp);
+            for (int i = 0; i < H; ++i) x[i] += tmp[i];
+        }
+    }
+    rmsnorm_t(x, &m->final_norm, H, c->rms_eps, xh);
+    matvec(m, &m->lm_head, c->vocab, H, xh, logits);
+
+    free(x); free(xh); free(q); free(k); free(v); free(att); free(tmp); free(hg); free(hu);
+    return ORA_OK;
+}
+
+/* Brute force: logits of the LAST of n tokens from the full model, recomputed
+ * from scratch, layer by layer over the whole sequence, with no cache and no
+ * decoding state.  Keys and values pass through the same storage rounding. */
+int ora_forward_nocache(ora_model *m, const int32_t *tokens, int n, double *logits) {
+    const ora_config *c = &m->c;
+    if (n <= 0) return ORA_EINVAL;
+    const int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, F = c->ffn;
+    const int Q = nq * d, KV = nkv * d, group = nq / nkv;
+    double *X = (double *)malloc(sizeof(double) * (size_t)n * H);
+    double *xh = (double *)malloc(sizeof(double) * (size_t)H);
+    double *Qm = (double *)malloc(sizeof(double) * (size_t)n * Q);
+    float *Km = (float *)malloc(sizeof(float) * (size_t)n * KV);
+    float *Vm = (float *)malloc(sizeof(float) * (size_t)n * KV);
+    double *kv = (double *)malloc(sizeof(double) * (size_t)KV);
+    double *att = (double *)malloc(sizeof(double) * (size_t)Q);
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)H);
+    double *hg = (double *)malloc(sizeof(double) * (size_t)F);
+    double *hu = (double *)malloc(sizeof(double) * (size_t)F);
+    for (int t = 0; t < n; ++t) {
+        if (tokens[t] < 0 || tokens[t] >= c->vocab) return ORA_EINVAL;
+        for (int i = 0; i < H; ++i) X[(int64_t)t * H + i] = tget(&m->embed, (int64_t)tokens[t] * H + i);
+    }
+    for (int l = 0; l < c->n_layers; ++l) {
+        const ora_layer *y = &m->layers[l];
+        for (int t = 0; t < n; ++t) {
+            rmsnorm_t(X + (int64_t)t * H, &y->attn_norm, H, c->rms_eps, xh);
+            matvec(m, &y->wq, Q, H, xh, Qm + (int64_t)t * Q);
+            for (int h = 0; h < nq; ++h) ora_rope(Qm + (int64_t)t * Q + h * d, d, t, c->rope_theta);
+            matvec(m, &y->wk, KV, H, xh, kv);
+            for (int h = 0; h < nkv; ++h) ora_rope(kv + h * d, d, t, c->rope_theta);
+            for (int i = 0; i < KV; ++i) Km[(int64_t)t * KV + i] = round_kv(c, kv[i]);
+            matvec(m, &y->wv, KV, H, xh, kv);
+            for (int i = 0; i < KV; ++i) Vm[(int64_t)t * KV + i] = round_kv(c, kv[i]);
+        }
+        for (int t = 0; t < n; ++t) {
+            for (int h = 0; h < nq; ++h) {
+                int g = h / group;
+                ora_attend(Qm + (int64_t)t * Q + h * d, Km + g * d, Vm + g * d, KV, t + 1, d, att + h * d);
+            }
+            matvec(m, &y->wo, H, Q, att, tmp);
+            for (int i = 0; i < H; ++i) X[(int64_t)t * H + i] += tmp[i];
+        }
+        for (int t = 0; t < n; ++t) {
+            rmsnorm_t(X + (int64_t)t * H, &y->mlp_norm, H, c->rms_eps, xh);
+            matvec(m, &y->wg, F, H, xh, hg);
+            matvec(m, &y->wu, F, H, xh, hu);
+            for (int i = 0; i < F; ++i) hg[i] = ora_swiglu(hg[i], hu[i]);
+            matvec(m, &y->wd, H, F, hg, tmp);
+            for (int i = 0; i < H; ++i) X[(int64_t)t * H + i] += tmp[i];
+        }
+    }
+    rmsnorm_t(X + (int64_t)(n - 1) * H, &m->final_norm, H, c->rms_eps, xh);
+    matvec(m, &m->lm_head, c->vocab, H, xh, logits);
+    free(X); free(xh); free(Qm); free(Km); free(Vm); free(kv); free(att); free(tmp); free(hg); free(hu);
+    return ORA_OK;
+}
+
+/* ---------------------------------------------------------------- decoding steps */
+
+int ora_reset(ora_model *m) {
+    m->n = 0;
+    m->pending = -1;
+    m->k_draft = -1;
+    m->k_verify = -1;
+    m->n_draft_passes = m->n_verify_passes = m->n_accepted = m->n_emitted = 0;
+    return ORA_OK;
+}
+
+/* Prefill: the full model over the prompt at positions 0..P-1; the arg-max of
+ * the last row is the first new token (becomes the pending token). */
+int ora_prefill(ora_model *m, const int32_t *prompt, int P, int32_t *first_token, double *last_logits) {
+    if (!m || !prompt || P <= 0) return ORA_EINVAL;
+    if (P >= m->c.max_seq) return ORA_ECAPACITY;
+    ora_reset(m);
+    double *lg = (double *)malloc(sizeof(double) * (size_t)m->c.vocab);
+    for (int t = 0; t < P; ++t) {
+        int rc = ora_forward_row(m, prompt[t], t, NULL, lg);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+    }
+    int32_t tok;
+    ora_argmax_conf(lg, m->c.vocab, &tok, NULL);
+    if (last_logits) memcpy(last_logits, lg, sizeof(double) * (size_t)m->c.vocab);
+    free(lg);
+    m->n = P;
+    m->pending = tok;
+    m->n_emitted = 1;
+    if (first_token) *first_token = tok;
+    return ORA_OK;
+}
+
+/* Drafting (Section 4.2, Eq. 5 and strategy 1): starting from the pending
+ * token at position n, run the draft model autoregressively; draft token j is
+ * the arg-max, its confidence the top-1 probability; stop after the token
+ * whose confidence is below the threshold (that token is kept) or after max_k
+ * tokens.  Draft keys/values go to slots n, n+1, ... of the non-skipped
+ * attention sublayers and are overwritten by the next verify. */
+int ora_draft_step(ora_model *m, const uint8_t *skip, int max_k, double conf_threshold, int32_t *draft_tokens,
+                   double *draft_conf, int *k_out) {
+    if (!m || !skip || max_k < 0 || max_k > ORA_MAX_BLOCK) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    if (m->n + max_k + 1 > m->c.max_seq) return ORA_ECAPACITY;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)m->c.vocab);
+    int32_t prev = m->pending;
+    int k = 0;
+    for (int j = 1; j <= max_k; ++j) {
+        int rc = ora_forward_row(m, prev, m->n + j - 1, skip, lg);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+        int32_t tok;
+        double p;
+        ora_argmax_conf(lg, m->c.vocab, &tok, &p);
+        m->n_draft_passes++;
+        m->draft[k] = tok;
+        if (draft_tokens) draft_tokens[k] = tok;
+        if (draft_conf) draft_conf[k] = p;
+        ++k;
+        prev = tok;
+        if (p < conf_threshold) break;
+    }
+    free(lg);
+    m->k_draft = k;
+    if (k_out) *k_out = k;
+    return ORA_OK;
+}
+
+/* Verification: the full model over rows [tokens[0..k]] at positions n..n+k;
+ * row i sees slots 0..n+i.  Target keys/values overwrite slots n..n+k in every
+ * layer.  target_tokens[i] = arg-max of row i.  logits_out: NULL or fp64 [k+1][vocab]. */
+int ora_verify(ora_model *m, const int32_t *tokens, int k, int32_t *target_tokens, double *logits_out) {
+    if (!m || !tokens || k < 0 || k > ORA_MAX_BLOCK) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    if (m->n + k + 1 > m->c.max_seq) return ORA_ECAPACITY;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)m->c.vocab);
+    for (int i = 0; i <= k; ++i) {
+        int rc = ora_forward_row(m, tokens[i], m->n + i, NULL, lg);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+        int32_t tok;
+        ora_argmax_conf(lg, m->c.vocab, &tok, NULL);
+        m->vtokens[i] = tokens[i];
+        m->target[i] = tok;
+        if (target_tokens) target_tokens[i] = tok;
+        if (logits_out) memcpy(logits_out + (int64_t)i * m->c.vocab, lg, sizeof(double) * (size_t)m->c.vocab);
+    }
+    free(lg);
+    m->k_verify = k;
+    m->n_verify_passes++;
+    return ORA_OK;
+}
+
+/* Acceptance and roll-back: m = longest prefix of the verified draft tokens
+ * that equals the target's greedy tokens; emit those m tokens and the target's
+ * own next token g_m; cache length becomes n + m + 1; g_m is the new pending token. */
+int ora_accept(ora_model *m, int32_t *emitted, int *n_emitted) {
+    if (!m) return ORA_EINVAL;
+    if (m->k_verify < 0) return ORA_ESTATE;
+    int k = m->k_verify;
+    int acc = ora_match_prefix(m->vtokens + 1, m->target, k);
+    for (int i = 0; i < acc; ++i)
+        if (emitted) emitted[i] = m->vtokens[1 + i];
+    if (emitted) emitted[acc] = m->target[acc];
+    if (n_emitted) *n_emitted = acc + 1;
+    m->n += acc + 1;
+    m->pending = m->target[acc];
+    m->n_accepted += acc;
+    m->n_emitted += acc + 1;
+    m->k_verify = -1;
+    m->k_draft = -1;
+    return ORA_OK;
+}
+
+int ora_cache_len(const ora_model *m) { return m->n; }
+int ora_pending(const ora_model *m) { return m->pending; }
+
+/* counters: [draft passes, verify passes, accepted draft tokens, emitted tokens] */
+void ora_get_stats(const ora_model *m, int64_t out[4]) {
+    out[0] = m->n_draft_passes;
+    out[1] = m->n_verify_passes;
+    out[2] = m->n_accepted;
+    out[3] = m->n_emitted;
+}
+
+/* Test hook: NaN-fill every cache slot at or beyond the cache length. */
+void ora_poison_kv(ora_model *m) {
+    const ora_config *c = &m->c;
+    int64_t w = (int64_t)c->n_kv_heads * c->head_dim;
+    for (int l = 0; l < c->n_layers; ++l)
+        for (int p = m->n; p < c->max_seq; ++p)
+            for (int64_t i = 0; i < w; ++i) kslot(m, l, p)[i] = vslot(m, l, p)[i] = NAN;
+}
+
+/* Test access to the cache: copy slot `pos` of layer l (keys then values, fp32). */
+void ora_read_kv(const ora_model *m, int l, int pos, float *k_out, float *v_out) {
+    int64_t w = (int64_t)m->c.n_kv_heads * m->c.head_dim;
+    memcpy(k_out, kslot(m, l, pos), sizeof(float) * (size_t)w);
+    memcpy(v_out, vslot(m, l, pos), sizeof(float) * (size_t)w);
+}

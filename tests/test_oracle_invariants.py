@@ -1,0 +1,175 @@
+"""Pins of the oracle's decoding loop: the lossless invariant (speculative greedy
+output == plain greedy output of the target model; Sections 1 and 3.1 state that
+verification leaves the output unchanged), brute-force recomputation without a
+cache, the degenerate settings of the method, and the counter identities behind
+M and alpha (Appendix B.3).  CPU only."""
+import numpy as np
+import pytest
+
+import synthetic_inputs as si
+from tests import helpers as hp
+
+
+@pytest.fixture(scope="module")
+def small(oracle_lib):
+    s = hp.SMALL_GQA
+    w = hp.shaped_weights(s, seed=21)
+    o = oracle_lib.Oracle(s, 96)
+    o.set_weights(w)
+    prompt = si.uniform_ids(11, 12, s.vocab)
+    ar = oracle_lib.generate_ar(o, prompt, 40)
+    return s, o, prompt, ar
+
+
+def _masks(n_layers):
+    L2 = 2 * n_layers
+    rng = np.random.default_rng(5)
+    out = {"none": np.zeros(L2, np.uint8), "all": np.ones(L2, np.uint8)}
+    for i in range(L2):
+        m = np.zeros(L2, np.uint8)
+        m[i] = 1
+        out[f"only{i}"] = m
+    for j in range(4):
+        out[f"rand{j}"] = (rng.random(L2) < 0.5).astype(np.uint8)
+    return out
+
+
+def test_cached_forward_equals_bruteforce_bitwise(oracle_lib, small):
+    s, o, prompt, ar = small
+    seq = np.concatenate([prompt, ar])[:30]
+    o.reset()
+    for t, tok in enumerate(seq):
+        cached = o.forward_row(int(tok), t)
+        if t in (0, 1, 2, 7, 13, 29):
+            assert np.array_equal(cached, o.forward_nocache(seq[:t + 1])), t
+
+
+def test_ar_tokens_equal_bruteforce_greedy(oracle_lib, small):
+    s, o, prompt, ar = small
+    seq = list(prompt)
+    for i in range(10):
+        tok, _ = oracle_lib.argmax_conf(o.forward_nocache(seq))
+        assert tok == ar[i]
+        seq.append(tok)
+
+
+@pytest.mark.parametrize("max_k,eps", [(1, 0.0), (3, 0.0), (4, 0.5), (7, 0.8), (5, 2.0)])
+def test_speculative_equals_autoregressive(oracle_lib, small, max_k, eps):
+    s, o, prompt, ar = small
+    seen_partial = False
+    for name, mask in _masks(s.n_layers).items():
+        out, trace = oracle_lib.generate_swift(o, prompt, len(ar), mask, max_k, eps)
+        assert np.array_equal(out, ar), (name, max_k, eps)
+        for st in trace:
+            k = len(st["draft"])
+            seen_partial |= 0 < st["m"] < k
+            # what was emitted: the accepted drafts, then the target's own token
+            assert list(st["emitted"][:-1]) == list(st["draft"][:st["m"]])
+            assert st["emitted"][-1] == st["target"][st["m"]]
+            assert st["m"] == k or st["draft"][st["m"]] != st["target"][st["m"]]
+    if max_k >= 3 and eps < 1:
+        assert seen_partial      # the inputs do exercise partial acceptance (0 < m < k)
+
+
+def test_poisoned_slots_beyond_cache_length_are_never_read(oracle_lib, small):
+    s, o, prompt, ar = small
+    for name, mask in list(_masks(s.n_layers).items())[:6]:
+        out, _ = oracle_lib.generate_swift(o, prompt, len(ar), mask, 4, 0.3, poison=True)
+        assert np.array_equal(out, ar), name
+
+
+def test_no_skip_mask_accepts_everything(oracle_lib, small):
+    s, o, prompt, ar = small
+    n_new, max_k = 33, 4
+    out, trace = oracle_lib.generate_swift(o, prompt, n_new, np.zeros(2 * s.n_layers, np.uint8), max_k, 0.0)
+    assert np.array_equal(out, ar[:n_new])
+    assert all(st["m"] == len(st["draft"]) for st in trace)
+    # eps = 0: every step drafts max_k tokens until the cap "tokens still wanted - 1" bites
+    assert [len(st["draft"]) for st in trace][:-1] == [max_k] * (len(trace) - 1)
+    st = o.stats()
+    assert st["accepted"] == st["draft_passes"]                          # alpha = 1
+    assert st["emitted"] == n_new
+    assert len(trace) == -(-(n_new - 1) // (max_k + 1))                  # M = max_k + 1 per full step
+
+
+def test_threshold_extremes_and_zero_draft_length(oracle_lib, small):
+    s, o, prompt, ar = small
+    mask = _masks(s.n_layers)["rand1"]
+    _, trace = oracle_lib.generate_swift(o, prompt, 20, mask, 5, 2.0)    # eps > 1: stop after one draft
+    assert all(len(st["draft"]) <= 1 for st in trace)
+    assert all(len(st["draft"]) == 1 for st in trace[:-1])
+    _, trace = oracle_lib.generate_swift(o, prompt, 20, mask, 5, 0.0)    # eps = 0: never stops early
+    assert all(len(st["draft"]) == min(5, 20 - 1 - sum(len(t["emitted"]) for t in trace[:i]) - 1)
+               for i, st in enumerate(trace))
+    out, trace = oracle_lib.generate_swift(o, prompt, 20, mask, 0, 0.5)  # no drafting = vanilla, M = 1
+    assert np.array_equal(out, ar[:20]) and len(trace) == 19 and o.stats()["draft_passes"] == 0
+
+
+def test_early_stop_keeps_the_low_confidence_token(oracle_lib, small):
+    s, o, prompt, ar = small
+    mask = _masks(s.n_layers)["rand0"]
+    _, trace = oracle_lib.generate_swift(o, prompt, 40, mask, 6, 0.6)
+    stops = 0
+    for st in trace:
+        c = st["conf"]
+        assert np.all(c[:-1] >= 0.6)          # drafting went on only while confident
+        if len(c) < 6 and len(c) > 0 and c[-1] < 0.6:
+            stops += 1                        # the sub-threshold token is in the verified block
+            assert len(st["block"]) == len(c) + 1
+    assert stops > 0
+    assert np.all((0 < np.concatenate([st["conf"] for st in trace])) &
+                  (np.concatenate([st["conf"] for st in trace]) <= 1))
+
+
+def test_counter_identities(oracle_lib, small):
+    s, o, prompt, ar = small
+    out, trace = oracle_lib.generate_swift(o, prompt, 37, _masks(s.n_layers)["rand2"], 4, 0.4)
+    st = o.stats()
+    assert st["emitted"] == 37 == len(out)
+    assert st["verify_passes"] == len(trace)
+    assert st["draft_passes"] == sum(len(t["draft"]) for t in trace)
+    assert st["accepted"] == sum(t["m"] for t in trace)
+    assert 1 + sum(t["m"] + 1 for t in trace) == 37       # prefill's token + (m+1) per target pass
+    assert o.cache_len == len(prompt) + 36                 # everything but the pending token is cached
+    assert o.pending == out[-1]
+
+
+def test_verify_block_rows_equal_single_row_forwards(oracle_lib, small):
+    """Row i of a verify block is the target's forward of that token at position
+    n+i: the same logits, bit for bit, as decoding the block one token at a time."""
+    s, o, prompt, ar = small
+    o.prefill(prompt)
+    block = np.array([o.pending, 5, 9, 150], np.int32)
+    tgt, lg = o.verify(block, want_logits=True)
+    o2 = oracle_lib.Oracle(s, 96)
+    o2._keep = o._keep
+    o2.set_weights(o._keep)
+    want = o2.forward_nocache(np.concatenate([prompt, block]))
+    assert np.array_equal(lg[3], want)
+    assert tgt[3] == oracle_lib.argmax_conf(want)[0]
+
+
+def test_state_and_capacity_errors(oracle_lib, small):
+    s, o, prompt, ar = small
+    o.reset()
+    with pytest.raises(oracle_lib.OracleError) as e:
+        o.verify([1])
+    assert e.value.code == -3
+    o.prefill(prompt)
+    with pytest.raises(oracle_lib.OracleError) as e:
+        o.accept()
+    assert e.value.code == -3
+    with pytest.raises(oracle_lib.OracleError) as e:
+        o.draft_step(np.zeros(2 * s.n_layers, np.uint8), 96, 0.5)
+    assert e.value.code in (-1, -2)
+
+
+def test_tiny_workload_runs_and_is_lossless(oracle_lib):
+    w = si.WORKLOADS["tiny"]
+    o = oracle_lib.Oracle(w.shape, w.n_prompt + w.n_new + w.max_k + 1)
+    o.set_weights(si.make_weights(w.shape, w.weight_seed))
+    prompt = si.workload_prompt(w)
+    ar = oracle_lib.generate_ar(o, prompt, w.n_new)
+    for eps in (w.conf_threshold, 0.0):
+        out, _ = oracle_lib.generate_swift(o, prompt, w.n_new, si.workload_mask(w), w.max_k, eps)
+        assert np.array_equal(out, ar)
