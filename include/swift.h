@@ -1,0 +1,190 @@
+/*
+ * swift.h -- C ABI of the MI355X (gfx950) hot path of on-the-fly self-speculative
+ * greedy decoding with a layer-skipping draft model.
+ *
+ * One decoding step of the method's acceleration phase (paper Section 4.2) is
+ *     swift_draft_step  ->  swift_verify  ->  swift_accept
+ * after one swift_prefill per input.  Plain autoregressive decoding of the
+ * target model is the same loop with no draft tokens (swift_verify with k = 0).
+ *
+ * Conventions
+ *  - Every function returns a status: SWIFT_OK (0) or a negative SWIFT_E* code.
+ *    Nothing throws or aborts across this boundary.  On an error the decoding
+ *    state (cache length, pending token, counters) is unchanged.
+ *  - "host" pointers are ordinary process memory owned by the caller; they are
+ *    only read or written during the call.  "device" pointers are HIP device
+ *    memory of the current device.
+ *  - The library allocates no device memory.  The caller hands it one device
+ *    arena (size from swift_device_bytes) that holds the re-laid-out weights,
+ *    the key/value cache, rotary tables and activations; the arena must stay
+ *    alive and untouched by others until swift_destroy.
+ *  - All GPU work is enqueued on the HIP stream given to swift_create; calls
+ *    that return results to the host synchronise that stream before returning.
+ *  - A context is not thread-safe; use one thread per context.
+ *
+ * Model (the paper names LLaMA-2 as backbone, Section 5.1): token embedding,
+ * n_layers x [RMSNorm -> rotary (half-split pairs) causal attention with
+ * n_q_heads query heads on n_kv_heads key/value heads -> residual add,
+ * RMSNorm -> SwiGLU MLP -> residual add], final RMSNorm, untied LM head; no
+ * biases.  Weights and the key/value cache are stored in `dtype`; the residual
+ * stream, normalised activations, queries, attention probabilities, MLP
+ * intermediates and logits are fp32 and every accumulation is fp32.
+ */
+#ifndef SWIFT_H_
+#define SWIFT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SWIFT_OK 0
+#define SWIFT_EINVAL (-1)    /* bad argument (null pointer, out-of-range value, unknown name, wrong size) */
+#define SWIFT_ECAPACITY (-2) /* the call would write a cache slot >= max_seq, or the arena is too small */
+#define SWIFT_ESTATE (-3)    /* call out of order (e.g. verify before prefill, accept before verify) */
+#define SWIFT_EDEVICE (-4)   /* a HIP call failed; swift_last_error() has the text */
+
+#define SWIFT_F32 0
+#define SWIFT_BF16 1
+
+/* Largest number of rows one verify block may hold (pending token + k drafts): k <= SWIFT_MAX_BLOCK - 1. */
+#define SWIFT_MAX_BLOCK 16
+
+typedef struct swift_model_config {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    int32_t max_seq;   /* capacity of the key/value cache in tokens */
+    float rms_eps, rope_theta;
+    int32_t dtype;     /* SWIFT_F32 or SWIFT_BF16: storage of weights and of the key/value cache */
+} swift_model_config;
+
+/* Counters behind the paper's metrics (Appendix B.3): mean generated length
+ * M = emitted_by_verify / verify_passes, acceptance rate alpha = accepted / draft_passes. */
+typedef struct swift_stats {
+    int64_t draft_passes;      /* draft-model forward passes (= drafted tokens) */
+    int64_t verify_passes;     /* target-model block passes */
+    int64_t accepted;          /* draft tokens that passed verification */
+    int64_t emitted_by_verify; /* tokens emitted by swift_accept (accepted + one target token per pass) */
+    int64_t emitted_total;     /* emitted_by_verify + the token produced by swift_prefill */
+} swift_stats;
+
+typedef struct swift_ctx swift_ctx; /* opaque, owned by the library */
+
+/* ---- host-only helpers (no GPU work; usable without a device) ------------------------------- */
+
+/* Checks a configuration: positive sizes, even head_dim <= 256 and a multiple of 8, n_q_heads a
+ * multiple of n_kv_heads, hidden / ffn / n_q_heads*head_dim multiples of 8, known dtype. */
+int swift_check_config(const swift_model_config *cfg);
+
+/* Bytes of device memory swift_create needs for this configuration (weights in the library's
+ * layout + key/value cache [layer][k|v][kv head][slot][head_dim] + tables + activations). */
+int swift_device_bytes(const swift_model_config *cfg, uint64_t *bytes);
+
+/* Expected wall-time speedup of the acceleration phase (Appendix B.3, Eq. 6):
+ * M * alpha / ((M - 1) * c + alpha), c = cost of a draft pass relative to a target pass. */
+double swift_expected_speedup(double mean_generated_length, double acceptance_rate, double cost_coefficient);
+
+/* Greedy prefix acceptance (Section 4.2; draft-then-verify under greedy decoding): the largest
+ * m <= k with draft[r] == target[r] for all r < m, where draft[r] is the (r+1)-th draft token and
+ * target[r] the target model's arg-max after block row r.  Both arrays: host, k entries read. */
+int swift_match_prefix(const int32_t *draft, const int32_t *target, int k);
+
+/* Bytes the method has to move from HBM for ONE forward pass (weights of the non-skipped sublayers
+ * and the LM head once, key/value slots [0, n_ctx) of the non-skipped attention sublayers, embedding
+ * rows, key/value writes of `rows` rows).  skip_mask: host, uint8[2*n_layers] or NULL (= full model). */
+int swift_pass_bytes(const swift_model_config *cfg, const uint8_t *skip_mask, int n_ctx, int rows, uint64_t *bytes);
+
+/* Text of the last error of the calling thread ("" if none).  Owned by the library. */
+const char *swift_last_error(void);
+
+/* ---- context ------------------------------------------------------------------------------- */
+
+/* Creates a context on the current HIP device.  device_mem: device arena of device_bytes bytes
+ * (>= swift_device_bytes, 256-byte aligned).  hip_stream: a hipStream_t (NULL = default stream).
+ * Builds the rotary cos/sin tables (angles in fp64 on the host, rounded to fp32). */
+int swift_create(const swift_model_config *cfg, void *device_mem, uint64_t device_bytes, void *hip_stream,
+                 swift_ctx **out);
+int swift_destroy(swift_ctx *ctx);
+
+/* Copies one tensor into the arena, converting to the library's layout.  data: host OR device
+ * pointer, row-major [out][in], n_elems elements of type `dtype`, which must equal the model's
+ * dtype for matrices and be SWIFT_F32 for the RMSNorm gains.  Names: "embed" [vocab][hidden],
+ * "lm_head" [vocab][hidden], "final_norm" [hidden], and for layer i: "l<i>.attn_norm" [hidden],
+ * "l<i>.wq" [n_q*d][hidden], "l<i>.wk", "l<i>.wv" [n_kv*d][hidden], "l<i>.wo" [hidden][n_q*d],
+ * "l<i>.mlp_norm" [hidden], "l<i>.wg", "l<i>.wu" [ffn][hidden], "l<i>.wd" [hidden][ffn].
+ * The caller's buffer may be freed after the call returns.  All tensors must be loaded before
+ * swift_prefill (else SWIFT_ESTATE). */
+int swift_load_tensor(swift_ctx *ctx, const char *name, const void *data, int dtype, int64_t n_elems);
+
+/* ---- the decoding path ----------------------------------------------------------------------- */
+
+/* Prefill: the full model over prompt[0..n_prompt) (host) at positions 0..n_prompt-1; fills the
+ * key/value cache; *first_token = arg-max of the last row, which becomes the pending token (the
+ * last emitted token, not yet in the cache).  Resets counters and state.  Needs
+ * 1 <= n_prompt < max_seq. */
+int swift_prefill(swift_ctx *ctx, const int32_t *prompt, int n_prompt, int32_t *first_token);
+
+/* Drafting (Section 4.2, Eq. 5 with early stopping): starting from the pending token at position
+ * n = cache length, runs the draft model -- the target model with the sublayers in skip_mask
+ * bypassed (Section 3.1) -- autoregressively for up to max_k tokens.  Draft token j is the arg-max
+ * of the draft logits (lowest index on ties), draft_conf[j-1] its top-1 softmax probability; drafting
+ * stops after the first token whose confidence is < conf_threshold (that token is kept).
+ * skip_mask: host, uint8[2*n_layers], entry 2l = attention sublayer of layer l, 2l+1 = its MLP,
+ * non-zero = skipped.  A skipped sublayer leaves the residual stream unchanged and writes no
+ * key/value.  Draft keys/values go to slots n.. of the non-skipped attention sublayers.
+ * draft_tokens / draft_conf: host arrays of max_k entries; *k_out in [0, max_k].
+ * Needs 0 <= max_k <= SWIFT_MAX_BLOCK - 1 and n + max_k + 1 <= max_seq (SWIFT_ECAPACITY). */
+int swift_draft_step(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold,
+                     int32_t *draft_tokens, float *draft_conf, int *k_out);
+
+/* Verification (Sections 1, 3.1: drafts are validated in parallel by the full model): the target
+ * model over the k+1 rows tokens[0..k] (host; tokens[0] must be the pending token) at positions
+ * n..n+k, row i attending slots 0..n+i; target keys/values overwrite slots n..n+k of every layer.
+ * target_tokens[i] (host, k+1 entries) = arg-max of row i.  logits_out: NULL, or host fp32
+ * [k+1][vocab].  k = 0 is one step of plain autoregressive decoding.
+ * Needs 0 <= k <= SWIFT_MAX_BLOCK - 1 and n + k + 1 <= max_seq. */
+int swift_verify(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out);
+
+/* Acceptance + roll-back after a swift_verify: m = swift_match_prefix(tokens[1..k], targets);
+ * emitted (host, capacity >= k+1) receives the m accepted draft tokens followed by the target's own
+ * token; *n_emitted = m + 1; the cache length becomes n + m + 1 and the last emitted token becomes
+ * the pending token.  Slots at or beyond the new cache length are don't-care from here on. */
+int swift_accept(swift_ctx *ctx, int32_t *emitted, int *n_emitted);
+
+/* Sets the cache length to new_cache_len <= current (no data is touched) and makes
+ * `pending_token` the pending token.  For callers that manage acceptance themselves. */
+int swift_rollback(swift_ctx *ctx, int new_cache_len, int32_t pending_token);
+
+int swift_get_state(swift_ctx *ctx, int *cache_len, int32_t *pending_token);
+int swift_get_stats(swift_ctx *ctx, swift_stats *out);
+
+/* ---- test and measurement hooks -------------------------------------------------------------- */
+
+/* NaN-fills every key/value slot at or beyond the cache length (results must not change). */
+int swift_debug_poison_kv(swift_ctx *ctx);
+/* Copies logits row `row` of the most recent pass (draft: row 0) to out (host fp32 [vocab]). */
+int swift_debug_read_logits(swift_ctx *ctx, int row, float *out);
+/* Copies slot `pos` of layer `layer` to k_out / v_out (host fp32 [n_kv_heads*head_dim] each). */
+int swift_debug_read_kv(swift_ctx *ctx, int layer, int pos, float *k_out, float *v_out);
+
+/* Kernel classes for per-kernel timing. */
+#define SWIFT_KC_QKV 0      /* RMSNorm + fused Q/K/V projection + rotation + cache append */
+#define SWIFT_KC_ATTN 1     /* attention over the cache (+ split combine) */
+#define SWIFT_KC_OPROJ 2    /* output projection + residual add */
+#define SWIFT_KC_GATEUP 3   /* RMSNorm + gate/up projections + SwiGLU */
+#define SWIFT_KC_DOWN 4     /* down projection + residual add */
+#define SWIFT_KC_LMHEAD 5   /* final RMSNorm + LM head + arg-max/softmax partials */
+#define SWIFT_KC_OTHER 6    /* embedding gather, arg-max finalisation */
+#define SWIFT_KC_COUNT 7
+
+/* Turns per-launch timing of one kernel class on (kernel_class in [0, SWIFT_KC_COUNT)) or off (-1).
+ * While on, every launch of that class is bracketed by HIP events on the context's stream. */
+int swift_profile_class(swift_ctx *ctx, int kernel_class);
+/* Synchronises, then returns the launches recorded since the last call, their summed duration in
+ * milliseconds and the summed algorithmic HBM bytes of those launches; resets the record. */
+int swift_profile_read(swift_ctx *ctx, int64_t *launches, double *total_ms, uint64_t *total_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIFT_H_ */

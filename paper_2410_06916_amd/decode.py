@@ -1,0 +1,46 @@
+"""Generation loops over the C-ABI calls (host control flow only; every forward pass,
+arg-max and confidence runs in the HIP library)."""
+from __future__ import annotations
+
+from typing import List, Sequence
+
+import numpy as np
+
+
+def generate_ar(m, prompt: Sequence[int], n_new: int, want_logits: bool = False):
+    """Plain greedy decoding: prefill, then one-row verify + accept per token."""
+    out = [m.prefill(prompt)]
+    logits = []
+    while len(out) < n_new:
+        tgt, lg = m.verify([m.pending], want_logits)
+        m.accept()
+        out.append(int(tgt[0]))
+        if want_logits:
+            logits.append(lg[0])
+    if want_logits:
+        return np.array(out, np.int32), logits
+    return np.array(out, np.int32)
+
+
+def generate_swift(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k: int, conf_threshold: float,
+                   poison: bool = False, want_logits: bool = False):
+    """Draft-then-verify greedy decoding (paper Section 4.2).  The draft length of a step is
+    capped at (tokens still wanted - 1), so exactly n_new tokens come out.
+    Returns (tokens, trace) with one dict per decoding step."""
+    out: List[int] = [m.prefill(prompt)]
+    trace: List[dict] = []
+    while len(out) < n_new:
+        if poison:
+            m.poison_kv()
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = m.cache_len
+        if k_cap > 0:
+            d, conf = m.draft_step(skip, k_cap, conf_threshold)
+        else:
+            d, conf = np.zeros(0, np.int32), np.zeros(0, np.float32)
+        block = np.concatenate([[m.pending], d]).astype(np.int32)
+        tgt, lg = m.verify(block, want_logits)
+        em = m.accept()
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, block=block, draft=d, conf=conf, target=tgt, emitted=em, m=len(em) - 1, logits=lg))
+    return np.array(out, np.int32), trace

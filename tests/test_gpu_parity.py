@@ -1,0 +1,193 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Token ids, draft lengths and accepted counts must match
+exactly; logits within 1e-4 (fp32 storage) / 2e-2 (bf16 storage) of the row's
+largest magnitude; confidences to the same relative tolerance."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as si
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def _pair(oracle_lib, shape, weights, max_seq, threads=8):
+    import paper_2410_06916_amd as P
+    o = oracle_lib.Oracle(shape, max_seq, threads=threads)
+    o.set_weights(weights)
+    g = P.SwiftModel(shape, max_seq)
+    g.load_weights(weights)
+    return o, g
+
+
+def _compare_traces(shape, to, tg):
+    tol = TOL[shape.dtype]
+    assert len(to) == len(tg)
+    for so, sg in zip(to, tg):
+        assert so["n"] == sg["n"]
+        assert np.array_equal(so["draft"], sg["draft"]), (so["draft"], sg["draft"])
+        assert np.array_equal(so["target"], sg["target"])
+        assert so["m"] == sg["m"] and np.array_equal(so["emitted"], sg["emitted"])
+        if len(so["conf"]):
+            assert np.allclose(sg["conf"], so["conf"], rtol=max(tol, 1e-4) * 5, atol=1e-7)
+        if so["logits"] is not None:
+            assert np.all(hp.rel_err_rowmax(sg["logits"], so["logits"]) <= tol)
+
+
+@pytest.fixture(scope="module")
+def tiny(oracle_lib):
+    w = si.WORKLOADS["tiny"]
+    weights = si.make_weights(w.shape, w.weight_seed)
+    o, g = _pair(oracle_lib, w.shape, weights, w.n_prompt + w.n_new + w.max_k + 1)
+    yield w, o, g
+    g.close()
+
+
+def test_tiny_workload_autoregressive(oracle_lib, tiny):
+    import paper_2410_06916_amd as P
+    w, o, g = tiny
+    prompt = si.workload_prompt(w)
+    want, wl = oracle_lib.generate_ar(o, prompt, w.n_new, want_logits=True)
+    got, gl = P.generate_ar(g, prompt, w.n_new, want_logits=True)
+    assert np.array_equal(got, want)
+    err = hp.rel_err_rowmax(np.stack(gl), wl[1:])
+    assert err.max() <= TOL["fp32"], err.max()
+    assert g.cache_len == o.cache_len and g.pending == o.pending
+
+
+@pytest.mark.parametrize("eps", [0.8, 0.0])
+def test_tiny_workload_speculative(oracle_lib, tiny, eps):
+    import paper_2410_06916_amd as P
+    w, o, g = tiny
+    prompt = si.workload_prompt(w)
+    mask = si.workload_mask(w)
+    want, to = oracle_lib.generate_swift(o, prompt, w.n_new, mask, w.max_k, eps, want_logits=True)
+    got, tg = P.generate_swift(g, prompt, w.n_new, mask, w.max_k, eps, want_logits=True)
+    assert np.array_equal(got, want)
+    _compare_traces(w.shape, to, tg)
+    so, sg = o.stats(), g.stats()
+    assert (sg["draft_passes"], sg["verify_passes"], sg["accepted"], sg["emitted_total"]) == \
+           (so["draft_passes"], so["verify_passes"], so["accepted"], so["emitted"])
+    assert sg["emitted_by_verify"] == sg["emitted_total"] - 1
+
+
+@pytest.mark.parametrize("shape", [hp.SMALL_GQA, hp.SMALL_GQA_BF16], ids=lambda s: s.name)
+def test_small_gqa_masks_thresholds_and_poison(oracle_lib, shape):
+    """Grouped-query shape with shaped weights: partial acceptance and early stops
+    really happen; slots beyond the cache length are NaN-filled before every step."""
+    import paper_2410_06916_amd as P
+    weights = hp.shaped_weights(shape, seed=21)
+    o, g = _pair(oracle_lib, shape, weights, 96, threads=1)
+    prompt = si.uniform_ids(11, 12, shape.vocab)
+    rng = np.random.default_rng(5)
+    L2 = 2 * shape.n_layers
+    masks = [np.zeros(L2, np.uint8), np.ones(L2, np.uint8)] + [(rng.random(L2) < 0.5).astype(np.uint8)
+                                                               for _ in range(4)]
+    partial = 0
+    for i, mask in enumerate(masks):
+        for max_k, eps in ((4, 0.5), (7, 0.0), (15, 0.3)):
+            want, to = oracle_lib.generate_swift(o, prompt, 40, mask, max_k, eps, poison=True, want_logits=True)
+            got, tg = P.generate_swift(g, prompt, 40, mask, max_k, eps, poison=True, want_logits=True)
+            assert np.array_equal(got, want), (i, max_k, eps)
+            _compare_traces(shape, to, tg)
+            partial += sum(0 < s["m"] < len(s["draft"]) for s in tg)
+    assert partial > 0
+    g.close()
+
+
+def test_draft_logits_and_cache_contents(oracle_lib):
+    """Draft-pass logits (read back through the debug hook) and the key/value slots a
+    draft pass and a verify pass leave behind."""
+    shape = hp.SMALL_GQA
+    weights = hp.shaped_weights(shape, seed=3)
+    o, g = _pair(oracle_lib, shape, weights, 64, threads=1)
+    prompt = si.uniform_ids(4, 20, shape.vocab)
+    assert g.prefill(prompt) == o.prefill(prompt)[0]
+    mask = np.zeros(2 * shape.n_layers, np.uint8)
+    mask[2] = 1   # attention of layer 1
+    mask[5] = 1   # MLP of layer 2
+    do, co = o.draft_step(mask, 1, 0.0)
+    dg, cg = g.draft_step(mask, 1, 0.0)
+    assert np.array_equal(do, dg)
+    want = o.forward_row(int(o.pending), o.cache_len, mask)      # same pass again, same slot
+    assert hp.rel_err_rowmax(g.read_logits(0), want)[0] <= 1e-4
+    for layer in (0, 2):                                           # non-skipped attention sublayers
+        ko, vo = o.read_kv(layer, o.cache_len)
+        kg, vg = g.read_kv(layer, g.cache_len)
+        assert np.allclose(kg, ko, rtol=1e-5, atol=1e-6) and np.allclose(vg, vo, rtol=1e-5, atol=1e-6)
+    block = np.concatenate([[o.pending], do]).astype(np.int32)
+    to, _ = o.verify(block)
+    tg, _ = g.verify(block)
+    assert np.array_equal(to, tg)
+    for layer in range(shape.n_layers):                            # verify rewrote every layer's slots
+        for pos in (o.cache_len, o.cache_len + 1):
+            ko, vo = o.read_kv(layer, pos)
+            kg, vg = g.read_kv(layer, pos)
+            assert np.allclose(kg, ko, rtol=1e-5, atol=1e-6) and np.allclose(vg, vo, rtol=1e-5, atol=1e-6)
+    g.close()
+
+
+def test_errors_and_state_machine_on_device(oracle_lib):
+    import paper_2410_06916_amd as P
+    shape = hp.SMALL_GQA
+    g = P.SwiftModel(shape, 16)
+    with pytest.raises(P.SwiftError) as e:
+        g.prefill([1, 2, 3])                       # weights not loaded
+    assert e.value.code == -3
+    g.load_weights(hp.shaped_weights(shape, seed=1))
+    with pytest.raises(P.SwiftError) as e:
+        g.verify([1])                              # before prefill
+    assert e.value.code == -3
+    with pytest.raises(P.SwiftError) as e:
+        g.prefill(list(range(16)))                 # no room left
+    assert e.value.code == -2
+    with pytest.raises(P.SwiftError) as e:
+        g.prefill([1, 2, shape.vocab])             # id out of range
+    assert e.value.code == -1
+    t = g.prefill([1, 2, 3])
+    with pytest.raises(P.SwiftError) as e:
+        g.accept()                                 # nothing verified
+    assert e.value.code == -3
+    with pytest.raises(P.SwiftError) as e:
+        g.verify([t + 1 if t + 1 < shape.vocab else 0])   # first row is not the pending token
+    assert e.value.code == -1
+    with pytest.raises(P.SwiftError) as e:
+        g.draft_step(np.zeros(2 * shape.n_layers, np.uint8), 16, 0.5)
+    assert e.value.code == -1
+    n0 = g.cache_len
+    with pytest.raises(P.SwiftError) as e:
+        g.draft_step(np.zeros(2 * shape.n_layers, np.uint8), 15, 0.5)   # 3 + 15 + 1 > 16 slots
+    assert e.value.code == -2
+    with pytest.raises(P.SwiftError) as e:
+        g.verify([t] * 14)
+    assert e.value.code == -2
+    assert g.cache_len == n0 and g.pending == t     # state untouched by failed calls
+    # explicit roll-back: decode two tokens, rewind, decode them again
+    a1, _ = g.verify([g.pending]); g.accept()
+    a2, _ = g.verify([g.pending]); g.accept()
+    g.rollback(n0, t)
+    b1, _ = g.verify([g.pending]); g.accept()
+    b2, _ = g.verify([g.pending]); g.accept()
+    assert (a1[0], a2[0]) == (b1[0], b2[0])
+    g.close()
+
+
+@pytest.mark.parametrize("base,n_layers", [(si.LLAMA2_7B, 2)], ids=["7b-width-2-layers"])
+def test_full_width_narrow_depth(oracle_lib, base, n_layers):
+    """Same widths, heads, FFN, vocab and dtype as the 7B workload, two layers deep."""
+    import paper_2410_06916_amd as P
+    shape = base.with_layers(n_layers)
+    weights = si.make_weights(shape, 0)
+    o, g = _pair(oracle_lib, shape, weights, 48, threads=8)
+    prompt = si.uniform_ids(1, 12, shape.vocab)
+    mask = np.array([0, 1, 1, 0], np.uint8)
+    want, to = oracle_lib.generate_swift(o, prompt, 10, mask, 3, 0.0, want_logits=True)
+    got, tg = P.generate_swift(g, prompt, 10, mask, 3, 0.0, want_logits=True)
+    assert np.array_equal(got, want)
+    _compare_traces(shape, to, tg)
+    g.close()
