@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the self-speculative decoding hot path on one MI355X.
+
+One "step" is one whole pass of the hot path over one synthetic input of the
+7B workload: prefill of the 512-token prompt, then 256 greedy new tokens through
+draft (skip mask, max 8 drafts, confidence stop 0.8) -> verify -> accept.
+`value` is decode throughput (new tokens after the prefill token / time from the
+end of prefill to the last token), inputs and weights resident in HBM.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def run_generation(P, g, prompt, n_new, mask, max_k, eps):
+    """One step.  Returns (tokens, prefill_s, decode_s, trace)."""
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    out = [g.prefill(prompt)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    trace = []
+    while len(out) < n_new:
+        k_cap = min(max_k, n_new - len(out) - 1)
+        if k_cap > 0:
+            d, conf = g.draft_step(mask, k_cap, eps)
+        else:
+            d = np.zeros(0, np.int32)
+        block = np.concatenate([[g.pending], d]).astype(np.int32)
+        g.verify(block)
+        em = g.accept()
+        out.extend(int(t) for t in em)
+        trace.append((len(d), len(em) - 1))
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    return np.array(out, np.int32), t1 - t0, t2 - t1, trace
+
+
+def cpu_baseline(shape, workload, mask, seed, device, seconds_hint=25.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same
+    workload: same model shape, mask and speculation settings, short prompt, few tokens."""
+    import synthetic_inputs as si
+    from oracle import reference as R
+    cores = min(os.cpu_count() or 1, R.threads_available(), 16)
+    n_prompt, n_new = 16, 24
+    o = R.Oracle(shape, n_prompt + n_new + workload.max_k + 2, threads=cores)
+    t0 = time.perf_counter()
+    for name, t in si.iter_weights(shape, seed, device):
+        o.set_tensor(name, t.cpu())
+    log(f"[cpu_baseline] weights on host in {time.perf_counter() - t0:.1f}s, {cores} threads")
+    prompt = si.uniform_ids(workload.prompt_seed, n_prompt, shape.vocab)
+    t0 = time.perf_counter()
+    o.prefill(prompt)
+    t1 = time.perf_counter()
+    emitted = 1
+    while emitted < n_new:
+        k_cap = min(workload.max_k, n_new - emitted - 1)
+        d = o.draft_step(mask, k_cap, workload.conf_threshold)[0] if k_cap > 0 else np.zeros(0, np.int32)
+        o.verify(np.concatenate([[o.pending], d]).astype(np.int32))
+        emitted += len(o.accept())
+    t2 = time.perf_counter()
+    log(f"[cpu_baseline] prefill {t1 - t0:.1f}s, decode {t2 - t1:.1f}s")
+    st = o.stats()
+    o.close()
+    return {"value": (emitted - 1) / (t2 - t1), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"same 7B-shape weights and mask, prompt {n_prompt}, {emitted - 1} new tokens after prefill "
+                      f"({st['draft_passes']} draft + {st['verify_passes']} verify passes), fp64 arithmetic"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-modes", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import synthetic_inputs as si
+    import paper_2410_06916_amd as P
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    dev = "cuda:0"
+    w = si.WORKLOADS[args.workload]
+    shape = w.shape
+    mask = si.workload_mask(w)
+    prompt = si.workload_prompt(w)
+    max_seq = w.n_prompt + w.n_new + w.max_k + 8
+
+    t0 = time.perf_counter()
+    g = P.SwiftModel(shape, max_seq, dev)
+    for name, t in si.iter_weights(shape, w.weight_seed, dev):
+        g.load_tensor(name, t)
+    torch.cuda.synchronize()
+    log(f"[bench] {shape.name}: weights generated and loaded in {time.perf_counter() - t0:.1f}s; "
+        f"arena {P.device_bytes(g.cfg) / 1e9:.2f} GB")
+
+    for i in range(args.warmup):
+        toks, pf, dc, _ = run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold)
+        log(f"[bench] warmup {i}: prefill {pf * 1e3:.1f} ms, decode {dc * 1e3:.1f} ms")
+
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    pf_s = dc_s = 0.0
+    ref = None
+    for i in range(args.steps):
+        toks, pf, dc, trace = run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold)
+        pf_s += pf
+        dc_s += dc
+        if ref is None:
+            ref = toks
+        assert np.array_equal(ref, toks), "non-deterministic output"
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    st = g.stats()
+    n_after = w.n_new - 1
+    value = n_after * args.steps / dc_s
+    log(f"[bench] timed: {args.steps} steps, {wall / args.steps * 1e3:.1f} ms/step, decode {value:.1f} tok/s")
+
+    # ---- roofline of the dominant kernel (gate/up projection + SwiGLU): same step, its launches
+    # bracketed by HIP events on the library's stream
+    g.profile_class("gateup")
+    run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold)
+    n_l, ms, nbytes = g.profile_read()
+    g.profile_class(None)
+    per_launch_bytes = nbytes / max(n_l, 1)
+    avg_us = ms * 1e3 / max(n_l, 1)
+    achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if n_l else 0.0
+    roofline = {"bound": "hbm", "kernel": "k_gemv<bf16, gate/up + SwiGLU>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches": n_l, "avg_us": round(avg_us, 2), "bytes_per_launch": int(per_launch_bytes)}
+    log(f"[bench] gate/up kernel: {n_l} launches, avg {avg_us:.2f} us, {achieved:.0f} GB/s")
+
+    per_class = {}
+    if not args.no_extra_modes:
+        for kc in ("qkv", "attn", "oproj", "down", "lmhead"):
+            g.profile_class(kc)
+            g.prefill(prompt[:8])
+            for _ in range(16):
+                d, _c = g.draft_step(mask, 1, 2.0)
+                g.verify(np.concatenate([[g.pending], d]).astype(np.int32))
+                g.accept()
+            n_l2, ms2, b2 = g.profile_read()
+            g.profile_class(None)
+            if n_l2:
+                per_class[kc] = {"avg_us": round(ms2 * 1e3 / n_l2, 2),
+                                 "GBps": round(b2 / max(ms2, 1e-9) / 1e6, 1), "launches": n_l2}
+        per_class["gateup"] = {"avg_us": roofline["avg_us"], "GBps": roofline["achieved"], "launches": n_l}
+
+    # ---- other modes (one step each): plain autoregressive, forced-length drafts
+    modes = {"as_configured": {"tokens_per_s": round(value, 2),
+                               "M": round(st["emitted_by_verify"] / max(st["verify_passes"], 1), 3),
+                               "alpha": round(st["accepted"] / max(st["draft_passes"], 1), 4)}}
+    if not args.no_extra_modes:
+        _, pf, dc, _ = run_generation(P, g, prompt, w.n_new, mask, 0, 0.0)
+        modes["autoregressive"] = {"tokens_per_s": round(n_after / dc, 2)}
+        _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, w.max_k, 0.0)
+        s2 = g.stats()
+        modes["forced_max_draft"] = {"tokens_per_s": round(n_after / dc, 2),
+                                     "M": round(s2["emitted_by_verify"] / max(s2["verify_passes"], 1), 3),
+                                     "alpha": round(s2["accepted"] / max(s2["draft_passes"], 1), 4)}
+        none = np.zeros_like(mask)
+        _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, none, w.max_k, 0.0)
+        s3 = g.stats()
+        modes["forced_max_draft_no_skip"] = {"tokens_per_s": round(n_after / dc, 2),
+                                             "M": round(s3["emitted_by_verify"] / max(s3["verify_passes"], 1), 3),
+                                             "alpha": round(s3["accepted"] / max(s3["draft_passes"], 1), 4)}
+        log(f"[bench] modes: {modes}")
+
+    draft_bytes = P.pass_bytes(g.cfg, mask, w.n_prompt, 1)
+    full_bytes = P.pass_bytes(g.cfg, None, w.n_prompt, 1)
+    g.close()
+    del g
+    torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, w, mask, w.weight_seed, dev)
+
+    result = {
+        "metric": "decode tokens/s at batch 1 (7B shape)" if args.workload == "7b" else f"decode tokens/s at batch 1 ({args.workload})",
+        "value": round(value, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{shape.name} random-init N(0,0.02), batch 1, prompt {w.n_prompt}, {w.n_new} greedy new "
+                               f"tokens, skip {int(mask.sum())} of {mask.size} sublayers, max draft {w.max_k}, "
+                               f"confidence stop {w.conf_threshold}",
+                   "prefill_ms": round(pf_s / args.steps * 1e3, 2), "decode_ms": round(dc_s / args.steps * 1e3, 2),
+                   "draft_pass_bytes": draft_bytes, "full_pass_bytes": full_bytes},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "modes": modes,
+        "kernels": per_class,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
