@@ -72,8 +72,9 @@ typedef struct swift_ctx swift_ctx; /* opaque, owned by the library */
 
 /* ---- host-only helpers (no GPU work; usable without a device) ------------------------------- */
 
-/* Checks a configuration: positive sizes, even head_dim <= 256 and a multiple of 8, n_q_heads a
- * multiple of n_kv_heads, hidden / ffn / n_q_heads*head_dim multiples of 8, known dtype. */
+/* Checks a configuration: positive sizes; head_dim 16, 32, 64 or 128; n_q_heads = 1, 2, 4 or 8
+ * times n_kv_heads; hidden and ffn multiples of 8, vocab even, each at most 40704 (one fp32
+ * activation row has to fit in LDS); known dtype. */
 int swift_check_config(const swift_model_config *cfg);
 
 /* Bytes of device memory swift_create needs for this configuration (weights in the library's
@@ -176,6 +177,11 @@ int swift_debug_read_kv(swift_ctx *ctx, int layer, int pos, float *k_out, float 
 #define SWIFT_KC_LMHEAD 5   /* final RMSNorm + LM head + arg-max/softmax partials */
 #define SWIFT_KC_OTHER 6    /* embedding gather, arg-max finalisation */
 #define SWIFT_KC_COUNT 7
+
+/* Overrides the launch shape of the tiled single-row projection kernel of one class: wavefronts
+ * that share a 16-row group (0 = automatic, else 1, 2, 4 or 8) and workgroups (0 = automatic).
+ * Results do not depend on it bit for bit only within one setting; it exists for tuning runs. */
+int swift_debug_tune(swift_ctx *ctx, int kernel_class, int waves_per_row_group, int workgroups);
 
 /* Turns per-launch timing of one kernel class on (kernel_class in [0, SWIFT_KC_COUNT)) or off (-1).
  * While on, every launch of that class is bracketed by HIP events on the context's stream. */

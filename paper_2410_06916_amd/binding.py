@@ -71,6 +71,7 @@ def lib():
     L.swift_debug_poison_kv.argtypes = [vp]
     L.swift_debug_read_logits.argtypes = [vp, C.c_int, f32p]
     L.swift_debug_read_kv.argtypes = [vp, C.c_int, C.c_int, f32p, f32p]
+    L.swift_debug_tune.argtypes = [vp, C.c_int, C.c_int, C.c_int]
     L.swift_profile_class.argtypes = [vp, C.c_int]
     L.swift_profile_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     _lib = L
@@ -237,6 +238,9 @@ class SwiftModel:
         v = np.empty(w, np.float32)
         _chk(lib().swift_debug_read_kv(self._h, layer, pos, _p(k, C.c_float), _p(v, C.c_float)), "swift_debug_read_kv")
         return k, v
+
+    def tune(self, name: str, waves_per_row_group: int = 0, workgroups: int = 0):
+        _chk(lib().swift_debug_tune(self._h, KERNEL_CLASSES[name], waves_per_row_group, workgroups), "swift_debug_tune")
 
     def profile_class(self, name: Optional[str]):
         _chk(lib().swift_profile_class(self._h, -1 if name is None else KERNEL_CLASSES[name]), "swift_profile_class")

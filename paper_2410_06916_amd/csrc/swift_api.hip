@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -71,9 +72,16 @@ struct Layout {
     std::vector<LayerOff> layers;
     uint64_t cos, sin, kv;
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf;
+    uint64_t stage, stage_bytes;  // staging for host tensors that are re-tiled on the device
     uint64_t total;
     int n_split_max;
+    // bf16 matrices whose activation row fits the MFMA kernel's LDS budget are stored tiled
+    bool tiled_h, tiled_q, tiled_f;  // for K = hidden, K = n_q*d, K = ffn
 };
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+// bytes of a tiled [rows][K] bf16 matrix whose row groups hold `rows_per_group` matrix rows... (16 tile rows)
+inline uint64_t tiled_bytes(uint64_t n_rg, uint64_t K) { return n_rg * ceil_div(K, 32) * 1024; }
 
 Layout make_layout(const swift_model_config &c) {
     Layout L;
@@ -86,17 +94,21 @@ Layout make_layout(const swift_model_config &c) {
         off = align_up(off + bytes);
         return o;
     };
+    const bool bf = c.dtype == SWIFT_BF16;
+    L.tiled_h = bf && mv_lds_bytes((int)H) <= kMvMaxLds;
+    L.tiled_q = bf && mv_lds_bytes((int)Q) <= kMvMaxLds;
+    L.tiled_f = bf && mv_lds_bytes((int)F) <= kMvMaxLds;
     L.embed = take(V * H * eb);
-    L.lm_head = take(V * H * eb);
+    L.lm_head = take(L.tiled_h ? tiled_bytes(ceil_div(V, 16), H) : V * H * eb);
     L.final_norm = take(H * 4);
     L.layers.resize(c.n_layers);
     for (auto &y : L.layers) {
         y.attn_norm = take(H * 4);
-        y.wqkv = take((Q + 2 * KV) * H * eb);
-        y.wo = take(H * Q * eb);
+        y.wqkv = take(L.tiled_h ? tiled_bytes((Q + 2 * KV) / 16, H) : (Q + 2 * KV) * H * eb);
+        y.wo = take(L.tiled_q ? tiled_bytes(ceil_div(H, 16), Q) : H * Q * eb);
         y.mlp_norm = take(H * 4);
-        y.wgu = take(2 * F * H * eb);
-        y.wd = take(H * F * eb);
+        y.wgu = take(L.tiled_h ? tiled_bytes(ceil_div(F, 8), H) : 2 * F * H * eb);
+        y.wd = take(L.tiled_f ? tiled_bytes(ceil_div(H, 16), F) : H * F * eb);
     }
     L.cos = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
     L.sin = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
@@ -111,6 +123,8 @@ Layout make_layout(const swift_model_config &c) {
     L.part_ml = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * 2 * 4);
     L.out_tok = take(kMaxRows * 4);
     L.out_conf = take(kMaxRows * 4);
+    L.stage_bytes = bf ? std::max(std::max(V * H, F * H), std::max(Q * H, KV * H)) * eb : 0;
+    L.stage = take(L.stage_bytes);
     L.total = off;
     return L;
 }
@@ -191,6 +205,8 @@ struct swift_ctx {
     int k_verify;     // -1: no verify outstanding
     int32_t vtokens[SWIFT_MAX_BLOCK], targets[SWIFT_MAX_BLOCK];
     swift_stats st;
+    // launch-shape overrides per kernel class (0 = automatic); measurement hook
+    int tune_ks[SWIFT_KC_COUNT], tune_wg[SWIFT_KC_COUNT];
     // profiling
     int prof_class;
     std::vector<ProfRec> prof;
@@ -234,46 +250,99 @@ char *kv_base(swift_ctx *x, int layer, int which) {
     return x->base + x->L.kv + ((uint64_t)layer * 2 + which) * per;
 }
 
+// One projection of one activation row: tiled MFMA kernel when the matrix is stored tiled,
+// otherwise the generic row-major kernel.  `rope_pos` >= 0 selects the q|k|v epilogue.
+struct LinearCall {
+    int kc, epi;
+    uint64_t w_off;
+    bool tiled;
+    int O, K, n_rg;
+    const float *xin, *gain;
+    float *out;
+    int layer, pos;
+};
+
+int run_linear(swift_ctx *x, const LinearCall &lc) {
+    const swift_model_config &c = x->c;
+    const int d = c.head_dim;
+    const uint64_t eb = elem_bytes(c.dtype);
+    hipStream_t s = x->stream;
+    void *kc = lc.epi == EPI_QKV ? kv_base(x, lc.layer, 0) : nullptr;
+    void *vc = lc.epi == EPI_QKV ? kv_base(x, lc.layer, 1) : nullptr;
+    const float *cr = lc.epi == EPI_QKV ? dptr<float>(x, x->L.cos) + (size_t)lc.pos * (d / 2) : nullptr;
+    const float *sr = lc.epi == EPI_QKV ? dptr<float>(x, x->L.sin) + (size_t)lc.pos * (d / 2) : nullptr;
+    const uint64_t bytes = (uint64_t)lc.O * lc.K * eb;
+    if (lc.tiled) {
+        MvArgs m{};
+        m.Wt = x->base + lc.w_off;
+        m.O = lc.O;
+        m.K = lc.K;
+        m.T = (lc.K + 31) / 32;
+        m.n_rg = lc.n_rg;
+        m.xin = lc.xin;
+        m.gain = lc.gain;
+        m.eps = c.rms_eps;
+        m.out = lc.out;
+        m.kcache = kc;
+        m.vcache = vc;
+        m.cos_row = cr;
+        m.sin_row = sr;
+        m.pos = lc.pos;
+        m.max_seq = c.max_seq;
+        m.head_dim = d;
+        m.n_q_heads = c.n_q_heads;
+        m.n_kv_heads = c.n_kv_heads;
+        HIP_TRY(timed(x, lc.kc, bytes, [&] {
+            return launch_mv1(lc.epi, m, x->n_cu, x->tune_ks[lc.kc], x->tune_wg[lc.kc], s);
+        }));
+    } else {
+        GemvArgs g{};
+        g.W = x->base + lc.w_off;
+        g.O = lc.O;
+        g.K = lc.K;
+        g.xin = lc.xin;
+        g.gain = lc.gain;
+        g.eps = c.rms_eps;
+        g.out = lc.out;
+        g.kcache = kc;
+        g.vcache = vc;
+        g.cos_row = cr;
+        g.sin_row = sr;
+        g.pos = lc.pos;
+        g.max_seq = c.max_seq;
+        g.head_dim = d;
+        g.n_q_heads = c.n_q_heads;
+        g.n_kv_heads = c.n_kv_heads;
+        HIP_TRY(timed(x, lc.kc, bytes, [&] { return launch_gemv(c.dtype, lc.epi, g, x->n_cu, s); }));
+    }
+    return SWIFT_OK;
+}
+
 // One token through the network at position `pos`; row = which row of the activation /
 // logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM head and
 // the arg-max for this row.
 int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int row, bool want_logits) {
     const swift_model_config &c = x->c;
+    const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
     const uint64_t eb = elem_bytes(c.dtype);
     hipStream_t s = x->stream;
-    float *xr = dptr<float>(x, x->L.x) + (size_t)row * H;
-    float *qr = dptr<float>(x, x->L.q) + (size_t)row * Q;
-    float *ar = dptr<float>(x, x->L.att) + (size_t)row * Q;
-    float *hr = dptr<float>(x, x->L.h) + (size_t)row * F;
-    float *lr = dptr<float>(x, x->L.logits) + (size_t)row * V;
+    float *xr = dptr<float>(x, L.x) + (size_t)row * H;
+    float *qr = dptr<float>(x, L.q) + (size_t)row * Q;
+    float *ar = dptr<float>(x, L.att) + (size_t)row * Q;
+    float *hr = dptr<float>(x, L.h) + (size_t)row * F;
+    float *lr = dptr<float>(x, L.logits) + (size_t)row * V;
+    int rc;
 
-    EmbedArgs ea{x->base + x->L.embed, H, token, xr};
+    EmbedArgs ea{x->base + L.embed, H, token, xr};
     HIP_TRY(timed(x, SWIFT_KC_OTHER, H * eb, [&] { return launch_embed(c.dtype, ea, s); }));
 
     for (int l = 0; l < c.n_layers; ++l) {
-        const LayerOff &y = x->L.layers[l];
+        const LayerOff &y = L.layers[l];
         if (!(skip && skip[2 * l])) {
-            GemvArgs g{};
-            g.W = x->base + y.wqkv;
-            g.O = Q + 2 * KV;
-            g.K = H;
-            g.xin = xr;
-            g.gain = dptr<float>(x, y.attn_norm);
-            g.eps = c.rms_eps;
-            g.out = qr;
-            g.kcache = kv_base(x, l, 0);
-            g.vcache = kv_base(x, l, 1);
-            g.cos_row = dptr<float>(x, x->L.cos) + (size_t)pos * (d / 2);
-            g.sin_row = dptr<float>(x, x->L.sin) + (size_t)pos * (d / 2);
-            g.pos = pos;
-            g.max_seq = c.max_seq;
-            g.head_dim = d;
-            g.n_q_heads = c.n_q_heads;
-            g.n_kv_heads = c.n_kv_heads;
-            HIP_TRY(timed(x, SWIFT_KC_QKV, (uint64_t)g.O * g.K * eb,
-                          [&] { return launch_gemv(c.dtype, EPI_QKV, g, x->n_cu, s); }));
-
+            rc = run_linear(x, LinearCall{SWIFT_KC_QKV, EPI_QKV, y.wqkv, L.tiled_h, Q + 2 * KV, H, (Q + 2 * KV) / 16, xr,
+                                          dptr<float>(x, y.attn_norm), qr, l, pos});
+            if (rc) return rc;
             AttnArgs a{};
             a.q = qr;
             a.kcache = kv_base(x, l, 0);
@@ -283,60 +352,29 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.head_dim = d;
             a.n_q_heads = c.n_q_heads;
             a.n_kv_heads = c.n_kv_heads;
-            a.part_o = dptr<float>(x, x->L.part_o);
-            a.part_ml = dptr<float>(x, x->L.part_ml);
+            a.part_o = dptr<float>(x, L.part_o);
+            a.part_ml = dptr<float>(x, L.part_ml);
             a.out = ar;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
                           [&] { return launch_attn_decode(c.dtype, a, s); }));
-
-            GemvArgs o{};
-            o.W = x->base + y.wo;
-            o.O = H;
-            o.K = Q;
-            o.xin = ar;
-            o.gain = nullptr;
-            o.out = xr;
-            o.head_dim = d;
-            HIP_TRY(timed(x, SWIFT_KC_OPROJ, (uint64_t)o.O * o.K * eb,
-                          [&] { return launch_gemv(c.dtype, EPI_RESID, o, x->n_cu, s); }));
+            rc = run_linear(x, LinearCall{SWIFT_KC_OPROJ, EPI_RESID, y.wo, L.tiled_q, H, Q, (H + 15) / 16, ar, nullptr, xr,
+                                          l, pos});
+            if (rc) return rc;
         }
         if (!(skip && skip[2 * l + 1])) {
-            GemvArgs g{};
-            g.W = x->base + y.wgu;
-            g.O = 2 * F;
-            g.K = H;
-            g.xin = xr;
-            g.gain = dptr<float>(x, y.mlp_norm);
-            g.eps = c.rms_eps;
-            g.out = hr;
-            g.head_dim = d;
-            HIP_TRY(timed(x, SWIFT_KC_GATEUP, (uint64_t)g.O * g.K * eb,
-                          [&] { return launch_gemv(c.dtype, EPI_SWIGLU, g, x->n_cu, s); }));
-            GemvArgs w{};
-            w.W = x->base + y.wd;
-            w.O = H;
-            w.K = F;
-            w.xin = hr;
-            w.gain = nullptr;
-            w.out = xr;
-            w.head_dim = d;
-            HIP_TRY(timed(x, SWIFT_KC_DOWN, (uint64_t)w.O * w.K * eb,
-                          [&] { return launch_gemv(c.dtype, EPI_RESID, w, x->n_cu, s); }));
+            rc = run_linear(x, LinearCall{SWIFT_KC_GATEUP, EPI_SWIGLU, y.wgu, L.tiled_h, 2 * F, H, (F + 7) / 8, xr,
+                                          dptr<float>(x, y.mlp_norm), hr, l, pos});
+            if (rc) return rc;
+            rc = run_linear(x, LinearCall{SWIFT_KC_DOWN, EPI_RESID, y.wd, L.tiled_f, H, F, (H + 15) / 16, hr, nullptr, xr,
+                                          l, pos});
+            if (rc) return rc;
         }
     }
     if (want_logits) {
-        GemvArgs g{};
-        g.W = x->base + x->L.lm_head;
-        g.O = V;
-        g.K = H;
-        g.xin = xr;
-        g.gain = dptr<float>(x, x->L.final_norm);
-        g.eps = c.rms_eps;
-        g.out = lr;
-        g.head_dim = d;
-        HIP_TRY(timed(x, SWIFT_KC_LMHEAD, (uint64_t)g.O * g.K * eb,
-                      [&] { return launch_gemv(c.dtype, EPI_LOGITS, g, x->n_cu, s); }));
-        ArgmaxArgs m{lr, V, 1, dptr<int32_t>(x, x->L.out_tok) + row, dptr<float>(x, x->L.out_conf) + row};
+        rc = run_linear(x, LinearCall{SWIFT_KC_LMHEAD, EPI_LOGITS, L.lm_head, L.tiled_h, V, H, (V + 15) / 16, xr,
+                                      dptr<float>(x, L.final_norm), lr, 0, pos});
+        if (rc) return rc;
+        ArgmaxArgs m{lr, V, 1, dptr<int32_t>(x, L.out_tok) + row, dptr<float>(x, L.out_conf) + row};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)V * 4, [&] { return launch_argmax_conf(m, s); }));
     }
     return SWIFT_OK;
@@ -357,41 +395,61 @@ struct Slot {
     int64_t n;          // expected element count
     bool is_gain;
     int rows, cols;     // matrix shape [rows][cols] as given by the caller
-    uint64_t dst_pitch; // bytes between consecutive destination rows (0 = contiguous)
+    uint64_t dst_pitch; // row-major destination: bytes between consecutive rows (0 = contiguous)
+    bool tiled;         // destination is in the tiled MFMA layout
+    int tile_mode, part;
+    int n_rg;           // row groups this tensor fills
 };
 
 bool find_slot(swift_ctx *x, const char *name, Slot *out) {
     const swift_model_config &c = x->c;
+    const Layout &L = x->L;
     const uint64_t eb = elem_bytes(c.dtype);
-    const int H = c.hidden, Q = c.n_q_heads * c.head_dim, KV = c.n_kv_heads * c.head_dim, F = c.ffn, V = c.vocab;
+    const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
     auto mat = [&](int idx, uint64_t off, int r, int k, uint64_t pitch = 0) {
-        *out = Slot{idx, off, (int64_t)r * k, false, r, k, pitch};
+        *out = Slot{idx, off, (int64_t)r * k, false, r, k, pitch, false, 0, 0, 0};
+        return true;
+    };
+    auto tiled = [&](int idx, uint64_t off, int r, int k, int mode, int part, int n_rg) {
+        *out = Slot{idx, off, (int64_t)r * k, false, r, k, 0, true, mode, part, n_rg};
         return true;
     };
     auto gain = [&](int idx, uint64_t off) {
-        *out = Slot{idx, off, H, true, 1, H, 0};
+        *out = Slot{idx, off, H, true, 1, H, 0, false, 0, 0, 0};
         return true;
     };
-    if (!strcmp(name, "embed")) return mat(0, x->L.embed, V, H);
-    if (!strcmp(name, "lm_head")) return mat(1, x->L.lm_head, V, H);
-    if (!strcmp(name, "final_norm")) return gain(2, x->L.final_norm);
+    const uint64_t TH = (uint64_t)((H + 31) / 32) * 1024;  // bytes of one row group with K = hidden
+    if (!strcmp(name, "embed")) return mat(0, L.embed, V, H);
+    if (!strcmp(name, "lm_head"))
+        return L.tiled_h ? tiled(1, L.lm_head, V, H, TILE_PLAIN, 0, (V + 15) / 16) : mat(1, L.lm_head, V, H);
+    if (!strcmp(name, "final_norm")) return gain(2, L.final_norm);
     if (name[0] != 'l') return false;
     char *end;
     long l = strtol(name + 1, &end, 10);
     if (end == name + 1 || *end != '.' || l < 0 || l >= c.n_layers) return false;
     const char *f = end + 1;
-    const LayerOff &y = x->L.layers[l];
+    const LayerOff &y = L.layers[l];
     const int b = 3 + 9 * (int)l;
     if (!strcmp(f, "attn_norm")) return gain(b + 0, y.attn_norm);
-    if (!strcmp(f, "wq")) return mat(b + 1, y.wqkv, Q, H);
-    if (!strcmp(f, "wk")) return mat(b + 2, y.wqkv + (uint64_t)Q * H * eb, KV, H);
-    if (!strcmp(f, "wv")) return mat(b + 3, y.wqkv + (uint64_t)(Q + KV) * H * eb, KV, H);
-    if (!strcmp(f, "wo")) return mat(b + 4, y.wo, H, Q);
+    if (L.tiled_h) {
+        // fused q|k|v, rotary pairs in one row group; d/16 row groups per head
+        if (!strcmp(f, "wq")) return tiled(b + 1, y.wqkv, Q, H, TILE_PAIR, 0, Q / 16);
+        if (!strcmp(f, "wk")) return tiled(b + 2, y.wqkv + (uint64_t)(Q / 16) * TH, KV, H, TILE_PAIR, 0, KV / 16);
+        if (!strcmp(f, "wv"))
+            return tiled(b + 3, y.wqkv + (uint64_t)((Q + KV) / 16) * TH, KV, H, TILE_PAIR, 0, KV / 16);
+        if (!strcmp(f, "wg")) return tiled(b + 6, y.wgu, F, H, TILE_GATEUP, 0, (F + 7) / 8);
+        if (!strcmp(f, "wu")) return tiled(b + 7, y.wgu, F, H, TILE_GATEUP, 1, (F + 7) / 8);
+    } else {
+        if (!strcmp(f, "wq")) return mat(b + 1, y.wqkv, Q, H);
+        if (!strcmp(f, "wk")) return mat(b + 2, y.wqkv + (uint64_t)Q * H * eb, KV, H);
+        if (!strcmp(f, "wv")) return mat(b + 3, y.wqkv + (uint64_t)(Q + KV) * H * eb, KV, H);
+        // gate and up rows are interleaved: row 2f = gate f, row 2f+1 = up f
+        if (!strcmp(f, "wg")) return mat(b + 6, y.wgu, F, H, 2 * (uint64_t)H * eb);
+        if (!strcmp(f, "wu")) return mat(b + 7, y.wgu + (uint64_t)H * eb, F, H, 2 * (uint64_t)H * eb);
+    }
+    if (!strcmp(f, "wo")) return L.tiled_q ? tiled(b + 4, y.wo, H, Q, TILE_PLAIN, 0, (H + 15) / 16) : mat(b + 4, y.wo, H, Q);
     if (!strcmp(f, "mlp_norm")) return gain(b + 5, y.mlp_norm);
-    // gate and up rows are interleaved: row 2f = gate f, row 2f+1 = up f
-    if (!strcmp(f, "wg")) return mat(b + 6, y.wgu, F, H, 2 * (uint64_t)H * eb);
-    if (!strcmp(f, "wu")) return mat(b + 7, y.wgu + (uint64_t)H * eb, F, H, 2 * (uint64_t)H * eb);
-    if (!strcmp(f, "wd")) return mat(b + 8, y.wd, H, F);
+    if (!strcmp(f, "wd")) return L.tiled_f ? tiled(b + 8, y.wd, H, F, TILE_PLAIN, 0, (H + 15) / 16) : mat(b + 8, y.wd, H, F);
     return false;
 }
 
@@ -422,6 +480,8 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->k_verify = -1;
     memset(&x->st, 0, sizeof(x->st));
     x->prof_class = -1;
+    memset(x->tune_ks, 0, sizeof(x->tune_ks));
+    memset(x->tune_wg, 0, sizeof(x->tune_wg));
     x->h_tok = nullptr;
     x->h_conf = nullptr;
     hipError_t e = hipHostMalloc((void **)&x->h_tok, 2 * kMaxRows * 4, hipHostMallocDefault);
@@ -475,7 +535,30 @@ extern "C" int swift_load_tensor(swift_ctx *x, const char *name, const void *dat
     const int want = sl.is_gain ? SWIFT_F32 : x->c.dtype;
     if (dtype != want) return fail(SWIFT_EINVAL, std::string("wrong dtype for ") + name);
     const uint64_t eb = elem_bytes(want);
-    if (sl.dst_pitch == 0) {
+    if (sl.tiled) {
+        // re-tile on the device; a host tensor goes through the staging area first
+        hipPointerAttribute_t pa;
+        const void *src = data;
+        hipError_t pe = hipPointerGetAttributes(&pa, data);
+        const bool on_device = pe == hipSuccess && pa.type == hipMemoryTypeDevice;
+        if (pe != hipSuccess) (void)hipGetLastError();  // plain host memory is reported as an error by some runtimes
+        if (!on_device) {
+            if ((uint64_t)sl.n * eb > x->L.stage_bytes) return fail(SWIFT_ECAPACITY, "staging area too small");
+            HIP_TRY(hipMemcpyAsync(x->base + x->L.stage, data, (uint64_t)sl.n * eb, hipMemcpyHostToDevice, x->stream));
+            src = x->base + x->L.stage;
+        }
+        TileArgs t{};
+        t.src = src;
+        t.src_rows = sl.rows;
+        t.K = sl.cols;
+        t.dst = x->base + sl.off;
+        t.T = (sl.cols + 31) / 32;
+        t.n_rg = sl.n_rg;
+        t.mode = sl.tile_mode;
+        t.head_dim = x->c.head_dim;
+        t.part = sl.part;
+        HIP_TRY(launch_tile_weights(t, x->stream));
+    } else if (sl.dst_pitch == 0) {
         HIP_TRY(hipMemcpyAsync(x->base + sl.off, data, (uint64_t)sl.n * eb, hipMemcpyDefault, x->stream));
     } else {
         HIP_TRY(hipMemcpy2DAsync(x->base + sl.off, sl.dst_pitch, data, (uint64_t)sl.cols * eb, (uint64_t)sl.cols * eb,
@@ -651,6 +734,16 @@ extern "C" int swift_debug_read_kv(swift_ctx *x, int layer, int pos, float *k_ou
                                x->stream));
         HIP_TRY(hipStreamSynchronize(x->stream));
     }
+    return SWIFT_OK;
+}
+
+extern "C" int swift_debug_tune(swift_ctx *x, int kernel_class, int waves_per_row_group, int workgroups) {
+    if (!x || kernel_class < 0 || kernel_class >= SWIFT_KC_COUNT) return fail(SWIFT_EINVAL, "bad argument");
+    if (!(waves_per_row_group == 0 || waves_per_row_group == 1 || waves_per_row_group == 2 ||
+          waves_per_row_group == 4 || waves_per_row_group == 8) || workgroups < 0 || workgroups > 65535)
+        return fail(SWIFT_EINVAL, "bad argument");
+    x->tune_ks[kernel_class] = waves_per_row_group;
+    x->tune_wg[kernel_class] = workgroups;
     return SWIFT_OK;
 }
 

@@ -68,4 +68,46 @@ hipError_t launch_fill_nan(int dtype, void *p, int64_t n_elems, hipStream_t s);
 // dst[i] (fp32) = src[i] (dtype)
 hipError_t launch_to_f32(int dtype, const void *src, float *dst, int64_t n, hipStream_t s);
 
+// ---- tiled bf16 weights -------------------------------------------------------------------
+// A bf16 matrix [O][K] is stored as 1 KB tiles of 16 rows x 32 k, tile (rg, t) at element offset
+// ((rg * T) + t) * 512 with T = ceil(K/32); inside a tile lane l of a wavefront owns the 8
+// consecutive k values 32t + 8(l>>4) .. +7 of tile row (l & 15), i.e. exactly the A operand of
+// v_mfma_f32_16x16x32_bf16, so one 128-bit load per lane feeds one MFMA.  Rows beyond O and k
+// beyond K are zero.  Which matrix row sits in tile row j of row group rg depends on the mode:
+enum TileMode : int {
+    TILE_PLAIN = 0,   // row = 16 rg + j
+    TILE_PAIR = 1,    // rotary pairs together: head = rg / (d/16), g = rg % (d/16);
+                      //   j < 8: row = head*d + 8g + j ;  j >= 8: row = head*d + d/2 + 8g + (j-8)
+    TILE_GATEUP = 2,  // j < 8: gate row 8 rg + j ;  j >= 8: up row 8 rg + (j-8)
+};
+
+struct TileArgs {
+    const void *src;  // row-major [src_rows][K] bf16 (device)
+    int src_rows, K;
+    void *dst;        // tiled destination (start of the first row group written)
+    int T, n_rg;      // k-tiles per row group, row groups to write
+    int mode, head_dim;
+    int part;         // TILE_GATEUP: 0 = src holds the gate rows, 1 = the up rows
+};
+hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s);
+
+// One activation row against a tiled matrix (MFMA, fp32 activation split into three bf16 terms).
+struct MvArgs {
+    const void *Wt;
+    int O, K, T, n_rg;
+    const float *xin;   // [K] fp32
+    const float *gain;  // [K] fp32 or nullptr
+    float eps;
+    float *out;
+    void *kcache, *vcache;
+    const float *cos_row, *sin_row;
+    int pos, max_seq, head_dim, n_q_heads, n_kv_heads;
+    int S;              // row-group rounds per workgroup (set by the launcher)
+};
+// LDS bytes the kernel needs for a K-wide activation; the launcher refuses more than kMvMaxLds.
+constexpr size_t kMvMaxLds = 150 * 1024;
+inline size_t mv_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 1024 + 16 + 512; }
+// ks_override / wg_override: 0 = choose automatically.
+hipError_t launch_mv1(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
+
 }  // namespace swift

@@ -62,7 +62,7 @@ def test_arena_size_covers_weights_and_cache(P):
     n = P.device_bytes(B.make_config(s, max_seq))
     weights = 2 * (2 * s.vocab * s.hidden + s.n_layers * (s.attn_sublayer_elems() + s.mlp_sublayer_elems()))
     kv = 2 * s.n_layers * 2 * s.kv_dim * max_seq
-    assert weights + kv < n < weights + kv + 200e6
+    assert weights + kv < n < weights + kv + 500e6   # + staging for the largest tensor, activations, tables
 
 
 def test_pass_bytes_accounting(P):
