@@ -72,11 +72,15 @@ struct Layout {
     std::vector<LayerOff> layers;
     uint64_t cos, sin, kv;
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf;
+    // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
+    uint64_t xs, as_, hs, pss, mv_part, mv_counters;
+    int mv_part_capacity;
     uint64_t stage, stage_bytes;  // staging for host tensors that are re-tiled on the device
     uint64_t total;
     int n_split_max;
     // bf16 matrices whose activation row fits the MFMA kernel's LDS budget are stored tiled
     bool tiled_h, tiled_q, tiled_f;  // for K = hidden, K = n_q*d, K = ffn
+    bool tiled;                      // all three: the whole model runs on the tiled MFMA kernels
 };
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -95,9 +99,9 @@ Layout make_layout(const swift_model_config &c) {
         return o;
     };
     const bool bf = c.dtype == SWIFT_BF16;
-    L.tiled_h = bf && mv_lds_bytes((int)H) <= kMvMaxLds;
-    L.tiled_q = bf && mv_lds_bytes((int)Q) <= kMvMaxLds;
-    L.tiled_f = bf && mv_lds_bytes((int)F) <= kMvMaxLds;
+    L.tiled = bf && mv1_lds_bytes((int)H) <= kMvMaxLds && mv1_lds_bytes((int)Q) <= kMvMaxLds &&
+              mv1_lds_bytes((int)F) <= kMvMaxLds;
+    L.tiled_h = L.tiled_q = L.tiled_f = L.tiled;
     L.embed = take(V * H * eb);
     L.lm_head = take(L.tiled_h ? tiled_bytes(ceil_div(V, 16), H) : V * H * eb);
     L.final_norm = take(H * 4);
@@ -123,6 +127,13 @@ Layout make_layout(const swift_model_config &c) {
     L.part_ml = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * 2 * 4);
     L.out_tok = take(kMaxRows * 4);
     L.out_conf = take(kMaxRows * 4);
+    L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxRows * 16);
+    L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxRows * 16);
+    L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxRows * 16);
+    L.pss = take(ceil_div(H, 16) * 16 * 4);
+    L.mv_part_capacity = 8192;
+    L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxRows * 4);
+    L.mv_counters = take(4096 * 4);
     L.stage_bytes = bf ? std::max(std::max(V * H, F * H), std::max(Q * H, KV * H)) * eb : 0;
     L.stage = take(L.stage_bytes);
     L.total = off;
@@ -203,6 +214,7 @@ struct swift_ctx {
     int n;            // cache length
     int32_t pending;  // -1 before prefill
     int k_verify;     // -1: no verify outstanding
+    int last_logits_row;
     int32_t vtokens[SWIFT_MAX_BLOCK], targets[SWIFT_MAX_BLOCK];
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
@@ -250,77 +262,9 @@ char *kv_base(swift_ctx *x, int layer, int which) {
     return x->base + x->L.kv + ((uint64_t)layer * 2 + which) * per;
 }
 
-// One projection of one activation row: tiled MFMA kernel when the matrix is stored tiled,
-// otherwise the generic row-major kernel.  `rope_pos` >= 0 selects the q|k|v epilogue.
-struct LinearCall {
-    int kc, epi;
-    uint64_t w_off;
-    bool tiled;
-    int O, K, n_rg;
-    const float *xin, *gain;
-    float *out;
-    int layer, pos;
-};
-
-int run_linear(swift_ctx *x, const LinearCall &lc) {
-    const swift_model_config &c = x->c;
-    const int d = c.head_dim;
-    const uint64_t eb = elem_bytes(c.dtype);
-    hipStream_t s = x->stream;
-    void *kc = lc.epi == EPI_QKV ? kv_base(x, lc.layer, 0) : nullptr;
-    void *vc = lc.epi == EPI_QKV ? kv_base(x, lc.layer, 1) : nullptr;
-    const float *cr = lc.epi == EPI_QKV ? dptr<float>(x, x->L.cos) + (size_t)lc.pos * (d / 2) : nullptr;
-    const float *sr = lc.epi == EPI_QKV ? dptr<float>(x, x->L.sin) + (size_t)lc.pos * (d / 2) : nullptr;
-    const uint64_t bytes = (uint64_t)lc.O * lc.K * eb;
-    if (lc.tiled) {
-        MvArgs m{};
-        m.Wt = x->base + lc.w_off;
-        m.O = lc.O;
-        m.K = lc.K;
-        m.T = (lc.K + 31) / 32;
-        m.n_rg = lc.n_rg;
-        m.xin = lc.xin;
-        m.gain = lc.gain;
-        m.eps = c.rms_eps;
-        m.out = lc.out;
-        m.kcache = kc;
-        m.vcache = vc;
-        m.cos_row = cr;
-        m.sin_row = sr;
-        m.pos = lc.pos;
-        m.max_seq = c.max_seq;
-        m.head_dim = d;
-        m.n_q_heads = c.n_q_heads;
-        m.n_kv_heads = c.n_kv_heads;
-        HIP_TRY(timed(x, lc.kc, bytes, [&] {
-            return launch_mv1(lc.epi, m, x->n_cu, x->tune_ks[lc.kc], x->tune_wg[lc.kc], s);
-        }));
-    } else {
-        GemvArgs g{};
-        g.W = x->base + lc.w_off;
-        g.O = lc.O;
-        g.K = lc.K;
-        g.xin = lc.xin;
-        g.gain = lc.gain;
-        g.eps = c.rms_eps;
-        g.out = lc.out;
-        g.kcache = kc;
-        g.vcache = vc;
-        g.cos_row = cr;
-        g.sin_row = sr;
-        g.pos = lc.pos;
-        g.max_seq = c.max_seq;
-        g.head_dim = d;
-        g.n_q_heads = c.n_q_heads;
-        g.n_kv_heads = c.n_kv_heads;
-        HIP_TRY(timed(x, lc.kc, bytes, [&] { return launch_gemv(c.dtype, lc.epi, g, x->n_cu, s); }));
-    }
-    return SWIFT_OK;
-}
-
-// One token through the network at position `pos`; row = which row of the activation /
-// logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM head and
-// the arg-max for this row.
+// ---- storage-generic path: one token through the network at position `pos`; row = which row of
+// the activation / logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM
+// head and the arg-max for this row.
 int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int row, bool want_logits) {
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
@@ -332,22 +276,44 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
     float *ar = dptr<float>(x, L.att) + (size_t)row * Q;
     float *hr = dptr<float>(x, L.h) + (size_t)row * F;
     float *lr = dptr<float>(x, L.logits) + (size_t)row * V;
-    int rc;
 
+    auto linear = [&](int kc, int epi, uint64_t w_off, int O, int K, const float *xin, const float *gain, float *out,
+                      int layer) -> int {
+        GemvArgs g{};
+        g.W = x->base + w_off;
+        g.O = O;
+        g.K = K;
+        g.xin = xin;
+        g.gain = gain;
+        g.eps = c.rms_eps;
+        g.out = out;
+        if (epi == EPI_QKV) {
+            g.kcache = kv_base(x, layer, 0);
+            g.vcache = kv_base(x, layer, 1);
+            g.cos_row = dptr<float>(x, L.cos) + (size_t)pos * (d / 2);
+            g.sin_row = dptr<float>(x, L.sin) + (size_t)pos * (d / 2);
+        }
+        g.pos = pos;
+        g.max_seq = c.max_seq;
+        g.head_dim = d;
+        g.n_q_heads = c.n_q_heads;
+        g.n_kv_heads = c.n_kv_heads;
+        HIP_TRY(timed(x, kc, (uint64_t)O * K * eb, [&] { return launch_gemv(c.dtype, epi, g, x->n_cu, s); }));
+        return SWIFT_OK;
+    };
+    int rc;
     EmbedArgs ea{x->base + L.embed, H, token, xr};
     HIP_TRY(timed(x, SWIFT_KC_OTHER, H * eb, [&] { return launch_embed(c.dtype, ea, s); }));
-
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerOff &y = L.layers[l];
         if (!(skip && skip[2 * l])) {
-            rc = run_linear(x, LinearCall{SWIFT_KC_QKV, EPI_QKV, y.wqkv, L.tiled_h, Q + 2 * KV, H, (Q + 2 * KV) / 16, xr,
-                                          dptr<float>(x, y.attn_norm), qr, l, pos});
-            if (rc) return rc;
+            if ((rc = linear(SWIFT_KC_QKV, EPI_QKV, y.wqkv, Q + 2 * KV, H, xr, dptr<float>(x, y.attn_norm), qr, l))) return rc;
             AttnArgs a{};
             a.q = qr;
             a.kcache = kv_base(x, l, 0);
             a.vcache = kv_base(x, l, 1);
             a.n_ctx = pos + 1;
+            a.rows = 1;
             a.max_seq = c.max_seq;
             a.head_dim = d;
             a.n_q_heads = c.n_q_heads;
@@ -355,27 +321,168 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.part_o = dptr<float>(x, L.part_o);
             a.part_ml = dptr<float>(x, L.part_ml);
             a.out = ar;
+            a.out_s = nullptr;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
                           [&] { return launch_attn_decode(c.dtype, a, s); }));
-            rc = run_linear(x, LinearCall{SWIFT_KC_OPROJ, EPI_RESID, y.wo, L.tiled_q, H, Q, (H + 15) / 16, ar, nullptr, xr,
-                                          l, pos});
-            if (rc) return rc;
+            if ((rc = linear(SWIFT_KC_OPROJ, EPI_RESID, y.wo, H, Q, ar, nullptr, xr, l))) return rc;
         }
         if (!(skip && skip[2 * l + 1])) {
-            rc = run_linear(x, LinearCall{SWIFT_KC_GATEUP, EPI_SWIGLU, y.wgu, L.tiled_h, 2 * F, H, (F + 7) / 8, xr,
-                                          dptr<float>(x, y.mlp_norm), hr, l, pos});
-            if (rc) return rc;
-            rc = run_linear(x, LinearCall{SWIFT_KC_DOWN, EPI_RESID, y.wd, L.tiled_f, H, F, (H + 15) / 16, hr, nullptr, xr,
-                                          l, pos});
-            if (rc) return rc;
+            if ((rc = linear(SWIFT_KC_GATEUP, EPI_SWIGLU, y.wgu, 2 * F, H, xr, dptr<float>(x, y.mlp_norm), hr, l))) return rc;
+            if ((rc = linear(SWIFT_KC_DOWN, EPI_RESID, y.wd, H, F, hr, nullptr, xr, l))) return rc;
         }
     }
     if (want_logits) {
-        rc = run_linear(x, LinearCall{SWIFT_KC_LMHEAD, EPI_LOGITS, L.lm_head, L.tiled_h, V, H, (V + 15) / 16, xr,
-                                      dptr<float>(x, L.final_norm), lr, 0, pos});
-        if (rc) return rc;
+        if ((rc = linear(SWIFT_KC_LMHEAD, EPI_LOGITS, L.lm_head, V, H, xr, dptr<float>(x, L.final_norm), lr, 0))) return rc;
         ArgmaxArgs m{lr, V, 1, dptr<int32_t>(x, L.out_tok) + row, dptr<float>(x, L.out_conf) + row};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)V * 4, [&] { return launch_argmax_conf(m, s); }));
+    }
+    return SWIFT_OK;
+}
+
+// ---- tiled bf16 path: a block of R rows (tokens[0..R) at positions pos0..pos0+R-1) through the
+// network in one sweep over the weights.  Row r attends cache slots [0, pos0 + r].
+int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits) {
+    const swift_model_config &c = x->c;
+    const Layout &L = x->L;
+    const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
+    hipStream_t s = x->stream;
+    float *xf = dptr<float>(x, L.x);
+    float *qf = dptr<float>(x, L.q);
+    uint16_t *xs = dptr<uint16_t>(x, L.xs), *as_ = dptr<uint16_t>(x, L.as_), *hs = dptr<uint16_t>(x, L.hs);
+    float *pss = dptr<float>(x, L.pss);
+    const int n_pss = (H + 15) / 16;
+
+    // non-skipped sublayers in order; the kernel that updates the residual stream pre-multiplies
+    // its split output with the RMSNorm gain of whichever sublayer (or the final norm) reads it next
+    struct Stage { int layer, kind; };
+    std::vector<Stage> stages;
+    stages.reserve(2 * c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        if (!(skip && skip[2 * l])) stages.push_back({l, 0});
+        if (!(skip && skip[2 * l + 1])) stages.push_back({l, 1});
+    }
+    auto gain_of = [&](size_t i) -> const float * {
+        if (i >= stages.size()) return dptr<float>(x, L.final_norm);
+        const LayerOff &y = L.layers[stages[i].layer];
+        return dptr<float>(x, stages[i].kind == 0 ? y.attn_norm : y.mlp_norm);
+    };
+    auto base_args = [&](uint64_t w_off, int O, int K, int n_rg) {
+        MvArgs m{};
+        m.Wt = x->base + w_off;
+        m.O = O;
+        m.K = K;
+        m.T = (K + 31) / 32;
+        m.n_rg = n_rg;
+        m.R = R;
+        m.eps = c.rms_eps;
+        m.norm_dim = H;
+        m.pos0 = pos0;
+        m.max_seq = c.max_seq;
+        m.head_dim = d;
+        m.n_q_heads = c.n_q_heads;
+        m.n_kv_heads = c.n_kv_heads;
+        m.cos_tab = dptr<float>(x, L.cos);
+        m.sin_tab = dptr<float>(x, L.sin);
+        m.part = dptr<float>(x, L.mv_part);
+        m.counters = dptr<int>(x, L.mv_counters);
+        m.part_capacity = L.mv_part_capacity;
+        return m;
+    };
+    auto run = [&](int kc, int epi, const MvArgs &m) -> int {
+        HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
+                      [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }));
+        return SWIFT_OK;
+    };
+    int rc;
+
+    EmbedRowsArgs ea{};
+    ea.E = dptr<uint16_t>(x, L.embed);
+    ea.H = H;
+    ea.R = R;
+    for (int r = 0; r < R; ++r) ea.tokens[r] = tokens[r];
+    ea.x = xf;
+    ea.xs = xs;
+    ea.gain_next = gain_of(0);
+    ea.pss = pss;
+    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
+
+    for (size_t i = 0; i < stages.size(); ++i) {
+        const int l = stages[i].layer;
+        const LayerOff &y = L.layers[l];
+        const float *gnext = gain_of(i + 1);
+        if (stages[i].kind == 0) {
+            MvArgs m = base_args(y.wqkv, Q + 2 * KV, H, (Q + 2 * KV) / 16);
+            m.in_s = xs;
+            m.pss = pss;
+            m.n_pss = n_pss;
+            m.out_f32 = qf;
+            m.ld_out = Q;
+            m.kcache = kv_base(x, l, 0);
+            m.vcache = kv_base(x, l, 1);
+            if ((rc = run(SWIFT_KC_QKV, EPI_QKV, m))) return rc;
+
+            AttnArgs a{};
+            a.q = qf;
+            a.kcache = kv_base(x, l, 0);
+            a.vcache = kv_base(x, l, 1);
+            a.n_ctx = pos0 + 1;
+            a.rows = R;
+            a.max_seq = c.max_seq;
+            a.head_dim = d;
+            a.n_q_heads = c.n_q_heads;
+            a.n_kv_heads = c.n_kv_heads;
+            a.part_o = dptr<float>(x, L.part_o);
+            a.part_ml = dptr<float>(x, L.part_ml);
+            a.out = nullptr;
+            a.out_s = as_;
+            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
+                          [&] { return launch_attn_decode(c.dtype, a, s); }));
+
+            MvArgs o = base_args(y.wo, H, Q, (H + 15) / 16);
+            o.in_s = as_;
+            o.out_f32 = xf;
+            o.ld_out = H;
+            o.out_s = xs;
+            o.gain_next = gnext;
+            o.pss_out = pss;
+            if ((rc = run(SWIFT_KC_OPROJ, EPI_RESID, o))) return rc;
+        } else {
+            MvArgs m = base_args(y.wgu, 2 * F, H, (F + 7) / 8);
+            m.in_s = xs;
+            m.pss = pss;
+            m.n_pss = n_pss;
+            m.out_s = hs;
+            if ((rc = run(SWIFT_KC_GATEUP, EPI_SWIGLU, m))) return rc;
+            MvArgs w = base_args(y.wd, H, F, (H + 15) / 16);
+            w.in_s = hs;
+            w.out_f32 = xf;
+            w.ld_out = H;
+            w.out_s = xs;
+            w.gain_next = gnext;
+            w.pss_out = pss;
+            if ((rc = run(SWIFT_KC_DOWN, EPI_RESID, w))) return rc;
+        }
+    }
+    if (want_logits) {
+        MvArgs m = base_args(L.lm_head, V, H, (V + 15) / 16);
+        m.in_s = xs;
+        m.pss = pss;
+        m.n_pss = n_pss;
+        m.out_f32 = dptr<float>(x, L.logits);
+        m.ld_out = V;
+        if ((rc = run(SWIFT_KC_LMHEAD, EPI_LOGITS, m))) return rc;
+        ArgmaxArgs am{dptr<float>(x, L.logits), V, R, dptr<int32_t>(x, L.out_tok), dptr<float>(x, L.out_conf)};
+        HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * V * 4, [&] { return launch_argmax_conf(am, s); }));
+    }
+    return SWIFT_OK;
+}
+
+// R rows through the network; results (token, confidence, logits) land in rows [0, R).
+int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits) {
+    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits);
+    for (int r = 0; r < R; ++r) {
+        int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits);
+        if (rc) return rc;
     }
     return SWIFT_OK;
 }
@@ -502,7 +609,8 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
             stb[(size_t)p * half + i] = (float)std::sin(ang);
         }
     }
-    e = hipMemcpyAsync(x->base + L.cos, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, x->stream);
+    e = hipMemsetAsync(x->base + L.mv_counters, 0, 4096 * 4, x->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.cos, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.sin, stb.data(), stb.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(x->stream);
     if (e != hipSuccess) {
@@ -582,14 +690,17 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     if (x->n_loaded != n_tensors(x->c)) return fail(SWIFT_ESTATE, "not all tensors are loaded");
     for (int i = 0; i < n_prompt; ++i)
         if (prompt[i] < 0 || prompt[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
-    for (int i = 0; i < n_prompt; ++i) {
-        int rc = forward_row(x, prompt[i], i, nullptr, 0, i == n_prompt - 1);
+    int last_rows = 0;
+    for (int i = 0; i < n_prompt; i += kMaxRows) {
+        last_rows = std::min(kMaxRows, n_prompt - i);
+        int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt);
         if (rc) return rc;
     }
-    int rc = read_results(x, 1);
+    int rc = read_results(x, last_rows);
     if (rc) return rc;
     x->n = n_prompt;
-    x->pending = x->h_tok[0];
+    x->pending = x->h_tok[last_rows - 1];
+    x->last_logits_row = last_rows - 1;
     x->k_verify = -1;
     memset(&x->st, 0, sizeof(x->st));
     x->st.emitted_total = 1;
@@ -607,7 +718,7 @@ extern "C" int swift_draft_step(swift_ctx *x, const uint8_t *skip_mask, int max_
     int32_t prev = x->pending;
     int k = 0;
     for (int j = 1; j <= max_k; ++j) {
-        int rc = forward_row(x, prev, x->n + j - 1, skip_mask, 0, true);
+        int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
         if (rc) return rc;
         rc = read_results(x, 1);
         if (rc) return rc;
@@ -630,11 +741,9 @@ extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t 
     for (int i = 0; i <= k; ++i)
         if (tokens[i] < 0 || tokens[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
     if (x->n + k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
-    for (int i = 0; i <= k; ++i) {
-        int rc = forward_row(x, tokens[i], x->n + i, nullptr, i, true);
-        if (rc) return rc;
-    }
-    int rc = read_results(x, k + 1);
+    int rc = forward_block(x, tokens, k + 1, x->n, nullptr, true);
+    if (rc) return rc;
+    rc = read_results(x, k + 1);
     if (rc) return rc;
     if (logits_out) {
         HIP_TRY(hipMemcpyAsync(logits_out, dptr<float>(x, x->L.logits), (size_t)(k + 1) * x->c.vocab * 4,
@@ -740,7 +849,8 @@ extern "C" int swift_debug_read_kv(swift_ctx *x, int layer, int pos, float *k_ou
 extern "C" int swift_debug_tune(swift_ctx *x, int kernel_class, int waves_per_row_group, int workgroups) {
     if (!x || kernel_class < 0 || kernel_class >= SWIFT_KC_COUNT) return fail(SWIFT_EINVAL, "bad argument");
     if (!(waves_per_row_group == 0 || waves_per_row_group == 1 || waves_per_row_group == 2 ||
-          waves_per_row_group == 4 || waves_per_row_group == 8) || workgroups < 0 || workgroups > 65535)
+          waves_per_row_group == 4 || waves_per_row_group == 8 || waves_per_row_group == 16) || workgroups < 0 ||
+        workgroups > 65535)
         return fail(SWIFT_EINVAL, "bad argument");
     x->tune_ks[kernel_class] = waves_per_row_group;
     x->tune_wg[kernel_class] = workgroups;

@@ -1,6 +1,7 @@
 // Launch interface between the C-ABI layer (swift_api.hip) and the gfx950 kernels
-// (swift_kernels.hip).  Plain structs and functions; every launcher enqueues on the
-// given stream and returns the hipError_t of the launch.
+// (swift_kernels.hip: storage-generic single-row path; swift_tiled.hip: bf16 tiled MFMA path).
+// Plain structs and functions; every launcher enqueues on the given stream and returns the
+// hipError_t of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -13,14 +14,17 @@ constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
 enum Dtype : int { F32 = 0, BF16 = 1 };
 
-// Which computation precedes / follows the row dot products of a weight-streaming pass.
+// Which computation follows the row dot products of a weight-streaming pass.
 enum Epilogue : int {
-    EPI_QKV = 0,     // rotate q,k at `pos`; q -> out (fp32); k,v -> cache slot `pos`
-    EPI_RESID = 1,   // out[o] += y[o]                       (o_proj, down_proj)
-    EPI_SWIGLU = 2,  // out[f] = silu(y[2f]) * y[2f+1]        (gate/up rows interleaved)
-    EPI_LOGITS = 3,  // out[o] = y[o]                         (LM head)
+    EPI_QKV = 0,     // rotate q,k at the row's position; q -> fp32 buffer; k,v -> cache slot
+    EPI_RESID = 1,   // x += y                                (o_proj, down_proj)
+    EPI_SWIGLU = 2,  // h = silu(gate) * up
+    EPI_LOGITS = 3,  // logits = y                            (LM head)
 };
 
+// ------------------------------------------------------------------------------------------
+// storage-generic path (fp32 or bf16 row-major weights, one activation row)
+// ------------------------------------------------------------------------------------------
 struct GemvArgs {
     const void *W;      // [O][K] in the model's storage dtype, row-major
     int O, K;
@@ -29,11 +33,10 @@ struct GemvArgs {
     float eps;
     float *out;
     // EPI_QKV only
-    void *kcache, *vcache;        // this layer's [n_kv][max_seq][d]
+    void *kcache, *vcache;           // this layer's [n_kv][max_seq][d]
     const float *cos_row, *sin_row;  // rotary table rows for `pos`: [d/2] each
     int pos, max_seq, head_dim, n_q_heads, n_kv_heads;
 };
-
 hipError_t launch_gemv(int dtype, int epilogue, const GemvArgs &a, int n_cu, hipStream_t s);
 
 struct EmbedArgs {
@@ -45,13 +48,15 @@ struct EmbedArgs {
 hipError_t launch_embed(int dtype, const EmbedArgs &a, hipStream_t s);
 
 struct AttnArgs {
-    const float *q;               // [n_q][d] fp32 (already rotated)
+    const float *q;               // [rows][n_q][d] fp32 (already rotated)
     const void *kcache, *vcache;  // this layer's [n_kv][max_seq][d]
-    int n_ctx;                    // slots [0, n_ctx) are attended
+    int n_ctx;                    // row r attends slots [0, n_ctx + r)
+    int rows;
     int max_seq, head_dim, n_q_heads, n_kv_heads;
-    float *part_o;                // [n_q][n_split][d]   unnormalised partial outputs
-    float *part_ml;               // [n_q][n_split][2]   running max, running sum
-    float *out;                   // [n_q][d]
+    float *part_o;                // [rows][n_q][n_split][d]   unnormalised partial outputs
+    float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
+    float *out;                   // fp32 [rows][n_q][d], or nullptr
+    uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*rows][8], or nullptr
 };
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, hipStream_t s);
 
@@ -68,12 +73,14 @@ hipError_t launch_fill_nan(int dtype, void *p, int64_t n_elems, hipStream_t s);
 // dst[i] (fp32) = src[i] (dtype)
 hipError_t launch_to_f32(int dtype, const void *src, float *dst, int64_t n, hipStream_t s);
 
-// ---- tiled bf16 weights -------------------------------------------------------------------
-// A bf16 matrix [O][K] is stored as 1 KB tiles of 16 rows x 32 k, tile (rg, t) at element offset
-// ((rg * T) + t) * 512 with T = ceil(K/32); inside a tile lane l of a wavefront owns the 8
-// consecutive k values 32t + 8(l>>4) .. +7 of tile row (l & 15), i.e. exactly the A operand of
-// v_mfma_f32_16x16x32_bf16, so one 128-bit load per lane feeds one MFMA.  Rows beyond O and k
-// beyond K are zero.  Which matrix row sits in tile row j of row group rg depends on the mode:
+// ------------------------------------------------------------------------------------------
+// tiled bf16 path
+// ------------------------------------------------------------------------------------------
+// Weights.  A bf16 matrix [O][K] is stored as 1 KB tiles of 16 rows x 32 k, tile (rg, t) at
+// element offset ((rg * T) + t) * 512 with T = ceil(K/32); inside a tile lane l of a wavefront
+// owns the 8 consecutive k values 32t + 8(l>>4) .. +7 of tile row (l & 15), i.e. exactly the A
+// operand of v_mfma_f32_16x16x32_bf16, so one 128-bit load per lane feeds one MFMA.  Rows beyond
+// O and k beyond K are zero.  Which matrix row sits in tile row j of row group rg:
 enum TileMode : int {
     TILE_PLAIN = 0,   // row = 16 rg + j
     TILE_PAIR = 1,    // rotary pairs together: head = rg / (d/16), g = rg % (d/16);
@@ -91,23 +98,51 @@ struct TileArgs {
 };
 hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s);
 
-// One activation row against a tiled matrix (MFMA, fp32 activation split into three bf16 terms).
+// Activations between the tiled kernels.  An fp32 activation vector of R rows (tokens) that
+// feeds a projection is kept as three bf16 terms per value (value = hi + mid + lo exactly), laid
+// out as the MFMA B operand: [K/8 chunks][NC = 3R columns][8 k] bf16, column 3r + term.  The
+// residual stream itself stays fp32 [R][H]; the kernel that updates it also writes the split of
+// (x * gain of the next consumer) and, per 16-row group, the partial sums of squares of x, so the
+// consumer only adds up the partials (fixed order) to get the RMSNorm scale 1/sqrt(mean x^2 + eps)
+// and applies it to its results (W.(x*g) * scale == W.(x*scale*g) up to fp32 rounding).
 struct MvArgs {
-    const void *Wt;
-    int O, K, T, n_rg;
-    const float *xin;   // [K] fp32
-    const float *gain;  // [K] fp32 or nullptr
+    const void *Wt;        // tiled weights
+    int O, K, T, n_rg;     // real rows / depth, k-tiles, row groups
+    int R;                 // activation rows, 1..16
+    const uint16_t *in_s;  // split input [K/8][3R][8]
+    const float *pss;      // [n_pss][16] partial sums of squares of the producer, or nullptr: no norm
+    int n_pss, norm_dim;
     float eps;
-    float *out;
-    void *kcache, *vcache;
-    const float *cos_row, *sin_row;
-    int pos, max_seq, head_dim, n_q_heads, n_kv_heads;
-    int S;              // row-group rounds per workgroup (set by the launcher)
+    float *out_f32;        // QKV: q [R][ld_out]; LOGITS: logits [R][ld_out]; RESID: x [R][ld_out] (in/out)
+    int ld_out;
+    uint16_t *out_s;       // SWIGLU: split h [F/8][3R][8]; RESID: split of x*gain_next [O/8][3R][8]
+    const float *gain_next;  // RESID: [O]
+    float *pss_out;        // RESID: [n_rg][16]
+    void *kcache, *vcache;   // QKV: this layer's [n_kv][max_seq][d]
+    const float *cos_tab, *sin_tab;  // QKV: [max_seq][d/2]
+    int pos0, max_seq, head_dim, n_q_heads, n_kv_heads;
+    // multi-row kernel only: split-K scratch
+    float *part;           // [k splits][row group][R][16] fp32 partial results
+    int *counters;         // one per 8-row-group block, zero between launches
+    int part_capacity;     // row-group-splits the scratch can hold
+    int S;                 // set by the launcher
 };
-// LDS bytes the kernel needs for a K-wide activation; the launcher refuses more than kMvMaxLds.
 constexpr size_t kMvMaxLds = 150 * 1024;
-inline size_t mv_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 1024 + 16 + 512; }
-// ks_override / wg_override: 0 = choose automatically.
-hipError_t launch_mv1(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
+// LDS bytes of the single-row kernel for depth K
+inline size_t mv1_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 16 + 1024 + 64 + 2048; }
+// ks_override / wg_override: 0 = choose automatically (single-row kernel only).
+hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
+
+// x[r] = E[token r] (fp32), split of x * gain_next, partial sums of squares per 16 elements.
+struct EmbedRowsArgs {
+    const uint16_t *E;  // [V][H] bf16 row-major
+    int H, R;
+    int32_t tokens[kMaxRows];
+    float *x;           // [R][H]
+    uint16_t *xs;       // [H/8][3R][8]
+    const float *gain_next;
+    float *pss;         // [ceil(H/16)][16]
+};
+hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s);
 
 }  // namespace swift

@@ -1,4 +1,5 @@
-// gfx950 kernels of the draft / verify forward pass (single-row path).
+// gfx950 kernels of the draft / verify forward pass: storage-generic single-row projections,
+// attention over the cache, arg-max/confidence, utilities.
 //
 // Every projection of the decoder is a weight-streaming pass: the weight matrix is read
 // from HBM exactly once with 128-bit loads, the activation vector lives in LDS, and the
@@ -10,55 +11,9 @@
 
 #include <math.h>
 
+#include "swift_device.h"
+
 namespace swift {
-
-// ------------------------------------------------------------------------------------------
-// storage types
-// ------------------------------------------------------------------------------------------
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
-
-struct F32T {
-    static constexpr int VEC = 4;  // elements per 16-byte load
-    using elem = float;
-    __device__ static void unpack(const u32x4 &v, float *f) {
-        f[0] = __uint_as_float(v.x);
-        f[1] = __uint_as_float(v.y);
-        f[2] = __uint_as_float(v.z);
-        f[3] = __uint_as_float(v.w);
-    }
-    __device__ static float load1(const elem *p) { return *p; }
-    __device__ static void store1(elem *p, float f) { *p = f; }
-};
-
-__device__ inline uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-struct BF16T {
-    static constexpr int VEC = 8;
-    using elem = uint16_t;
-    __device__ static void unpack(const u32x4 &v, float *f) {
-        f[0] = __uint_as_float(v.x << 16);
-        f[1] = __uint_as_float(v.x & 0xffff0000u);
-        f[2] = __uint_as_float(v.y << 16);
-        f[3] = __uint_as_float(v.y & 0xffff0000u);
-        f[4] = __uint_as_float(v.z << 16);
-        f[5] = __uint_as_float(v.z & 0xffff0000u);
-        f[6] = __uint_as_float(v.w << 16);
-        f[7] = __uint_as_float(v.w & 0xffff0000u);
-    }
-    __device__ static float load1(const elem *p) { return __uint_as_float((uint32_t)(*p) << 16); }
-    __device__ static void store1(elem *p, float f) { *p = f32_to_bf16_rne(f); }
-};
-
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
 
 // Sum over the whole workgroup (blockDim.x = 256); every thread gets the result.
 // The order of additions is fixed, so every workgroup computes the same bits.
@@ -237,18 +192,21 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
     const int LPP = d / VEC;        // lanes per cache slot (power of two, <= 32)
     const int SPW = 64 / LPP;       // slots per wavefront step
     const int n_split = gridDim.y;
-    const int g = blockIdx.x, sp = blockIdx.y;
+    const int g = blockIdx.x, sp = blockIdx.y, row = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lj = lane & (LPP - 1), lg = lane / LPP;
+    const int n_ctx = a.n_ctx + row;  // block row r sees the cache up to its own slot
     const int lo = sp * kAttnChunk;
-    const int hi = min(a.n_ctx, lo + kAttnChunk);
+    if (lo >= n_ctx) return;          // this row has fewer chunks than the longest row of the block
+    const int hi = min(n_ctx, lo + kAttnChunk);
     const float scale = 1.0f / sqrtf((float)d);
+    const int nq = a.n_q_heads;
 
     float q[GROUP][VEC];
 #pragma unroll
     for (int h = 0; h < GROUP; ++h)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[(size_t)(g * GROUP + h) * d + lj * VEC + j];
+        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
 
     float m[GROUP], l[GROUP], o[GROUP][VEC];
 #pragma unroll
@@ -334,36 +292,49 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
             ls += sl[w][h] * c;
             os += so[w][h][j] * c;
         }
-        const int head = g * GROUP + h;
-        a.part_o[((size_t)head * n_split + sp) * d + j] = os;
+        const size_t slot = ((size_t)row * nq + g * GROUP + h) * n_split + sp;
+        a.part_o[slot * d + j] = os;
         if (j == 0) {
-            a.part_ml[((size_t)head * n_split + sp) * 2 + 0] = mn;
-            a.part_ml[((size_t)head * n_split + sp) * 2 + 1] = ls;
+            a.part_ml[slot * 2 + 0] = mn;
+            a.part_ml[slot * 2 + 1] = ls;
         }
     }
 }
 
-// out[head][j] = sum_s o_s[j] e^{m_s - M} / sum_s l_s e^{m_s - M}
-__global__ void k_attn_combine(const float *part_o, const float *part_ml, int n_split, int d, float *out) {
-    const int head = blockIdx.x;
+// out[row][head][j] = sum_s o_s[j] e^{m_s - M} / sum_s l_s e^{m_s - M} over the row's own chunks;
+// written as fp32 and/or as the three-term bf16 split that the output projection consumes
+__global__ void k_attn_combine(AttnArgs a, int n_split) {
+    const int head = blockIdx.x, row = blockIdx.y, d = a.head_dim;
+    const int ns = (a.n_ctx + row + kAttnChunk - 1) / kAttnChunk;
+    const size_t base = ((size_t)row * a.n_q_heads + head) * n_split;
     float M = -INFINITY;
-    for (int s = 0; s < n_split; ++s) M = fmaxf(M, part_ml[((size_t)head * n_split + s) * 2]);
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(base + s) * 2]);
     for (int j = threadIdx.x; j < d; j += blockDim.x) {
         float L = 0.f, O = 0.f;
-        for (int s = 0; s < n_split; ++s) {
-            const float c = expf(part_ml[((size_t)head * n_split + s) * 2] - M);
-            L += part_ml[((size_t)head * n_split + s) * 2 + 1] * c;
-            O += part_o[((size_t)head * n_split + s) * d + j] * c;
+        for (int s = 0; s < ns; ++s) {
+            const float c = expf(a.part_ml[(base + s) * 2] - M);
+            L += a.part_ml[(base + s) * 2 + 1] * c;
+            O += a.part_o[(base + s) * d + j] * c;
         }
-        out[(size_t)head * d + j] = O / L;
+        const float y = O / L;
+        const int e = head * d + j;
+        if (a.out) a.out[(size_t)row * a.n_q_heads * d + e] = y;
+        if (a.out_s) {
+            uint16_t hi, mid, lo;
+            split3(y, hi, mid, lo);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * a.rows) + 3 * row) * 8 + (e & 7);
+            p[0] = hi;
+            p[8] = mid;
+            p[16] = lo;
+        }
     }
 }
 
 template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
-    const int n_split = (a.n_ctx + kAttnChunk - 1) / kAttnChunk;
-    dim3 grid(a.n_kv_heads, n_split), block(256);
+    const int n_split = (a.n_ctx + a.rows - 1 + kAttnChunk - 1) / kAttnChunk;
+    dim3 grid(a.n_kv_heads, n_split, a.rows), block(256);
     switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_decode<T, 1>), grid, block, 0, s, a); break;
         case 2: hipLaunchKernelGGL((k_attn_decode<T, 2>), grid, block, 0, s, a); break;
@@ -373,8 +344,8 @@ static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a.part_o,
-                       a.part_ml, n_split, a.head_dim, a.out);
+    hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads, a.rows), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a,
+                       n_split);
     return hipGetLastError();
 }
 
@@ -472,342 +443,6 @@ hipError_t launch_to_f32(int dtype, const void *src, float *dst, int64_t n, hipS
     else
         hipLaunchKernelGGL(k_to_f32<BF16T>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, dst, n);
     return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------
-// tiled bf16 weights: layout conversion
-// ------------------------------------------------------------------------------------------
-__global__ void k_tile_weights(TileArgs a) {
-    // one thread per 16-byte chunk of the destination
-    const int64_t n_chunks = (int64_t)a.n_rg * a.T * 64;
-    const uint16_t *src = (const uint16_t *)a.src;
-    u32x4 *dst = (u32x4 *)a.dst;
-    const int d = a.head_dim, half = d >> 1, gph = half >> 3;  // row groups per head (TILE_PAIR)
-    for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < n_chunks;
-         c += (int64_t)gridDim.x * blockDim.x) {
-        const int l = (int)(c & 63);
-        const int64_t tile = c >> 6;
-        const int t = (int)(tile % a.T);
-        const int rg = (int)(tile / a.T);
-        const int j = l & 15, k0 = 32 * t + 8 * (l >> 4);
-        int row;
-        if (a.mode == TILE_PLAIN) {
-            row = 16 * rg + j;
-        } else if (a.mode == TILE_PAIR) {
-            const int head = rg / gph, g = rg - head * gph;
-            row = head * d + 8 * g + (j & 7) + (j >= 8 ? half : 0);
-        } else {
-            if ((j >= 8) != (a.part == 1)) continue;  // the other half of the tile comes from the other tensor
-            row = 8 * rg + (j & 7);
-        }
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (row < a.src_rows) {
-            if (k0 + 8 <= a.K) {
-                v = *(const u32x4 *)(src + (size_t)row * a.K + k0);
-            } else {
-                uint16_t e[8];
-                for (int i = 0; i < 8; ++i) e[i] = (k0 + i < a.K) ? src[(size_t)row * a.K + k0 + i] : (uint16_t)0;
-                v.x = e[0] | ((uint32_t)e[1] << 16);
-                v.y = e[2] | ((uint32_t)e[3] << 16);
-                v.z = e[4] | ((uint32_t)e[5] << 16);
-                v.w = e[6] | ((uint32_t)e[7] << 16);
-            }
-        }
-        dst[c] = v;
-    }
-}
-
-hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s) {
-    const int64_t n_chunks = (int64_t)a.n_rg * a.T * 64;
-    if (n_chunks <= 0) return hipSuccess;
-    int64_t grid = (n_chunks + 255) / 256;
-    if (grid > 65536) grid = 65536;
-    hipLaunchKernelGGL(k_tile_weights, dim3((unsigned)grid), dim3(256), 0, s, a);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------
-// weight-streaming pass over a tiled matrix, one activation row, MFMA
-// ------------------------------------------------------------------------------------------
-// y = W . xhat with xhat kept in fp32 precision: xhat = hi + mid + lo, three bf16 terms that go
-// into columns 0..2 of the MFMA B operand (the other 13 columns are zero); y is the sum of the
-// three result columns.  A workgroup has 8 wavefronts; KS of them share one row group (each takes
-// a contiguous slice of its k-tiles), so a workgroup works on G = 8/KS row groups at a time and the
-// slices are added in LDS in a fixed order.  Every wavefront keeps two batches of eight 1 KB tile
-// loads in flight, and the first batch is issued before the activation is staged.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-template <int EPI, int KS>
-__global__ __launch_bounds__(512) void k_mv1(MvArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    // LDS: [16 B of zeros][4T chunks x 3 terms x 8 bf16][2 x 8 wavefronts x 16 rows fp32][cos|sin row]
-    uint16_t *Bs = (uint16_t *)(smem + 16);
-    float *red = (float *)(smem + 16 + (size_t)a.T * 192);
-    float *rot = red + 256;  // [d/2] cos then [d/2] sin (q|k|v epilogue only)
-    __shared__ float ssum[8];
-    constexpr int G = 8 / KS;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform from here on
-    const int g = wave / KS, ks = wave - g * KS;
-    const int T = a.T;
-    const int n = (T + KS - 1) / KS;           // k-tiles per wavefront and row group
-    const int t0 = min(ks * n, T - 1);
-    const int nv = max(0, min(n, T - ks * n)); // ... of which exist
-    const int nvm1 = max(nv - 1, 0);
-    const u32x4 *Wt = (const u32x4 *)a.Wt;
-    const int W = gridDim.x;
-    const int last_rg = a.n_rg - 1;
-    const int col = lane & 15, kg = lane >> 4;
-    // byte address of this lane's B chunk for tile t: boff + t * bstride; lanes of columns >= 3
-    // (and tiles past the wavefront's slice) read the zero chunk at address 0
-    const int boff = col < 3 ? 16 + (kg * 3 + col) * 16 : 0;
-    const int bstride = col < 3 ? 192 : 0;
-
-    // Rolling window of 16 tile loads (16 KB) per wavefront: slot u of the next batch is issued as
-    // soon as slot u of the current batch has been consumed.  Loads are unconditional: a slot past
-    // the slice is clamped to the slice's last tile and multiplied by the zero chunk.
-    u32x4 buf[16];
-    const u32x4 *base = nullptr;
-    auto load_slot = [&](int i) { return __builtin_nontemporal_load(base + (size_t)min(i, nvm1) * 64); };
-    auto mma_slot = [&](int i, const u32x4 &av, f32x4 &acc, int live_mask) {
-        const int m = (i < nv) ? live_mask : 0;              // all ones or zero, wavefront-uniform
-        const int addr = (boff + (t0 + i) * bstride) & m;
-        const u32x4 bv = *(const u32x4 *)(smem + addr);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
-                                                      acc, 0, 0, 0);
-    };
-    auto prime = [&](int seg) {
-        const int rg = min((seg * W + (int)blockIdx.x) * G + g, last_rg);
-        base = Wt + ((size_t)rg * T + t0) * 64 + lane;
-#pragma unroll
-        for (int u = 0; u < 16; ++u) buf[u] = load_slot(u);
-    };
-
-    // ---- stage the activation: optional RMSNorm, then the three-term bf16 split.  The activation
-    // loads are issued before the first weight loads so that they return first; the weight loads
-    // are then in flight while the norm and the split run.
-    auto split_store = [&](int i, float v) {
-        const uint16_t hi = f32_to_bf16_rne(v);
-        const float r1 = v - __uint_as_float((uint32_t)hi << 16);
-        const uint16_t mid = f32_to_bf16_rne(r1);
-        const float r2 = r1 - __uint_as_float((uint32_t)mid << 16);
-        const uint16_t lo = f32_to_bf16_rne(r2);
-        uint16_t *p = Bs + (size_t)(i >> 3) * 24 + (i & 7);
-        p[0] = hi;
-        p[8] = mid;
-        p[16] = lo;
-    };
-    if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
-    const int Kp = T * 32;
-    if (a.gain && Kp <= 16 * 512) {
-        float xv[16], gv[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = tid + 512 * e;
-            xv[e] = (i < a.K) ? a.xin[i] : 0.f;
-            gv[e] = (i < a.K) ? a.gain[i] : 0.f;
-        }
-        prime(0);
-        if (EPI == EPI_QKV) {
-            const int half = a.head_dim >> 1;
-            if (tid < half) {
-                rot[tid] = a.cos_row[tid];
-                rot[half + tid] = a.sin_row[tid];
-            }
-        }
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) ss += xv[e] * xv[e];
-        ss = wave_sum(ss);
-        if (lane == 0) ssum[wave] = ss;
-        __syncthreads();
-        ss = ((ssum[0] + ssum[1]) + (ssum[2] + ssum[3])) + ((ssum[4] + ssum[5]) + (ssum[6] + ssum[7]));
-        const float r = 1.0f / sqrtf(ss / (float)a.K + a.eps);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = tid + 512 * e;
-            if (i < Kp) split_store(i, xv[e] * r * gv[e]);
-        }
-    } else {
-        prime(0);
-        float r = 1.0f;
-        if (a.gain) {
-            float ss = 0.f;
-            for (int i = tid; i < a.K; i += 512) {
-                const float v = a.xin[i];
-                ss += v * v;
-            }
-            ss = wave_sum(ss);
-            if (lane == 0) ssum[wave] = ss;
-            __syncthreads();
-            ss = ((ssum[0] + ssum[1]) + (ssum[2] + ssum[3])) + ((ssum[4] + ssum[5]) + (ssum[6] + ssum[7]));
-            r = 1.0f / sqrtf(ss / (float)a.K + a.eps);
-        }
-        if (EPI == EPI_QKV) {
-            const int half = a.head_dim >> 1;
-            if (tid < half) {
-                rot[tid] = a.cos_row[tid];
-                rot[half + tid] = a.sin_row[tid];
-            }
-        }
-        for (int i0 = 0; i0 < Kp; i0 += 8 * 512) {
-            float xv[8], gv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = i0 + tid + 512 * e;
-                xv[e] = (i < a.K) ? a.xin[i] : 0.f;
-                gv[e] = (a.gain && i < a.K) ? a.gain[i] : 1.f;
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = i0 + tid + 512 * e;
-                if (i < Kp) split_store(i, a.gain ? xv[e] * r * gv[e] : xv[e]);
-            }
-        }
-    }
-    __syncthreads();
-
-    for (int seg = 0; seg < a.S; ++seg) {
-        if (seg > 0) prime(seg);
-        const int rg = (seg * W + (int)blockIdx.x) * G + g;
-        const bool live = rg <= last_rg;
-        const int live_mask = live ? -1 : 0;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-
-        const int nb16 = (n + 15) >> 4;
-        for (int b = 0; b + 1 < nb16; ++b) {
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                mma_slot(b * 16 + u, buf[u], acc, live_mask);
-                buf[u] = load_slot((b + 1) * 16 + u);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
-
-        // ---- end of the row group: add the three term columns, then the KS slices, then the epilogue
-        float *rp = red + (size_t)(seg & 1) * 128;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float c1 = __shfl_down(acc[r], 1, 64), c2 = __shfl_down(acc[r], 2, 64);
-            const float y = (acc[r] + c1) + c2;
-            if (col == 0) rp[wave * 16 + 4 * kg + r] = y;
-        }
-        __syncthreads();
-        if (!live || ks != 0 || lane >= 16) continue;
-        float ya = 0.f, yb = 0.f;
-        const bool paired = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
-#pragma unroll
-        for (int k2 = 0; k2 < KS; ++k2) {
-            ya += rp[(g * KS + k2) * 16 + (paired ? (lane & 7) : lane)];
-            if (paired) yb += rp[(g * KS + k2) * 16 + (lane & 7) + 8];
-        }
-        if (EPI == EPI_RESID) {
-            // x[row] += y as a fire-and-forget atomic: one add per element per launch, so the
-            // result is the plain sum, and no load sits in the weight stream's wait counter
-            const int row = 16 * rg + lane;
-            if (row < a.O) atomicAdd(a.out + row, ya);
-        } else if (EPI == EPI_LOGITS) {
-            const int row = 16 * rg + lane;
-            if (row < a.O) a.out[row] = ya;
-        } else if (EPI == EPI_SWIGLU) {
-            const int f = 8 * rg + lane;
-            if (lane < 8 && 2 * f < a.O) a.out[f] = ya / (1.0f + expf(-ya)) * yb;
-        } else {
-            if (lane < 8) {
-                const int d = a.head_dim, half = d >> 1, gph = half >> 3;
-                const int hh = rg / gph, i = 8 * (rg - hh * gph) + lane;
-                const int nq = a.n_q_heads, nkv = a.n_kv_heads;
-                if (hh < nq + nkv) {
-                    const float c = rot[i], s = rot[half + i];
-                    const float qa = ya * c - yb * s, qb = yb * c + ya * s;
-                    if (hh < nq) {
-                        a.out[hh * d + i] = qa;
-                        a.out[hh * d + i + half] = qb;
-                    } else {
-                        uint16_t *kc = (uint16_t *)a.kcache + ((size_t)(hh - nq) * a.max_seq + a.pos) * d;
-                        kc[i] = f32_to_bf16_rne(qa);
-                        kc[i + half] = f32_to_bf16_rne(qb);
-                    }
-                } else {
-                    uint16_t *vc = (uint16_t *)a.vcache + ((size_t)(hh - nq - nkv) * a.max_seq + a.pos) * d;
-                    vc[i] = f32_to_bf16_rne(ya);
-                    vc[i + half] = f32_to_bf16_rne(yb);
-                }
-            }
-        }
-    }
-}
-
-template <int EPI, int KS>
-static hipError_t launch_mv1_t(const MvArgs &a, int grid, size_t lds, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mv1<EPI, KS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)kMvMaxLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((k_mv1<EPI, KS>), dim3(grid), dim3(512), lds, s, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
-    const size_t lds = mv_lds_bytes(a.K);
-    if (lds > kMvMaxLds) return hipErrorInvalidValue;
-    // Work split: KS wavefronts per row group, W workgroups, S rounds, chosen so that every
-    // workgroup gets the same number of row groups (a weight stream is only as fast as its
-    // slowest wavefront) with 6..16 wavefronts per compute unit and >= 8 k-tiles per wavefront.
-    int occ = (int)((160 * 1024) / (lds + 512));
-    if (occ > 2) occ = 2;  // 16 wavefronts per compute unit at most
-    if (occ < 1) occ = 1;
-    const int max_wg = n_cu * occ;
-    int best_ks = 8, best_w = 1, best_s = 1;
-    double best_score = 1e30;
-    for (int ks = 8; ks >= 1; ks /= 2) {
-        if (ks_override && ks != ks_override) continue;
-        const int G = 8 / ks;
-        const int n = (a.T + ks - 1) / ks;
-        // many short slices beat few long ones (measured: 16 tiles per wavefront is the sweet spot),
-        // as long as a slice still fills most of the 16-deep load window
-        if (n < 12 && ks > 1 && !ks_override) continue;
-        for (int S = 1; S <= 8; ++S) {
-            int W = (a.n_rg + G * S - 1) / (G * S);
-            if (W > max_wg) continue;
-            const double waste = (double)W * G * S / a.n_rg;           // >= 1
-            const double fill = (double)W / max_wg;                     // fraction of resident slots used
-            const double score = waste + (fill < 0.5 ? (0.5 - fill) : 0.0) + 0.002 * S + 0.01 * (8 / ks - 1);
-            if (score < best_score) {
-                best_score = score;
-                best_ks = ks;
-                best_w = W;
-                best_s = S;
-            }
-        }
-    }
-    if (wg_override > 0) {
-        const int G = 8 / best_ks;
-        best_w = wg_override;
-        best_s = (a.n_rg + G * best_w - 1) / (G * best_w);
-    }
-    a.S = best_s;
-#define SWIFT_MV_CASE(E)                                                                   \
-    case E:                                                                                \
-        switch (best_ks) {                                                                 \
-            case 1: return launch_mv1_t<E, 1>(a, best_w, lds, s);                          \
-            case 2: return launch_mv1_t<E, 2>(a, best_w, lds, s);                          \
-            case 4: return launch_mv1_t<E, 4>(a, best_w, lds, s);                          \
-            default: return launch_mv1_t<E, 8>(a, best_w, lds, s);                         \
-        }
-    switch (epi) {
-        SWIFT_MV_CASE(EPI_QKV)
-        SWIFT_MV_CASE(EPI_RESID)
-        SWIFT_MV_CASE(EPI_SWIGLU)
-        SWIFT_MV_CASE(EPI_LOGITS)
-    }
-#undef SWIFT_MV_CASE
-    return hipErrorInvalidValue;
 }
 
 }  // namespace swift

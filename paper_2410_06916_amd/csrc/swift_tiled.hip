@@ -1,0 +1,620 @@
+// gfx950 kernels of the bf16 path: tiled weights streamed once from HBM into MFMA, activations
+// kept in fp32 precision as three bf16 terms.  k_mv1 handles one activation row (draft pass,
+// plain decoding), k_mvN a block of 2..16 rows (verify, prefill).
+#include <math.h>
+
+#include "swift_device.h"
+#include "swift_kernels.h"
+
+namespace swift {
+
+// ------------------------------------------------------------------------------------------
+// weight layout conversion
+// ------------------------------------------------------------------------------------------
+__global__ void k_tile_weights(TileArgs a) {
+    // one thread per 16-byte chunk of the destination
+    const int64_t n_chunks = (int64_t)a.n_rg * a.T * 64;
+    const uint16_t *src = (const uint16_t *)a.src;
+    u32x4 *dst = (u32x4 *)a.dst;
+    const int d = a.head_dim, half = d >> 1, gph = half >> 3;  // row groups per head (TILE_PAIR)
+    for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < n_chunks;
+         c += (int64_t)gridDim.x * blockDim.x) {
+        const int l = (int)(c & 63);
+        const int64_t tile = c >> 6;
+        const int t = (int)(tile % a.T);
+        const int rg = (int)(tile / a.T);
+        const int j = l & 15, k0 = 32 * t + 8 * (l >> 4);
+        int row;
+        if (a.mode == TILE_PLAIN) {
+            row = 16 * rg + j;
+        } else if (a.mode == TILE_PAIR) {
+            const int head = rg / gph, g = rg - head * gph;
+            row = head * d + 8 * g + (j & 7) + (j >= 8 ? half : 0);
+        } else {
+            if ((j >= 8) != (a.part == 1)) continue;  // the other half of the tile comes from the other tensor
+            row = 8 * rg + (j & 7);
+        }
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row < a.src_rows) {
+            if (k0 + 8 <= a.K) {
+                v = *(const u32x4 *)(src + (size_t)row * a.K + k0);
+            } else {
+                uint16_t e[8];
+                for (int i = 0; i < 8; ++i) e[i] = (k0 + i < a.K) ? src[(size_t)row * a.K + k0 + i] : (uint16_t)0;
+                v.x = e[0] | ((uint32_t)e[1] << 16);
+                v.y = e[2] | ((uint32_t)e[3] << 16);
+                v.z = e[4] | ((uint32_t)e[5] << 16);
+                v.w = e[6] | ((uint32_t)e[7] << 16);
+            }
+        }
+        dst[c] = v;
+    }
+}
+
+hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s) {
+    const int64_t n_chunks = (int64_t)a.n_rg * a.T * 64;
+    if (n_chunks <= 0) return hipSuccess;
+    int64_t grid = (n_chunks + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL(k_tile_weights, dim3((unsigned)grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------------------------------------
+// embedding gather for R rows: fp32 residual, split of x * gain_next, partial sums of squares
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
+    // one thread per (row r, element i); 16 consecutive lanes share a 16-element group
+    const int NC = 3 * a.R;
+    const int Hp = (a.H + 15) & ~15;
+    const int total = a.R * Hp;
+    for (int idx0 = blockIdx.x * 256; idx0 < total; idx0 += gridDim.x * 256) {
+        const int idx = idx0 + threadIdx.x;
+        const int r = idx / Hp, i = idx - r * Hp;
+        float v = 0.f;
+        const bool ok = idx < total && i < a.H;
+        if (ok) {
+            v = __uint_as_float((uint32_t)a.E[(size_t)a.tokens[r] * a.H + i] << 16);
+            a.x[(size_t)r * a.H + i] = v;
+            uint16_t hi, mid, lo;
+            split3(v * a.gain_next[i], hi, mid, lo);
+            uint16_t *p = a.xs + ((size_t)(i >> 3) * NC + 3 * r) * 8 + (i & 7);
+            p[0] = hi;
+            p[8] = mid;
+            p[16] = lo;
+        }
+        float ss = v * v;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        if (idx < total && (i & 15) == 0) a.pss[(size_t)(i >> 4) * 16 + r] = ss;
+    }
+}
+
+hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s) {
+    const int Hp = (a.H + 15) & ~15;
+    const int grid = (a.R * Hp + 255) / 256;
+    hipLaunchKernelGGL(k_embed_rows, dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// shared pieces of the projection kernels
+// ------------------------------------------------------------------------------------------
+// RMSNorm scale per block row from the producer's partial sums of squares [n_pss][16].  All 512
+// threads load (thread = (partial p mod 32, row r), independent loads issued together), then 16
+// threads add the 32 per-lane sums in order: the summation order is fixed.  Ends with a barrier.
+__device__ inline void mv_norm_scale(const MvArgs &a, float *rs /* LDS [16] */, float *scratch /* LDS [512] */) {
+    const int tid = threadIdx.x, r = tid & 15, q = tid >> 4;
+    if (a.pss) {
+        float ss = 0.f;
+        for (int p0 = 0; p0 < a.n_pss; p0 += 512) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int p = p0 + q + 32 * u;
+                v[u] = p < a.n_pss ? a.pss[(size_t)p * 16 + r] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) ss += v[u];
+        }
+        scratch[q * 16 + r] = ss;
+    }
+    __syncthreads();
+    if (tid < 16) {
+        float ss = 0.f;
+        if (a.pss)
+            for (int q2 = 0; q2 < 32; ++q2) ss += scratch[q2 * 16 + tid];
+        rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
+    }
+    __syncthreads();
+}
+
+// What follows the dot products of one 16-row group, run by one whole wavefront.
+// Y(r, j): finished dot product of block row r and tile row j (before the norm scale).
+template <int EPI, typename YF>
+__device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, YF Y) {
+    const int R = a.R, NC = 3 * R;
+    if (EPI == EPI_RESID || EPI == EPI_LOGITS) {
+        const int iters = (16 * R + 63) >> 6;
+        for (int it = 0; it < iters; ++it) {
+            const int idx = it * 64 + lane;
+            const int r = idx >> 4, j = idx & 15;
+            const int row = 16 * rg + j;
+            const bool ok = r < R && row < a.O;
+            if (EPI == EPI_LOGITS) {
+                if (ok) a.out_f32[(size_t)r * a.ld_out + row] = Y(r, j) * rs[r];
+            } else {
+                float xn = 0.f;
+                if (ok) {
+                    float *xp = a.out_f32 + (size_t)r * a.ld_out + row;
+                    xn = *xp + Y(r, j);
+                    *xp = xn;
+                    uint16_t hi, mid, lo;
+                    split3(xn * a.gain_next[row], hi, mid, lo);
+                    uint16_t *p = a.out_s + ((size_t)(row >> 3) * NC + 3 * r) * 8 + (row & 7);
+                    p[0] = hi;
+                    p[8] = mid;
+                    p[16] = lo;
+                }
+                float ss = xn * xn;
+#pragma unroll
+                for (int off = 8; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+                if (r < R && j == 0) a.pss_out[(size_t)rg * 16 + r] = ss;
+            }
+        }
+    } else {
+        const int iters = (8 * R + 63) >> 6;
+        for (int it = 0; it < iters; ++it) {
+            const int idx = it * 64 + lane;
+            const int r = idx >> 3, j = idx & 7;
+            if (r >= R) continue;
+            const float sc = rs[r];
+            const float ya = Y(r, j) * sc, yb = Y(r, j + 8) * sc;
+            if (EPI == EPI_SWIGLU) {
+                if (2 * (8 * rg + j) < a.O) {
+                    uint16_t hi, mid, lo;
+                    split3(ya / (1.0f + expf(-ya)) * yb, hi, mid, lo);
+                    uint16_t *p = a.out_s + ((size_t)rg * NC + 3 * r) * 8 + j;
+                    p[0] = hi;
+                    p[8] = mid;
+                    p[16] = lo;
+                }
+            } else {
+                const int d = a.head_dim, half = d >> 1, gph = half >> 3;
+                const int hh = rg / gph, i = 8 * (rg - hh * gph) + j;
+                const int nq = a.n_q_heads, nkv = a.n_kv_heads, pos = a.pos0 + r;
+                if (hh < nq + nkv) {
+                    const float c = a.cos_tab[(size_t)pos * half + i], s = a.sin_tab[(size_t)pos * half + i];
+                    const float qa = ya * c - yb * s, qb = yb * c + ya * s;
+                    if (hh < nq) {
+                        float *qp = a.out_f32 + (size_t)r * a.ld_out + hh * d + i;
+                        qp[0] = qa;
+                        qp[half] = qb;
+                    } else {
+                        uint16_t *kc = (uint16_t *)a.kcache + ((size_t)(hh - nq) * a.max_seq + pos) * d + i;
+                        kc[0] = f32_to_bf16_rne(qa);
+                        kc[half] = f32_to_bf16_rne(qb);
+                    }
+                } else {
+                    uint16_t *vc = (uint16_t *)a.vcache + ((size_t)(hh - nq - nkv) * a.max_seq + pos) * d + i;
+                    vc[0] = f32_to_bf16_rne(ya);
+                    vc[half] = f32_to_bf16_rne(yb);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// one activation row: y = W . x, MFMA, whole activation in LDS, K split over wavefronts
+// ------------------------------------------------------------------------------------------
+// The three terms of x go into columns 0..2 of the MFMA B operand (the other 13 columns read a
+// zero chunk); y is the sum of the three result columns.  A workgroup has 8 wavefronts; KS of
+// them share one row group, each taking a contiguous slice of its k-tiles, so a workgroup works
+// on G = 8/KS row groups at a time and the slices are added in LDS in a fixed order.  Every
+// wavefront keeps a rolling window of sixteen 1 KB tile loads in flight; the first window is
+// issued before the activation is staged.
+template <int EPI, int KS>
+__global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per SIMD: <= 128 VGPRs, two workgroups per CU
+    extern __shared__ __align__(16) unsigned char smem[];
+    // LDS: [16 B zeros][4T chunks x 3 terms x 8 bf16][2 x 8 wavefronts x 16 rows fp32][16 scales]
+    float *red = (float *)(smem + 16 + (size_t)a.T * 192);
+    float *rs = red + 256;
+    float *nscratch = rs + 16;  // [512]
+    constexpr int G = 8 / KS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform from here on
+    const int g = wave / KS, ks = wave - g * KS;
+    const int T = a.T;
+    const int n = (T + KS - 1) / KS;           // k-tiles per wavefront and row group
+    const int t0 = min(ks * n, T - 1);
+    const int nv = max(0, min(n, T - ks * n)); // ... of which exist
+    const int nvm1 = max(nv - 1, 0);
+    const u32x4 *Wt = (const u32x4 *)a.Wt;
+    const int W = gridDim.x;
+    const int last_rg = a.n_rg - 1;
+    const int col = lane & 15, kg = lane >> 4;
+    // byte address of this lane's B chunk for tile t: boff + t * bstride; lanes of columns >= 3
+    // (and slots past the wavefront's slice) read the zero chunk at address 0
+    const int boff = col < 3 ? 16 + (kg * 3 + col) * 16 : 0;
+    const int bstride = col < 3 ? 192 : 0;
+
+    u32x4 buf[16];
+    const u32x4 *base = nullptr;
+    auto load_slot = [&](int i) { return __builtin_nontemporal_load(base + (size_t)min(i, nvm1) * 64); };
+    auto mma_slot = [&](int i, const u32x4 &av, f32x4 &acc, int live_mask) {
+        const int m = (i < nv) ? live_mask : 0;              // all ones or zero, wavefront-uniform
+        const int addr = (boff + (t0 + i) * bstride) & m;
+        const u32x4 bv = *(const u32x4 *)(smem + addr);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
+                                                      acc, 0, 0, 0);
+    };
+    auto prime = [&](int seg) {
+        const int rg = min((seg * W + (int)blockIdx.x) * G + g, last_rg);
+        base = Wt + ((size_t)rg * T + t0) * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) buf[u] = load_slot(u);
+    };
+
+    // ---- stage the split activation (a plain copy: the producer kernel already wrote it in B
+    // layout); its first loads go out ahead of the weight loads so that they return first
+    {
+        const u32x4 *src = (const u32x4 *)a.in_s;
+        u32x4 *dst = (u32x4 *)(smem + 16);
+        const int n_units = T * 12, real_units = (a.K >> 3) * 3;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 tmp[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = tid + 512 * q;
+            tmp[q] = i < real_units ? src[i] : zero;
+        }
+        prime(0);
+        if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = tid + 512 * q;
+            if (i < n_units) dst[i] = tmp[q];
+        }
+        for (int i0 = 2048; i0 < n_units; i0 += 2048) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = i0 + tid + 512 * q;
+                tmp[q] = i < real_units ? src[i] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = i0 + tid + 512 * q;
+                if (i < n_units) dst[i] = tmp[q];
+            }
+        }
+        mv_norm_scale(a, rs, nscratch);
+    }
+
+    for (int seg = 0; seg < a.S; ++seg) {
+        if (seg > 0) prime(seg);
+        const int rg = (seg * W + (int)blockIdx.x) * G + g;
+        const bool live = rg <= last_rg;
+        const int live_mask = live ? -1 : 0;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+
+        const int nb16 = (n + 15) >> 4;
+        for (int b = 0; b + 1 < nb16; ++b) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                mma_slot(b * 16 + u, buf[u], acc, live_mask);
+                buf[u] = load_slot((b + 1) * 16 + u);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+
+        // ---- end of the row group: add the three term columns, then the KS slices, then the epilogue
+        float *rp = red + (size_t)(seg & 1) * 128;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float c1 = __shfl_down(acc[r], 1, 64), c2 = __shfl_down(acc[r], 2, 64);
+            const float y = (acc[r] + c1) + c2;
+            if (col == 0) rp[wave * 16 + 4 * kg + r] = y;
+        }
+        __syncthreads();
+        if (!live || ks != 0) continue;
+        mv_epilogue<EPI>(a, rg, lane, rs, [&](int, int j) {
+            float y = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2) y += rp[(g * KS + k2) * 16 + j];
+            return y;
+        });
+    }
+}
+
+template <int EPI, int KS>
+static hipError_t launch_mv1_t(const MvArgs &a, int grid, size_t lds, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_mv1<EPI, KS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kMvMaxLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_mv1<EPI, KS>), dim3(grid), dim3(512), lds, s, a);
+    return hipGetLastError();
+}
+
+static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
+    const size_t lds = mv1_lds_bytes(a.K);
+    if (lds > kMvMaxLds) return hipErrorInvalidValue;
+    // Work split: KS wavefronts per row group, W workgroups, S rounds, chosen so that every
+    // workgroup gets the same number of row groups (a weight stream is only as fast as its
+    // slowest wavefront) with at most 16 wavefronts per compute unit.
+    int occ = (int)((160 * 1024) / (lds + 512));
+    if (occ > 2) occ = 2;
+    if (occ < 1) occ = 1;
+    const int max_wg = n_cu * occ;
+    int best_ks = 8, best_w = 1, best_s = 1;
+    double best_score = 1e30;
+    for (int ks = 8; ks >= 1; ks /= 2) {
+        if (ks_override && ks != ks_override) continue;
+        const int G = 8 / ks;
+        const int n = (a.T + ks - 1) / ks;
+        // many short slices beat few long ones (measured: 16 tiles per wavefront is the sweet spot),
+        // as long as a slice still fills most of the 16-deep load window
+        if (n < 12 && ks > 1 && !ks_override) continue;
+        for (int S = 1; S <= 8; ++S) {
+            int W = (a.n_rg + G * S - 1) / (G * S);
+            if (W > max_wg) continue;
+            const double waste = (double)W * G * S / a.n_rg;           // >= 1
+            const double fill = (double)W / max_wg;                     // fraction of resident slots used
+            const double score = waste + (fill < 0.5 ? (0.5 - fill) : 0.0) + 0.002 * S + 0.01 * (8 / ks - 1);
+            if (score < best_score) {
+                best_score = score;
+                best_ks = ks;
+                best_w = W;
+                best_s = S;
+            }
+        }
+    }
+    if (wg_override > 0) {
+        const int G = 8 / best_ks;
+        best_w = wg_override;
+        best_s = (a.n_rg + G * best_w - 1) / (G * best_w);
+    }
+    a.S = best_s;
+#define SWIFT_MV_CASE(E)                                                                   \
+    case E:                                                                                \
+        switch (best_ks) {                                                                 \
+            case 1: return launch_mv1_t<E, 1>(a, best_w, lds, s);                          \
+            case 2: return launch_mv1_t<E, 2>(a, best_w, lds, s);                          \
+            case 4: return launch_mv1_t<E, 4>(a, best_w, lds, s);                          \
+            default: return launch_mv1_t<E, 8>(a, best_w, lds, s);                         \
+        }
+    switch (epi) {
+        SWIFT_MV_CASE(EPI_QKV)
+        SWIFT_MV_CASE(EPI_RESID)
+        SWIFT_MV_CASE(EPI_SWIGLU)
+        SWIFT_MV_CASE(EPI_LOGITS)
+    }
+#undef SWIFT_MV_CASE
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------
+// a block of 2..16 activation rows: Y = W . X, MFMA, K chunked through LDS, optional split-K
+// ------------------------------------------------------------------------------------------
+// Each of the 8 wavefronts of a workgroup owns one 16-row group of W; the workgroup walks its K
+// range in chunks of 16 tiles.  The B operand of a chunk (64 k-chunks x NC = 3R columns x 16 B,
+// already in B layout in global memory) is copied into one of two LDS buffers while the MFMAs of
+// the previous chunk run; the A tiles of the next chunk are loaded into a second register set at
+// the same time.  NCB = ceil(NC/16) MFMAs per tile.  With gridDim.y > 1 the K range is split over
+// workgroups: each writes its partial results, and the workgroup that arrives last at a counter
+// adds the partials in split order (so the result does not depend on arrival order) and runs the
+// epilogue.
+template <int NCB>
+struct MvNRegs {
+    f32x4 acc[NCB];
+};
+
+template <int EPI, int NCB>
+__global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int R = a.R, NC = 3 * R;
+    const int buf_bytes = 64 * NC * 16;
+    // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
+    const int main_bytes = max(2 * buf_bytes, NCB * 8192);
+    float *rs = (float *)(smem + 16 + (size_t)main_bytes);
+    int *flag = (int *)(rs + 16);
+    float *nscratch = rs + 32;  // [512]
+    float *dump = (float *)(smem + 16);  // reuses the B buffers after the last MFMA
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T = a.T;
+    const int rg = (int)blockIdx.x * 8 + wave;
+    const bool live = rg < a.n_rg;
+    const int rgc = min(rg, a.n_rg - 1);
+    const int tb = (int)blockIdx.y * TS;
+    const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
+    const int nch = (nt + 15) >> 4;
+    const int col = lane & 15, kg = lane >> 4;
+    const u32x4 *base = (const u32x4 *)a.Wt + ((size_t)rgc * T + tb) * 64 + lane;
+    const u32x4 *bsrc = (const u32x4 *)a.in_s;
+    const int real_units = (a.K >> 3) * NC;
+    const int chunk_units = 64 * NC;  // 16-byte units of one B chunk
+
+    // per-lane B addressing: byte offset inside a buffer for tile u, column block cb:
+    //   ((4u + kg) * NC + 16 cb + col) * 16, or the zero chunk when the column does not exist
+    int cboff[NCB], cbmask[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        const bool okc = 16 * cb + col < NC;
+        cboff[cb] = okc ? 16 + (kg * NC + 16 * cb + col) * 16 : 0;
+        cbmask[cb] = okc ? -1 : 0;
+    }
+    const int tstride = 4 * NC * 16;
+
+    f32x4 acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto loadA = [&](int c, u32x4(&A)[16]) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) A[u] = __builtin_nontemporal_load(base + (size_t)min(c * 16 + u, nt - 1) * 64);
+    };
+    auto loadB = [&](int c, u32x4(&tmp)[6]) {
+        const int gu0 = 4 * (tb + 16 * c) * NC;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            const int i = tid + 512 * q;
+            tmp[q] = (i < chunk_units && gu0 + i < real_units) ? bsrc[gu0 + i] : zero;
+        }
+    };
+    auto storeB = [&](int bi, const u32x4(&tmp)[6]) {
+        u32x4 *dst = (u32x4 *)(smem + 16 + (size_t)bi * buf_bytes);
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            const int i = tid + 512 * q;
+            if (i < chunk_units) dst[i] = tmp[q];
+        }
+    };
+    auto mfmas = [&](int c, const u32x4(&A)[16], int bi) {
+        const int bbase = bi * buf_bytes;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int m = (live && c * 16 + u < nt) ? -1 : 0;  // wavefront-uniform
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const int addr = (cboff[cb] + ((bbase + u * tstride) & cbmask[cb])) & m;
+                const u32x4 bv = *(const u32x4 *)(smem + addr);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[u]),
+                                                                  __builtin_bit_cast(bf16x8, bv), acc[cb], 0, 0, 0);
+            }
+        }
+    };
+
+    u32x4 A0[16], A1[16], tmp[6];
+    loadB(0, tmp);
+    loadA(0, A0);
+    if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+    storeB(0, tmp);
+    mv_norm_scale(a, rs, nscratch);
+
+    auto step_full = [&](int c, const u32x4(&Ac)[16], int bc, u32x4(&An)[16], int bn) {
+        loadB(c + 1, tmp);
+        loadA(c + 1, An);
+        __syncthreads();  // chunk c's B is visible; nobody reads buffer bn any more
+        storeB(bn, tmp);
+        mfmas(c, Ac, bc);
+    };
+    auto step_last = [&](int c, const u32x4(&Ac)[16], int bc) {
+        __syncthreads();
+        mfmas(c, Ac, bc);
+    };
+    int c = 0;
+    for (; c + 2 < nch; c += 2) {
+        step_full(c, A0, 0, A1, 1);
+        step_full(c + 1, A1, 1, A0, 0);
+    }
+    if (nch - c == 2) {
+        step_full(c, A0, 0, A1, 1);
+        step_last(c + 1, A1, 1);
+    } else {
+        step_last(c, A0, 0);
+    }
+
+    // ---- results to LDS: dump[wave][column][tile row]
+    __syncthreads();
+    float *dw = dump + (size_t)wave * (NCB * 256);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) dw[(16 * cb + col) * 16 + 4 * kg + r4] = acc[cb][r4];
+    __syncthreads();
+    auto y_local = [&](int r, int j) { return (dw[(3 * r) * 16 + j] + dw[(3 * r + 1) * 16 + j]) + dw[(3 * r + 2) * 16 + j]; };
+
+    if (gridDim.y == 1) {
+        if (live) mv_epilogue<EPI>(a, rg, lane, rs, y_local);
+        return;
+    }
+    // ---- split-K: publish the partial, last workgroup of this row block reduces
+    const int KSP = gridDim.y;
+    if (live) {
+        float *pp = a.part + ((size_t)blockIdx.y * a.n_rg + rg) * (16 * R);
+        for (int idx = lane; idx < 16 * R; idx += 64) pp[idx] = y_local(idx >> 4, idx & 15);
+    }
+    // One release per workgroup: the barrier orders every wavefront's partial stores before thread
+    // 0's device-scope fence, which publishes them ahead of the counter increment.
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        const int old = atomicAdd(a.counters + blockIdx.x, 1);
+        *flag = (old == KSP - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (*flag == 0) return;
+    __threadfence();  // acquire: the other workgroups' partials
+    if (live) {
+        const float *p0 = a.part + (size_t)rg * (16 * R);
+        const size_t sstride = (size_t)a.n_rg * (16 * R);
+        // (plain loads: the fence above makes the other workgroups' released partials visible)
+        mv_epilogue<EPI>(a, rg, lane, rs, [&](int r, int j) {
+            float v[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) v[s2] = s2 < KSP ? p0[s2 * sstride + r * 16 + j] : 0.f;
+            float y = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < 8; ++s2) y += v[s2];
+            return y;
+        });
+    }
+    if (tid == 0) a.counters[blockIdx.x] = 0;
+}
+
+template <int EPI, int NCB>
+static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kMvMaxLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int NC = 3 * a.R;
+    const size_t buf2 = 2 * (size_t)64 * NC * 16;
+    const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 128 + 2048;
+    const int n_rb = (a.n_rg + 7) / 8;
+    // split K over workgroups until about one workgroup per compute unit exists
+    // (never more workgroups than compute units: one workgroup fills a compute unit's registers,
+    // so a partial second round would double the kernel's duration)
+    int ksp = n_cu / n_rb;
+    if (ksp < 1) ksp = 1;
+    if (ksp > 8) ksp = 8;
+    while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
+    int TS = (a.T + ksp - 1) / ksp;
+    ksp = (a.T + TS - 1) / TS;
+    hipLaunchKernelGGL((k_mvN<EPI, NCB>), dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
+    return hipGetLastError();
+}
+
+hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
+    if (a.R < 1 || a.R > kMaxRows) return hipErrorInvalidValue;
+    if (a.R == 1 && ks_override != 16) return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
+    const int ncb = (3 * a.R + 15) / 16;
+#define SWIFT_MVN_CASE(E)                                               \
+    case E:                                                             \
+        switch (ncb) {                                                  \
+            case 1: return launch_mvN_t<E, 1>(a, n_cu, s);              \
+            case 2: return launch_mvN_t<E, 2>(a, n_cu, s);              \
+            default: return launch_mvN_t<E, 3>(a, n_cu, s);             \
+        }
+    switch (epi) {
+        SWIFT_MVN_CASE(EPI_QKV)
+        SWIFT_MVN_CASE(EPI_RESID)
+        SWIFT_MVN_CASE(EPI_SWIGLU)
+        SWIFT_MVN_CASE(EPI_LOGITS)
+    }
+#undef SWIFT_MVN_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace swift
