@@ -117,7 +117,7 @@ Layout make_layout(const swift_model_config &c) {
     L.cos = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
     L.sin = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
     L.kv = take((uint64_t)c.n_layers * 2 * KV * c.max_seq * eb);
-    L.n_split_max = (c.max_seq + kAttnChunk - 1) / kAttnChunk;
+    L.n_split_max = kAttnMaxSplit;
     L.x = take(kMaxRows * H * 4);
     L.q = take(kMaxRows * Q * 4);
     L.att = take(kMaxRows * Q * 4);
@@ -320,10 +320,12 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.n_kv_heads = c.n_kv_heads;
             a.part_o = dptr<float>(x, L.part_o);
             a.part_ml = dptr<float>(x, L.part_ml);
+            a.max_split = L.n_split_max;
+            a.counters = dptr<int>(x, L.mv_counters) + 2048;
             a.out = ar;
             a.out_s = nullptr;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
-                          [&] { return launch_attn_decode(c.dtype, a, s); }));
+                          [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
             if ((rc = linear(SWIFT_KC_OPROJ, EPI_RESID, y.wo, H, Q, ar, nullptr, xr, l))) return rc;
         }
         if (!(skip && skip[2 * l + 1])) {
@@ -433,10 +435,12 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.n_kv_heads = c.n_kv_heads;
             a.part_o = dptr<float>(x, L.part_o);
             a.part_ml = dptr<float>(x, L.part_ml);
+            a.max_split = L.n_split_max;
+            a.counters = dptr<int>(x, L.mv_counters) + 2048;
             a.out = nullptr;
             a.out_s = as_;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
-                          [&] { return launch_attn_decode(c.dtype, a, s); }));
+                          [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
 
             MvArgs o = base_args(y.wo, H, Q, (H + 15) / 16);
             o.in_s = as_;

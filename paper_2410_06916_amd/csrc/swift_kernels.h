@@ -9,7 +9,7 @@
 namespace swift {
 
 constexpr int kMaxRows = 16;       // rows of one block pass (SWIFT_MAX_BLOCK)
-constexpr int kAttnChunk = 128;    // cache slots handled by one attention workgroup
+constexpr int kAttnMaxSplit = 64;  // most cache-length splits of one (row, kv head)
 constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
 enum Dtype : int { F32 = 0, BF16 = 1 };
@@ -55,10 +55,12 @@ struct AttnArgs {
     int max_seq, head_dim, n_q_heads, n_kv_heads;
     float *part_o;                // [rows][n_q][n_split][d]   unnormalised partial outputs
     float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
+    int max_split;                // splits the partial buffers can hold
+    int *counters;                // [rows][n_kv] arrival counters, zero between launches
     float *out;                   // fp32 [rows][n_q][d], or nullptr
     uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*rows][8], or nullptr
 };
-hipError_t launch_attn_decode(int dtype, const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
 
 struct ArgmaxArgs {
     const float *logits;  // [rows][V]
@@ -129,7 +131,7 @@ struct MvArgs {
 };
 constexpr size_t kMvMaxLds = 150 * 1024;
 // LDS bytes of the single-row kernel for depth K
-inline size_t mv1_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 16 + 1024 + 64 + 2048; }
+inline size_t mv1_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 16 + 1024 + 64 + 2048 + 1024; }
 // ks_override / wg_override: 0 = choose automatically (single-row kernel only).
 hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
 

@@ -178,27 +178,32 @@ hipError_t launch_embed(int dtype, const EmbedArgs &a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
-// decode attention: one query row, all heads, split over the cache length
+// attention over the cache for a block of query rows, split over the cache length
 // ------------------------------------------------------------------------------------------
-// Workgroup (kv head g, split s) handles cache slots [s*kAttnChunk, ...) for the query heads
-// that share kv head g.  A group of LPP = d / VEC lanes owns one cache slot at a time; lane j
-// of the group holds elements [j*VEC, (j+1)*VEC) of that slot's key and value.  Each lane
-// group keeps a running (max, sum, weighted value) per query head (online softmax); groups,
-// then wavefronts, are merged at the end and the workgroup writes one partial per head.
+// Workgroup (kv head g, split sp, block row r) handles `chunk` cache slots for the query heads
+// that share kv head g; row r attends slots [0, n_ctx + r).  A group of LPP = d / VEC lanes owns
+// one cache slot at a time (lane j of the group holds elements [j*VEC, (j+1)*VEC) of that slot's
+// key and value); step s of wavefront w covers slots lo + (4 s + w) * SPW .., so the four
+// wavefronts read consecutive slots, and the loads of NB steps are issued together.  Each lane
+// group keeps a running (max, sum, weighted value) per query head (online softmax); groups, then
+// wavefronts, are merged.  With one split the workgroup normalises and writes the result;
+// otherwise it writes its partial and k_attn_combine merges the partials in split order.
 template <typename T, int GROUP>
-__global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
+__global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
     constexpr int VEC = T::VEC;
+    constexpr int NB = GROUP <= 2 ? 4 : 1;
     const int d = a.head_dim;
-    const int LPP = d / VEC;        // lanes per cache slot (power of two, <= 32)
-    const int SPW = 64 / LPP;       // slots per wavefront step
+    const int LPP = d / VEC;   // lanes per cache slot (power of two, <= 32)
+    const int SPW = 64 / LPP;  // slots per wavefront step
     const int n_split = gridDim.y;
     const int g = blockIdx.x, sp = blockIdx.y, row = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lj = lane & (LPP - 1), lg = lane / LPP;
     const int n_ctx = a.n_ctx + row;  // block row r sees the cache up to its own slot
-    const int lo = sp * kAttnChunk;
-    if (lo >= n_ctx) return;          // this row has fewer chunks than the longest row of the block
-    const int hi = min(n_ctx, lo + kAttnChunk);
+    const int ns_row = (n_ctx + chunk - 1) / chunk;  // splits this row really has
+    if (sp >= ns_row) return;
+    const int lo = sp * chunk;
+    const int hi = min(n_ctx, lo + chunk);
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
 
@@ -219,31 +224,40 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
 
     const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
     const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
+    const int steps = (hi - lo + 4 * SPW - 1) / (4 * SPW);
 
-    for (int p0 = lo + wave * SPW; p0 < hi; p0 += 4 * SPW) {
-        const int p = p0 + lg;
-        const bool live = p < hi;
-        const int pc = live ? p : hi - 1;  // clamp: dead lane groups recompute a live slot and discard it
-        const u32x4 kv = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
-        const u32x4 vv = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
-        float kf[VEC], vf[VEC];
-        T::unpack(kv, kf);
-        T::unpack(vv, vf);
+    for (int s0 = 0; s0 < steps; s0 += NB) {
+        u32x4 kv[NB], vv[NB];
 #pragma unroll
-        for (int h = 0; h < GROUP; ++h) {
-            float s = 0.f;
+        for (int b = 0; b < NB; ++b) {
+            const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
+            const int pc = min(p, hi - 1);  // clamp: dead lane groups recompute a live slot and discard it
+            kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
+            vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
+        }
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) s = fmaf(q[h][j], kf[j], s);
-            for (int off = LPP >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-            s *= scale;
-            if (live) {
-                const float mn = fmaxf(m[h], s);
-                const float corr = expf(m[h] - mn);  // exp(-inf) = 0 on the first slot
-                const float pr = expf(s - mn);
-                l[h] = l[h] * corr + pr;
+        for (int b = 0; b < NB; ++b) {
+            const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
+            const bool live = p < hi;
+            float kf[VEC], vf[VEC];
+            T::unpack(kv[b], kf);
+            T::unpack(vv[b], vf);
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) o[h][j] = o[h][j] * corr + pr * vf[j];
-                m[h] = mn;
+            for (int h = 0; h < GROUP; ++h) {
+                float sc = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) sc = fmaf(q[h][j], kf[j], sc);
+                for (int off = LPP >> 1; off > 0; off >>= 1) sc += __shfl_xor(sc, off, 64);
+                sc *= scale;
+                if (live) {
+                    const float mn = fmaxf(m[h], sc);
+                    const float corr = __expf(m[h] - mn);  // exp(-inf) = 0 on the first slot
+                    const float pr = __expf(sc - mn);
+                    l[h] = l[h] * corr + pr;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o[h][j] = o[h][j] * corr + pr * vf[j];
+                    m[h] = mn;
+                }
             }
         }
     }
@@ -255,8 +269,8 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
             const float m2 = __shfl_xor(m[h], off, 64);
             const float l2 = __shfl_xor(l[h], off, 64);
             const float mn = fmaxf(m[h], m2);
-            const float c1 = (m[h] == -INFINITY) ? 0.f : expf(m[h] - mn);
-            const float c2 = (m2 == -INFINITY) ? 0.f : expf(m2 - mn);
+            const float c1 = (m[h] == -INFINITY) ? 0.f : __expf(m[h] - mn);
+            const float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
             l[h] = l[h] * c1 + l2 * c2;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
@@ -269,7 +283,7 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
 
     // merge the four wavefronts through LDS
     __shared__ float sm[4][GROUP], sl[4][GROUP];
-    __shared__ float so[4][GROUP][256];
+    __shared__ float so[4][GROUP][128];
     if (lg == 0) {
 #pragma unroll
         for (int h = 0; h < GROUP; ++h) {
@@ -282,37 +296,57 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a) {
         }
     }
     __syncthreads();
+
+    auto write_out = [&](int h, int j, float y) {
+        const int e = (g * GROUP + h) * d + j;
+        if (a.out) a.out[(size_t)row * nq * d + e] = y;
+        if (a.out_s) {
+            uint16_t hi16, mid16, lo16;
+            split3(y, hi16, mid16, lo16);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * a.rows) + 3 * row) * 8 + (e & 7);
+            p[0] = hi16;
+            p[8] = mid16;
+            p[16] = lo16;
+        }
+    };
+
     for (int idx = tid; idx < GROUP * d; idx += 256) {
         const int h = idx / d, j = idx - h * d;
-        float mn = fmaxf(fmaxf(sm[0][h], sm[1][h]), fmaxf(sm[2][h], sm[3][h]));
+        const float mn = fmaxf(fmaxf(sm[0][h], sm[1][h]), fmaxf(sm[2][h], sm[3][h]));
         float ls = 0.f, os = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float c = (sm[w][h] == -INFINITY) ? 0.f : expf(sm[w][h] - mn);
+            const float c = (sm[w][h] == -INFINITY) ? 0.f : __expf(sm[w][h] - mn);
             ls += sl[w][h] * c;
             os += so[w][h][j] * c;
         }
-        const size_t slot = ((size_t)row * nq + g * GROUP + h) * n_split + sp;
-        a.part_o[slot * d + j] = os;
-        if (j == 0) {
-            a.part_ml[slot * 2 + 0] = mn;
-            a.part_ml[slot * 2 + 1] = ls;
+        if (ns_row == 1) {
+            write_out(h, j, os / ls);
+        } else {
+            const size_t slot = ((size_t)row * nq + g * GROUP + h) * n_split + sp;
+            a.part_o[slot * d + j] = os;
+            if (j == 0) {
+                a.part_ml[slot * 2 + 0] = mn;
+                a.part_ml[slot * 2 + 1] = ls;
+            }
         }
     }
 }
 
-// out[row][head][j] = sum_s o_s[j] e^{m_s - M} / sum_s l_s e^{m_s - M} over the row's own chunks;
-// written as fp32 and/or as the three-term bf16 split that the output projection consumes
-__global__ void k_attn_combine(AttnArgs a, int n_split) {
+// Merges the split partials of every (row, head) in split order and writes the result.  A second
+// launch rather than a last-arriver merge inside k_attn_split: device-scope fences inside a kernel
+// cost more than the launch on this multi-die part.
+__global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
     const int head = blockIdx.x, row = blockIdx.y, d = a.head_dim;
-    const int ns = (a.n_ctx + row + kAttnChunk - 1) / kAttnChunk;
+    const int ns = (a.n_ctx + row + chunk - 1) / chunk;
+    if (ns == 1) return;  // written directly by the split kernel
     const size_t base = ((size_t)row * a.n_q_heads + head) * n_split;
     float M = -INFINITY;
     for (int s = 0; s < ns; ++s) M = fmaxf(M, a.part_ml[(base + s) * 2]);
     for (int j = threadIdx.x; j < d; j += blockDim.x) {
         float L = 0.f, O = 0.f;
         for (int s = 0; s < ns; ++s) {
-            const float c = expf(a.part_ml[(base + s) * 2] - M);
+            const float c = __expf(a.part_ml[(base + s) * 2] - M);
             L += a.part_ml[(base + s) * 2 + 1] * c;
             O += a.part_o[(base + s) * d + j] * c;
         }
@@ -330,27 +364,187 @@ __global__ void k_attn_combine(AttnArgs a, int n_split) {
     }
 }
 
+// Short contexts: one workgroup of 16 wavefronts per (kv head, block row) walks the whole cache
+// range, so nothing goes through global memory and one launch suffices.  Step s of wavefront w
+// covers slots (16 s + w) * SPW ..; the loads of NB steps are issued together.
+template <typename T, int GROUP>
+__global__ __launch_bounds__(1024) void k_attn_head(AttnArgs a) {
+    constexpr int VEC = T::VEC;
+    constexpr int NB = GROUP <= 2 ? 4 : 1;
+    extern __shared__ __align__(16) float sh[];  // [16*GROUP] max, [16*GROUP] sum, [16*GROUP*d] weighted values
+    const int d = a.head_dim;
+    const int LPP = d / VEC, SPW = 64 / LPP;
+    const int g = blockIdx.x, row = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane & (LPP - 1), lg = lane / LPP;
+    const int n_ctx = a.n_ctx + row;
+    const float scale = 1.0f / sqrtf((float)d);
+    const int nq = a.n_q_heads;
+    float *sm = sh, *sl = sh + 16 * GROUP, *so = sh + 32 * GROUP;
+
+    float q[GROUP][VEC];
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
+    float m[GROUP], l[GROUP], o[GROUP][VEC];
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        m[h] = -INFINITY;
+        l[h] = 0.f;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) o[h][j] = 0.f;
+    }
+    const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
+    const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
+    const int steps = (n_ctx + 16 * SPW - 1) / (16 * SPW);
+
+    for (int s0 = 0; s0 < steps; s0 += NB) {
+        u32x4 kv[NB], vv[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int p = ((s0 + b) * 16 + wave) * SPW + lg;
+            const int pc = min(p, n_ctx - 1);
+            kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
+            vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int p = ((s0 + b) * 16 + wave) * SPW + lg;
+            const bool live = p < n_ctx;
+            float kf[VEC], vf[VEC];
+            T::unpack(kv[b], kf);
+            T::unpack(vv[b], vf);
+#pragma unroll
+            for (int h = 0; h < GROUP; ++h) {
+                float sc = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) sc = fmaf(q[h][j], kf[j], sc);
+                for (int off = LPP >> 1; off > 0; off >>= 1) sc += __shfl_xor(sc, off, 64);
+                sc *= scale;
+                if (live) {
+                    const float mn = fmaxf(m[h], sc);
+                    const float corr = __expf(m[h] - mn);
+                    const float pr = __expf(sc - mn);
+                    l[h] = l[h] * corr + pr;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) o[h][j] = o[h][j] * corr + pr * vf[j];
+                    m[h] = mn;
+                }
+            }
+        }
+    }
+    // merge the lane groups of a wavefront
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        for (int off = LPP; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(m[h], off, 64);
+            const float l2 = __shfl_xor(l[h], off, 64);
+            const float mn = fmaxf(m[h], m2);
+            const float c1 = (m[h] == -INFINITY) ? 0.f : __expf(m[h] - mn);
+            const float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
+            l[h] = l[h] * c1 + l2 * c2;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float o2 = __shfl_xor(o[h][j], off, 64);
+                o[h][j] = o[h][j] * c1 + o2 * c2;
+            }
+            m[h] = mn;
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int h = 0; h < GROUP; ++h) {
+            if (lj == 0) {
+                sm[wave * GROUP + h] = m[h];
+                sl[wave * GROUP + h] = l[h];
+            }
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) so[((size_t)wave * GROUP + h) * d + lj * VEC + j] = o[h][j];
+        }
+    }
+    __syncthreads();
+    // merge the 16 wavefronts, normalise, write
+    for (int idx = tid; idx < GROUP * d; idx += 1024) {
+        const int h = idx / d, j = idx - h * d;
+        float mn = -INFINITY;
+        for (int w = 0; w < 16; ++w) mn = fmaxf(mn, sm[w * GROUP + h]);
+        float ls = 0.f, os = 0.f;
+        for (int w = 0; w < 16; ++w) {
+            const float mw = sm[w * GROUP + h];
+            const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mn);
+            ls += sl[w * GROUP + h] * c;
+            os += so[((size_t)w * GROUP + h) * d + j] * c;
+        }
+        const float y = os / ls;
+        const int e = (g * GROUP + h) * d + j;
+        if (a.out) a.out[(size_t)row * nq * d + e] = y;
+        if (a.out_s) {
+            uint16_t hi, mid, lo;
+            split3(y, hi, mid, lo);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * a.rows) + 3 * row) * 8 + (e & 7);
+            p[0] = hi;
+            p[8] = mid;
+            p[16] = lo;
+        }
+    }
+}
+
+template <typename T, int GROUP>
+static hipError_t launch_attn_head_t(const AttnArgs &a, hipStream_t s) {
+    const size_t lds = (size_t)(32 * GROUP + 16 * GROUP * a.head_dim) * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_head<T, GROUP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_attn_head<T, GROUP>), dim3(a.n_kv_heads, a.rows), dim3(1024), lds, s, a);
+    return hipGetLastError();
+}
+
 template <typename T>
-static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
+static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
-    const int n_split = (a.n_ctx + a.rows - 1 + kAttnChunk - 1) / kAttnChunk;
+    const int ctx = a.n_ctx + a.rows - 1;          // longest row of the block
+    if (ctx <= 1536) {
+        switch (group) {
+            case 1: return launch_attn_head_t<T, 1>(a, s);
+            case 2: return launch_attn_head_t<T, 2>(a, s);
+            case 4: return launch_attn_head_t<T, 4>(a, s);
+            case 8: return launch_attn_head_t<T, 8>(a, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
+    const int d = a.head_dim, VEC = T::VEC, SPW = 64 / (d / VEC);
+    const int gran = 4 * SPW;                      // slots one workgroup step covers
+    // enough splits for about two workgroups per compute unit, at least one step per workgroup
+    int n_split = (2 * n_cu + a.n_kv_heads * a.rows - 1) / (a.n_kv_heads * a.rows);
+    const int max_split = (ctx + gran - 1) / gran;
+    if (n_split > max_split) n_split = max_split;
+    if (n_split > a.max_split) n_split = a.max_split;
+    if (n_split < 1) n_split = 1;
+    int chunk = (ctx + n_split - 1) / n_split;
+    chunk = (chunk + gran - 1) / gran * gran;
+    n_split = (ctx + chunk - 1) / chunk;
     dim3 grid(a.n_kv_heads, n_split, a.rows), block(256);
     switch (group) {
-        case 1: hipLaunchKernelGGL((k_attn_decode<T, 1>), grid, block, 0, s, a); break;
-        case 2: hipLaunchKernelGGL((k_attn_decode<T, 2>), grid, block, 0, s, a); break;
-        case 4: hipLaunchKernelGGL((k_attn_decode<T, 4>), grid, block, 0, s, a); break;
-        case 8: hipLaunchKernelGGL((k_attn_decode<T, 8>), grid, block, 0, s, a); break;
+        case 1: hipLaunchKernelGGL((k_attn_split<T, 1>), grid, block, 0, s, a, chunk); break;
+        case 2: hipLaunchKernelGGL((k_attn_split<T, 2>), grid, block, 0, s, a, chunk); break;
+        case 4: hipLaunchKernelGGL((k_attn_split<T, 4>), grid, block, 0, s, a, chunk); break;
+        case 8: hipLaunchKernelGGL((k_attn_split<T, 8>), grid, block, 0, s, a, chunk); break;
         default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads, a.rows), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a,
+    if (e != hipSuccess || n_split == 1) return e;
+    hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads, a.rows), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a, chunk,
                        n_split);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_decode(int dtype, const AttnArgs &a, hipStream_t s) {
-    return dtype == F32 ? launch_attn_t<F32T>(a, s) : launch_attn_t<BF16T>(a, s);
+hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s) {
+    return dtype == F32 ? launch_attn_t<F32T>(a, n_cu, s) : launch_attn_t<BF16T>(a, n_cu, s);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -132,8 +132,9 @@ __device__ inline void mv_norm_scale(const MvArgs &a, float *rs /* LDS [16] */, 
 
 // What follows the dot products of one 16-row group, run by one whole wavefront.
 // Y(r, j): finished dot product of block row r and tile row j (before the norm scale).
+// rot: optional LDS copy of the rotary rows, [R][d/2 cos | d/2 sin]; nullptr = read the tables.
 template <int EPI, typename YF>
-__device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, YF Y) {
+__device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, const float *rot, YF Y) {
     const int R = a.R, NC = 3 * R;
     if (EPI == EPI_RESID || EPI == EPI_LOGITS) {
         const int iters = (16 * R + 63) >> 6;
@@ -185,7 +186,8 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                 const int hh = rg / gph, i = 8 * (rg - hh * gph) + j;
                 const int nq = a.n_q_heads, nkv = a.n_kv_heads, pos = a.pos0 + r;
                 if (hh < nq + nkv) {
-                    const float c = a.cos_tab[(size_t)pos * half + i], s = a.sin_tab[(size_t)pos * half + i];
+                    const float c = rot ? rot[r * d + i] : a.cos_tab[(size_t)pos * half + i];
+                    const float s = rot ? rot[r * d + half + i] : a.sin_tab[(size_t)pos * half + i];
                     const float qa = ya * c - yb * s, qb = yb * c + ya * s;
                     if (hh < nq) {
                         float *qp = a.out_f32 + (size_t)r * a.ld_out + hh * d + i;
@@ -222,6 +224,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     float *red = (float *)(smem + 16 + (size_t)a.T * 192);
     float *rs = red + 256;
     float *nscratch = rs + 16;  // [512]
+    float *rot = nscratch + 512;  // [d/2 cos | d/2 sin] of this row's position (q|k|v epilogue)
     constexpr int G = 8 / KS;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform from here on
@@ -272,6 +275,13 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         }
         prime(0);
         if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+        if (EPI == EPI_QKV) {
+            const int half = a.head_dim >> 1;
+            if (tid < half) {
+                rot[tid] = a.cos_tab[(size_t)a.pos0 * half + tid];
+                rot[half + tid] = a.sin_tab[(size_t)a.pos0 * half + tid];
+            }
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int i = tid + 512 * q;
@@ -320,7 +330,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         }
         __syncthreads();
         if (!live || ks != 0) continue;
-        mv_epilogue<EPI>(a, rg, lane, rs, [&](int, int j) {
+        mv_epilogue<EPI>(a, rg, lane, rs, EPI == EPI_QKV ? rot : nullptr, [&](int, int j) {
             float y = 0.f;
 #pragma unroll
             for (int k2 = 0; k2 < KS; ++k2) y += rp[(g * KS + k2) * 16 + j];
@@ -533,7 +543,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     auto y_local = [&](int r, int j) { return (dw[(3 * r) * 16 + j] + dw[(3 * r + 1) * 16 + j]) + dw[(3 * r + 2) * 16 + j]; };
 
     if (gridDim.y == 1) {
-        if (live) mv_epilogue<EPI>(a, rg, lane, rs, y_local);
+        if (live) mv_epilogue<EPI>(a, rg, lane, rs, nullptr, y_local);
         return;
     }
     // ---- split-K: publish the partial, last workgroup of this row block reduces
@@ -557,7 +567,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
         const float *p0 = a.part + (size_t)rg * (16 * R);
         const size_t sstride = (size_t)a.n_rg * (16 * R);
         // (plain loads: the fence above makes the other workgroups' released partials visible)
-        mv_epilogue<EPI>(a, rg, lane, rs, [&](int r, int j) {
+        mv_epilogue<EPI>(a, rg, lane, rs, nullptr, [&](int r, int j) {
             float v[8];
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) v[s2] = s2 < KSP ? p0[s2 * sstride + r * 16 + j] : 0.f;

@@ -191,3 +191,20 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     assert np.array_equal(got, want)
     _compare_traces(shape, to, tg)
     g.close()
+
+
+def test_long_context_uses_split_attention(oracle_lib):
+    """A context beyond the single-workgroup attention range (1536 slots): the split kernel and
+    its merge, for one row and for a block, with a ragged last chunk."""
+    import paper_2410_06916_amd as P
+    shape = dataclasses.replace(hp.SMALL_GQA_BF16, name="small-gqa-bf16-long", n_layers=2)
+    weights = hp.shaped_weights(shape, seed=33)
+    n_prompt = 1601
+    o, g = _pair(oracle_lib, shape, weights, n_prompt + 40, threads=8)
+    prompt = si.uniform_ids(9, n_prompt, shape.vocab)
+    mask = np.array([0, 1, 0, 0], np.uint8)
+    want, to = oracle_lib.generate_swift(o, prompt, 12, mask, 5, 0.0, want_logits=True)
+    got, tg = P.generate_swift(g, prompt, 12, mask, 5, 0.0, want_logits=True)
+    assert np.array_equal(got, want)
+    _compare_traces(shape, to, tg)
+    g.close()
