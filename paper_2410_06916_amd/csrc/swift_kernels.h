@@ -130,8 +130,13 @@ struct MvArgs {
     int S;                 // set by the launcher
 };
 constexpr size_t kMvMaxLds = 150 * 1024;
-// LDS bytes of the single-row kernel for depth K
-inline size_t mv1_lds_bytes(int K) { return (size_t)((K + 31) / 32) * 192 + 16 + 1024 + 64 + 2048 + 1024; }
+// Rows the LDS-resident kernel takes (3R term columns must fit one MFMA column block)
+constexpr int kMvSmallRows = 5;
+// LDS bytes of the LDS-resident kernel for depth K and R rows
+inline size_t mv1_lds_bytes(int K, int R, int head_dim) {
+    const size_t NC = 3 * (size_t)R;
+    return 16 + (size_t)((K + 31) / 32) * 64 * NC + 2 * 8 * 16 * NC * 4 + 64 + 2048 + (size_t)R * head_dim * 4 + 64;
+}
 // ks_override / wg_override: 0 = choose automatically (single-row kernel only).
 hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
 

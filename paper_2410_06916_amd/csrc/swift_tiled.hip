@@ -209,22 +209,23 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
 }
 
 // ------------------------------------------------------------------------------------------
-// one activation row: y = W . x, MFMA, whole activation in LDS, K split over wavefronts
+// 1..5 activation rows: Y = W . X, MFMA, whole activation in LDS, K split over wavefronts
 // ------------------------------------------------------------------------------------------
-// The three terms of x go into columns 0..2 of the MFMA B operand (the other 13 columns read a
-// zero chunk); y is the sum of the three result columns.  A workgroup has 8 wavefronts; KS of
-// them share one row group, each taking a contiguous slice of its k-tiles, so a workgroup works
-// on G = 8/KS row groups at a time and the slices are added in LDS in a fixed order.  Every
-// wavefront keeps a rolling window of sixteen 1 KB tile loads in flight; the first window is
-// issued before the activation is staged.
+// The NC = 3R term columns of X (R <= 5, so NC <= 15) fit one MFMA column block; lanes of columns
+// >= NC read a zero chunk.  A workgroup has 8 wavefronts; KS of them share one 16-row group of W,
+// each taking a contiguous slice of its k-tiles, so a workgroup works on G = 8/KS row groups at a
+// time and the slices (and the three terms) are added in LDS in a fixed order.  Every wavefront
+// keeps a rolling window of sixteen 1 KB tile loads in flight; the first window is issued before
+// the activation is staged.
 template <int EPI, int KS>
 __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per SIMD: <= 128 VGPRs, two workgroups per CU
     extern __shared__ __align__(16) unsigned char smem[];
-    // LDS: [16 B zeros][4T chunks x 3 terms x 8 bf16][2 x 8 wavefronts x 16 rows fp32][16 scales]
-    float *red = (float *)(smem + 16 + (size_t)a.T * 192);
-    float *rs = red + 256;
-    float *nscratch = rs + 16;  // [512]
-    float *rot = nscratch + 512;  // [d/2 cos | d/2 sin] of this row's position (q|k|v epilogue)
+    const int R = a.R, NC = 3 * R;
+    // LDS: [16 B zeros][4T chunks x NC x 8 bf16][2 x 8 wavefronts x NC x 16 fp32][16 scales][512 scratch][R x d rotary]
+    float *red = (float *)(smem + 16 + (size_t)a.T * 64 * NC);
+    float *rs = red + 2 * 8 * 16 * NC;
+    float *nscratch = rs + 16;
+    float *rot = nscratch + 512;  // per block row: [d/2 cos | d/2 sin] at that row's position
     constexpr int G = 8 / KS;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform from here on
@@ -238,10 +239,10 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     const int W = gridDim.x;
     const int last_rg = a.n_rg - 1;
     const int col = lane & 15, kg = lane >> 4;
-    // byte address of this lane's B chunk for tile t: boff + t * bstride; lanes of columns >= 3
+    // byte address of this lane's B chunk for tile t: boff + t * bstride; lanes of columns >= NC
     // (and slots past the wavefront's slice) read the zero chunk at address 0
-    const int boff = col < 3 ? 16 + (kg * 3 + col) * 16 : 0;
-    const int bstride = col < 3 ? 192 : 0;
+    const int boff = col < NC ? 16 + (kg * NC + col) * 16 : 0;
+    const int bstride = col < NC ? 64 * NC : 0;
 
     u32x4 buf[16];
     const u32x4 *base = nullptr;
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     {
         const u32x4 *src = (const u32x4 *)a.in_s;
         u32x4 *dst = (u32x4 *)(smem + 16);
-        const int n_units = T * 12, real_units = (a.K >> 3) * 3;
+        const int n_units = T * 4 * NC, real_units = (a.K >> 3) * NC;
         const u32x4 zero = {0u, 0u, 0u, 0u};
         u32x4 tmp[4];
 #pragma unroll
@@ -276,10 +277,11 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         prime(0);
         if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
         if (EPI == EPI_QKV) {
-            const int half = a.head_dim >> 1;
-            if (tid < half) {
-                rot[tid] = a.cos_tab[(size_t)a.pos0 * half + tid];
-                rot[half + tid] = a.sin_tab[(size_t)a.pos0 * half + tid];
+            const int d = a.head_dim, half = d >> 1;
+            for (int i = tid; i < R * half; i += 512) {
+                const int r = i / half, e = i - r * half;
+                rot[r * d + e] = a.cos_tab[(size_t)(a.pos0 + r) * half + e];
+                rot[r * d + half + e] = a.sin_tab[(size_t)(a.pos0 + r) * half + e];
             }
         }
 #pragma unroll
@@ -320,20 +322,22 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
 #pragma unroll
         for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
 
-        // ---- end of the row group: add the three term columns, then the KS slices, then the epilogue
-        float *rp = red + (size_t)(seg & 1) * 128;
+        // ---- end of the row group: every wavefront parks its NC result columns in LDS; one
+        // wavefront per row group adds terms and K slices and runs the epilogue
+        float *rp = red + (size_t)(seg & 1) * (8 * 16 * NC);
+        if (col < NC) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float c1 = __shfl_down(acc[r], 1, 64), c2 = __shfl_down(acc[r], 2, 64);
-            const float y = (acc[r] + c1) + c2;
-            if (col == 0) rp[wave * 16 + 4 * kg + r] = y;
+            for (int r4 = 0; r4 < 4; ++r4) rp[(wave * NC + col) * 16 + 4 * kg + r4] = acc[r4];
         }
         __syncthreads();
         if (!live || ks != 0) continue;
-        mv_epilogue<EPI>(a, rg, lane, rs, EPI == EPI_QKV ? rot : nullptr, [&](int, int j) {
+        mv_epilogue<EPI>(a, rg, lane, rs, EPI == EPI_QKV ? rot : nullptr, [&](int r, int j) {
             float y = 0.f;
-#pragma unroll
-            for (int k2 = 0; k2 < KS; ++k2) y += rp[(g * KS + k2) * 16 + j];
+#pragma unroll 1
+            for (int k2 = 0; k2 < KS; ++k2) {
+                const float *w = rp + ((g * KS + k2) * NC + 3 * r) * 16 + j;
+                y += (w[0] + w[16]) + w[32];
+            }
             return y;
         });
     }
@@ -353,7 +357,7 @@ static hipError_t launch_mv1_t(const MvArgs &a, int grid, size_t lds, hipStream_
 }
 
 static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
-    const size_t lds = mv1_lds_bytes(a.K);
+    const size_t lds = mv1_lds_bytes(a.K, a.R, a.head_dim);
     if (lds > kMvMaxLds) return hipErrorInvalidValue;
     // Work split: KS wavefronts per row group, W workgroups, S rounds, chosen so that every
     // workgroup gets the same number of row groups (a weight stream is only as fast as its
@@ -608,7 +612,9 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
     if (a.R < 1 || a.R > kMaxRows) return hipErrorInvalidValue;
-    if (a.R == 1 && ks_override != 16) return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
+    // small blocks whose whole activation fits in LDS take the single-pass kernel
+    if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
+        return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
     const int ncb = (3 * a.R + 15) / 16;
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
