@@ -234,8 +234,10 @@ T *dptr(swift_ctx *x, uint64_t off) {
 
 int n_tensors(const swift_model_config &c) { return 3 + 9 * c.n_layers; }
 
+// kernel_events: the launch goes through launch_mv, which can attach the events to the dispatch
+// itself; otherwise the launch is bracketed by two event records on the stream.
 template <typename F>
-hipError_t timed(swift_ctx *x, int kc, uint64_t bytes, F &&f) {
+hipError_t timed(swift_ctx *x, int kc, uint64_t bytes, F &&f, bool kernel_events = false) {
     if (x->prof_class != kc) return f();
     hipEvent_t ev[2];
     for (auto &e : ev) {
@@ -247,11 +249,18 @@ hipError_t timed(swift_ctx *x, int kc, uint64_t bytes, F &&f) {
             if (r != hipSuccess) return r;
         }
     }
-    hipError_t r = hipEventRecord(ev[0], x->stream);
-    if (r != hipSuccess) return r;
-    r = f();
-    if (r != hipSuccess) return r;
-    r = hipEventRecord(ev[1], x->stream);
+    hipError_t r;
+    if (kernel_events) {
+        set_launch_events(ev[0], ev[1]);
+        r = f();
+        set_launch_events(nullptr, nullptr);
+    } else {
+        r = hipEventRecord(ev[0], x->stream);
+        if (r != hipSuccess) return r;
+        r = f();
+        if (r != hipSuccess) return r;
+        r = hipEventRecord(ev[1], x->stream);
+    }
     x->prof.push_back({ev[0], ev[1], bytes});
     return r;
 }
@@ -392,7 +401,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     };
     auto run = [&](int kc, int epi, const MvArgs &m) -> int {
         HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
-                      [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }));
+                      [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }, true));
         return SWIFT_OK;
     };
     int rc;

@@ -137,7 +137,10 @@ inline size_t mv1_lds_bytes(int K, int R, int head_dim) {
     const size_t NC = 3 * (size_t)R;
     return 16 + (size_t)((K + 31) / 32) * 64 * NC + 2 * 8 * 16 * NC * 4 + 64 + 2048 + (size_t)R * head_dim * 4 + 64;
 }
-// ks_override / wg_override: 0 = choose automatically (single-row kernel only).
+// Kernel-precise timing: the next launch_mv on this thread records `start` when its kernel begins
+// and `stop` when it ends (timestamps of the dispatch itself, no extra packets on the stream).
+void set_launch_events(hipEvent_t start, hipEvent_t stop);
+// ks_override / wg_override: 0 = choose automatically (LDS-resident kernel only).
 hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
 
 // x[r] = E[token r] (fp32), split of x * gain_next, partial sums of squares per 16 elements.

@@ -3,10 +3,30 @@
 // plain decoding), k_mvN a block of 2..16 rows (verify, prefill).
 #include <math.h>
 
+#include <hip/hip_ext.h>
+
 #include "swift_device.h"
 #include "swift_kernels.h"
 
 namespace swift {
+
+// Events for the next projection launch (see set_launch_events in swift_kernels.h).
+static thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+void set_launch_events(hipEvent_t start, hipEvent_t stop) {
+    g_ev_start = start;
+    g_ev_stop = stop;
+}
+template <typename K, typename... Args>
+static hipError_t launch_maybe_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args) {
+    if (g_ev_start) {
+        hipEvent_t a = g_ev_start, b = g_ev_stop;
+        g_ev_start = g_ev_stop = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, a, b, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+    }
+    return hipGetLastError();
+}
 
 // ------------------------------------------------------------------------------------------
 // weight layout conversion
@@ -102,21 +122,39 @@ hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s) {
 // shared pieces of the projection kernels
 // ------------------------------------------------------------------------------------------
 // RMSNorm scale per block row from the producer's partial sums of squares [n_pss][16].  All 512
-// threads load (thread = (partial p mod 32, row r), independent loads issued together), then 16
-// threads add the 32 per-lane sums in order: the summation order is fixed.  Ends with a barrier.
-__device__ inline void mv_norm_scale(const MvArgs &a, float *rs /* LDS [16] */, float *scratch /* LDS [512] */) {
+// threads load (thread = (partial p mod 32, row r)); mv_norm_load issues the first eight loads per
+// thread (enough for 256 partials, hidden <= 4096) so that the caller can put them ahead of the
+// weight loads; mv_norm_finish adds the rest, then 16 threads add the 32 per-lane sums in order:
+// the summation order is fixed.  Ends with a barrier.
+struct NormPart {
+    float v[8];
+};
+__device__ inline NormPart mv_norm_load(const MvArgs &a) {
+    NormPart np;
+    const int tid = threadIdx.x, r = tid & 15, q = tid >> 4;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int p = q + 32 * u;
+        np.v[u] = (a.pss && p < a.n_pss) ? a.pss[(size_t)p * 16 + r] : 0.f;
+    }
+    return np;
+}
+__device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float *rs /* LDS [16] */,
+                                      float *scratch /* LDS [512] */) {
     const int tid = threadIdx.x, r = tid & 15, q = tid >> 4;
     if (a.pss) {
         float ss = 0.f;
-        for (int p0 = 0; p0 < a.n_pss; p0 += 512) {
-            float v[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+        for (int u = 0; u < 8; ++u) ss += np.v[u];
+        for (int p0 = 256; p0 < a.n_pss; p0 += 256) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
                 const int p = p0 + q + 32 * u;
                 v[u] = p < a.n_pss ? a.pss[(size_t)p * 16 + r] : 0.f;
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) ss += v[u];
+            for (int u = 0; u < 8; ++u) ss += v[u];
         }
         scratch[q * 16 + r] = ss;
     }
@@ -262,46 +300,66 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     };
 
     // ---- stage the split activation (a plain copy: the producer kernel already wrote it in B
-    // layout); its first loads go out ahead of the weight loads so that they return first
+    // layout).  Its loads, and those of the norm partials, go out ahead of the weight loads so
+    // that they return first; the first weight window is in flight while LDS is filled.
     {
         const u32x4 *src = (const u32x4 *)a.in_s;
         u32x4 *dst = (u32x4 *)(smem + 16);
         const int n_units = T * 4 * NC, real_units = (a.K >> 3) * NC;
         const u32x4 zero = {0u, 0u, 0u, 0u};
-        u32x4 tmp[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int i = tid + 512 * q;
-            tmp[q] = i < real_units ? src[i] : zero;
-        }
-        prime(0);
-        if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
-        if (EPI == EPI_QKV) {
-            const int d = a.head_dim, half = d >> 1;
-            for (int i = tid; i < R * half; i += 512) {
-                const int r = i / half, e = i - r * half;
-                rot[r * d + e] = a.cos_tab[(size_t)(a.pos0 + r) * half + e];
-                rot[r * d + half + e] = a.sin_tab[(size_t)(a.pos0 + r) * half + e];
+        auto side_loads = [&]() {
+            if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+            if (EPI == EPI_QKV) {
+                const int d = a.head_dim, half = d >> 1;
+                for (int i = tid; i < R * half; i += 512) {
+                    const int r = i / half, e = i - r * half;
+                    rot[r * d + e] = a.cos_tab[(size_t)(a.pos0 + r) * half + e];
+                    rot[r * d + half + e] = a.sin_tab[(size_t)(a.pos0 + r) * half + e];
+                }
             }
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int i = tid + 512 * q;
-            if (i < n_units) dst[i] = tmp[q];
-        }
-        for (int i0 = 2048; i0 < n_units; i0 += 2048) {
+        };
+        if (n_units <= 4 * 512) {  // depth <= 5461 for one row: four loads per thread cover it
+            u32x4 tmp[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int i = i0 + tid + 512 * q;
+                const int i = tid + 512 * q;
                 tmp[q] = i < real_units ? src[i] : zero;
             }
+            prime(0);
+            side_loads();
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int i = i0 + tid + 512 * q;
+                const int i = tid + 512 * q;
                 if (i < n_units) dst[i] = tmp[q];
             }
+        } else {
+            u32x4 tmp[9];
+#pragma unroll
+            for (int q = 0; q < 9; ++q) {
+                const int i = tid + 512 * q;
+                tmp[q] = i < real_units ? src[i] : zero;
+            }
+            prime(0);
+            side_loads();
+#pragma unroll
+            for (int q = 0; q < 9; ++q) {
+                const int i = tid + 512 * q;
+                if (i < n_units) dst[i] = tmp[q];
+            }
+            for (int i0 = 9 * 512; i0 < n_units; i0 += 4 * 512) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = i0 + tid + 512 * q;
+                    tmp[q] = i < real_units ? src[i] : zero;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int i = i0 + tid + 512 * q;
+                    if (i < n_units) dst[i] = tmp[q];
+                }
+            }
         }
-        mv_norm_scale(a, rs, nscratch);
+        mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
     }
 
     for (int seg = 0; seg < a.S; ++seg) {
@@ -352,8 +410,7 @@ static hipError_t launch_mv1_t(const MvArgs &a, int grid, size_t lds, hipStream_
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_mv1<EPI, KS>), dim3(grid), dim3(512), lds, s, a);
-    return hipGetLastError();
+    return launch_maybe_timed(k_mv1<EPI, KS>, dim3(grid), dim3(512), lds, s, a);
 }
 
 static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
@@ -511,7 +568,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     loadA(0, A0);
     if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
     storeB(0, tmp);
-    mv_norm_scale(a, rs, nscratch);
+    mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
 
     auto step_full = [&](int c, const u32x4(&Ac)[16], int bc, u32x4(&An)[16], int bn) {
         loadB(c + 1, tmp);
@@ -606,8 +663,7 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
     int TS = (a.T + ksp - 1) / ksp;
     ksp = (a.T + TS - 1) / TS;
-    hipLaunchKernelGGL((k_mvN<EPI, NCB>), dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
-    return hipGetLastError();
+    return launch_maybe_timed(k_mvN<EPI, NCB>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
