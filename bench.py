@@ -30,7 +30,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def run_generation(P, g, prompt, n_new, mask, max_k, eps):
+def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None):
     """One step.  Returns (tokens, prefill_s, decode_s, trace)."""
     import torch
     torch.cuda.synchronize()
@@ -38,6 +38,9 @@ def run_generation(P, g, prompt, n_new, mask, max_k, eps):
     out = [g.prefill(prompt)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    if after_prefill:
+        after_prefill()
+        t1 = time.perf_counter()
     trace = []
     while len(out) < n_new:
         k_cap = min(max_k, n_new - len(out) - 1)
@@ -94,6 +97,9 @@ def main():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-modes", action="store_true")
+    ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's number of new tokens")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -106,6 +112,9 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     dev = "cuda:0"
     w = si.WORKLOADS[args.workload]
+    if args.new_tokens > 0:
+        import dataclasses
+        w = dataclasses.replace(w, n_new=args.new_tokens)
     shape = w.shape
     mask = si.workload_mask(w)
     prompt = si.workload_prompt(w)
@@ -143,15 +152,22 @@ def main():
 
     # ---- roofline of the dominant kernel (gate/up projection + SwiGLU): same step, its launches
     # bracketed by HIP events on the library's stream
-    g.profile_class("gateup")
-    run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold)
+    # (decode phase only: draft passes run it with one row, verify passes with two)
+    run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold,
+                   after_prefill=lambda: g.profile_class("gateup"))
     n_l, ms, nbytes = g.profile_read()
     g.profile_class(None)
     per_launch_bytes = nbytes / max(n_l, 1)
     avg_us = ms * 1e3 / max(n_l, 1)
     achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if n_l else 0.0
-    roofline = {"bound": "hbm", "kernel": "k_gemv<bf16, gate/up + SwiGLU>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gateup_7b_hbm_traffic.json")
+    if args.workload == "7b" and os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "k_mv1<SwiGLU> (RMSNorm scale + gate/up projection + SwiGLU, 1-2 rows)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "launches": n_l, "avg_us": round(avg_us, 2), "bytes_per_launch": int(per_launch_bytes)}
     log(f"[bench] gate/up kernel: {n_l} launches, avg {avg_us:.2f} us, {achieved:.0f} GB/s")
 
@@ -190,6 +206,14 @@ def main():
                                              "M": round(s3["emitted_by_verify"] / max(s3["verify_passes"], 1), 3),
                                              "alpha": round(s3["accepted"] / max(s3["draft_passes"], 1), 4)}
         log(f"[bench] modes: {modes}")
+
+    if args.pmc_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)      # plain device-to-device copy: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
 
     draft_bytes = P.pass_bytes(g.cfg, mask, w.n_prompt, 1)
     full_bytes = P.pass_bytes(g.cfg, None, w.n_prompt, 1)
