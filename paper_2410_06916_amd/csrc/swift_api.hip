@@ -99,8 +99,9 @@ Layout make_layout(const swift_model_config &c) {
         return o;
     };
     const bool bf = c.dtype == SWIFT_BF16;
-    L.tiled = bf && mv1_lds_bytes((int)H, 1, c.head_dim) <= kMvMaxLds && mv1_lds_bytes((int)Q, 1, c.head_dim) <= kMvMaxLds &&
-              mv1_lds_bytes((int)F, 1, c.head_dim) <= kMvMaxLds;
+    // bf16 models run on the tiled MFMA kernels (a depth too large for the LDS-resident kernel goes
+    // through the K-chunked block kernel, whatever the row count)
+    L.tiled = bf;
     L.tiled_h = L.tiled_q = L.tiled_f = L.tiled;
     L.embed = take(V * H * eb);
     L.lm_head = take(L.tiled_h ? tiled_bytes(ceil_div(V, 16), H) : V * H * eb);

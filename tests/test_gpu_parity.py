@@ -208,3 +208,59 @@ def test_long_context_uses_split_attention(oracle_lib):
     assert np.array_equal(got, want)
     _compare_traces(shape, to, tg)
     g.close()
+
+
+def _gpu_weights(shape, seed=0):
+    """Weights drawn on the GPU (fast at full size); the same tensors feed both sides."""
+    return si.iter_weights(shape, seed, "cuda:0")
+
+
+def test_7b_full_depth_against_oracle(oracle_lib):
+    """The full 32-layer 7B shape, in the launch configuration bench.py times, on an input the
+    oracle can still afford: short prompt, a few forced-length decoding steps with the workload's
+    own skip mask (one-row drafts, a 4-row verify block, 16-row and ragged prefill blocks)."""
+    import paper_2410_06916_amd as P
+    w = si.WORKLOADS["7b"]
+    shape = w.shape
+    g = P.SwiftModel(shape, 96)
+    o = oracle_lib.Oracle(shape, 96, threads=16)
+    for name, t in _gpu_weights(shape, w.weight_seed):
+        g.load_tensor(name, t)
+        o.set_tensor(name, t.cpu())
+    prompt = si.uniform_ids(w.prompt_seed, 21, shape.vocab)
+    mask = si.workload_mask(w)
+    want, to = oracle_lib.generate_swift(o, prompt, 5, mask, 3, 0.0, want_logits=True)
+    got, tg = P.generate_swift(g, prompt, 5, mask, 3, 0.0, want_logits=True)
+    assert np.array_equal(got, want)
+    _compare_traces(shape, to, tg)
+    g.close()
+
+
+@pytest.mark.parametrize("name,n_prompt,n_new", [("7b", 512, 256), ("13b", 1024, 48), ("7b-long", 8192, 24),
+                                                  ("70b", 160, 12)])
+def test_full_size_workloads_are_lossless_on_gpu(name, n_prompt, n_new):
+    """At the workloads' full shapes (where the oracle is out of reach) the property that holds at
+    any size: plain greedy decoding, as-configured speculation and forced-length speculation emit
+    the same tokens (Sections 1, 3.1: verification leaves the output unchanged), and the counters
+    add up."""
+    import paper_2410_06916_amd as P
+    w = si.WORKLOADS[name]
+    shape = w.shape
+    g = P.SwiftModel(shape, n_prompt + n_new + w.max_k + 8)
+    for nm, t in _gpu_weights(shape, w.weight_seed):
+        g.load_tensor(nm, t)
+    prompt = si.uniform_ids(w.prompt_seed, n_prompt, shape.vocab)
+    mask = si.workload_mask(w)
+    ar = P.generate_ar(g, prompt, n_new)
+    assert ar.min() >= 0 and ar.max() < shape.vocab
+    for eps, max_k in ((w.conf_threshold, w.max_k), (0.0, w.max_k), (0.0, 15)):
+        out, trace = P.generate_swift(g, prompt, n_new, mask, max_k, eps)
+        assert np.array_equal(out, ar), (name, eps, max_k)
+        st = g.stats()
+        assert st["emitted_total"] == n_new and st["verify_passes"] == len(trace)
+        assert st["accepted"] == sum(t["m"] for t in trace)
+        assert 1 + sum(t["m"] + 1 for t in trace) == n_new
+    # no-skip mask: the draft model is the target model, every draft is accepted
+    out, trace = P.generate_swift(g, prompt, n_new, np.zeros_like(mask), w.max_k, 0.0)
+    assert np.array_equal(out, ar) and all(t["m"] == len(t["draft"]) for t in trace)
+    g.close()
