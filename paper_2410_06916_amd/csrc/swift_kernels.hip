@@ -508,7 +508,8 @@ template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
     const int ctx = a.n_ctx + a.rows - 1;          // longest row of the block
-    if (ctx <= 1536) {
+    // the one-workgroup-per-head kernel needs enough (kv head, row) pairs to occupy the chip
+    if (ctx <= 1536 && a.n_kv_heads * a.rows >= 24) {
         switch (group) {
             case 1: return launch_attn_head_t<T, 1>(a, s);
             case 2: return launch_attn_head_t<T, 2>(a, s);
