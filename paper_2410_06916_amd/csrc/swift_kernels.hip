@@ -178,6 +178,72 @@ hipError_t launch_embed(int dtype, const EmbedArgs &a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
+// attention: shared inner step
+// ------------------------------------------------------------------------------------------
+// Sum over the lanes that share one cache slot.  Sixteen lanes are one DPP row: butterfly inside
+// quads, then half-row and row mirrors (every lane ends with the total), four single instructions.
+__device__ inline float slot_sum(float v, int lpp) {
+    if (lpp == 16) {
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
+        return v;
+    }
+    for (int off = lpp >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// One batch of NB cache slots per lane group against GROUP query heads: scores, one running-max
+// update for the whole batch, probabilities, weighted values (online softmax).
+template <typename T, int GROUP, int NB>
+__device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], const bool (&live)[NB],
+                                  const float (&q)[GROUP][T::VEC], float scale, int lpp, float (&m)[GROUP],
+                                  float (&l)[GROUP], float (&o)[GROUP][T::VEC]) {
+    constexpr int VEC = T::VEC;
+    float vf[NB][VEC];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) T::unpack(vv[b], vf[b]);
+    float sc[GROUP][NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float kf[VEC];
+        T::unpack(kv[b], kf);
+#pragma unroll
+        for (int h = 0; h < GROUP; ++h) {
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) s = fmaf(q[h][j], kf[j], s);
+            s = slot_sum(s, lpp) * scale;
+            sc[h][b] = live[b] ? s : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        float mn = m[h];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) mn = fmaxf(mn, sc[h][b]);
+        if (mn == -INFINITY) continue;  // nothing live yet
+        const float corr = __expf(m[h] - mn);  // exp(-inf) = 0 on the first live batch
+        float pr[NB], ps = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            pr[b] = __expf(sc[h][b] - mn);
+            ps += pr[b];
+        }
+        l[h] = l[h] * corr + ps;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            float acc = o[h][j] * corr;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc = fmaf(pr[b], vf[b][j], acc);
+            o[h][j] = acc;
+        }
+        m[h] = mn;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // attention over the cache for a block of query rows, split over the cache length
 // ------------------------------------------------------------------------------------------
 // Workgroup (kv head g, split sp, block row r) handles `chunk` cache slots for the query heads
@@ -228,38 +294,16 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
+        bool live[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
-            const int pc = min(p, hi - 1);  // clamp: dead lane groups recompute a live slot and discard it
+            const int pc = min(p, hi - 1);  // clamp: dead lane groups load a live slot and discard it
+            live[b] = p < hi;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
         }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
-            const bool live = p < hi;
-            float kf[VEC], vf[VEC];
-            T::unpack(kv[b], kf);
-            T::unpack(vv[b], vf);
-#pragma unroll
-            for (int h = 0; h < GROUP; ++h) {
-                float sc = 0.f;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) sc = fmaf(q[h][j], kf[j], sc);
-                for (int off = LPP >> 1; off > 0; off >>= 1) sc += __shfl_xor(sc, off, 64);
-                sc *= scale;
-                if (live) {
-                    const float mn = fmaxf(m[h], sc);
-                    const float corr = __expf(m[h] - mn);  // exp(-inf) = 0 on the first slot
-                    const float pr = __expf(sc - mn);
-                    l[h] = l[h] * corr + pr;
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) o[h][j] = o[h][j] * corr + pr * vf[j];
-                    m[h] = mn;
-                }
-            }
-        }
+        attn_batch<T, GROUP, NB>(kv, vv, live, q, scale, LPP, m, l, o);
     }
 
     // merge lane groups of one wavefront (butterfly over the lane bits above LPP)
@@ -401,38 +445,16 @@ __global__ __launch_bounds__(1024) void k_attn_head(AttnArgs a) {
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
+        bool live[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = ((s0 + b) * 16 + wave) * SPW + lg;
             const int pc = min(p, n_ctx - 1);
+            live[b] = p < n_ctx;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
         }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int p = ((s0 + b) * 16 + wave) * SPW + lg;
-            const bool live = p < n_ctx;
-            float kf[VEC], vf[VEC];
-            T::unpack(kv[b], kf);
-            T::unpack(vv[b], vf);
-#pragma unroll
-            for (int h = 0; h < GROUP; ++h) {
-                float sc = 0.f;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) sc = fmaf(q[h][j], kf[j], sc);
-                for (int off = LPP >> 1; off > 0; off >>= 1) sc += __shfl_xor(sc, off, 64);
-                sc *= scale;
-                if (live) {
-                    const float mn = fmaxf(m[h], sc);
-                    const float corr = __expf(m[h] - mn);
-                    const float pr = __expf(sc - mn);
-                    l[h] = l[h] * corr + pr;
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) o[h][j] = o[h][j] * corr + pr * vf[j];
-                    m[h] = mn;
-                }
-            }
-        }
+        attn_batch<T, GROUP, NB>(kv, vv, live, q, scale, LPP, m, l, o);
     }
     // merge the lane groups of a wavefront
 #pragma unroll
