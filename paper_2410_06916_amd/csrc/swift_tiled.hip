@@ -611,23 +611,25 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     const int KSP = gridDim.y;
     if (live) {
         float *pp = a.part + ((size_t)blockIdx.y * a.n_rg + rg) * (16 * R);
-        for (int idx = lane; idx < 16 * R; idx += 64) pp[idx] = y_local(idx >> 4, idx & 15);
+        // (device-scope atomic stores write through, so the release below has nothing to flush)
+        for (int idx = lane; idx < 16 * R; idx += 64)
+            __hip_atomic_store(pp + idx, y_local(idx >> 4, idx & 15), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // One release per workgroup: the barrier orders every wavefront's partial stores before thread
-    // 0's device-scope fence, which publishes them ahead of the counter increment.
+    // One release/acquire per workgroup: the barrier orders every wavefront's partial stores before
+    // thread 0's device-scope read-modify-write on the counter, which publishes them (release) and,
+    // in the workgroup that arrives last, makes the other workgroups' partials visible (acquire).
+    // Separate fences around a relaxed atomic cost 10+ us more per launch on this multi-die part.
     __syncthreads();
     if (tid == 0) {
-        __threadfence();
-        const int old = atomicAdd(a.counters + blockIdx.x, 1);
+        const int old = __hip_atomic_fetch_add(a.counters + blockIdx.x, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
         *flag = (old == KSP - 1) ? 1 : 0;
     }
     __syncthreads();
     if (*flag == 0) return;
-    __threadfence();  // acquire: the other workgroups' partials
     if (live) {
         const float *p0 = a.part + (size_t)rg * (16 * R);
         const size_t sstride = (size_t)a.n_rg * (16 * R);
-        // (plain loads: the fence above makes the other workgroups' released partials visible)
+        // (plain loads: ordered after thread 0's acquire by the barrier)
         mv_epilogue<EPI>(a, rg, lane, rs, nullptr, [&](int r, int j) {
             float v[8];
 #pragma unroll
