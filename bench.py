@@ -207,6 +207,62 @@ def main():
                                              "alpha": round(s3["accepted"] / max(s3["draft_passes"], 1), 4)}
         log(f"[bench] modes: {modes}")
 
+    # ---- per-pass times (host clock around calls that end in a device synchronisation), the
+    # cost coefficient c of Eq. 6, end-to-end HBM fraction per pass, and Eq. 6 at the measured c
+    passes = None
+    projection = None
+    prefill_info = None
+    if not args.no_extra_modes:
+        draft_bytes_ = P.pass_bytes(g.cfg, mask, w.n_prompt, 1)
+        full_bytes_ = P.pass_bytes(g.cfg, None, w.n_prompt, 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.prefill(prompt)
+        torch.cuda.synchronize()
+        t_pf = time.perf_counter() - t0
+        td, tv2, tf = [], [], []
+        for _ in range(24):
+            t0 = time.perf_counter()
+            d, _c = g.draft_step(mask, 1, 2.0)
+            t1 = time.perf_counter()
+            g.verify(np.concatenate([[g.pending], d]).astype(np.int32))
+            t2 = time.perf_counter()
+            g.accept()
+            td.append(t1 - t0)
+            tv2.append(t2 - t1)
+        for _ in range(24):
+            t0 = time.perf_counter()
+            g.verify(np.array([g.pending], np.int32))
+            t1 = time.perf_counter()
+            g.accept()
+            tf.append(t1 - t0)
+        t_d, t_v2, t_f = (float(np.median(x)) for x in (td, tv2, tf))
+        c_meas = t_d / t_f
+        passes = {"draft_pass_ms": round(t_d * 1e3, 4), "full_pass_1row_ms": round(t_f * 1e3, 4),
+                  "verify_2row_ms": round(t_v2 * 1e3, 4),
+                  "c_measured": round(c_meas, 4), "c_bytes": round(draft_bytes_ / full_bytes_, 4),
+                  "draft_pass_hbm_frac": round(draft_bytes_ / t_d / 1e9 / HBM_PEAK_GBS, 4),
+                  "full_pass_hbm_frac": round(full_bytes_ / t_f / 1e9 / HBM_PEAK_GBS, 4),
+                  "note": "median of 24 calls each, host clock, includes launch gaps and the result read-back"}
+        # Eq. 6 for the (M, alpha) pairs of the paper's Table 4 (trained models, other hardware) at
+        # this machine's measured c: a projection, not a measurement
+        pairs = [(4.34, 0.99), (3.13, 0.98), (8.21, 1.00), (3.85, 0.99), (2.99, 0.98), (6.17, 0.99)]
+        projection = {"kind": "projection: Eq. 6 at the measured c with the paper's Table 4 (M, alpha); not measured here",
+                      "c": round(c_meas, 4),
+                      "expected_speedup": [{"M": m_, "alpha": a_, "speedup": round(P.expected_speedup(m_, a_, c_meas), 3)}
+                                           for m_, a_ in pairs]}
+        # prefill: flops the method asks for (2 per weight element per row + causal attention)
+        # against the dense bf16 MFMA peak
+        Hh, Ff, Ll, Vv = shape.hidden, shape.ffn, shape.n_layers, shape.vocab
+        kvw = shape.n_kv_heads * shape.head_dim
+        w_el = Ll * (Hh * Hh * 2 + 2 * Hh * kvw + 3 * Hh * Ff)
+        flops = 2.0 * w.n_prompt * w_el + 2.0 * Vv * Hh + 4.0 * Ll * Hh * w.n_prompt * (w.n_prompt + 1) / 2
+        prefill_info = {"ms": round(t_pf * 1e3, 2), "tokens_per_s": round(w.n_prompt / t_pf, 1),
+                        "algorithmic_TFLOPs": round(flops / t_pf / 1e12, 2),
+                        "mfma_frac_of_2500_TFLOPs": round(flops / t_pf / 2.5e15, 4),
+                        "note": "16-row blocks: each block streams all weights once, so prefill is HBM-bound here"}
+        log(f"[bench] passes: {passes}")
+
     if args.pmc_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
@@ -239,6 +295,9 @@ def main():
         "cpu_baseline": cpu,
         "modes": modes,
         "kernels": per_class,
+        "passes": passes,
+        "projection": projection,
+        "prefill": prefill_info,
     }
     print(json.dumps(result), flush=True)
 
