@@ -215,7 +215,6 @@ struct swift_ctx {
     int n;            // cache length
     int32_t pending;  // -1 before prefill
     int k_verify;     // -1: no verify outstanding
-    int last_logits_row;
     int32_t vtokens[SWIFT_MAX_BLOCK], targets[SWIFT_MAX_BLOCK];
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
@@ -331,7 +330,6 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.part_o = dptr<float>(x, L.part_o);
             a.part_ml = dptr<float>(x, L.part_ml);
             a.max_split = L.n_split_max;
-            a.counters = dptr<int>(x, L.mv_counters) + 2048;
             a.out = ar;
             a.out_s = nullptr;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
@@ -446,7 +444,6 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.part_o = dptr<float>(x, L.part_o);
             a.part_ml = dptr<float>(x, L.part_ml);
             a.max_split = L.n_split_max;
-            a.counters = dptr<int>(x, L.mv_counters) + 2048;
             a.out = nullptr;
             a.out_s = as_;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
@@ -714,7 +711,6 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     if (rc) return rc;
     x->n = n_prompt;
     x->pending = x->h_tok[last_rows - 1];
-    x->last_logits_row = last_rows - 1;
     x->k_verify = -1;
     memset(&x->st, 0, sizeof(x->st));
     x->st.emitted_total = 1;

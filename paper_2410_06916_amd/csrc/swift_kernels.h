@@ -56,7 +56,6 @@ struct AttnArgs {
     float *part_o;                // [rows][n_q][n_split][d]   unnormalised partial outputs
     float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
     int max_split;                // splits the partial buffers can hold
-    int *counters;                // [rows][n_kv] arrival counters, zero between launches
     float *out;                   // fp32 [rows][n_q][d], or nullptr
     uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*rows][8], or nullptr
 };
