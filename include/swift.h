@@ -183,6 +183,23 @@ int swift_debug_read_kv(swift_ctx *ctx, int layer, int pos, float *k_out, float 
  * Results do not depend on it bit for bit only within one setting; it exists for tuning runs. */
 int swift_debug_tune(swift_ctx *ctx, int kernel_class, int waves_per_row_group, int workgroups);
 
+/* Experimental path, off by default.  on = 1: blocks of up to four rows of a bf16 model whose
+ * deepest activation fits one workgroup's LDS, at positions below 1536, run as ONE persistent launch
+ * (decoder stack + LM head; stages separated by grid-wide barriers with bounded polling, the weight
+ * stream kept going across them) instead of one launch per projection / attention.  Results match
+ * the launch-per-stage path within rounding (the k-slices are summed in a different grouping).  It
+ * is measured slower than the default on MI355X and exists for that comparison.  Per-class timing
+ * (swift_profile_class) selects the launch-per-stage path while it is on.  If a grid-wide wait ever
+ * runs out, the call that was running returns SWIFT_EDEVICE, its results are invalid, and the
+ * context continues launch per stage. */
+int swift_debug_persistent(swift_ctx *ctx, int on);
+/* With swift_debug_persistent(ctx, 2) every persistent launch also records, for its first and its
+ * last workgroup, the device's 100 MHz clock after each stage's grid-wide wait and at the end of the
+ * workgroup's share of the stage (a measurement hook: a profiler sees the launch as one kernel).
+ * Returns the readings of the last such launch: ticks[((w * n_stages) + s) * 2 + {0, 1}], w = 0
+ * (first workgroup) or 1 (last); capacity = elements of `ticks`, at least 4 * n_stages. */
+int swift_debug_read_stack_trace(swift_ctx *ctx, uint64_t *ticks, int capacity, int *n_stages);
+
 /* Turns per-launch timing of one kernel class on (kernel_class in [0, SWIFT_KC_COUNT)) or off (-1).
  * While on, every launch of that class is bracketed by HIP events on the context's stream. */
 int swift_profile_class(swift_ctx *ctx, int kernel_class);

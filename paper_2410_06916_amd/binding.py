@@ -72,6 +72,8 @@ def lib():
     L.swift_debug_read_logits.argtypes = [vp, C.c_int, f32p]
     L.swift_debug_read_kv.argtypes = [vp, C.c_int, C.c_int, f32p, f32p]
     L.swift_debug_tune.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    L.swift_debug_persistent.argtypes = [vp, C.c_int]
+    L.swift_debug_read_stack_trace.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_int)]
     L.swift_profile_class.argtypes = [vp, C.c_int]
     L.swift_profile_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     _lib = L
@@ -238,6 +240,18 @@ class SwiftModel:
         v = np.empty(w, np.float32)
         _chk(lib().swift_debug_read_kv(self._h, layer, pos, _p(k, C.c_float), _p(v, C.c_float)), "swift_debug_read_kv")
         return k, v
+
+    def persistent(self, on: bool, trace: bool = False):
+        _chk(lib().swift_debug_persistent(self._h, (2 if trace else 1) if on else 0), "swift_debug_persistent")
+
+    def stack_trace(self) -> np.ndarray:
+        """Clock readings (100 MHz ticks) of the last traced persistent launch: [2 workgroups][stages][2]."""
+        cap = 4 * (5 * self.cfg.n_layers + 1)
+        buf = np.zeros(cap, np.uint64)
+        n = C.c_int(0)
+        _chk(lib().swift_debug_read_stack_trace(self._h, buf.ctypes.data_as(C.POINTER(C.c_uint64)), cap, C.byref(n)),
+             "swift_debug_read_stack_trace")
+        return buf[:4 * n.value].reshape(2, n.value, 2)
 
     def tune(self, name: str, waves_per_row_group: int = 0, workgroups: int = 0):
         _chk(lib().swift_debug_tune(self._h, KERNEL_CLASSES[name], waves_per_row_group, workgroups), "swift_debug_tune")

@@ -8,8 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswift_hip.so")
-SOURCES = ["swift_api.hip", "swift_kernels.hip", "swift_tiled.hip"]
-HEADERS = ["swift_kernels.h", "swift_device.h", os.path.join("..", "..", "include", "swift.h")]
+SOURCES = ["swift_api.hip", "swift_kernels.hip", "swift_tiled.hip", "swift_stack.hip"]
+HEADERS = ["swift_kernels.h", "swift_device.h", "swift_attn.h", "swift_mv.h", os.path.join("..", "..", "include", "swift.h")]
 
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-Wall", "-Wno-unused-result",

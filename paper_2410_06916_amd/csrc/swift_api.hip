@@ -63,6 +63,8 @@ extern "C" int swift_check_config(const swift_model_config *c) {
 
 namespace {
 
+constexpr int kStackTables = 4;  // stage lists kept on the device (draft mask, verify, plain decoding, ...)
+
 struct LayerOff {
     uint64_t attn_norm, wqkv, wo, mlp_norm, wgu, wd;
 };
@@ -74,6 +76,9 @@ struct Layout {
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf;
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
     uint64_t xs, as_, hs, pss, mv_part, mv_counters;
+    // persistent stack kernel: cached stage lists, barrier counter + error flag
+    uint64_t stack_tab, stack_sync, stack_trace;
+    int stack_max_stages;
     int mv_part_capacity;
     uint64_t stage, stage_bytes;  // staging for host tensors that are re-tiled on the device
     uint64_t total;
@@ -135,6 +140,10 @@ Layout make_layout(const swift_model_config &c) {
     L.mv_part_capacity = 8192;
     L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxRows * 4);
     L.mv_counters = take(4096 * 4);
+    L.stack_max_stages = 5 * c.n_layers + 1;
+    L.stack_tab = take((uint64_t)kStackTables * L.stack_max_stages * sizeof(StackStage));
+    L.stack_sync = take(256);
+    L.stack_trace = take((uint64_t)2 * L.stack_max_stages * 2 * 8);
     L.stage_bytes = bf ? std::max(std::max(V * H, F * H), std::max(Q * H, KV * H)) * eb : 0;
     L.stage = take(L.stage_bytes);
     L.total = off;
@@ -195,6 +204,13 @@ extern "C" int swift_pass_bytes(const swift_model_config *cfg, const uint8_t *sk
 // ------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------
+// identifies a cached stage list: rows, LM head included or not, skip mask (empty = none)
+struct StackKey {
+    int R = 0, n_stages = 0;
+    bool logits = false, valid = false;
+    std::vector<uint8_t> mask;
+};
+
 struct ProfRec {
     hipEvent_t a, b;
     uint64_t bytes;
@@ -219,6 +235,15 @@ struct swift_ctx {
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
     int tune_ks[SWIFT_KC_COUNT], tune_wg[SWIFT_KC_COUNT];
+    // persistent stack kernel
+    bool stack_on;              // use it where a block qualifies
+    bool stack_trace;           // record per-stage clock readings of the next persistent launches
+    int stack_trace_stages;     // stages of the last traced launch
+    unsigned stack_base;        // value of the device barrier counter before the next launch
+    int stack_next;             // table slot to overwrite next
+    std::vector<StackKey> stack_keys;  // what each device table slot holds
+    int32_t *h_err;             // pinned: the kernel's error flag after a pass
+    bool stack_used;            // a persistent launch happened since the flag was last read
     // profiling
     int prof_class;
     std::vector<ProfRec> prof;
@@ -398,24 +423,20 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.part_capacity = L.mv_part_capacity;
         return m;
     };
-    auto run = [&](int kc, int epi, const MvArgs &m) -> int {
-        HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
-                      [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }, true));
-        return SWIFT_OK;
+    // ---- the pass as a list of stages
+    std::vector<StackStage> list;
+    std::vector<int> classes;  // kernel class of each stage (profiling, launch-shape overrides)
+    list.reserve(5 * stages.size() + 1);
+    auto push_mv = [&](int kc, int epi, const MvArgs &m, int wg_first) {
+        StackStage st{};
+        st.type = ST_MV;
+        st.epi = epi;
+        st.wg_first = wg_first;
+        st.mv = m;
+        list.push_back(st);
+        classes.push_back(kc);
     };
-    int rc;
-
-    EmbedRowsArgs ea{};
-    ea.E = dptr<uint16_t>(x, L.embed);
-    ea.H = H;
-    ea.R = R;
-    for (int r = 0; r < R; ++r) ea.tokens[r] = tokens[r];
-    ea.x = xf;
-    ea.xs = xs;
-    ea.gain_next = gain_of(0);
-    ea.pss = pss;
-    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
-
+    const int n_att = c.n_kv_heads * R;  // workgroups busy with attention (persistent kernel)
     for (size_t i = 0; i < stages.size(); ++i) {
         const int l = stages[i].layer;
         const LayerOff &y = L.layers[l];
@@ -429,9 +450,12 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.ld_out = Q;
             m.kcache = kv_base(x, l, 0);
             m.vcache = kv_base(x, l, 1);
-            if ((rc = run(SWIFT_KC_QKV, EPI_QKV, m))) return rc;
+            push_mv(SWIFT_KC_QKV, EPI_QKV, m, 0);
 
-            AttnArgs a{};
+            StackStage at{};
+            at.type = ST_ATTN;
+            at.n_units = n_att;
+            AttnArgs &a = at.at;
             a.q = qf;
             a.kcache = kv_base(x, l, 0);
             a.vcache = kv_base(x, l, 1);
@@ -446,8 +470,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.max_split = L.n_split_max;
             a.out = nullptr;
             a.out_s = as_;
-            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
-                          [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+            list.push_back(at);
+            classes.push_back(SWIFT_KC_ATTN);
 
             MvArgs o = base_args(y.wo, H, Q, (H + 15) / 16);
             o.in_s = as_;
@@ -456,14 +480,16 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             o.out_s = xs;
             o.gain_next = gnext;
             o.pss_out = pss;
-            if ((rc = run(SWIFT_KC_OPROJ, EPI_RESID, o))) return rc;
+            // (persistent kernel: the workgroups that computed the attention sit this one out, so
+            // that their cold start after the attention falls into the stage after it)
+            push_mv(SWIFT_KC_OPROJ, EPI_RESID, o, n_att);
         } else {
             MvArgs m = base_args(y.wgu, 2 * F, H, (F + 7) / 8);
             m.in_s = xs;
             m.pss = pss;
             m.n_pss = n_pss;
             m.out_s = hs;
-            if ((rc = run(SWIFT_KC_GATEUP, EPI_SWIGLU, m))) return rc;
+            push_mv(SWIFT_KC_GATEUP, EPI_SWIGLU, m, 0);
             MvArgs w = base_args(y.wd, H, F, (H + 15) / 16);
             w.in_s = hs;
             w.out_f32 = xf;
@@ -471,7 +497,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             w.out_s = xs;
             w.gain_next = gnext;
             w.pss_out = pss;
-            if ((rc = run(SWIFT_KC_DOWN, EPI_RESID, w))) return rc;
+            push_mv(SWIFT_KC_DOWN, EPI_RESID, w, 0);
         }
     }
     if (want_logits) {
@@ -481,7 +507,88 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.n_pss = n_pss;
         m.out_f32 = dptr<float>(x, L.logits);
         m.ld_out = V;
-        if ((rc = run(SWIFT_KC_LMHEAD, EPI_LOGITS, m))) return rc;
+        push_mv(SWIFT_KC_LMHEAD, EPI_LOGITS, m, 0);
+    }
+
+    EmbedRowsArgs ea{};
+    ea.E = dptr<uint16_t>(x, L.embed);
+    ea.H = H;
+    ea.R = R;
+    for (int r = 0; r < R; ++r) ea.tokens[r] = tokens[r];
+    ea.x = xf;
+    ea.xs = xs;
+    ea.gain_next = gain_of(0);
+    ea.pss = pss;
+    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
+
+    // ---- one persistent launch where the block qualifies, else one launch per stage
+    const int group = c.n_q_heads / c.n_kv_heads;
+    const int max_T = (std::max(std::max(H, Q), F) + 31) / 32;
+    const size_t stack_lds = stack_lds_bytes(max_T, R, d, group, (int)list.size());
+    const bool use_stack = x->stack_on && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
+                           pos0 + R <= 1536 && n_att <= x->n_cu / 2 && (int)list.size() <= L.stack_max_stages &&
+                           (group == 1 || group == 2 || group == 4 || group == 8);
+    if (use_stack) {
+        // find or upload the stage list (pointers and shapes only; the position is a launch argument)
+        int slot = -1;
+        const size_t mask_len = skip ? (size_t)2 * c.n_layers : 0;
+        for (int t = 0; t < kStackTables; ++t) {
+            const StackKey &k = x->stack_keys[t];
+            if (k.valid && k.R == R && k.logits == want_logits && k.mask.size() == mask_len &&
+                (mask_len == 0 || memcmp(k.mask.data(), skip, mask_len) == 0)) {
+                slot = t;
+                break;
+            }
+        }
+        StackStage *tab = nullptr;
+        if (slot < 0) {
+            slot = x->stack_next;
+            x->stack_next = (x->stack_next + 1) % kStackTables;
+            tab = dptr<StackStage>(x, L.stack_tab) + (size_t)slot * L.stack_max_stages;
+            HIP_TRY(hipStreamSynchronize(s));  // an earlier launch may still read this slot
+            HIP_TRY(hipMemcpyAsync(tab, list.data(), list.size() * sizeof(StackStage), hipMemcpyHostToDevice, s));
+            HIP_TRY(hipStreamSynchronize(s));  // `list` goes out of scope
+            StackKey &k = x->stack_keys[slot];
+            k.valid = true;
+            k.R = R;
+            k.logits = want_logits;
+            k.n_stages = (int)list.size();
+            k.mask.assign(skip ? skip : nullptr, skip ? skip + mask_len : nullptr);
+        } else {
+            tab = dptr<StackStage>(x, L.stack_tab) + (size_t)slot * L.stack_max_stages;
+        }
+        StackArgs sa{};
+        sa.stages = tab;
+        sa.n_stages = (int)list.size();
+        sa.pos0 = pos0;
+        sa.R = R;
+        sa.head_dim = d;
+        sa.act_bytes = (int)stack_act_bytes(max_T, R, d, group);
+        sa.barrier = dptr<unsigned>(x, L.stack_sync);
+        sa.barrier_base = x->stack_base;
+        sa.spin_limit = 1 << 20;
+        sa.error = dptr<int>(x, L.stack_sync) + 16;
+        sa.trace = x->stack_trace ? dptr<uint64_t>(x, L.stack_trace) : nullptr;
+        if (x->stack_trace) x->stack_trace_stages = (int)list.size();
+        HIP_TRY(launch_stack(sa, group, stack_lds, x->n_cu, s));
+        x->stack_base += (unsigned)(list.size() - 1) * (unsigned)x->n_cu;
+        x->stack_used = true;
+    } else {
+        for (size_t i = 0; i < list.size(); ++i) {
+            const int kc = classes[i];
+            if (list[i].type == ST_ATTN) {
+                const AttnArgs &a = list[i].at;
+                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
+                              [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+            } else {
+                const MvArgs &m = list[i].mv;
+                const int epi = list[i].epi;
+                HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
+                              [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }, true));
+            }
+        }
+    }
+    if (want_logits) {
         ArgmaxArgs am{dptr<float>(x, L.logits), V, R, dptr<int32_t>(x, L.out_tok), dptr<float>(x, L.out_conf)};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * V * 4, [&] { return launch_argmax_conf(am, s); }));
     }
@@ -502,7 +609,22 @@ int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const ui
 int read_results(swift_ctx *x, int rows) {
     HIP_TRY(hipMemcpyAsync(x->h_tok, dptr<int32_t>(x, x->L.out_tok), rows * 4, hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipMemcpyAsync(x->h_conf, dptr<float>(x, x->L.out_conf), rows * 4, hipMemcpyDeviceToHost, x->stream));
+    if (x->stack_used)
+        HIP_TRY(hipMemcpyAsync(x->h_err, dptr<int>(x, x->L.stack_sync) + 16, 4, hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipStreamSynchronize(x->stream));
+    if (x->stack_used) {
+        x->stack_used = false;
+        if (x->h_err[0] != 0) {
+            // a grid-wide wait of the persistent kernel ran out: its results are invalid and the
+            // barrier counter no longer matches the host's count.  Start over without it.
+            x->h_err[0] = 0;
+            x->stack_on = false;
+            x->stack_base = 0;
+            HIP_TRY(hipMemsetAsync(x->base + x->L.stack_sync, 0, 256, x->stream));
+            HIP_TRY(hipStreamSynchronize(x->stream));
+            return fail(SWIFT_EDEVICE, "persistent kernel: a grid-wide wait ran out; the pass is invalid (persistent path now off)");
+        }
+    }
     return SWIFT_OK;
 }
 
@@ -602,12 +724,22 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     memset(x->tune_wg, 0, sizeof(x->tune_wg));
     x->h_tok = nullptr;
     x->h_conf = nullptr;
-    hipError_t e = hipHostMalloc((void **)&x->h_tok, 2 * kMaxRows * 4, hipHostMallocDefault);
+    x->stack_on = false;
+    x->stack_trace = false;
+    x->stack_trace_stages = 0;
+    x->stack_base = 0;
+    x->stack_next = 0;
+    x->stack_used = false;
+    x->stack_keys.assign(kStackTables, StackKey());
+    x->h_err = nullptr;
+    hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxRows + 4) * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete x;
         return fail(SWIFT_EDEVICE, std::string("hipHostMalloc: ") + hipGetErrorString(e));
     }
     x->h_conf = (float *)(x->h_tok + kMaxRows);
+    x->h_err = x->h_tok + 2 * kMaxRows;
+    x->h_err[0] = 0;
 
     // rotary tables: angle = pos * theta^(-2i/d) in fp64, cos/sin rounded to fp32
     const int half = cfg->head_dim / 2;
@@ -621,6 +753,7 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
         }
     }
     e = hipMemsetAsync(x->base + L.mv_counters, 0, 4096 * 4, x->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(x->base + L.stack_sync, 0, 256, x->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.cos, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.sin, stb.data(), stb.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(x->stream);
@@ -853,6 +986,23 @@ extern "C" int swift_debug_read_kv(swift_ctx *x, int layer, int pos, float *k_ou
                                x->stream));
         HIP_TRY(hipStreamSynchronize(x->stream));
     }
+    return SWIFT_OK;
+}
+
+extern "C" int swift_debug_persistent(swift_ctx *x, int on) {
+    if (!x) return fail(SWIFT_EINVAL, "null context");
+    x->stack_on = on != 0;
+    x->stack_trace = on == 2;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_debug_read_stack_trace(swift_ctx *x, uint64_t *ticks, int capacity, int *n_stages) {
+    if (!x || !ticks || !n_stages) return fail(SWIFT_EINVAL, "null argument");
+    const int n = x->stack_trace_stages;
+    if (capacity < 4 * n) return fail(SWIFT_EINVAL, "capacity < 4 * stages of the last traced launch");
+    HIP_TRY(hipStreamSynchronize(x->stream));
+    if (n > 0) HIP_TRY(hipMemcpy(ticks, x->base + x->L.stack_trace, (size_t)4 * n * 8, hipMemcpyDeviceToHost));
+    *n_stages = n;
     return SWIFT_OK;
 }
 

@@ -1,0 +1,179 @@
+// Attention device code shared by the attention kernels and the persistent decoder-stack kernel.
+#pragma once
+#include <math.h>
+
+#include "swift_device.h"
+#include "swift_kernels.h"
+
+namespace swift {
+
+// ------------------------------------------------------------------------------------------
+// attention: shared inner step
+// ------------------------------------------------------------------------------------------
+// Sum over the lanes that share one cache slot.  Sixteen lanes are one DPP row: butterfly inside
+// quads, then half-row and row mirrors (every lane ends with the total), four single instructions.
+__device__ inline float slot_sum(float v, int lpp) {
+    if (lpp == 16) {
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
+        return v;
+    }
+    for (int off = lpp >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// One batch of NB cache slots per lane group against GROUP query heads: scores, one running-max
+// update for the whole batch, probabilities, weighted values (online softmax).
+template <typename T, int GROUP, int NB>
+__device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], const bool (&live)[NB],
+                                  const float (&q)[GROUP][T::VEC], float scale, int lpp, float (&m)[GROUP],
+                                  float (&l)[GROUP], float (&o)[GROUP][T::VEC]) {
+    constexpr int VEC = T::VEC;
+    float vf[NB][VEC];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) T::unpack(vv[b], vf[b]);
+    float sc[GROUP][NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float kf[VEC];
+        T::unpack(kv[b], kf);
+#pragma unroll
+        for (int h = 0; h < GROUP; ++h) {
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) s = fmaf(q[h][j], kf[j], s);
+            s = slot_sum(s, lpp) * scale;
+            sc[h][b] = live[b] ? s : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        float mn = m[h];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) mn = fmaxf(mn, sc[h][b]);
+        if (mn == -INFINITY) continue;  // nothing live yet
+        const float corr = __expf(m[h] - mn);  // exp(-inf) = 0 on the first live batch
+        float pr[NB], ps = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            pr[b] = __expf(sc[h][b] - mn);
+            ps += pr[b];
+        }
+        l[h] = l[h] * corr + ps;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            float acc = o[h][j] * corr;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc = fmaf(pr[b], vf[b][j], acc);
+            o[h][j] = acc;
+        }
+        m[h] = mn;
+    }
+}
+
+// One workgroup of 16 wavefronts (1024 threads, all of them call this) computes the attention of
+// block row `row` for the GROUP query heads that share kv head g over the whole cache range
+// [0, n_ctx + row).  Step s of wavefront w covers slots (16 s + w) * SPW ..; the loads of NB steps
+// are issued together.  sh: LDS, [16*GROUP] max, [16*GROUP] sum, [16*GROUP*d] weighted values.
+template <typename T, int GROUP>
+__device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *sh) {
+    constexpr int VEC = T::VEC;
+    constexpr int NB = GROUP <= 2 ? 4 : 1;
+    const int d = a.head_dim;
+    const int LPP = d / VEC, SPW = 64 / LPP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane & (LPP - 1), lg = lane / LPP;
+    const int n_ctx = a.n_ctx + row;
+    const float scale = 1.0f / sqrtf((float)d);
+    const int nq = a.n_q_heads;
+    float *sm = sh, *sl = sh + 16 * GROUP, *so = sh + 32 * GROUP;
+
+    float q[GROUP][VEC];
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
+    float m[GROUP], l[GROUP], o[GROUP][VEC];
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        m[h] = -INFINITY;
+        l[h] = 0.f;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) o[h][j] = 0.f;
+    }
+    const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
+    const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
+    const int steps = (n_ctx + 16 * SPW - 1) / (16 * SPW);
+
+    for (int s0 = 0; s0 < steps; s0 += NB) {
+        u32x4 kv[NB], vv[NB];
+        bool live[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int p = ((s0 + b) * 16 + wave) * SPW + lg;
+            const int pc = min(p, n_ctx - 1);
+            live[b] = p < n_ctx;
+            kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
+            vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
+        }
+        attn_batch<T, GROUP, NB>(kv, vv, live, q, scale, LPP, m, l, o);
+    }
+    // merge the lane groups of a wavefront
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) {
+        for (int off = LPP; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(m[h], off, 64);
+            const float l2 = __shfl_xor(l[h], off, 64);
+            const float mn = fmaxf(m[h], m2);
+            const float c1 = (m[h] == -INFINITY) ? 0.f : __expf(m[h] - mn);
+            const float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
+            l[h] = l[h] * c1 + l2 * c2;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const float o2 = __shfl_xor(o[h][j], off, 64);
+                o[h][j] = o[h][j] * c1 + o2 * c2;
+            }
+            m[h] = mn;
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int h = 0; h < GROUP; ++h) {
+            if (lj == 0) {
+                sm[wave * GROUP + h] = m[h];
+                sl[wave * GROUP + h] = l[h];
+            }
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) so[((size_t)wave * GROUP + h) * d + lj * VEC + j] = o[h][j];
+        }
+    }
+    __syncthreads();
+    // merge the 16 wavefronts, normalise, write
+    for (int idx = tid; idx < GROUP * d; idx += 1024) {
+        const int h = idx / d, j = idx - h * d;
+        float mn = -INFINITY;
+        for (int w = 0; w < 16; ++w) mn = fmaxf(mn, sm[w * GROUP + h]);
+        float ls = 0.f, os = 0.f;
+        for (int w = 0; w < 16; ++w) {
+            const float mw = sm[w * GROUP + h];
+            const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mn);
+            ls += sl[w * GROUP + h] * c;
+            os += so[((size_t)w * GROUP + h) * d + j] * c;
+        }
+        const float y = os / ls;
+        const int e = (g * GROUP + h) * d + j;
+        if (a.out) a.out[(size_t)row * nq * d + e] = y;
+        if (a.out_s) {
+            uint16_t hi, mid, lo;
+            split3(y, hi, mid, lo);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * a.rows) + 3 * row) * 8 + (e & 7);
+            p[0] = hi;
+            p[8] = mid;
+            p[16] = lo;
+        }
+    }
+}
+
+}  // namespace swift

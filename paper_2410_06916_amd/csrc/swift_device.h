@@ -34,6 +34,11 @@ __device__ inline void split3(float v, uint16_t &hi, uint16_t &mid, uint16_t &lo
     lo = (uint16_t)f32_to_bf16_rne_finite(r2);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store of the wavefront (its release fence covers global memory), which would drain a
+// window of weight loads that is deliberately kept in flight across the barrier.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct F32T {
     static constexpr int VEC = 4;  // elements per 16-byte load
     using elem = float;

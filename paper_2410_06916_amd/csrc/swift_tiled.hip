@@ -7,6 +7,7 @@
 
 #include "swift_device.h"
 #include "swift_kernels.h"
+#include "swift_mv.h"
 
 namespace swift {
 
@@ -168,84 +169,6 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
     __syncthreads();
 }
 
-// What follows the dot products of one 16-row group, run by one whole wavefront.
-// Y(r, j): finished dot product of block row r and tile row j (before the norm scale).
-// rot: optional LDS copy of the rotary rows, [R][d/2 cos | d/2 sin]; nullptr = read the tables.
-template <int EPI, typename YF>
-__device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, const float *rot, YF Y) {
-    const int R = a.R, NC = 3 * R;
-    if (EPI == EPI_RESID || EPI == EPI_LOGITS) {
-        const int iters = (16 * R + 63) >> 6;
-        for (int it = 0; it < iters; ++it) {
-            const int idx = it * 64 + lane;
-            const int r = idx >> 4, j = idx & 15;
-            const int row = 16 * rg + j;
-            const bool ok = r < R && row < a.O;
-            if (EPI == EPI_LOGITS) {
-                if (ok) a.out_f32[(size_t)r * a.ld_out + row] = Y(r, j) * rs[r];
-            } else {
-                float xn = 0.f;
-                if (ok) {
-                    float *xp = a.out_f32 + (size_t)r * a.ld_out + row;
-                    xn = *xp + Y(r, j);
-                    *xp = xn;
-                    uint16_t hi, mid, lo;
-                    split3(xn * a.gain_next[row], hi, mid, lo);
-                    uint16_t *p = a.out_s + ((size_t)(row >> 3) * NC + 3 * r) * 8 + (row & 7);
-                    p[0] = hi;
-                    p[8] = mid;
-                    p[16] = lo;
-                }
-                float ss = xn * xn;
-#pragma unroll
-                for (int off = 8; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-                if (r < R && j == 0) a.pss_out[(size_t)rg * 16 + r] = ss;
-            }
-        }
-    } else {
-        const int iters = (8 * R + 63) >> 6;
-        for (int it = 0; it < iters; ++it) {
-            const int idx = it * 64 + lane;
-            const int r = idx >> 3, j = idx & 7;
-            if (r >= R) continue;
-            const float sc = rs[r];
-            const float ya = Y(r, j) * sc, yb = Y(r, j + 8) * sc;
-            if (EPI == EPI_SWIGLU) {
-                if (2 * (8 * rg + j) < a.O) {
-                    uint16_t hi, mid, lo;
-                    split3(ya / (1.0f + expf(-ya)) * yb, hi, mid, lo);
-                    uint16_t *p = a.out_s + ((size_t)rg * NC + 3 * r) * 8 + j;
-                    p[0] = hi;
-                    p[8] = mid;
-                    p[16] = lo;
-                }
-            } else {
-                const int d = a.head_dim, half = d >> 1, gph = half >> 3;
-                const int hh = rg / gph, i = 8 * (rg - hh * gph) + j;
-                const int nq = a.n_q_heads, nkv = a.n_kv_heads, pos = a.pos0 + r;
-                if (hh < nq + nkv) {
-                    const float c = rot ? rot[r * d + i] : a.cos_tab[(size_t)pos * half + i];
-                    const float s = rot ? rot[r * d + half + i] : a.sin_tab[(size_t)pos * half + i];
-                    const float qa = ya * c - yb * s, qb = yb * c + ya * s;
-                    if (hh < nq) {
-                        float *qp = a.out_f32 + (size_t)r * a.ld_out + hh * d + i;
-                        qp[0] = qa;
-                        qp[half] = qb;
-                    } else {
-                        uint16_t *kc = (uint16_t *)a.kcache + ((size_t)(hh - nq) * a.max_seq + pos) * d + i;
-                        kc[0] = f32_to_bf16_rne(qa);
-                        kc[half] = f32_to_bf16_rne(qb);
-                    }
-                } else {
-                    uint16_t *vc = (uint16_t *)a.vcache + ((size_t)(hh - nq - nkv) * a.max_seq + pos) * d + i;
-                    vc[0] = f32_to_bf16_rne(ya);
-                    vc[half] = f32_to_bf16_rne(yb);
-                }
-            }
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 // 1..5 activation rows: Y = W . X, MFMA, whole activation in LDS, K split over wavefronts
 // ------------------------------------------------------------------------------------------
@@ -363,7 +286,6 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     }
 
     for (int seg = 0; seg < a.S; ++seg) {
-        if (seg > 0) prime(seg);
         const int rg = (seg * W + (int)blockIdx.x) * G + g;
         const bool live = rg <= last_rg;
         const int live_mask = live ? -1 : 0;
@@ -377,8 +299,19 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
                 buf[u] = load_slot((b + 1) * 16 + u);
             }
         }
+        if (seg + 1 < a.S) {
+            // the window rolls on into the next round's row group: the stream never drains
+            const int rgn = min(((seg + 1) * W + (int)blockIdx.x) * G + g, last_rg);
+            base = Wt + ((size_t)rgn * T + t0) * 64 + lane;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+            for (int u = 0; u < 16; ++u) {
+                mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+                buf[u] = load_slot(u);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+        }
 
         // ---- end of the row group: every wavefront parks its NC result columns in LDS; one
         // wavefront per row group adds terms and K slices and runs the epilogue
@@ -387,7 +320,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) rp[(wave * NC + col) * 16 + 4 * kg + r4] = acc[r4];
         }
-        __syncthreads();
+        lds_barrier();  // (the next round's tile loads stay in flight)
         if (!live || ks != 0) continue;
         mv_epilogue<EPI>(a, rg, lane, rs, EPI == EPI_QKV ? rot : nullptr, [&](int r, int j) {
             float y = 0.f;

@@ -193,6 +193,38 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     g.close()
 
 
+@pytest.mark.parametrize("case", ["small-gqa-bf16", "7b-width-2-layers"])
+def test_persistent_stack_kernel_matches_oracle(oracle_lib, case):
+    """The opt-in one-launch-per-pass path (grid-wide barriers between stages, bounded polling):
+    same tokens, drafts, acceptance and logits as the oracle, for skip masks that remove whole
+    attention / MLP stages, blocks of 1-4 rows, and GQA."""
+    import paper_2410_06916_amd as P
+    if case == "small-gqa-bf16":
+        shape = hp.SMALL_GQA_BF16
+        weights = hp.shaped_weights(shape, seed=21)
+        max_seq, n_prompt, n_new, threads = 96, 12, 40, 1
+        rng = np.random.default_rng(9)
+        L2 = 2 * shape.n_layers
+        masks = [np.zeros(L2, np.uint8), np.ones(L2, np.uint8), (rng.random(L2) < 0.5).astype(np.uint8)]
+        settings = ((3, 0.0), (3, 0.5), (1, 2.0))
+    else:
+        shape = si.LLAMA2_7B.with_layers(2)
+        weights = si.make_weights(shape, 0)
+        max_seq, n_prompt, n_new, threads = 48, 12, 10, 8
+        masks = [np.array([0, 1, 1, 0], np.uint8)]
+        settings = ((3, 0.0),)
+    o, g = _pair(oracle_lib, shape, weights, max_seq, threads=threads)
+    g.persistent(True)
+    prompt = si.uniform_ids(11, n_prompt, shape.vocab)
+    for mask in masks:
+        for max_k, eps in settings:
+            want, to = oracle_lib.generate_swift(o, prompt, n_new, mask, max_k, eps, want_logits=True)
+            got, tg = P.generate_swift(g, prompt, n_new, mask, max_k, eps, want_logits=True)
+            assert np.array_equal(got, want), (case, max_k, eps)
+            _compare_traces(shape, to, tg)
+    g.close()
+
+
 def test_long_context_uses_split_attention(oracle_lib):
     """A context beyond the single-workgroup attention range (1536 slots): the split kernel and
     its merge, for one row and for a block, with a ragged last chunk."""
