@@ -176,9 +176,10 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
 // >= NC read a zero chunk.  A workgroup has 8 wavefronts; KS of them share one 16-row group of W,
 // each taking a contiguous slice of its k-tiles, so a workgroup works on G = 8/KS row groups at a
 // time and the slices (and the three terms) are added in LDS in a fixed order.  Every wavefront
-// keeps a rolling window of sixteen 1 KB tile loads in flight; the first window is issued before
-// the activation is staged.
-template <int EPI, int KS>
+// keeps a rolling window of NS (10..16) 1 KB tile loads in flight, walked in blocks of NS slots (the
+// launcher picks the depth that cuts the slice with the fewest unused slots); the first window is
+// issued before the activation is staged, and the window rolls on from one round into the next.
+template <int EPI, int KS, int NS>
 __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per SIMD: <= 128 VGPRs, two workgroups per CU
     extern __shared__ __align__(16) unsigned char smem[];
     const int R = a.R, NC = 3 * R;
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     const int boff = col < NC ? 16 + (kg * NC + col) * 16 : 0;
     const int bstride = col < NC ? 64 * NC : 0;
 
-    u32x4 buf[16];
+    u32x4 buf[NS];
     const u32x4 *base = nullptr;
     auto load_slot = [&](int i) { return __builtin_nontemporal_load(base + (size_t)min(i, nvm1) * 64); };
     auto mma_slot = [&](int i, const u32x4 &av, f32x4 &acc, int live_mask) {
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         const int rg = min((seg * W + (int)blockIdx.x) * G + g, last_rg);
         base = Wt + ((size_t)rg * T + t0) * 64 + lane;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) buf[u] = load_slot(u);
+        for (int u = 0; u < NS; ++u) buf[u] = load_slot(u);
     };
 
     // ---- stage the split activation (a plain copy: the producer kernel already wrote it in B
@@ -291,12 +292,12 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         const int live_mask = live ? -1 : 0;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 
-        const int nb16 = (n + 15) >> 4;
+        const int nb16 = (n + NS - 1) / NS;
         for (int b = 0; b + 1 < nb16; ++b) {
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                mma_slot(b * 16 + u, buf[u], acc, live_mask);
-                buf[u] = load_slot((b + 1) * 16 + u);
+            for (int u = 0; u < NS; ++u) {
+                mma_slot(b * NS + u, buf[u], acc, live_mask);
+                buf[u] = load_slot((b + 1) * NS + u);
             }
         }
         if (seg + 1 < a.S) {
@@ -304,13 +305,13 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
             const int rgn = min(((seg + 1) * W + (int)blockIdx.x) * G + g, last_rg);
             base = Wt + ((size_t)rgn * T + t0) * 64 + lane;
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+            for (int u = 0; u < NS; ++u) {
+                mma_slot((nb16 - 1) * NS + u, buf[u], acc, live_mask);
                 buf[u] = load_slot(u);
             }
         } else {
 #pragma unroll
-            for (int u = 0; u < 16; ++u) mma_slot((nb16 - 1) * 16 + u, buf[u], acc, live_mask);
+            for (int u = 0; u < NS; ++u) mma_slot((nb16 - 1) * NS + u, buf[u], acc, live_mask);
         }
 
         // ---- end of the row group: every wavefront parks its NC result columns in LDS; one
@@ -334,16 +335,16 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     }
 }
 
-template <int EPI, int KS>
+template <int EPI, int KS, int NS>
 static hipError_t launch_mv1_t(const MvArgs &a, int grid, size_t lds, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mv1<EPI, KS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)k_mv1<EPI, KS, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMvMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    return launch_maybe_timed(k_mv1<EPI, KS>, dim3(grid), dim3(512), lds, s, a);
+    return launch_maybe_timed(k_mv1<EPI, KS, NS>, dim3(grid), dim3(512), lds, s, a);
 }
 
 static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
@@ -385,13 +386,37 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
         best_s = (a.n_rg + G * best_w - 1) / (G * best_w);
     }
     a.S = best_s;
+    // Slots per block of the load window (= loads in flight per wavefront): 16 unless another depth
+    // cuts a slice of n tiles with fewer wasted slots (n = 43: 3 x 15 instead of 3 x 16; n = 20:
+    // 2 x 10 instead of 2 x 16).  Only for the 8-way split, which is what the big shapes use.
+    int ns = 16;
+    if (best_ks == 8) {
+        const int n = (a.T + 7) / 8;
+        int best_waste = (n + 15) / 16 * 16 - n;
+        for (int c = 15; c >= 10; --c) {
+            const int waste = (n + c - 1) / c * c - n;
+            if (waste < best_waste && (n + c - 1) / c <= (n + 15) / 16 + 1) {
+                best_waste = waste;
+                ns = c;
+            }
+        }
+    }
 #define SWIFT_MV_CASE(E)                                                                   \
     case E:                                                                                \
         switch (best_ks) {                                                                 \
-            case 1: return launch_mv1_t<E, 1>(a, best_w, lds, s);                          \
-            case 2: return launch_mv1_t<E, 2>(a, best_w, lds, s);                          \
-            case 4: return launch_mv1_t<E, 4>(a, best_w, lds, s);                          \
-            default: return launch_mv1_t<E, 8>(a, best_w, lds, s);                         \
+            case 1: return launch_mv1_t<E, 1, 16>(a, best_w, lds, s);                      \
+            case 2: return launch_mv1_t<E, 2, 16>(a, best_w, lds, s);                      \
+            case 4: return launch_mv1_t<E, 4, 16>(a, best_w, lds, s);                      \
+            default:                                                                       \
+                switch (ns) {                                                              \
+                    case 10: return launch_mv1_t<E, 8, 10>(a, best_w, lds, s);             \
+                    case 11: return launch_mv1_t<E, 8, 11>(a, best_w, lds, s);             \
+                    case 12: return launch_mv1_t<E, 8, 12>(a, best_w, lds, s);             \
+                    case 13: return launch_mv1_t<E, 8, 13>(a, best_w, lds, s);             \
+                    case 14: return launch_mv1_t<E, 8, 14>(a, best_w, lds, s);             \
+                    case 15: return launch_mv1_t<E, 8, 15>(a, best_w, lds, s);             \
+                    default: return launch_mv1_t<E, 8, 16>(a, best_w, lds, s);             \
+                }                                                                          \
         }
     switch (epi) {
         SWIFT_MV_CASE(EPI_QKV)
