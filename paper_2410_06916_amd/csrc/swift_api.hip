@@ -124,21 +124,21 @@ Layout make_layout(const swift_model_config &c) {
     L.sin = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
     L.kv = take((uint64_t)c.n_layers * 2 * KV * c.max_seq * eb);
     L.n_split_max = kAttnMaxSplit;
-    L.x = take(kMaxRows * H * 4);
-    L.q = take(kMaxRows * Q * 4);
-    L.att = take(kMaxRows * Q * 4);
-    L.h = take(kMaxRows * F * 4);
-    L.logits = take(kMaxRows * V * 4);
+    L.x = take(kMaxBlockRows * H * 4);
+    L.q = take(kMaxBlockRows * Q * 4);
+    L.att = take(kMaxBlockRows * Q * 4);
+    L.h = take(kMaxBlockRows * F * 4);
+    L.logits = take(kMaxBlockRows * V * 4);
     L.part_o = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * c.head_dim * 4);
     L.part_ml = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * 2 * 4);
-    L.out_tok = take(kMaxRows * 4);
-    L.out_conf = take(kMaxRows * 4);
-    L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxRows * 16);
-    L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxRows * 16);
-    L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxRows * 16);
-    L.pss = take(ceil_div(H, 16) * 16 * 4);
+    L.out_tok = take(kMaxBlockRows * 4);
+    L.out_conf = take(kMaxBlockRows * 4);
+    L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxBlockRows * 16);
+    L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxBlockRows * 16);
+    L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxBlockRows * 16);
+    L.pss = take(ceil_div(H, 16) * kMaxBlockRows * 4);
     L.mv_part_capacity = 8192;
-    L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxRows * 4);
+    L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxBlockRows * 4);
     L.mv_counters = take(4096 * 4);
     L.stack_max_stages = 5 * c.n_layers + 1;
     L.stack_tab = take((uint64_t)kStackTables * L.stack_max_stages * sizeof(StackStage));
@@ -409,6 +409,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.T = (K + 31) / 32;
         m.n_rg = n_rg;
         m.R = R;
+        m.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
         m.eps = c.rms_eps;
         m.norm_dim = H;
         m.pos0 = pos0;
@@ -519,6 +520,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     ea.xs = xs;
     ea.gain_next = gain_of(0);
     ea.pss = pss;
+    ea.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
     HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
 
     // ---- one persistent launch where the block qualifies, else one launch per stage
@@ -577,9 +579,17 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         for (size_t i = 0; i < list.size(); ++i) {
             const int kc = classes[i];
             if (list[i].type == ST_ATTN) {
-                const AttnArgs &a = list[i].at;
-                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
-                              [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+                // an attention launch covers up to 16 rows of the block
+                for (int row0 = 0; row0 < R; row0 += kMaxRows) {
+                    AttnArgs a = list[i].at;
+                    a.q += (size_t)row0 * Q;
+                    a.n_ctx += row0;
+                    a.rows = std::min(kMaxRows, R - row0);
+                    a.out_s += 24 * row0;  // first of this part's 3 * rows term columns
+                    a.out_rows = R;
+                    HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
+                                  [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+                }
             } else {
                 const MvArgs &m = list[i].mv;
                 const int epi = list[i].epi;
@@ -732,13 +742,13 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->stack_used = false;
     x->stack_keys.assign(kStackTables, StackKey());
     x->h_err = nullptr;
-    hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxRows + 4) * 4, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxBlockRows + 4) * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete x;
         return fail(SWIFT_EDEVICE, std::string("hipHostMalloc: ") + hipGetErrorString(e));
     }
-    x->h_conf = (float *)(x->h_tok + kMaxRows);
-    x->h_err = x->h_tok + 2 * kMaxRows;
+    x->h_conf = (float *)(x->h_tok + kMaxBlockRows);
+    x->h_err = x->h_tok + 2 * kMaxBlockRows;
     x->h_err[0] = 0;
 
     // rotary tables: angle = pos * theta^(-2i/d) in fp64, cos/sin rounded to fp32
@@ -835,8 +845,10 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     for (int i = 0; i < n_prompt; ++i)
         if (prompt[i] < 0 || prompt[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
     int last_rows = 0;
-    for (int i = 0; i < n_prompt; i += kMaxRows) {
-        last_rows = std::min(kMaxRows, n_prompt - i);
+    // (bf16 models: blocks of up to 64 rows stream the weights once per block)
+    const int block = x->L.tiled ? kMaxBlockRows : kMaxRows;
+    for (int i = 0; i < n_prompt; i += block) {
+        last_rows = std::min(block, n_prompt - i);
         int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt);
         if (rc) return rc;
     }

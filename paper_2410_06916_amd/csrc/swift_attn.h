@@ -168,7 +168,7 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
         if (a.out_s) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
-            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * a.rows) + 3 * row) * 8 + (e & 7);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * (a.out_rows ? a.out_rows : a.rows)) + 3 * row) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;
             p[16] = lo;

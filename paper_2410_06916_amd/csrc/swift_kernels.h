@@ -8,7 +8,8 @@
 
 namespace swift {
 
-constexpr int kMaxRows = 16;       // rows of one block pass (SWIFT_MAX_BLOCK)
+constexpr int kMaxRows = 16;       // rows of one verify block (SWIFT_MAX_BLOCK)
+constexpr int kMaxBlockRows = 64;  // rows of one prefill block
 constexpr int kAttnMaxSplit = 64;  // most cache-length splits of one (row, kv head)
 constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
@@ -57,7 +58,9 @@ struct AttnArgs {
     float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
     int max_split;                // splits the partial buffers can hold
     float *out;                   // fp32 [rows][n_q][d], or nullptr
-    uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*rows][8], or nullptr
+    uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*out_rows][8], or nullptr
+    int out_rows;                 // rows of the block out_s belongs to (0: rows); a launch may cover a
+                                  // 16-row part of a larger block: out_s then points at its first column
 };
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
 
@@ -109,16 +112,17 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s);
 struct MvArgs {
     const void *Wt;        // tiled weights
     int O, K, T, n_rg;     // real rows / depth, k-tiles, row groups
-    int R;                 // activation rows, 1..16
+    int R;                 // activation rows, 1..64
     const uint16_t *in_s;  // split input [K/8][3R][8]
-    const float *pss;      // [n_pss][16] partial sums of squares of the producer, or nullptr: no norm
+    const float *pss;      // [n_pss][rp] partial sums of squares of the producer, or nullptr: no norm
     int n_pss, norm_dim;
+    int rp;                // row pitch of pss and pss_out: 16 for blocks of up to 16 rows, else 64
     float eps;
     float *out_f32;        // QKV: q [R][ld_out]; LOGITS: logits [R][ld_out]; RESID: x [R][ld_out] (in/out)
     int ld_out;
     uint16_t *out_s;       // SWIGLU: split h [F/8][3R][8]; RESID: split of x*gain_next [O/8][3R][8]
     const float *gain_next;  // RESID: [O]
-    float *pss_out;        // RESID: [n_rg][16]
+    float *pss_out;        // RESID: [n_rg][rp]
     void *kcache, *vcache;   // QKV: this layer's [n_kv][max_seq][d]
     const float *cos_tab, *sin_tab;  // QKV: [max_seq][d/2]
     int pos0, max_seq, head_dim, n_q_heads, n_kv_heads;
@@ -146,11 +150,12 @@ hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_o
 struct EmbedRowsArgs {
     const uint16_t *E;  // [V][H] bf16 row-major
     int H, R;
-    int32_t tokens[kMaxRows];
+    int32_t tokens[kMaxBlockRows];
     float *x;           // [R][H]
     uint16_t *xs;       // [H/8][3R][8]
     const float *gain_next;
-    float *pss;         // [ceil(H/16)][16]
+    float *pss;         // [ceil(H/16)][rp]
+    int rp;             // row pitch of pss (16 or 64)
 };
 hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s);
 

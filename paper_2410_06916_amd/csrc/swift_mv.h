@@ -40,7 +40,7 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                 float ss = xn * xn;
 #pragma unroll
                 for (int off = 8; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-                if (r < R && j == 0) a.pss_out[(size_t)rg * 16 + r] = ss;
+                if (r < R && j == 0) a.pss_out[(size_t)rg * a.rp + r] = ss;
             }
         }
     } else {

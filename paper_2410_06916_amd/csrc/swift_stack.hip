@@ -54,6 +54,7 @@ __device__ inline MvArgs uni(const MvArgs &g) {
     m.pss = uni(g.pss);
     m.n_pss = uni(g.n_pss);
     m.norm_dim = uni(g.norm_dim);
+    m.rp = uni(g.rp);
     m.eps = uni(g.eps);
     m.out_f32 = uni(g.out_f32);
     m.ld_out = uni(g.ld_out);
@@ -91,6 +92,7 @@ __device__ inline AttnArgs uni(const AttnArgs &g) {
     t.max_split = 0;
     t.out = uni(g.out);
     t.out_s = uni(g.out_s);
+    t.out_rows = uni(g.out_rows);
     return t;
 }
 
@@ -345,7 +347,7 @@ __global__ __launch_bounds__(1024) void k_stack(StackArgs a) {
 #pragma unroll
                             for (int u = 0; u < 4; ++u) {
                                 const int p = p0 + qg + 64 * u;
-                                v[u] = p < m.n_pss ? m.pss[(size_t)p * 16 + r] : 0.f;
+                                v[u] = p < m.n_pss ? m.pss[(size_t)p * m.rp + r] : 0.f;
                             }
 #pragma unroll
                             for (int u = 0; u < 4; ++u) ss += v[u];

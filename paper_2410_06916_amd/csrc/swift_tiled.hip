@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
         float ss = v * v;
 #pragma unroll
         for (int off = 8; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-        if (idx < total && (i & 15) == 0) a.pss[(size_t)(i >> 4) * 16 + r] = ss;
+        if (idx < total && (i & 15) == 0) a.pss[(size_t)(i >> 4) * a.rp + r] = ss;
     }
 }
 
@@ -136,7 +136,7 @@ __device__ inline NormPart mv_norm_load(const MvArgs &a) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const int p = q + 32 * u;
-        np.v[u] = (a.pss && p < a.n_pss) ? a.pss[(size_t)p * 16 + r] : 0.f;
+        np.v[u] = (a.pss && p < a.n_pss) ? a.pss[(size_t)p * a.rp + r] : 0.f;
     }
     return np;
 }
@@ -152,7 +152,7 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int p = p0 + q + 32 * u;
-                v[u] = p < a.n_pss ? a.pss[(size_t)p * 16 + r] : 0.f;
+                v[u] = p < a.n_pss ? a.pss[(size_t)p * a.rp + r] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) ss += v[u];
@@ -164,6 +164,34 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
         float ss = 0.f;
         if (a.pss)
             for (int q2 = 0; q2 < 32; ++q2) ss += scratch[q2 * 16 + tid];
+        rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
+    }
+    __syncthreads();
+}
+
+// The same for blocks of up to 64 rows (row pitch 64): thread = (partial p mod 8, row r), then 64
+// threads add the 8 per-thread sums in order.  Ends with a barrier.  scratch: LDS [512].
+__device__ inline void mv_norm_rows64(const MvArgs &a, float *rs /* LDS [64] */, float *scratch) {
+    const int tid = threadIdx.x, r = tid & 63, q = tid >> 6;
+    if (a.pss) {
+        float ss = 0.f;
+        for (int p0 = 0; p0 < a.n_pss; p0 += 64) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + q + 8 * u;
+                v[u] = p < a.n_pss ? a.pss[(size_t)p * a.rp + r] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) ss += v[u];
+        }
+        scratch[q * 64 + r] = ss;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        float ss = 0.f;
+        if (a.pss)
+            for (int q2 = 0; q2 < 8; ++q2) ss += scratch[q2 * 64 + tid];
         rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
     }
     __syncthreads();
@@ -444,16 +472,16 @@ struct MvNRegs {
     f32x4 acc[NCB];
 };
 
-template <int EPI, int NCB>
+template <int EPI, int NCB, int CT>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int R = a.R, NC = 3 * R;
-    const int buf_bytes = 64 * NC * 16;
+    const int buf_bytes = 4 * CT * NC * 16;
     // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
     const int main_bytes = max(2 * buf_bytes, NCB * 8192);
     float *rs = (float *)(smem + 16 + (size_t)main_bytes);
-    int *flag = (int *)(rs + 16);
-    float *nscratch = rs + 32;  // [512]
+    int *flag = (int *)(rs + 64);
+    float *nscratch = rs + 80;  // [512]
     float *dump = (float *)(smem + 16);  // reuses the B buffers after the last MFMA
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -463,12 +491,12 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     const int rgc = min(rg, a.n_rg - 1);
     const int tb = (int)blockIdx.y * TS;
     const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
-    const int nch = (nt + 15) >> 4;
+    const int nch = (nt + CT - 1) / CT;
     const int col = lane & 15, kg = lane >> 4;
     const u32x4 *base = (const u32x4 *)a.Wt + ((size_t)rgc * T + tb) * 64 + lane;
     const u32x4 *bsrc = (const u32x4 *)a.in_s;
     const int real_units = (a.K >> 3) * NC;
-    const int chunk_units = 64 * NC;  // 16-byte units of one B chunk
+    const int chunk_units = 4 * CT * NC;  // 16-byte units of one B chunk (<= 3072)
 
     // per-lane B addressing: byte offset inside a buffer for tile u, column block cb:
     //   ((4u + kg) * NC + 16 cb + col) * 16, or the zero chunk when the column does not exist
@@ -485,12 +513,12 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto loadA = [&](int c, u32x4(&A)[16]) {
+    auto loadA = [&](int c, u32x4(&A)[CT]) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) A[u] = __builtin_nontemporal_load(base + (size_t)min(c * 16 + u, nt - 1) * 64);
+        for (int u = 0; u < CT; ++u) A[u] = __builtin_nontemporal_load(base + (size_t)min(c * CT + u, nt - 1) * 64);
     };
     auto loadB = [&](int c, u32x4(&tmp)[6]) {
-        const int gu0 = 4 * (tb + 16 * c) * NC;
+        const int gu0 = 4 * (tb + CT * c) * NC;
         const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int q = 0; q < 6; ++q) {
@@ -506,11 +534,11 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
             if (i < chunk_units) dst[i] = tmp[q];
         }
     };
-    auto mfmas = [&](int c, const u32x4(&A)[16], int bi) {
+    auto mfmas = [&](int c, const u32x4(&A)[CT], int bi) {
         const int bbase = bi * buf_bytes;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int m = (live && c * 16 + u < nt) ? -1 : 0;  // wavefront-uniform
+        for (int u = 0; u < CT; ++u) {
+            const int m = (live && c * CT + u < nt) ? -1 : 0;  // wavefront-uniform
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
                 const int addr = (cboff[cb] + ((bbase + u * tstride) & cbmask[cb])) & m;
@@ -521,21 +549,24 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
         }
     };
 
-    u32x4 A0[16], A1[16], tmp[6];
+    u32x4 A0[CT], A1[CT], tmp[6];
     loadB(0, tmp);
     loadA(0, A0);
     if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
     storeB(0, tmp);
-    mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+    if (a.rp == 16)
+        mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+    else
+        mv_norm_rows64(a, rs, nscratch);
 
-    auto step_full = [&](int c, const u32x4(&Ac)[16], int bc, u32x4(&An)[16], int bn) {
+    auto step_full = [&](int c, const u32x4(&Ac)[CT], int bc, u32x4(&An)[CT], int bn) {
         loadB(c + 1, tmp);
         loadA(c + 1, An);
         __syncthreads();  // chunk c's B is visible; nobody reads buffer bn any more
         storeB(bn, tmp);
         mfmas(c, Ac, bc);
     };
-    auto step_last = [&](int c, const u32x4(&Ac)[16], int bc) {
+    auto step_last = [&](int c, const u32x4(&Ac)[CT], int bc) {
         __syncthreads();
         mfmas(c, Ac, bc);
     };
@@ -601,18 +632,18 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     if (tid == 0) a.counters[blockIdx.x] = 0;
 }
 
-template <int EPI, int NCB>
+template <int EPI, int NCB, int CT>
 static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMvMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int NC = 3 * a.R;
-    const size_t buf2 = 2 * (size_t)64 * NC * 16;
-    const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 128 + 2048;
+    const size_t buf2 = 2 * (size_t)4 * CT * NC * 16;
+    const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 320 + 2048;
     const int n_rb = (a.n_rg + 7) / 8;
     // split K over workgroups until about one workgroup per compute unit exists
     // (never more workgroups than compute units: one workgroup fills a compute unit's registers,
@@ -623,21 +654,24 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
     int TS = (a.T + ksp - 1) / ksp;
     ksp = (a.T + TS - 1) / TS;
-    return launch_maybe_timed(k_mvN<EPI, NCB>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
+    return launch_maybe_timed(k_mvN<EPI, NCB, CT>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
-    if (a.R < 1 || a.R > kMaxRows) return hipErrorInvalidValue;
+    if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp) return hipErrorInvalidValue;
     // small blocks whose whole activation fits in LDS take the single-pass kernel
     if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
-    const int ncb = (3 * a.R + 15) / 16;
+    // up to 16 rows: 1-3 column blocks, K chunks of 16 tiles; 17-64 rows (prefill): 12 column
+    // blocks, K chunks of 4 tiles (a chunk of the split activation is at most 48 KB either way)
+    const int ncb = a.R > kMaxRows ? 12 : (3 * a.R + 15) / 16;
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
         switch (ncb) {                                                  \
-            case 1: return launch_mvN_t<E, 1>(a, n_cu, s);              \
-            case 2: return launch_mvN_t<E, 2>(a, n_cu, s);              \
-            default: return launch_mvN_t<E, 3>(a, n_cu, s);             \
+            case 1: return launch_mvN_t<E, 1, 16>(a, n_cu, s);          \
+            case 2: return launch_mvN_t<E, 2, 16>(a, n_cu, s);          \
+            case 3: return launch_mvN_t<E, 3, 16>(a, n_cu, s);          \
+            default: return launch_mvN_t<E, 12, 4>(a, n_cu, s);         \
         }
     switch (epi) {
         SWIFT_MVN_CASE(EPI_QKV)
