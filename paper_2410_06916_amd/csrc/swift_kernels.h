@@ -113,14 +113,16 @@ struct MvArgs {
     const void *Wt;        // tiled weights
     int O, K, T, n_rg;     // real rows / depth, k-tiles, row groups
     int R;                 // activation rows, 1..64
-    const uint16_t *in_s;  // split input [K/8][3R][8]
+    int RL;                // rows the split layouts (in_s, out_s) are pitched for: R up to 16 rows, else 64
+                           // (columns of rows that do not exist hold garbage that no result depends on)
+    const uint16_t *in_s;  // split input [K/8][3 RL][8]
     const float *pss;      // [n_pss][rp] partial sums of squares of the producer, or nullptr: no norm
     int n_pss, norm_dim;
     int rp;                // row pitch of pss and pss_out: 16 for blocks of up to 16 rows, else 64
     float eps;
     float *out_f32;        // QKV: q [R][ld_out]; LOGITS: logits [R][ld_out]; RESID: x [R][ld_out] (in/out)
     int ld_out;
-    uint16_t *out_s;       // SWIGLU: split h [F/8][3R][8]; RESID: split of x*gain_next [O/8][3R][8]
+    uint16_t *out_s;       // SWIGLU: split h [F/8][3 RL][8]; RESID: split of x*gain_next [O/8][3 RL][8]
     const float *gain_next;  // RESID: [O]
     float *pss_out;        // RESID: [n_rg][rp]
     void *kcache, *vcache;   // QKV: this layer's [n_kv][max_seq][d]
@@ -131,6 +133,7 @@ struct MvArgs {
     int *counters;         // one per 8-row-group block, zero between launches
     int part_capacity;     // row-group-splits the scratch can hold
     int S;                 // set by the launcher
+    int kgroup;            // set by the launcher: K slices whose sums are added first (see mv_slice_group)
 };
 constexpr size_t kMvMaxLds = 150 * 1024;
 // Rows the LDS-resident kernel takes (3R term columns must fit one MFMA column block)
@@ -150,9 +153,10 @@ hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_o
 struct EmbedRowsArgs {
     const uint16_t *E;  // [V][H] bf16 row-major
     int H, R;
+    int RL;             // rows the split layout xs is pitched for (R, or 64 for blocks of more than 16 rows)
     int32_t tokens[kMaxBlockRows];
     float *x;           // [R][H]
-    uint16_t *xs;       // [H/8][3R][8]
+    uint16_t *xs;       // [H/8][3 RL][8]
     const float *gain_next;
     float *pss;         // [ceil(H/16)][rp]
     int rp;             // row pitch of pss (16 or 64)

@@ -370,8 +370,11 @@ template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
     const int ctx = a.n_ctx + a.rows - 1;          // longest row of the block
-    // the one-workgroup-per-head kernel needs enough (kv head, row) pairs to occupy the chip
-    if (ctx <= 1536 && a.n_kv_heads * a.rows >= 24) {
+    // Which kernel runs, and where the cache range is cut, depends on the cache capacity and the head
+    // count only, never on the rows of the block or the current length: a row's result is then the
+    // same bit for bit whether it is computed alone or inside a block.
+    // The one-workgroup-per-head kernel needs enough kv heads to occupy the chip with a single row.
+    if (a.max_seq <= 1600 && a.n_kv_heads >= 24) {
         switch (group) {
             case 1: return launch_attn_head_t<T, 1>(a, s);
             case 2: return launch_attn_head_t<T, 2>(a, s);
@@ -382,15 +385,14 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     }
     const int d = a.head_dim, VEC = T::VEC, SPW = 64 / (d / VEC);
     const int gran = 4 * SPW;                      // slots one workgroup step covers
-    // enough splits for about two workgroups per compute unit, at least one step per workgroup
-    int n_split = (2 * n_cu + a.n_kv_heads * a.rows - 1) / (a.n_kv_heads * a.rows);
-    const int max_split = (ctx + gran - 1) / gran;
-    if (n_split > max_split) n_split = max_split;
-    if (n_split > a.max_split) n_split = a.max_split;
-    if (n_split < 1) n_split = 1;
-    int chunk = (ctx + n_split - 1) / n_split;
+    // chunk length: a full cache cut into enough pieces for about two workgroups per compute unit
+    // with one row
+    int want = (2 * n_cu + a.n_kv_heads - 1) / a.n_kv_heads;
+    if (want > a.max_split) want = a.max_split;
+    if (want < 1) want = 1;
+    int chunk = (a.max_seq + want - 1) / want;
     chunk = (chunk + gran - 1) / gran * gran;
-    n_split = (ctx + chunk - 1) / chunk;
+    const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
     dim3 grid(a.n_kv_heads, n_split, a.rows), block(256);
     switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1>), grid, block, 0, s, a, chunk); break;

@@ -50,6 +50,7 @@ __device__ inline MvArgs uni(const MvArgs &g) {
     m.T = uni(g.T);
     m.n_rg = uni(g.n_rg);
     m.R = uni(g.R);
+    m.RL = uni(g.RL);
     m.in_s = uni(g.in_s);
     m.pss = uni(g.pss);
     m.n_pss = uni(g.n_pss);

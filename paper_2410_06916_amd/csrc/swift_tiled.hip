@@ -87,7 +87,7 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
     // one thread per (row r, element i); 16 consecutive lanes share a 16-element group
-    const int NC = 3 * a.R;
+    const int NC = 3 * a.RL;
     const int Hp = (a.H + 15) & ~15;
     const int total = a.R * Hp;
     for (int idx0 = blockIdx.x * 256; idx0 < total; idx0 += gridDim.x * 256) {
@@ -195,6 +195,25 @@ __device__ inline void mv_norm_rows64(const MvArgs &a, float *rs /* LDS [64] */,
         rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
     }
     __syncthreads();
+}
+
+// Slices (of the 8 K slices of a row group) whose sums are added first, in slice order, before the
+// group sums are added in group order: 8, 4, 2 or 1.  It is the number of slices one workgroup of
+// the block kernel covers when that kernel splits K over workgroups to fill the chip, and it
+// depends on the matrix (and the device) only, so that every kernel adds a row's slice sums in the
+// same order whatever the number of rows in the pass.
+static int mv_slice_group(const MvArgs &a, int n_cu) {
+    const int n_rb = (a.n_rg + 7) / 8;
+    int ksp = n_cu / n_rb;
+    if (ksp < 1) ksp = 1;
+    if (ksp > 8) ksp = 8;
+    int p2 = 1;
+    while (p2 * 2 <= ksp) p2 *= 2;
+    ksp = p2;
+    const int n_c = (a.T + 7) / 8;
+    // (a workgroup's K range holds at least 8 tiles; the partial sums fit the scratch)
+    while (ksp > 1 && (n_c * (8 / ksp) < 8 || (int64_t)ksp * a.n_rg > a.part_capacity)) ksp /= 2;
+    return 8 / ksp;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -352,11 +371,26 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         lds_barrier();  // (the next round's tile loads stay in flight)
         if (!live || ks != 0) continue;
         mv_epilogue<EPI>(a, rg, lane, rs, EPI == EPI_QKV ? rot : nullptr, [&](int r, int j) {
+            // Slice sums are added per term in groups of kgroup slices (slice order), the three
+            // terms of a group are combined, and the groups are added in order.  (Rolled loops: this
+            // runs in one wavefront per row group while the load window stays in registers.)
+            const int kgroup = a.kgroup;
+            const float *w = rp + (g * KS * NC + 3 * r) * 16 + j;
+            const int ss = NC * 16;  // from one slice to the next
             float y = 0.f;
 #pragma unroll 1
-            for (int k2 = 0; k2 < KS; ++k2) {
-                const float *w = rp + ((g * KS + k2) * NC + 3 * r) * 16 + j;
-                y += (w[0] + w[16]) + w[32];
+            for (int k0 = 0; k0 < KS; k0 += kgroup) {
+                float hi = w[0], mid = w[16], lo = w[32];
+                w += ss;
+#pragma unroll 1
+                for (int k2 = 1; k2 < kgroup; ++k2) {
+                    hi += w[0];
+                    mid += w[16];
+                    lo += w[32];
+                    w += ss;
+                }
+                const float gs = (hi + mid) + lo;
+                y = k0 == 0 ? gs : y + gs;
             }
             return y;
         });
@@ -387,14 +421,14 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
     const int max_wg = n_cu * occ;
     int best_ks = 8, best_w = 1, best_s = 1;
     double best_score = 1e30;
+    // Always 8 K slices per row group (unless a tuning run overrides it): the slice boundaries and
+    // the order in which slice sums are added define a row's result bit for bit, and the block kernel
+    // for 6-16 rows uses the same ones, so that a token's logits do not depend on how many rows
+    // share its pass (speculative output == plain greedy output exactly, not just up to rounding).
     for (int ks = 8; ks >= 1; ks /= 2) {
-        if (ks_override && ks != ks_override) continue;
+        if (ks != (ks_override ? ks_override : 8)) continue;
         const int G = 8 / ks;
-        const int n = (a.T + ks - 1) / ks;
-        // many short slices beat few long ones (measured: 16 tiles per wavefront is the sweet spot),
-        // as long as a slice still fills most of the 16-deep load window
-        if (n < 12 && ks > 1 && !ks_override) continue;
-        for (int S = 1; S <= 8; ++S) {
+        for (int S = 1; S <= 64; ++S) {
             int W = (a.n_rg + G * S - 1) / (G * S);
             if (W > max_wg) continue;
             const double waste = (double)W * G * S / a.n_rg;           // >= 1
@@ -414,6 +448,7 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
         best_s = (a.n_rg + G * best_w - 1) / (G * best_w);
     }
     a.S = best_s;
+    a.kgroup = best_ks == 8 ? mv_slice_group(a, n_cu) : best_ks;
     // Slots per block of the load window (= loads in flight per wavefront): 16 unless another depth
     // cuts a slice of n tiles with fewer wasted slots (n = 43: 3 x 15 instead of 3 x 16; n = 20:
     // 2 x 10 instead of 2 x 16).  Only for the 8-way split, which is what the big shapes use.
@@ -457,25 +492,29 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 }
 
 // ------------------------------------------------------------------------------------------
-// a block of 2..16 activation rows: Y = W . X, MFMA, K chunked through LDS, optional split-K
+// a block of 2..64 activation rows: Y = W . X, MFMA, K chunked through LDS, optional split-K
 // ------------------------------------------------------------------------------------------
-// Each of the 8 wavefronts of a workgroup owns one 16-row group of W; the workgroup walks its K
-// range in chunks of 16 tiles.  The B operand of a chunk (64 k-chunks x NC = 3R columns x 16 B,
+// Each of the 8 wavefronts of a workgroup owns RG 16-row groups of W; the workgroup walks its K
+// range in chunks of CT tiles.  The B operand of a chunk (4 CT k-chunks x NC = 3R columns x 16 B,
 // already in B layout in global memory) is copied into one of two LDS buffers while the MFMAs of
 // the previous chunk run; the A tiles of the next chunk are loaded into a second register set at
-// the same time.  NCB = ceil(NC/16) MFMAs per tile.  With gridDim.y > 1 the K range is split over
-// workgroups: each writes its partial results, and the workgroup that arrives last at a counter
-// adds the partials in split order (so the result does not depend on arrival order) and runs the
-// epilogue.
-template <int NCB>
-struct MvNRegs {
-    f32x4 acc[NCB];
-};
-
-template <int EPI, int NCB, int CT>
+// the same time.  NCB = ceil(NC/16) column blocks; a B operand read from LDS feeds RG MFMAs (with
+// RG = 2 the LDS traffic per MFMA halves, which is what bounds the 64-row case).  With
+// gridDim.y > 1 the K range is split over workgroups: each writes its partial results, and the
+// workgroup that arrives last at a counter adds the partials in split order (so the result does
+// not depend on arrival order) and runs the epilogue.
+//
+// NCB <= 3 (verify blocks of up to 16 rows) reproduces the LDS-resident kernel bit for bit: the K
+// range of a row group is cut into the same 8 slices of ceil(T/8) tiles, a slice is accumulated from
+// zero tile by tile, a workgroup covers a group of 8, 4, 2 or 1 whole slices (mv_slice_group: a
+// function of the matrix alone, not of the row count) and adds their sums per term in slice order,
+// combines the three terms, and the last workgroup adds the group results in order.  The
+// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 12 (prefill) keeps its own
+// fixed order.
+template <int EPI, int NCB, int CT, int RG>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int R = a.R, NC = 3 * R;
+    const int R = a.R, NC = 3 * a.RL;  // NC: columns of the split input as laid out (= 16 NCB when NCB = 12)
     const int buf_bytes = 4 * CT * NC * 16;
     // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
     const int main_bytes = max(2 * buf_bytes, NCB * 8192);
@@ -486,124 +525,166 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = a.T;
-    const int rg = (int)blockIdx.x * 8 + wave;
-    const bool live = rg < a.n_rg;
-    const int rgc = min(rg, a.n_rg - 1);
+    const int rg0 = ((int)blockIdx.x * 8 + wave) * RG;  // first row group of this wavefront
     const int tb = (int)blockIdx.y * TS;
     const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
-    const int nch = (nt + CT - 1) / CT;
     const int col = lane & 15, kg = lane >> 4;
-    const u32x4 *base = (const u32x4 *)a.Wt + ((size_t)rgc * T + tb) * 64 + lane;
+    constexpr bool kCanon = NCB <= 3;  // verify blocks; the 12-column-block prefill variant keeps its own order
+    // A slice is walked in chunks of CT tiles that do not run over its end (the last chunk of a slice
+    // may be partial), so that slices end between chunks.  The prefill variant has one "slice": its
+    // whole K range.
+    const int n_c = kCanon ? (T + 7) >> 3 : nt;   // tiles of a slice
+    const int nchs = (n_c + CT - 1) / CT;         // chunks of a slice
+    const int nch = ((nt + n_c - 1) / n_c - 1) * nchs + ((nt - 1) % n_c) / CT + 1;  // chunks of this workgroup
+    const int KSP = gridDim.y;
+    // first tile (relative to tb) of chunk c, and the tiles of it that exist
+    auto chunk_t0 = [&](int c) { return (c / nchs) * n_c + (c % nchs) * CT; };
+    auto chunk_nt = [&](int c) { return min(min(CT, n_c - (c % nchs) * CT), nt - chunk_t0(c)); };
+    const u32x4 *base[RG];
+#pragma unroll
+    for (int g = 0; g < RG; ++g)  // row groups past the end repeat the last one; their results are dropped
+        base[g] = (const u32x4 *)a.Wt + ((size_t)min(rg0 + g, a.n_rg - 1) * T + tb) * 64 + lane;
     const u32x4 *bsrc = (const u32x4 *)a.in_s;
     const int real_units = (a.K >> 3) * NC;
-    const int chunk_units = 4 * CT * NC;  // 16-byte units of one B chunk (<= 3072)
+    const int chunk_units = 4 * CT * NC;  // 16-byte units of one B chunk (<= 512 NQ)
+    constexpr int NQ = (4 * CT * NCB * 16 + 511) / 512;  // ... per thread
 
     // per-lane B addressing: byte offset inside a buffer for tile u, column block cb:
     //   ((4u + kg) * NC + 16 cb + col) * 16, or the zero chunk when the column does not exist
-    int cboff[NCB], cbmask[NCB];
+    // (NCB = 12: the layout has exactly 192 columns, every column exists, and column block cb is
+    // 256 bytes after block 0: one register instead of two per block)
+    constexpr bool kFull = NCB == 12;
+    int cboff[kFull ? 1 : NCB], cbmask[kFull ? 1 : NCB];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
+    for (int cb = 0; cb < (kFull ? 1 : NCB); ++cb) {
         const bool okc = 16 * cb + col < NC;
         cboff[cb] = okc ? 16 + (kg * NC + 16 * cb + col) * 16 : 0;
         cbmask[cb] = okc ? -1 : 0;
     }
     const int tstride = 4 * NC * 16;
 
-    f32x4 acc[NCB];
+    f32x4 acc[RG][NCB];
+    // The sums of this workgroup's slices are added in slice order as the slices are completed.
+    f32x4 ssum[kCanon ? NCB : 1];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto loadA = [&](int c, u32x4(&A)[CT]) {
+    for (int g = 0; g < RG; ++g)
 #pragma unroll
-        for (int u = 0; u < CT; ++u) A[u] = __builtin_nontemporal_load(base + (size_t)min(c * CT + u, nt - 1) * 64);
+        for (int cb = 0; cb < NCB; ++cb) acc[g][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cb = 0; cb < (kCanon ? NCB : 1); ++cb) ssum[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto slice_end = [&]() {
+#pragma unroll
+        for (int cb = 0; cb < (kCanon ? NCB : 1); ++cb) {
+            ssum[cb] += acc[0][cb];
+            acc[0][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     };
-    auto loadB = [&](int c, u32x4(&tmp)[6]) {
-        const int gu0 = 4 * (tb + CT * c) * NC;
+    auto loadA = [&](int c, u32x4(&A)[RG][CT]) {
+        const int t0 = chunk_t0(c);
+#pragma unroll
+        for (int g = 0; g < RG; ++g)
+#pragma unroll
+            for (int u = 0; u < CT; ++u)
+                A[g][u] = __builtin_nontemporal_load(base[g] + (size_t)min(t0 + u, nt - 1) * 64);
+    };
+    auto loadB = [&](int c, u32x4(&tmp)[NQ]) {
+        const int gu0 = 4 * (tb + chunk_t0(c)) * NC;
         const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
+        for (int q = 0; q < NQ; ++q) {
             const int i = tid + 512 * q;
             tmp[q] = (i < chunk_units && gu0 + i < real_units) ? bsrc[gu0 + i] : zero;
         }
     };
-    auto storeB = [&](int bi, const u32x4(&tmp)[6]) {
+    auto storeB = [&](int bi, const u32x4(&tmp)[NQ]) {
         u32x4 *dst = (u32x4 *)(smem + 16 + (size_t)bi * buf_bytes);
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
+        for (int q = 0; q < NQ; ++q) {
             const int i = tid + 512 * q;
             if (i < chunk_units) dst[i] = tmp[q];
         }
     };
-    auto mfmas = [&](int c, const u32x4(&A)[CT], int bi) {
+    auto mfmas = [&](int c, const u32x4(&A)[RG][CT], int bi) {
         const int bbase = bi * buf_bytes;
+        const int ntc = chunk_nt(c);
 #pragma unroll
         for (int u = 0; u < CT; ++u) {
-            const int m = (live && c * CT + u < nt) ? -1 : 0;  // wavefront-uniform
+            const int m = (u < ntc) ? -1 : 0;  // wavefront-uniform: slots past the chunk's tiles add zeros
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const int addr = (cboff[cb] + ((bbase + u * tstride) & cbmask[cb])) & m;
+                const int addr = kFull ? ((cboff[0] + bbase + u * tstride + 256 * cb) & m)
+                                       : ((cboff[kFull ? 0 : cb] + ((bbase + u * tstride) & cbmask[kFull ? 0 : cb])) & m);
                 const u32x4 bv = *(const u32x4 *)(smem + addr);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[u]),
-                                                                  __builtin_bit_cast(bf16x8, bv), acc[cb], 0, 0, 0);
+#pragma unroll
+                for (int g = 0; g < RG; ++g)
+                    acc[g][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[g][u]),
+                                                                         __builtin_bit_cast(bf16x8, bv), acc[g][cb], 0, 0, 0);
             }
         }
+        if (kCanon && ((c + 1) % nchs == 0 || c + 1 == nch)) slice_end();
     };
 
-    u32x4 A0[CT], A1[CT], tmp[6];
+    // Pipeline: while the MFMAs of chunk c run, the A tiles of chunk c + 1 and the B operand of
+    // chunk c + 2 are on their way from memory, and the B operand of chunk c + 1 (loaded during
+    // the previous step) is copied into the other LDS buffer.  One LDS-only barrier per step: it
+    // does not wait for the loads in flight.
+    u32x4 A0[RG][CT], A1[RG][CT], tmp[NQ];
     loadB(0, tmp);
     loadA(0, A0);
     if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
     storeB(0, tmp);
+    if (nch > 1) loadB(1, tmp);
     if (a.rp == 16)
         mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
     else
         mv_norm_rows64(a, rs, nscratch);
 
-    auto step_full = [&](int c, const u32x4(&Ac)[CT], int bc, u32x4(&An)[CT], int bn) {
-        loadB(c + 1, tmp);
-        loadA(c + 1, An);
-        __syncthreads();  // chunk c's B is visible; nobody reads buffer bn any more
-        storeB(bn, tmp);
+    auto step = [&](int c, const u32x4(&Ac)[RG][CT], int bc, u32x4(&An)[RG][CT], int bn) {
+        lds_barrier();  // chunk c's B is visible; nobody reads buffer bn any more
+        if (c + 1 < nch) {
+            storeB(bn, tmp);
+            if (c + 2 < nch) loadB(c + 2, tmp);
+            loadA(c + 1, An);
+        }
         mfmas(c, Ac, bc);
     };
-    auto step_last = [&](int c, const u32x4(&Ac)[CT], int bc) {
-        __syncthreads();
-        mfmas(c, Ac, bc);
-    };
-    int c = 0;
-    for (; c + 2 < nch; c += 2) {
-        step_full(c, A0, 0, A1, 1);
-        step_full(c + 1, A1, 1, A0, 0);
-    }
-    if (nch - c == 2) {
-        step_full(c, A0, 0, A1, 1);
-        step_last(c + 1, A1, 1);
-    } else {
-        step_last(c, A0, 0);
+    for (int c = 0; c < nch; c += 2) {
+        step(c, A0, 0, A1, 1);
+        if (c + 1 < nch) step(c + 1, A1, 1, A0, 0);
     }
 
-    // ---- results to LDS: dump[wave][column][tile row]
-    __syncthreads();
+    // ---- per row group of the wavefront: results to LDS (dump[wave][column][tile row]), then the
+    // epilogue, or with split K the partial
     float *dw = dump + (size_t)wave * (NCB * 256);
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) dw[(16 * cb + col) * 16 + 4 * kg + r4] = acc[cb][r4];
-    __syncthreads();
     auto y_local = [&](int r, int j) { return (dw[(3 * r) * 16 + j] + dw[(3 * r + 1) * 16 + j]) + dw[(3 * r + 2) * 16 + j]; };
-
-    if (gridDim.y == 1) {
-        if (live) mv_epilogue<EPI>(a, rg, lane, rs, nullptr, y_local);
-        return;
+    auto dump_regs = [&](const f32x4(&v)[NCB]) {
+        __syncthreads();  // the B buffers / the previous dump are no longer read
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) dw[(16 * cb + col) * 16 + 4 * kg + r4] = v[cb][r4];
+        __syncthreads();
+    };
+#pragma unroll
+    for (int g = 0; g < RG; ++g) {
+        const int rg = rg0 + g;
+        const bool live = rg < a.n_rg;
+        if constexpr (kCanon)
+            dump_regs(ssum);  // (RG = 1) the sum of this workgroup's slices, per term
+        else
+            dump_regs(acc[g]);
+        if (KSP == 1) {
+            if (live) mv_epilogue<EPI>(a, rg, lane, rs, nullptr, y_local);
+        } else if (live) {
+            // publish the partial, terms combined (device-scope atomic stores write through, so the
+            // release below has nothing to flush)
+            float *pp = a.part + ((size_t)blockIdx.y * a.n_rg + rg) * (16 * R);
+            for (int idx = lane; idx < 16 * R; idx += 64)
+                __hip_atomic_store(pp + idx, y_local(idx >> 4, idx & 15), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
-    // ---- split-K: publish the partial, last workgroup of this row block reduces
-    const int KSP = gridDim.y;
-    if (live) {
-        float *pp = a.part + ((size_t)blockIdx.y * a.n_rg + rg) * (16 * R);
-        // (device-scope atomic stores write through, so the release below has nothing to flush)
-        for (int idx = lane; idx < 16 * R; idx += 64)
-            __hip_atomic_store(pp + idx, y_local(idx >> 4, idx & 15), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    if (KSP == 1) return;
+    // ---- split-K: the last workgroup of this row block to arrive reduces.
     // One release/acquire per workgroup: the barrier orders every wavefront's partial stores before
     // thread 0's device-scope read-modify-write on the counter, which publishes them (release) and,
     // in the workgroup that arrives last, makes the other workgroups' partials visible (acquire).
@@ -615,63 +696,73 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     }
     __syncthreads();
     if (*flag == 0) return;
-    if (live) {
+    // (plain loads below: ordered after thread 0's acquire by the barrier)
+#pragma unroll
+    for (int g = 0; g < RG; ++g) {
+        const int rg = rg0 + g;
+        if (rg >= a.n_rg) continue;
         const float *p0 = a.part + (size_t)rg * (16 * R);
         const size_t sstride = (size_t)a.n_rg * (16 * R);
-        // (plain loads: ordered after thread 0's acquire by the barrier)
         mv_epilogue<EPI>(a, rg, lane, rs, nullptr, [&](int r, int j) {
             float v[8];
 #pragma unroll
             for (int s2 = 0; s2 < 8; ++s2) v[s2] = s2 < KSP ? p0[s2 * sstride + r * 16 + j] : 0.f;
-            float y = 0.f;
+            float y = v[0];
 #pragma unroll
-            for (int s2 = 0; s2 < 8; ++s2) y += v[s2];
+            for (int s2 = 1; s2 < 8; ++s2) y += v[s2];
             return y;
         });
     }
     if (tid == 0) a.counters[blockIdx.x] = 0;
 }
 
-template <int EPI, int NCB, int CT>
+template <int EPI, int NCB, int CT, int RG>
 static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)kMvMaxLds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT, RG>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMvMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int NC = 3 * a.R;
+    const int NC = 3 * a.RL;
     const size_t buf2 = 2 * (size_t)4 * CT * NC * 16;
     const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 320 + 2048;
-    const int n_rb = (a.n_rg + 7) / 8;
+    const int n_rb = (a.n_rg + 8 * RG - 1) / (8 * RG);
     // split K over workgroups until about one workgroup per compute unit exists
     // (never more workgroups than compute units: one workgroup fills a compute unit's registers,
     // so a partial second round would double the kernel's duration)
     int ksp = n_cu / n_rb;
     if (ksp < 1) ksp = 1;
     if (ksp > 8) ksp = 8;
-    while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
-    int TS = (a.T + ksp - 1) / ksp;
-    ksp = (a.T + TS - 1) / TS;
-    return launch_maybe_timed(k_mvN<EPI, NCB, CT>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
+    int TS;
+    if (NCB <= 3) {
+        TS = ((a.T + 7) / 8) * mv_slice_group(a, n_cu);
+    } else {
+        while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
+        TS = (a.T + ksp - 1) / ksp;
+    }
+    ksp = (a.T + TS - 1) / TS;  // workgroups whose K range holds tiles
+    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
-    if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp) return hipErrorInvalidValue;
+    if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp ||
+        a.RL != (a.R <= kMaxRows ? a.R : kMaxBlockRows))
+        return hipErrorInvalidValue;
     // small blocks whose whole activation fits in LDS take the single-pass kernel
     if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
-    // up to 16 rows: 1-3 column blocks, K chunks of 16 tiles; 17-64 rows (prefill): 12 column
-    // blocks, K chunks of 4 tiles (a chunk of the split activation is at most 48 KB either way)
+    // up to 16 rows: 1-3 column blocks, K chunks of 8 tiles; 17-64 rows (prefill): 12 column
+    // blocks, K chunks of 4 tiles (48 KB of split activation per chunk)
     const int ncb = a.R > kMaxRows ? 12 : (3 * a.R + 15) / 16;
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
         switch (ncb) {                                                  \
-            case 1: return launch_mvN_t<E, 1, 16>(a, n_cu, s);          \
-            case 2: return launch_mvN_t<E, 2, 16>(a, n_cu, s);          \
-            case 3: return launch_mvN_t<E, 3, 16>(a, n_cu, s);          \
-            default: return launch_mvN_t<E, 12, 4>(a, n_cu, s);         \
+            case 1: return launch_mvN_t<E, 1, 8, 1>(a, n_cu, s);          \
+            case 2: return launch_mvN_t<E, 2, 8, 1>(a, n_cu, s);          \
+            case 3: return launch_mvN_t<E, 3, 8, 1>(a, n_cu, s);          \
+            default: return launch_mvN_t<E, 12, 4, 1>(a, n_cu, s);         \
         }
     switch (epi) {
         SWIFT_MVN_CASE(EPI_QKV)

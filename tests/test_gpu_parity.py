@@ -193,6 +193,43 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     g.close()
 
 
+@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers"])
+def test_block_rows_equal_single_rows_bit_for_bit(case):
+    """What makes speculative output equal plain greedy output exactly rather than up to rounding
+    (Sections 1 and 3.1: verification leaves the output unchanged): the logits of a token do not
+    depend on how many rows share its pass.  Rows of verify blocks of 2..16 tokens against the same
+    tokens decoded one at a time, compared bit for bit; both attention kernels, the LDS-resident and
+    the block projection kernel, split K over 1..8 workgroups."""
+    import paper_2410_06916_amd as P
+    if case == "7b-width-2-layers":
+        shape, weights, max_seq, n_prompt = si.LLAMA2_7B.with_layers(2), None, 64, 20
+    else:
+        shape = hp.SMALL_GQA_BF16
+        weights = hp.shaped_weights(shape, seed=3)
+        max_seq, n_prompt = (1700, 70) if case.endswith("long-cache") else (96, 12)
+    g = P.SwiftModel(shape, max_seq)
+    if weights is None:
+        for nm, t in _gpu_weights(shape, 0):
+            g.load_tensor(nm, t)
+    else:
+        g.load_weights(weights)
+    g.prefill(si.uniform_ids(4, n_prompt, shape.vocab))
+    n0, t0 = g.cache_len, g.pending
+    toks, rows = [t0], []
+    for _ in range(16):
+        tgt, lg = g.verify([g.pending], True)
+        g.accept()
+        toks.append(int(tgt[0]))
+        rows.append(lg[0].copy())
+    for R in (2, 5, 6, 9, 16):
+        g.rollback(n0, t0)
+        tgt, lg = g.verify(toks[:R], True)
+        assert [int(x) for x in tgt] == toks[1:R + 1]
+        for r in range(R):
+            assert np.array_equal(lg[r], rows[r]), (case, R, r, np.abs(lg[r] - rows[r]).max())
+    g.close()
+
+
 @pytest.mark.parametrize("case", ["small-gqa-bf16", "7b-width-2-layers"])
 def test_persistent_stack_kernel_matches_oracle(oracle_lib, case):
     """The opt-in one-launch-per-pass path (grid-wide barriers between stages, bounded polling):
