@@ -260,7 +260,8 @@ def main():
         prefill_info = {"ms": round(t_pf * 1e3, 2), "tokens_per_s": round(w.n_prompt / t_pf, 1),
                         "algorithmic_TFLOPs": round(flops / t_pf / 1e12, 2),
                         "mfma_frac_of_2500_TFLOPs": round(flops / t_pf / 2.5e15, 4),
-                        "note": "16-row blocks: each block streams all weights once, so prefill is HBM-bound here"}
+                        "note": "64-row blocks (192 MFMA columns per weight tile with the three-term activations); "
+                                "flops counted once per product, not per term"}
         log(f"[bench] passes: {passes}")
 
     if args.pmc_calibration:
