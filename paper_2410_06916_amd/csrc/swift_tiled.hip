@@ -550,17 +550,10 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     constexpr int NQ = (4 * CT * NCB * 16 + 511) / 512;  // ... per thread
 
     // per-lane B addressing: byte offset inside a buffer for tile u, column block cb:
-    //   ((4u + kg) * NC + 16 cb + col) * 16, or the zero chunk when the column does not exist
-    // (NCB = 12: the layout has exactly 192 columns, every column exists, and column block cb is
-    // 256 bytes after block 0: one register instead of two per block)
-    constexpr bool kFull = NCB == 12;
-    int cboff[kFull ? 1 : NCB], cbmask[kFull ? 1 : NCB];
-#pragma unroll
-    for (int cb = 0; cb < (kFull ? 1 : NCB); ++cb) {
-        const bool okc = 16 * cb + col < NC;
-        cboff[cb] = okc ? 16 + (kg * NC + 16 * cb + col) * 16 : 0;
-        cbmask[cb] = okc ? -1 : 0;
-    }
+    //   ((4u + kg) * NC + 16 cb + col) * 16 = boff0 + u * tstride + 256 cb.
+    // Columns that do not exist (col >= NC in the last block, rows >= R of a 64-row layout) read
+    // whatever lies there: they only produce result columns that nobody reads.
+    const int boff0 = 16 + (kg * NC + col) * 16;
     const int tstride = 4 * NC * 16;
 
     f32x4 acc[RG][NCB];
@@ -604,21 +597,35 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
             if (i < chunk_units) dst[i] = tmp[q];
         }
     };
+    // The B operands of a tile (NCB LDS reads) are requested one tile ahead of the MFMAs that use
+    // them.  Slots past the chunk's tiles multiply a zero A operand.
     auto mfmas = [&](int c, const u32x4(&A)[RG][CT], int bi) {
-        const int bbase = bi * buf_bytes;
         const int ntc = chunk_nt(c);
+        const unsigned char *bp = smem + boff0 + bi * buf_bytes;
+        u32x4 bq[2][NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bq[0][cb] = *(const u32x4 *)(bp + 256 * cb);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < CT; ++u) {
-            const int m = (u < ntc) ? -1 : 0;  // wavefront-uniform: slots past the chunk's tiles add zeros
+            if (u + 1 < CT) {
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                const int addr = kFull ? ((cboff[0] + bbase + u * tstride + 256 * cb) & m)
-                                       : ((cboff[kFull ? 0 : cb] + ((bbase + u * tstride) & cbmask[kFull ? 0 : cb])) & m);
-                const u32x4 bv = *(const u32x4 *)(smem + addr);
+                for (int cb = 0; cb < NCB; ++cb)
+                    bq[(u + 1) & 1][cb] = *(const u32x4 *)(bp + (u + 1) * tstride + 256 * cb);
+            }
+            // (keep the reads above the MFMAs: left alone, the scheduler sinks each read to just
+            // before its use to save registers, and every MFMA then waits out the LDS latency)
+            __builtin_amdgcn_sched_barrier(0);
+            const bool ok = u < ntc;  // wavefront-uniform
 #pragma unroll
-                for (int g = 0; g < RG; ++g)
-                    acc[g][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[g][u]),
-                                                                         __builtin_bit_cast(bf16x8, bv), acc[g][cb], 0, 0, 0);
+            for (int g = 0; g < RG; ++g) {
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                const u32x4 av = ok ? A[g][u] : zero;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    acc[g][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                         __builtin_bit_cast(bf16x8, bq[u & 1][cb]),
+                                                                         acc[g][cb], 0, 0, 0);
             }
         }
         if (kCanon && ((c + 1) % nchs == 0 || c + 1 == nch)) slice_end();
