@@ -423,11 +423,29 @@ __global__ __launch_bounds__(1024) void k_argmax_conf(ArgmaxArgs a) {
     __shared__ float ssum[16];
     float best = -INFINITY;
     int bi = 0x7fffffff;
-    for (int i = tid; i < a.V; i += 1024) {
-        const float v = lg[i];
-        if (v > best) {  // i increases per thread, so the first maximum is kept
-            best = v;
-            bi = i;
+    // up to 32 logits per thread stay in registers (one round of loads, all in flight together)
+    constexpr int PT = 32;
+    const bool in_regs = a.V <= 1024 * PT;
+    float v[PT];
+    if (in_regs) {
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+            const int i = tid + 1024 * k;
+            v[k] = i < a.V ? lg[i] : -INFINITY;
+        }
+#pragma unroll
+        for (int k = 0; k < PT; ++k)
+            if (v[k] > best) {  // i increases with k, so the first maximum is kept
+                best = v[k];
+                bi = tid + 1024 * k;
+            }
+    } else {
+        for (int i = tid; i < a.V; i += 1024) {
+            const float x = lg[i];
+            if (x > best) {  // i increases per thread, so the first maximum is kept
+                best = x;
+                bi = i;
+            }
         }
     }
 #pragma unroll
@@ -452,7 +470,13 @@ __global__ __launch_bounds__(1024) void k_argmax_conf(ArgmaxArgs a) {
             bi = sidx[w];
         }
     float sum = 0.f;
-    for (int i = tid; i < a.V; i += 1024) sum += expf(lg[i] - best);
+    if (in_regs) {
+#pragma unroll
+        for (int k = 0; k < PT; ++k)
+            if (tid + 1024 * k < a.V) sum += expf(v[k] - best);
+    } else {
+        for (int i = tid; i < a.V; i += 1024) sum += expf(lg[i] - best);
+    }
     sum = wave_sum(sum);
     if (lane == 0) ssum[wave] = sum;
     __syncthreads();

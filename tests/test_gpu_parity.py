@@ -132,6 +132,33 @@ def test_draft_logits_and_cache_contents(oracle_lib):
     g.close()
 
 
+def test_prefill_block_sizes_against_oracle(oracle_lib):
+    """Prompt lengths around the prefill block sizes (one row, the LDS-resident kernel's five, the
+    16-row verify variants, a ragged 64-row block, exactly 64, 64 + 1, two blocks and a tail): first
+    token, the cache a prompt leaves behind (bf16 slots: equal up to one rounding step) and the
+    greedy continuation."""
+    import paper_2410_06916_amd as P
+    shape = hp.SMALL_GQA_BF16
+    weights = hp.shaped_weights(shape, seed=8)
+    o, g = _pair(oracle_lib, shape, weights, 200, threads=1)
+    for n_prompt in (1, 5, 6, 16, 17, 63, 64, 65, 150):
+        prompt = si.uniform_ids(30 + n_prompt, n_prompt, shape.vocab)
+        want = oracle_lib.generate_ar(o, prompt, 6)
+        got = P.generate_ar(g, prompt, 6)
+        assert np.array_equal(got, want), n_prompt
+        o.prefill(prompt)
+        g.prefill(prompt)
+        for layer in range(shape.n_layers):
+            for pos in sorted({0, n_prompt // 2, n_prompt - 1}):
+                ko, vo = o.read_kv(layer, pos)
+                kg, vg = g.read_kv(layer, pos)
+                # a value next to a bf16 rounding boundary may land on the other side
+                assert np.allclose(kg, ko, rtol=2 ** -7, atol=1e-6), (n_prompt, layer, pos)
+                assert np.allclose(vg, vo, rtol=2 ** -7, atol=1e-6), (n_prompt, layer, pos)
+                assert (kg != ko).mean() < 0.05 and (vg != vo).mean() < 0.05
+    g.close()
+
+
 def test_errors_and_state_machine_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
