@@ -55,6 +55,7 @@ def lib():
         L.ora_set_threads.restype = None
         L.ora_set_tensor.argtypes = [vp, C.c_char_p, vp, C.c_int, C.c_int64]
         L.ora_forward_row.argtypes = [vp, C.c_int32, C.c_int, u8p, f64p]
+        L.ora_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int), f64p]
         L.ora_forward_nocache.argtypes = [vp, i32p, C.c_int, f64p]
         L.ora_reset.argtypes = [vp]
         L.ora_prefill.argtypes = [vp, i32p, C.c_int, i32p, f64p]
@@ -217,6 +218,20 @@ class Oracle:
         lg = np.empty(self.vocab, np.float64)
         _chk(lib().ora_forward_nocache(self._h, _p(t, C.c_int32), t.size, _p(lg, C.c_double)), "ora_forward_nocache")
         return lg
+
+    def eval_mask(self, skip: np.ndarray, window: Sequence[int], want_logits: bool = False):
+        """Parallel candidate evaluation (Section 4.1.2, Eq. 3-4).  window: the tokens at positions
+        n - gamma .. n (gamma committed tokens, then the pending token).  Returns (predicted[gamma],
+        n_match[, logits[gamma][vocab]]); matchness = n_match / gamma."""
+        w = np.ascontiguousarray(window, np.int32)
+        gamma = w.size - 1
+        skip = np.ascontiguousarray(skip, np.uint8)
+        pred = np.empty(max(gamma, 0), np.int32)
+        lg = np.empty((gamma, self.vocab), np.float64) if want_logits else None
+        nm = C.c_int(0)
+        _chk(lib().ora_eval_mask(self._h, _p(skip, C.c_uint8), _p(w, C.c_int32), gamma, _p(pred, C.c_int32),
+                                 C.byref(nm), _p(lg, C.c_double) if want_logits else None), "ora_eval_mask")
+        return (pred, nm.value, lg) if want_logits else (pred, nm.value)
 
     # -- decoding steps
     def reset(self):

@@ -25,6 +25,11 @@
  *   - Plain greedy autoregressive decoding (the definition the method must
  *     reproduce token for token), a brute-force forward without any cache,
  *     and the expected-speedup closed form (Appendix B.3, Eq. 6).
+ *   - Parallel candidate evaluation of the optimisation phase (Section 4.1.2,
+ *     Eq. 3 and Eq. 4): a candidate draft model predicts each of the last
+ *     gamma generated tokens from the context before it, reusing the target
+ *     model's cached keys and values, and the matchness score counts the
+ *     predictions that equal the generated tokens.
  *
  * Arithmetic
  *   Every floating-point step is carried out in fp64.  Rounding happens only
@@ -46,7 +51,10 @@
  * brute-force forward; closed forms for the all-skipped draft, single-slot
  * and equal-key attention, uniform logits; RoPE worked example and
  * relative-position property; RMSNorm invariances; Eq. 6 against the values
- * printed in the paper's Table 4.
+ * printed in the paper's Table 4; candidate evaluation: the empty skipped set
+ * scores gamma out of gamma on the model's own greedy output, the all-skipped
+ * set has a closed form, rows do not depend on later cache slots, the decoding
+ * state is left untouched.
  * Parity unpinned: behaviour on trained weights (acceptance rates, M, the
  * measured speedups) -- needs checkpoints and datasets that are not available.
  */
@@ -327,7 +335,11 @@ static float *vslot(const ora_model *m, int l, int pos) {
  * sublayers in `skip` bypassed (skip == NULL: the full target model).
  * Reads cache slots [0,pos) and writes slot pos in every non-skipped attention
  * sublayer.  logits: fp64 [vocab]. */
-int ora_forward_row(ora_model *m, int32_t token, int pos, const uint8_t *skip, double *logits) {
+/* One token through the network at position pos.  reuse_kv = 0: the row's keys and values are
+ * computed and written to cache slot pos before the row attends slots 0..pos.  reuse_kv = 1
+ * (candidate evaluation): nothing is written; the row attends the keys and values that slots
+ * 0..pos already hold. */
+static int forward_row_impl(ora_model *m, int32_t token, int pos, const uint8_t *skip, double *logits, int reuse_kv) {
     const ora_config *c = &m->c;
     if (token < 0 || token >= c->vocab) return ORA_EINVAL;
     if (pos < 0 || pos >= c->max_seq) return ORA_ECAPACITY;
@@ -350,14 +362,16 @@ int ora_forward_row(ora_model *m, int32_t token, int pos, const uint8_t *skip, d
         if (!(skip && skip[2 * l])) {
             rmsnorm_t(x, &y->attn_norm, H, c->rms_eps, xh);
             matvec(m, &y->wq, Q, H, xh, q);
-            matvec(m, &y->wk, KV, H, xh, k);
-            matvec(m, &y->wv, KV, H, xh, v);
             for (int h = 0; h < nq; ++h) ora_rope(q + h * d, d, pos, c->rope_theta);
-            for (int h = 0; h < nkv; ++h) ora_rope(k + h * d, d, pos, c->rope_theta);
-            float *ks = kslot(m, l, pos), *vs = vslot(m, l, pos);
-            for (int i = 0; i < KV; ++i) {
-                ks[i] = round_kv(c, k[i]);
-                vs[i] = round_kv(c, v[i]);
+            if (!reuse_kv) {
+                matvec(m, &y->wk, KV, H, xh, k);
+                matvec(m, &y->wv, KV, H, xh, v);
+                for (int h = 0; h < nkv; ++h) ora_rope(k + h * d, d, pos, c->rope_theta);
+                float *ks = kslot(m, l, pos), *vs = vslot(m, l, pos);
+                for (int i = 0; i < KV; ++i) {
+                    ks[i] = round_kv(c, k[i]);
+                    vs[i] = round_kv(c, v[i]);
+                }
             }
 #pragma omp parallel for schedule(static) num_threads(m->threads)
             for (int h = 0; h < nq; ++h) {
@@ -380,6 +394,43 @@ int ora_forward_row(ora_model *m, int32_t token, int pos, const uint8_t *skip, d
     matvec(m, &m->lm_head, c->vocab, H, xh, logits);
 
     free(x); free(xh); free(q); free(k); free(v); free(att); free(tmp); free(hg); free(hu);
+    return ORA_OK;
+}
+
+int ora_forward_row(ora_model *m, int32_t token, int pos, const uint8_t *skip, double *logits) {
+    return forward_row_impl(m, token, pos, skip, logits, 0);
+}
+
+/* Parallel candidate evaluation (Section 4.1.2).  window[0..gamma] are the tokens at positions
+ * n - gamma .. n of the sequence decoded so far: window[0..gamma-1] are committed to the cache
+ * (slots n - gamma .. n - 1 hold the target model's keys and values for them), window[gamma] is
+ * the pending token.  The draft model with skipped set `skip` reads window[i-1] at position
+ * n - gamma + i - 1, attends the target's cached keys and values of slots 0 .. n - gamma + i - 1
+ * (Eq. 3: conditioned on x and y_<i; the target's cache is reused, nothing is written), and its
+ * arg-max is the prediction y'_i of window[i], i = 1..gamma.  *n_match = number of i with
+ * y'_i == window[i] (Eq. 4: matchness = *n_match / gamma).  The decoding state is not changed.
+ * logits_out: NULL or fp64 [gamma][vocab]. */
+int ora_eval_mask(ora_model *m, const uint8_t *skip, const int32_t *window, int gamma, int32_t *predicted,
+                  int *n_match, double *logits_out) {
+    if (!m || !skip || !window || gamma < 1) return ORA_EINVAL;
+    if (m->pending < 0 || gamma > m->n) return ORA_ESTATE;
+    const int V = m->c.vocab;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)V);
+    int match = 0;
+    for (int i = 1; i <= gamma; ++i) {
+        int rc = forward_row_impl(m, window[i - 1], m->n - gamma + i - 1, skip, lg, 1);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+        int32_t tok;
+        ora_argmax_conf(lg, V, &tok, NULL);
+        if (predicted) predicted[i - 1] = tok;
+        if (logits_out) memcpy(logits_out + (size_t)(i - 1) * V, lg, sizeof(double) * (size_t)V);
+        if (tok == window[i]) ++match;
+    }
+    free(lg);
+    if (n_match) *n_match = match;
     return ORA_OK;
 }
 

@@ -149,6 +149,85 @@ def test_verify_block_rows_equal_single_row_forwards(oracle_lib, small):
     assert tgt[3] == oracle_lib.argmax_conf(want)[0]
 
 
+def _decode_to(o, oracle_lib, prompt, n_tokens):
+    """Greedy-decodes n_tokens tokens; returns the whole sequence prompt + generated (the last
+    generated token is the pending one)."""
+    out = oracle_lib.generate_ar(o, prompt, n_tokens)
+    return np.concatenate([np.asarray(prompt, np.int32), out])
+
+
+def test_candidate_evaluation_empty_set_scores_every_token(oracle_lib, small):
+    """Section 4.1.2, Eq. 3-4: with nothing skipped the draft model is the target model reading
+    the target's own cache, so it reproduces each of the last gamma generated tokens: matchness 1
+    exactly.  (A wrong position, a window shifted by one, an attention range one slot short or long,
+    or recomputed instead of reused keys would all break the equality with the generated tokens.)"""
+    s, o, prompt, ar = small
+    seq = _decode_to(o, oracle_lib, prompt, 30)
+    none = np.zeros(2 * s.n_layers, np.uint8)
+    for gamma in (1, 7, 29):
+        pred, n_match = o.eval_mask(none, seq[-(gamma + 1):])
+        assert n_match == gamma and np.array_equal(pred, seq[-gamma:])
+    # the logits of a row are those the target produced when it generated that token
+    n = o.cache_len
+    pred, n_match, lg = o.eval_mask(none, seq[-4:], want_logits=True)
+    o2 = oracle_lib.Oracle(s, 96)
+    o2.set_weights(hp.shaped_weights(s, seed=21))
+    o2.prefill(seq[:n - 2])                      # pending = seq[n - 2]
+    _, lg2 = o2.verify([o2.pending], True)       # row at position n - 2 predicts seq[n - 1]
+    assert np.array_equal(lg[1], lg2[0])
+    o2.close()
+
+
+def test_candidate_evaluation_all_skipped_closed_form(oracle_lib, small):
+    """Everything skipped: prediction i is arg-max W_lm . rmsnorm(E[window[i-1]]), whatever the
+    context; matchness counts the agreements with the generated tokens."""
+    s, o, prompt, ar = small
+    seq = _decode_to(o, oracle_lib, prompt, 20)
+    w = {k: v.double().numpy() for k, v in hp.shaped_weights(s, seed=21).items()}
+    allm = np.ones(2 * s.n_layers, np.uint8)
+    window = seq[-11:]
+    pred, n_match = o.eval_mask(allm, window)
+    want = []
+    for t in window[:-1]:
+        x = w["embed"][t]
+        xh = x / np.sqrt(np.mean(x * x) + s.rms_eps) * w["final_norm"]
+        want.append(int(np.argmax((w["lm_head"] @ xh).astype(np.float32))))
+    assert np.array_equal(pred, want)
+    assert n_match == int(np.sum(np.array(want) == window[1:]))
+
+
+def test_candidate_evaluation_reads_only_earlier_slots_and_changes_nothing(oracle_lib, small):
+    """A row's prediction depends on cache slots up to its own position only (the same rows
+    evaluated from a shorter cache give the same logits), and the evaluation leaves cache, length,
+    pending token and the continuation untouched."""
+    s, o, prompt, ar = small
+    masks = _masks(s.n_layers)
+    seq = _decode_to(o, oracle_lib, prompt, 24)
+    n, pend = o.cache_len, o.pending
+    kv_before = [o.read_kv(l, p) for l in range(s.n_layers) for p in (0, n // 2, n - 1)]
+    o2 = oracle_lib.Oracle(s, 96)
+    o2.set_weights(hp.shaped_weights(s, seed=21))
+    assert o2.prefill(seq[:n - 3])[0] == seq[n - 3]
+    for name in ("rand0", "rand1", "only2", "only5"):
+        m = masks[name]
+        pred, n_match, lg = o.eval_mask(m, seq[-9:], want_logits=True)      # rows at positions n-8 .. n-1
+        assert (o.cache_len, o.pending) == (n, pend)
+        # the same rows from a cache that is three tokens shorter: positions n-8 .. n-4
+        pred2, _, lg2 = o2.eval_mask(m, seq[n - 8:n - 2], want_logits=True)
+        assert np.array_equal(lg2, lg[:5]) and np.array_equal(pred2, pred[:5])
+        assert 0 <= n_match <= 8 and n_match == int(np.sum(pred == seq[-8:]))
+    kv_after = [o.read_kv(l, p) for l in range(s.n_layers) for p in (0, n // 2, n - 1)]
+    for (k0, v0), (k1, v1) in zip(kv_before, kv_after):
+        assert np.array_equal(k0, k1) and np.array_equal(v0, v1)
+    tgt, _ = o.verify([o.pending])
+    o.accept()
+    assert int(tgt[0]) == int(oracle_lib.generate_ar(o, prompt, 26)[24])
+    # window longer than the cache, evaluation before prefill
+    with pytest.raises(Exception):
+        o.eval_mask(masks["none"], np.zeros(o.cache_len + 2, np.int32))
+    o2.close()
+
+
 def test_state_and_capacity_errors(oracle_lib, small):
     s, o, prompt, ar = small
     o.reset()
