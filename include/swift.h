@@ -138,6 +138,20 @@ int swift_prefill(swift_ctx *ctx, const int32_t *prompt, int n_prompt, int32_t *
 int swift_draft_step(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold,
                      int32_t *draft_tokens, float *draft_conf, int *k_out);
 
+/* Parallel candidate evaluation of the paper's optimisation phase (Section 4.1.2, Eq. 3 and Eq. 4):
+ * a candidate draft model (skipped set skip_mask, as in swift_draft_step) predicts each of the last
+ * gamma generated tokens from the context before it, in one block pass that reuses the target
+ * model's cached keys and values.  window (host, gamma + 1 ids): the tokens at positions
+ * n - gamma .. n of the sequence, i.e. the last gamma committed tokens and then the pending token
+ * (n = cache length).  Row i reads window[i] at position n - gamma + i and attends the cache slots
+ * 0 .. n - gamma + i as they are (nothing is written; keys and values of the rows are not computed);
+ * predicted[i] (host, gamma ids, may be NULL) = its arg-max, the prediction of window[i + 1].
+ * *n_match = number of i with predicted[i] == window[i + 1]; matchness = *n_match / gamma.
+ * 1 <= gamma <= 64 and gamma <= n, else SWIFT_EINVAL / SWIFT_ESTATE.  Cache, cache length, pending
+ * token, outstanding draft/verify state and statistics are left unchanged. */
+int swift_eval_mask(swift_ctx *ctx, const uint8_t *skip_mask, const int32_t *window, int gamma,
+                    int32_t *predicted, int *n_match);
+
 /* Verification (Sections 1, 3.1: drafts are validated in parallel by the full model): the target
  * model over the k+1 rows tokens[0..k] (host; tokens[0] must be the pending token) at positions
  * n..n+k, row i attending slots 0..n+i; target keys/values overwrite slots n..n+k of every layer.

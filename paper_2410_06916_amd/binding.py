@@ -64,6 +64,7 @@ def lib():
     L.swift_prefill.argtypes = [vp, i32p, C.c_int, i32p]
     L.swift_draft_step.argtypes = [vp, u8p, C.c_int, C.c_float, i32p, f32p, C.POINTER(C.c_int)]
     L.swift_verify.argtypes = [vp, i32p, C.c_int, i32p, f32p]
+    L.swift_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int)]
     L.swift_accept.argtypes = [vp, i32p, C.POINTER(C.c_int)]
     L.swift_rollback.argtypes = [vp, C.c_int, C.c_int32]
     L.swift_get_state.argtypes = [vp, C.POINTER(C.c_int), i32p]
@@ -204,6 +205,18 @@ class SwiftModel:
         n = C.c_int()
         _chk(lib().swift_accept(self._h, _p(out, C.c_int32), C.byref(n)), "swift_accept")
         return out[:n.value].copy()
+
+    def eval_mask(self, skip: np.ndarray, window: Sequence[int]):
+        """Candidate evaluation (Section 4.1.2): window = last gamma committed tokens + the pending
+        token.  Returns (predicted[gamma], n_match)."""
+        w = np.ascontiguousarray(window, np.int32)
+        gamma = w.size - 1
+        skip = np.ascontiguousarray(skip, np.uint8)
+        pred = np.empty(max(gamma, 0), np.int32)
+        nm = C.c_int(0)
+        _chk(lib().swift_eval_mask(self._h, _p(skip, C.c_uint8), _p(w, C.c_int32), gamma, _p(pred, C.c_int32),
+                                   C.byref(nm)), "swift_eval_mask")
+        return pred, nm.value
 
     def rollback(self, new_cache_len: int, pending: int):
         _chk(lib().swift_rollback(self._h, new_cache_len, pending), "swift_rollback")

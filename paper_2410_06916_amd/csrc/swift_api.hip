@@ -299,7 +299,8 @@ char *kv_base(swift_ctx *x, int layer, int which) {
 // ---- storage-generic path: one token through the network at position `pos`; row = which row of
 // the activation / logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM
 // head and the arg-max for this row.
-int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int row, bool want_logits) {
+int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int row, bool want_logits,
+                bool reuse_kv = false) {
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -341,7 +342,10 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerOff &y = L.layers[l];
         if (!(skip && skip[2 * l])) {
-            if ((rc = linear(SWIFT_KC_QKV, EPI_QKV, y.wqkv, Q + 2 * KV, H, xr, dptr<float>(x, y.attn_norm), qr, l))) return rc;
+            // (reuse_kv: only the query rows of the fused matrix; the cache slot keeps what it holds)
+            if ((rc = linear(SWIFT_KC_QKV, EPI_QKV, y.wqkv, reuse_kv ? Q : Q + 2 * KV, H, xr, dptr<float>(x, y.attn_norm), qr,
+                             l)))
+                return rc;
             AttnArgs a{};
             a.q = qr;
             a.kcache = kv_base(x, l, 0);
@@ -376,7 +380,8 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
 
 // ---- tiled bf16 path: a block of R rows (tokens[0..R) at positions pos0..pos0+R-1) through the
 // network in one sweep over the weights.  Row r attends cache slots [0, pos0 + r].
-int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits) {
+int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
+                        bool reuse_kv = false) {
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -444,7 +449,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         const LayerOff &y = L.layers[l];
         const float *gnext = gain_of(i + 1);
         if (stages[i].kind == 0) {
-            MvArgs m = base_args(y.wqkv, Q + 2 * KV, H, (Q + 2 * KV) / 16);
+            // (reuse_kv: the query heads' row groups only; they come first in the fused matrix)
+            MvArgs m = reuse_kv ? base_args(y.wqkv, Q, H, Q / 16) : base_args(y.wqkv, Q + 2 * KV, H, (Q + 2 * KV) / 16);
             m.in_s = xs;
             m.pss = pss;
             m.n_pss = n_pss;
@@ -529,7 +535,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     const int group = c.n_q_heads / c.n_kv_heads;
     const int max_T = (std::max(std::max(H, Q), F) + 31) / 32;
     const size_t stack_lds = stack_lds_bytes(max_T, R, d, group, (int)list.size());
-    const bool use_stack = x->stack_on && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
+    const bool use_stack = x->stack_on && !reuse_kv && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
                            pos0 + R <= 1536 && n_att <= x->n_cu / 2 && (int)list.size() <= L.stack_max_stages &&
                            (group == 1 || group == 2 || group == 4 || group == 8);
     if (use_stack) {
@@ -608,10 +614,13 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
 }
 
 // R rows through the network; results (token, confidence, logits) land in rows [0, R).
-int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits) {
-    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits);
+// reuse_kv: the rows' keys and values are not computed; every row attends what the cache already holds
+// for slots up to its own position (candidate evaluation).
+int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
+                  bool reuse_kv = false) {
+    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits, reuse_kv);
     for (int r = 0; r < R; ++r) {
-        int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits);
+        int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits, reuse_kv);
         if (rc) return rc;
     }
     return SWIFT_OK;
@@ -865,6 +874,27 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     return SWIFT_OK;
 }
 
+extern "C" int swift_eval_mask(swift_ctx *x, const uint8_t *skip_mask, const int32_t *window, int gamma,
+                               int32_t *predicted, int *n_match) {
+    if (!x || !skip_mask || !window || !n_match) return fail(SWIFT_EINVAL, "null argument");
+    if (gamma < 1 || gamma > kMaxBlockRows) return fail(SWIFT_EINVAL, "gamma out of range (1..64)");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "candidate evaluation before prefill");
+    if (gamma > x->n) return fail(SWIFT_ESTATE, "window longer than the cache");
+    for (int i = 0; i <= gamma; ++i)
+        if (window[i] < 0 || window[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
+    int rc = forward_block(x, window, gamma, x->n - gamma, skip_mask, true, true);
+    if (rc) return rc;
+    rc = read_results(x, gamma);
+    if (rc) return rc;
+    int m = 0;
+    for (int i = 0; i < gamma; ++i) {
+        if (predicted) predicted[i] = x->h_tok[i];
+        if (x->h_tok[i] == window[i + 1]) ++m;
+    }
+    *n_match = m;
+    return SWIFT_OK;
+}
+
 extern "C" int swift_draft_step(swift_ctx *x, const uint8_t *skip_mask, int max_k, float conf_threshold,
                                 int32_t *draft_tokens, float *draft_conf, int *k_out) {
     if (!x || !skip_mask || !k_out) return fail(SWIFT_EINVAL, "null argument");
@@ -977,7 +1007,7 @@ extern "C" int swift_debug_poison_kv(swift_ctx *x) {
 }
 
 extern "C" int swift_debug_read_logits(swift_ctx *x, int row, float *out) {
-    if (!x || !out || row < 0 || row >= kMaxRows) return fail(SWIFT_EINVAL, "bad argument");
+    if (!x || !out || row < 0 || row >= kMaxBlockRows) return fail(SWIFT_EINVAL, "bad argument");
     HIP_TRY(hipMemcpyAsync(out, dptr<float>(x, x->L.logits) + (size_t)row * x->c.vocab, (size_t)x->c.vocab * 4,
                            hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipStreamSynchronize(x->stream));

@@ -159,6 +159,51 @@ def test_prefill_block_sizes_against_oracle(oracle_lib):
     g.close()
 
 
+@pytest.mark.parametrize("case", ["small-gqa", "small-gqa-bf16", "7b-width-2-layers"])
+def test_candidate_evaluation_against_oracle(oracle_lib, case):
+    """Section 4.1.2, Eq. 3-4: predictions of candidate draft models over the last gamma generated
+    tokens (block pass with the skip mask, target cache reused, nothing written) and the match
+    count, for windows of 1..64 tokens; the decoding state is untouched."""
+    import paper_2410_06916_amd as P
+    if case == "7b-width-2-layers":
+        shape = si.LLAMA2_7B.with_layers(2)
+        weights = si.make_weights(shape, 0)
+        n_prompt, n_gen, gammas, threads = 10, 24, (1, 5, 17, 32), 8
+        masks = [np.zeros(4, np.uint8), np.array([0, 1, 1, 0], np.uint8)]
+    else:
+        shape = hp.SMALL_GQA if case == "small-gqa" else hp.SMALL_GQA_BF16
+        weights = hp.shaped_weights(shape, seed=21)
+        n_prompt, n_gen, gammas, threads = 12, 70, (1, 4, 6, 16, 32, 64), 1
+        rng = np.random.default_rng(2)
+        L2 = 2 * shape.n_layers
+        masks = [np.zeros(L2, np.uint8), np.ones(L2, np.uint8)] + [(rng.random(L2) < 0.5).astype(np.uint8)
+                                                                   for _ in range(3)]
+    o, g = _pair(oracle_lib, shape, weights, n_prompt + n_gen + 8, threads=threads)
+    prompt = si.uniform_ids(5, n_prompt, shape.vocab)
+    want = oracle_lib.generate_ar(o, prompt, n_gen)
+    got = P.generate_ar(g, prompt, n_gen)
+    assert np.array_equal(got, want)
+    seq = np.concatenate([prompt, want]).astype(np.int32)
+    n, pend = g.cache_len, g.pending
+    for gamma in gammas:
+        for mi, mask in enumerate(masks):
+            po, mo = o.eval_mask(mask, seq[-(gamma + 1):])
+            pg, mg = g.eval_mask(mask, seq[-(gamma + 1):])
+            assert np.array_equal(pg, po) and mg == mo, (case, gamma, mi)
+            if mi == 0 and gamma + 1 <= n_gen:
+                assert mg == gamma      # nothing skipped, window inside the target model's own output
+    assert (g.cache_len, g.pending) == (n, pend)
+    # decoding goes on as if nothing had happened
+    t_o, _ = o.verify([o.pending]); o.accept()
+    t_g, _ = g.verify([g.pending]); g.accept()
+    assert int(t_o[0]) == int(t_g[0])
+    with pytest.raises(P.SwiftError):
+        g.eval_mask(masks[0], np.zeros(g.cache_len + 2, np.int32))
+    with pytest.raises(P.SwiftError):
+        g.eval_mask(masks[0], np.zeros(66, np.int32))       # gamma 65 > 64
+    g.close()
+
+
 def test_errors_and_state_machine_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
