@@ -587,12 +587,13 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         for (size_t i = 0; i < list.size(); ++i) {
             const int kc = classes[i];
             if (list[i].type == ST_ATTN) {
-                // an attention launch covers up to 16 rows of the block
-                for (int row0 = 0; row0 < R; row0 += kMaxRows) {
+                // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
+                const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
+                for (int row0 = 0; row0 < R; row0 += per_launch) {
                     AttnArgs a = list[i].at;
                     a.q += (size_t)row0 * Q;
                     a.n_ctx += row0;
-                    a.rows = std::min(kMaxRows, R - row0);
+                    a.rows = std::min(per_launch, R - row0);
                     a.out_s += 24 * row0;  // first of this part's 3 * rows term columns
                     a.out_rows = R <= kMaxRows ? R : kMaxBlockRows;
                     HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),

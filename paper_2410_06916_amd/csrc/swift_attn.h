@@ -26,10 +26,12 @@ __device__ inline float slot_sum(float v, int lpp) {
 
 // One batch of NB cache slots per lane group against GROUP query heads: scores, one running-max
 // update for the whole batch, probabilities, weighted values (online softmax).
+// Member h (a query head, or a (row, query head) pair when several block rows share the loads) takes
+// part in slot pos[b] iff pos[b] < lim[h].
 template <typename T, int GROUP, int NB>
-__device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], const bool (&live)[NB],
-                                  const float (&q)[GROUP][T::VEC], float scale, int lpp, float (&m)[GROUP],
-                                  float (&l)[GROUP], float (&o)[GROUP][T::VEC]) {
+__device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], const int (&pos)[NB],
+                                  const int (&lim)[GROUP], const float (&q)[GROUP][T::VEC], float scale, int lpp,
+                                  float (&m)[GROUP], float (&l)[GROUP], float (&o)[GROUP][T::VEC]) {
     constexpr int VEC = T::VEC;
     float vf[NB][VEC];
 #pragma unroll
@@ -45,7 +47,7 @@ __device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], 
 #pragma unroll
             for (int j = 0; j < VEC; ++j) s = fmaf(q[h][j], kf[j], s);
             s = slot_sum(s, lpp) * scale;
-            sc[h][b] = live[b] ? s : -INFINITY;
+            sc[h][b] = pos[b] < lim[h] ? s : -INFINITY;
         }
     }
 #pragma unroll
@@ -106,19 +108,22 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
     const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
     const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
     const int steps = (n_ctx + 16 * SPW - 1) / (16 * SPW);
+    int lim[GROUP];
+#pragma unroll
+    for (int h = 0; h < GROUP; ++h) lim[h] = n_ctx;
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
-        bool live[NB];
+        int pos[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = ((s0 + b) * 16 + wave) * SPW + lg;
             const int pc = min(p, n_ctx - 1);
-            live[b] = p < n_ctx;
+            pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
         }
-        attn_batch<T, GROUP, NB>(kv, vv, live, q, scale, LPP, m, l, o);
+        attn_batch<T, GROUP, NB>(kv, vv, pos, lim, q, scale, LPP, m, l, o);
     }
     // merge the lane groups of a wavefront
 #pragma unroll

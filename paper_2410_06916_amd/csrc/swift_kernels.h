@@ -62,6 +62,10 @@ struct AttnArgs {
     int out_rows;                 // rows of the block out_s belongs to (0: rows); a launch may cover a
                                   // 16-row part of a larger block: out_s then points at its first column
 };
+// True when the attention of a block runs on the one-workgroup-per-(kv head, row) kernel (no partial
+// buffers: one launch may then cover any number of rows); false: the split kernel, at most kMaxRows
+// rows per launch.  Depends on the cache capacity and the head count only.
+inline bool attn_uses_head_kernel(int max_seq, int n_kv_heads) { return max_seq <= 1600 && n_kv_heads >= 24; }
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
 
 struct ArgmaxArgs {

@@ -181,126 +181,137 @@ hipError_t launch_embed(int dtype, const EmbedArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 // attention over the cache for a block of query rows, split over the cache length
 // ------------------------------------------------------------------------------------------
-// Workgroup (kv head g, split sp, block row r) handles `chunk` cache slots for the query heads
-// that share kv head g; row r attends slots [0, n_ctx + r).  A group of LPP = d / VEC lanes owns
-// one cache slot at a time (lane j of the group holds elements [j*VEC, (j+1)*VEC) of that slot's
-// key and value); step s of wavefront w covers slots lo + (4 s + w) * SPW .., so the four
-// wavefronts read consecutive slots, and the loads of NB steps are issued together.  Each lane
-// group keeps a running (max, sum, weighted value) per query head (online softmax); groups, then
-// wavefronts, are merged.  With one split the workgroup normalises and writes the result;
-// otherwise it writes its partial and k_attn_combine merges the partials in split order.
-template <typename T, int GROUP>
+// Workgroup (kv head g, split sp, row block rb) handles `chunk` cache slots for the query heads
+// that share kv head g and for RB consecutive block rows, which share every key/value load; row r
+// attends slots [0, n_ctx + r).  A group of LPP = d / VEC lanes owns one cache slot at a time (lane j
+// of the group holds elements [j*VEC, (j+1)*VEC) of that slot's key and value); step s of wavefront w
+// covers slots lo + (4 s + w) * SPW .., so the four wavefronts read consecutive slots, and the loads
+// of NB steps are issued together.  Each lane group keeps a running (max, sum, weighted value) per
+// (row, query head) (online softmax); groups, then wavefronts, are merged.  A row whose range ends in
+// the first chunk is normalised and written directly; otherwise the workgroup writes the row's partial
+// and k_attn_combine merges the partials in split order.  What a row's result is does not depend on
+// which other rows share its workgroup: slots beyond a row's range leave its running values untouched.
+template <typename T, int GROUP, int RB>
 __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
     constexpr int VEC = T::VEC;
     constexpr int NB = GROUP <= 2 ? 4 : 1;
+    constexpr int M = GROUP * RB;  // members: (row rr, head h) -> rr * GROUP + h
     const int d = a.head_dim;
     const int LPP = d / VEC;   // lanes per cache slot (power of two, <= 32)
     const int SPW = 64 / LPP;  // slots per wavefront step
     const int n_split = gridDim.y;
-    const int g = blockIdx.x, sp = blockIdx.y, row = blockIdx.z;
+    const int g = blockIdx.x, sp = blockIdx.y, row0 = blockIdx.z * RB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lj = lane & (LPP - 1), lg = lane / LPP;
-    const int n_ctx = a.n_ctx + row;  // block row r sees the cache up to its own slot
-    const int ns_row = (n_ctx + chunk - 1) / chunk;  // splits this row really has
-    if (sp >= ns_row) return;
     const int lo = sp * chunk;
-    const int hi = min(n_ctx, lo + chunk);
+    const int n_rows = min(RB, a.rows - row0);
+    const int hi_max = min(a.n_ctx + row0 + n_rows - 1, lo + chunk);  // end of the longest row's range here
+    if (hi_max <= lo) return;  // no row of this block reaches this chunk
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
 
-    float q[GROUP][VEC];
+    float q[M][VEC];
+    int lim[M];
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h)
+    for (int mm = 0; mm < M; ++mm) {
+        const int rr = mm / GROUP, h = mm - rr * GROUP;
+        const int row = min(row0 + rr, a.rows - 1);
+        // block row r sees the cache up to its own slot; rows past the block take part in nothing
+        lim[mm] = rr < n_rows ? min(a.n_ctx + row0 + rr, lo + chunk) : 0;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
+        for (int j = 0; j < VEC; ++j) q[mm][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
+    }
 
-    float m[GROUP], l[GROUP], o[GROUP][VEC];
+    float m[M], l[M], o[M][VEC];
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h) {
-        m[h] = -INFINITY;
-        l[h] = 0.f;
+    for (int mm = 0; mm < M; ++mm) {
+        m[mm] = -INFINITY;
+        l[mm] = 0.f;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) o[h][j] = 0.f;
+        for (int j = 0; j < VEC; ++j) o[mm][j] = 0.f;
     }
 
     const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
     const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
-    const int steps = (hi - lo + 4 * SPW - 1) / (4 * SPW);
+    const int steps = (hi_max - lo + 4 * SPW - 1) / (4 * SPW);
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
-        bool live[NB];
+        int pos[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
-            const int pc = min(p, hi - 1);  // clamp: dead lane groups load a live slot and discard it
-            live[b] = p < hi;
+            const int pc = min(p, hi_max - 1);  // clamp: slots past the range are loaded and discarded
+            pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
         }
-        attn_batch<T, GROUP, NB>(kv, vv, live, q, scale, LPP, m, l, o);
+        attn_batch<T, M, NB>(kv, vv, pos, lim, q, scale, LPP, m, l, o);
     }
 
     // merge lane groups of one wavefront (butterfly over the lane bits above LPP)
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h) {
+    for (int mm = 0; mm < M; ++mm) {
         for (int off = LPP; off < 64; off <<= 1) {
-            const float m2 = __shfl_xor(m[h], off, 64);
-            const float l2 = __shfl_xor(l[h], off, 64);
-            const float mn = fmaxf(m[h], m2);
-            const float c1 = (m[h] == -INFINITY) ? 0.f : __expf(m[h] - mn);
+            const float m2 = __shfl_xor(m[mm], off, 64);
+            const float l2 = __shfl_xor(l[mm], off, 64);
+            const float mn = fmaxf(m[mm], m2);
+            const float c1 = (m[mm] == -INFINITY) ? 0.f : __expf(m[mm] - mn);
             const float c2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - mn);
-            l[h] = l[h] * c1 + l2 * c2;
+            l[mm] = l[mm] * c1 + l2 * c2;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                const float o2 = __shfl_xor(o[h][j], off, 64);
-                o[h][j] = o[h][j] * c1 + o2 * c2;
+                const float o2 = __shfl_xor(o[mm][j], off, 64);
+                o[mm][j] = o[mm][j] * c1 + o2 * c2;
             }
-            m[h] = mn;
+            m[mm] = mn;
         }
     }
 
     // merge the four wavefronts through LDS
-    __shared__ float sm[4][GROUP], sl[4][GROUP];
-    __shared__ float so[4][GROUP][128];
+    __shared__ float sm[4][M], sl[4][M];
+    __shared__ float so[4][M][128];
     if (lg == 0) {
 #pragma unroll
-        for (int h = 0; h < GROUP; ++h) {
+        for (int mm = 0; mm < M; ++mm) {
             if (lj == 0) {
-                sm[wave][h] = m[h];
-                sl[wave][h] = l[h];
+                sm[wave][mm] = m[mm];
+                sl[wave][mm] = l[mm];
             }
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) so[wave][h][lj * VEC + j] = o[h][j];
+            for (int j = 0; j < VEC; ++j) so[wave][mm][lj * VEC + j] = o[mm][j];
         }
     }
     __syncthreads();
 
-    auto write_out = [&](int h, int j, float y) {
-        const int e = (g * GROUP + h) * d + j;
-        if (a.out) a.out[(size_t)row * nq * d + e] = y;
-        if (a.out_s) {
-            uint16_t hi16, mid16, lo16;
-            split3(y, hi16, mid16, lo16);
-            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * (a.out_rows ? a.out_rows : a.rows)) + 3 * row) * 8 + (e & 7);
-            p[0] = hi16;
-            p[8] = mid16;
-            p[16] = lo16;
-        }
-    };
-
-    for (int idx = tid; idx < GROUP * d; idx += 256) {
-        const int h = idx / d, j = idx - h * d;
-        const float mn = fmaxf(fmaxf(sm[0][h], sm[1][h]), fmaxf(sm[2][h], sm[3][h]));
+    const int orows = a.out_rows ? a.out_rows : a.rows;
+    for (int idx = tid; idx < M * d; idx += 256) {
+        const int mm = idx / d, j = idx - mm * d;
+        const int rr = mm / GROUP, h = mm - rr * GROUP;
+        const int row = row0 + rr;
+        const int n_ctx = a.n_ctx + row;
+        if (rr >= n_rows || lo >= n_ctx) continue;       // no such row, or the row ends before this chunk
+        const int ns_row = (n_ctx + chunk - 1) / chunk;  // splits this row really has
+        const float mn = fmaxf(fmaxf(sm[0][mm], sm[1][mm]), fmaxf(sm[2][mm], sm[3][mm]));
         float ls = 0.f, os = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float c = (sm[w][h] == -INFINITY) ? 0.f : __expf(sm[w][h] - mn);
-            ls += sl[w][h] * c;
-            os += so[w][h][j] * c;
+            const float c = (sm[w][mm] == -INFINITY) ? 0.f : __expf(sm[w][mm] - mn);
+            ls += sl[w][mm] * c;
+            os += so[w][mm][j] * c;
         }
         if (ns_row == 1) {
-            write_out(h, j, os / ls);
+            const float y = os / ls;
+            const int e = (g * GROUP + h) * d + j;
+            if (a.out) a.out[(size_t)row * nq * d + e] = y;
+            if (a.out_s) {
+                uint16_t hi16, mid16, lo16;
+                split3(y, hi16, mid16, lo16);
+                uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * orows) + 3 * row) * 8 + (e & 7);
+                p[0] = hi16;
+                p[8] = mid16;
+                p[16] = lo16;
+            }
         } else {
             const size_t slot = ((size_t)row * nq + g * GROUP + h) * n_split + sp;
             a.part_o[slot * d + j] = os;
@@ -374,7 +385,7 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     // count only, never on the rows of the block or the current length: a row's result is then the
     // same bit for bit whether it is computed alone or inside a block.
     // The one-workgroup-per-head kernel needs enough kv heads to occupy the chip with a single row.
-    if (a.max_seq <= 1600 && a.n_kv_heads >= 24) {
+    if (attn_uses_head_kernel(a.max_seq, a.n_kv_heads)) {
         switch (group) {
             case 1: return launch_attn_head_t<T, 1>(a, s);
             case 2: return launch_attn_head_t<T, 2>(a, s);
@@ -393,12 +404,15 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     int chunk = (a.max_seq + want - 1) / want;
     chunk = (chunk + gran - 1) / gran * gran;
     const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
-    dim3 grid(a.n_kv_heads, n_split, a.rows), block(256);
+    // block rows that share their key/value loads in one workgroup (the more, the less cache traffic;
+    // bounded by registers: members = heads per kv head x rows)
+    const int rb = group == 1 ? 4 : group == 2 ? 2 : 1;
+    dim3 grid(a.n_kv_heads, n_split, (a.rows + rb - 1) / rb), block(256);
     switch (group) {
-        case 1: hipLaunchKernelGGL((k_attn_split<T, 1>), grid, block, 0, s, a, chunk); break;
-        case 2: hipLaunchKernelGGL((k_attn_split<T, 2>), grid, block, 0, s, a, chunk); break;
-        case 4: hipLaunchKernelGGL((k_attn_split<T, 4>), grid, block, 0, s, a, chunk); break;
-        case 8: hipLaunchKernelGGL((k_attn_split<T, 8>), grid, block, 0, s, a, chunk); break;
+        case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 4>), grid, block, 0, s, a, chunk); break;
+        case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 2>), grid, block, 0, s, a, chunk); break;
+        case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1>), grid, block, 0, s, a, chunk); break;
+        case 8: hipLaunchKernelGGL((k_attn_split<T, 8, 1>), grid, block, 0, s, a, chunk); break;
         default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
