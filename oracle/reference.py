@@ -43,6 +43,11 @@ class _Config(C.Structure):
 _lib = None
 
 
+class OptConfig(C.Structure):
+    _fields_ = [("n_sublayers", C.c_int), ("skip_ratio", C.c_double), ("max_steps", C.c_int), ("max_stale", C.c_int),
+                ("stop_matchness", C.c_double), ("seed", C.c_uint64)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -56,6 +61,14 @@ def lib():
         L.ora_set_tensor.argtypes = [vp, C.c_char_p, vp, C.c_int, C.c_int64]
         L.ora_forward_row.argtypes = [vp, C.c_int32, C.c_int, u8p, f64p]
         L.ora_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int), f64p]
+        L.ora_opt_create.argtypes = [C.POINTER(OptConfig), u8p, C.POINTER(vp)]
+        L.ora_opt_destroy.argtypes = [vp]
+        L.ora_opt_destroy.restype = None
+        L.ora_opt_initial_mask.argtypes = [vp, u8p]
+        L.ora_opt_initial_mask.restype = None
+        L.ora_opt_candidate.argtypes = [vp, C.c_int, u8p]
+        L.ora_opt_candidate.restype = None
+        L.ora_opt_step.argtypes = [vp, vp, i32p, C.c_int, u8p, f64p, u8p, f64p, C.POINTER(C.c_int)]
         L.ora_forward_nocache.argtypes = [vp, i32p, C.c_int, f64p]
         L.ora_reset.argtypes = [vp]
         L.ora_prefill.argtypes = [vp, i32p, C.c_int, i32p, f64p]
@@ -155,6 +168,47 @@ def threads_available() -> int:
 
 
 # ---- model -----------------------------------------------------------------
+class Optimizer:
+    """Optimisation-phase bookkeeping of the oracle (Section 4.1, Appendix B.2): uniform initial
+    pattern, random-search candidates under a fixed skip ratio, best candidate retained,
+    termination rules."""
+
+    def __init__(self, n_sublayers: int, skip_ratio: float, max_steps: int = 1000, max_stale: int = 300,
+                 stop_matchness: float = 0.95, seed: int = 0, eligible: Optional[np.ndarray] = None):
+        self.n = n_sublayers
+        cfg = OptConfig(n_sublayers, skip_ratio, max_steps, max_stale, stop_matchness, seed)
+        el = None if eligible is None else np.ascontiguousarray(eligible, np.uint8)
+        h = C.c_void_p()
+        _chk(lib().ora_opt_create(C.byref(cfg), None if el is None else _p(el, C.c_uint8), C.byref(h)), "ora_opt_create")
+        self._h = h
+
+    def close(self):
+        if self._h:
+            lib().ora_opt_destroy(self._h)
+            self._h = None
+
+    def initial_mask(self) -> np.ndarray:
+        m = np.zeros(self.n, np.uint8)
+        lib().ora_opt_initial_mask(self._h, _p(m, C.c_uint8))
+        return m
+
+    def candidate(self, step: int) -> np.ndarray:
+        m = np.zeros(self.n, np.uint8)
+        lib().ora_opt_candidate(self._h, step, _p(m, C.c_uint8))
+        return m
+
+    def step(self, oracle: "Oracle", window: Sequence[int]):
+        """One optimisation step on the window (last gamma committed tokens + pending token).
+        Returns dict(candidate, score, best, best_score, finished)."""
+        w = np.ascontiguousarray(window, np.int32)
+        cand = np.zeros(self.n, np.uint8)
+        best = np.zeros(self.n, np.uint8)
+        cs, bs, fin = C.c_double(), C.c_double(), C.c_int()
+        _chk(lib().ora_opt_step(oracle._h, self._h, _p(w, C.c_int32), w.size - 1, _p(cand, C.c_uint8), C.byref(cs),
+                                _p(best, C.c_uint8), C.byref(bs), C.byref(fin)), "ora_opt_step")
+        return dict(candidate=cand, score=cs.value, best=best, best_score=bs.value, finished=bool(fin.value))
+
+
 class Oracle:
     """One model instance + decoding state.  `shape` is any object with the
     attributes n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,

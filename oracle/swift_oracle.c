@@ -30,6 +30,13 @@
  *     gamma generated tokens from the context before it, reusing the target
  *     model's cached keys and values, and the matchness score counts the
  *     predictions that equal the generated tokens.
+ *   - The random-search part of the layer set suggestion (Section 4.1.2,
+ *     Eq. 2 with a fixed skip ratio r) and the bookkeeping of the optimisation
+ *     phase: the uniform initial skipping pattern (Section 4.1.1), one
+ *     candidate per optimisation step, the best-scoring candidate retained,
+ *     and the termination rules of Appendix B.2 (step limit, no improvement
+ *     for a number of steps, matchness above a bound).  Bayesian optimisation
+ *     is not part of it.
  *
  * Arithmetic
  *   Every floating-point step is carried out in fp64.  Rounding happens only
@@ -431,6 +438,139 @@ int ora_eval_mask(ora_model *m, const uint8_t *skip, const int32_t *window, int 
     }
     free(lg);
     if (n_match) *n_match = match;
+    return ORA_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Optimisation phase: layer set suggestion by random search, candidate bookkeeping, termination
+ * (Section 4.1, Appendix B.2).  Random numbers come from a counter-based generator that the GPU
+ * library implements independently from the same definition:
+ *     mix64(x): z = x + 0x9E3779B97F4A7C15; z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9;
+ *               z = (z ^ z >> 27) * 0x94D049BB133111EB; return z ^ z >> 31          (64-bit wrap)
+ *     key(step) = mix64(mix64(seed ^ 0x53574946544F5054) + step)
+ *     draw j of a step = mix64(key(step) + j)
+ * The candidate of a step picks n_skip of the E eligible sublayers by a partial Fisher-Yates
+ * shuffle of the eligible list (in index order): for j = 0 .. n_skip-1 swap entry j with entry
+ * j + draw_j mod (E - j); the first n_skip entries are skipped.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int n_sublayers;        /* 2 * layers */
+    double skip_ratio;      /* r: round(r * n_sublayers) sublayers are skipped */
+    int max_steps;          /* S */
+    int max_stale;          /* stop after this many steps without improvement */
+    double stop_matchness;  /* stop when the best matchness exceeds this */
+    uint64_t seed;
+} ora_opt_config;
+
+typedef struct ora_opt {
+    ora_opt_config c;
+    int *elig;              /* indices of the eligible sublayers, ascending */
+    int n_elig, n_skip;
+    uint8_t *best;
+    double best_score;      /* -1 before the first evaluation */
+    int step, stale, finished;
+} ora_opt;
+
+static uint64_t opt_mix64(uint64_t x) {
+    uint64_t z = x + 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+int ora_opt_create(const ora_opt_config *c, const uint8_t *eligible, ora_opt **out) {
+    if (!c || !out || c->n_sublayers < 1 || !(c->skip_ratio >= 0.0 && c->skip_ratio <= 1.0) || c->max_steps < 1 ||
+        c->max_stale < 1)
+        return ORA_EINVAL;
+    ora_opt *o = (ora_opt *)calloc(1, sizeof(ora_opt));
+    o->c = *c;
+    o->elig = (int *)malloc(sizeof(int) * (size_t)c->n_sublayers);
+    for (int i = 0; i < c->n_sublayers; ++i)
+        if (!eligible || eligible[i]) o->elig[o->n_elig++] = i;
+    o->n_skip = (int)floor(c->skip_ratio * (double)c->n_sublayers + 0.5);
+    if (o->n_skip > o->n_elig) {
+        free(o->elig);
+        free(o);
+        return ORA_EINVAL;
+    }
+    o->best = (uint8_t *)calloc((size_t)c->n_sublayers, 1);
+    o->best_score = -1.0;
+    *out = o;
+    return ORA_OK;
+}
+
+void ora_opt_destroy(ora_opt *o) {
+    if (!o) return;
+    free(o->elig);
+    free(o->best);
+    free(o);
+}
+
+/* Uniform initial pattern (Section 4.1.1): the n_skip skipped sublayers are spread evenly over the
+ * eligible ones: entry floor((j + 1/2) * E / n_skip) of the eligible list, j = 0 .. n_skip-1. */
+void ora_opt_initial_mask(const ora_opt *o, uint8_t *mask) {
+    memset(mask, 0, (size_t)o->c.n_sublayers);
+    for (int j = 0; j < o->n_skip; ++j)
+        mask[o->elig[(int)(((2 * (int64_t)j + 1) * o->n_elig) / (2 * (int64_t)o->n_skip))]] = 1;
+}
+
+/* Random-search candidate of optimisation step `step` (>= 1). */
+void ora_opt_candidate(const ora_opt *o, int step, uint8_t *mask) {
+    const int E = o->n_elig;
+    int *perm = (int *)malloc(sizeof(int) * (size_t)(E > 0 ? E : 1));
+    for (int i = 0; i < E; ++i) perm[i] = o->elig[i];
+    const uint64_t key = opt_mix64(opt_mix64(o->c.seed ^ 0x53574946544F5054ULL) + (uint64_t)step);
+    memset(mask, 0, (size_t)o->c.n_sublayers);
+    for (int j = 0; j < o->n_skip; ++j) {
+        const int pick = j + (int)(opt_mix64(key + (uint64_t)j) % (uint64_t)(E - j));
+        const int t = perm[j];
+        perm[j] = perm[pick];
+        perm[pick] = t;
+        mask[perm[j]] = 1;
+    }
+    free(perm);
+}
+
+/* One optimisation step before a decoding step: step 1 evaluates the uniform initial pattern,
+ * every later step a random-search candidate, on the current context window (ora_eval_mask).  The
+ * candidate replaces the retained one if its matchness is strictly higher.  finished: the step
+ * limit is reached, or max_stale steps in a row brought no improvement, or the best matchness
+ * exceeds stop_matchness.  Outputs (each may be NULL): the candidate and its matchness, the retained
+ * set and its matchness, the finished flag.  ORA_ESTATE once finished. */
+int ora_opt_step(ora_model *m, ora_opt *o, const int32_t *window, int gamma, uint8_t *cand_out, double *cand_score,
+                 uint8_t *best_out, double *best_score, int *finished) {
+    if (!m || !o || !window) return ORA_EINVAL;
+    if (o->finished) return ORA_ESTATE;
+    const int n = o->c.n_sublayers;
+    if (n != 2 * m->c.n_layers) return ORA_EINVAL;
+    uint8_t *cand = (uint8_t *)malloc((size_t)n);
+    const int step = o->step + 1;
+    if (step == 1)
+        ora_opt_initial_mask(o, cand);
+    else
+        ora_opt_candidate(o, step, cand);
+    int n_match = 0;
+    int rc = ora_eval_mask(m, cand, window, gamma, NULL, &n_match, NULL);
+    if (rc) {
+        free(cand);
+        return rc;
+    }
+    o->step = step;
+    const double score = (double)n_match / (double)gamma;
+    if (score > o->best_score) {
+        memcpy(o->best, cand, (size_t)n);
+        o->best_score = score;
+        o->stale = 0;
+    } else {
+        o->stale++;
+    }
+    o->finished = o->step >= o->c.max_steps || o->stale >= o->c.max_stale || o->best_score > o->c.stop_matchness;
+    if (cand_out) memcpy(cand_out, cand, (size_t)n);
+    if (cand_score) *cand_score = score;
+    if (best_out) memcpy(best_out, o->best, (size_t)n);
+    if (best_score) *best_score = o->best_score;
+    if (finished) *finished = o->finished;
+    free(cand);
     return ORA_OK;
 }
 

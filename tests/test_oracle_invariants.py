@@ -230,6 +230,86 @@ def test_candidate_evaluation_reads_only_earlier_slots_and_changes_nothing(oracl
     o2.close()
 
 
+def test_layer_set_suggestion_candidates(oracle_lib):
+    """Section 4.1.2, Eq. 2 (random search under a fixed skip ratio r) and Section 4.1.1 (uniform
+    initial pattern): every candidate skips exactly round(r L) sublayers, all of them eligible; the
+    stream is a function of (seed, step) only; every eligible sublayer is picked about equally
+    often; the initial pattern is evenly spaced."""
+    el = np.zeros(64, np.uint8)
+    el[4:60] = 1                                     # layers 2..29 of 32
+    opt = oracle_lib.Optimizer(64, 0.5, seed=7, eligible=el)
+    again = oracle_lib.Optimizer(64, 0.5, seed=7, eligible=el)
+    other = oracle_lib.Optimizer(64, 0.5, seed=8, eligible=el)
+    counts = np.zeros(64)
+    differs = 0
+    for step in range(2, 2002):
+        c = opt.candidate(step)
+        assert c.sum() == 32 and not np.any(c[el == 0])
+        assert np.array_equal(c, again.candidate(step))
+        differs += int(not np.array_equal(c, other.candidate(step)))
+        counts += c
+    assert differs > 1990
+    freq = counts[4:60] / 2000.0                     # expected 32/56 each, binomial sd 0.011
+    assert np.all(np.abs(freq - 32 / 56) < 0.05)
+    assert len({opt.candidate(s).tobytes() for s in range(2, 200)}) > 190
+    # evenly spaced initial pattern: every other sublayer for r = 1/2 over all, and inside a range
+    assert np.array_equal(oracle_lib.Optimizer(8, 0.5).initial_mask(), [0, 1, 0, 1, 0, 1, 0, 1])
+    init = opt.initial_mask()
+    assert init.sum() == 32 and not np.any(init[el == 0])
+    gaps = np.diff(np.nonzero(init)[0])
+    assert gaps.min() >= 1 and gaps.max() <= 2
+    assert oracle_lib.Optimizer(10, 0.0).initial_mask().sum() == 0
+    with pytest.raises(Exception):
+        oracle_lib.Optimizer(8, 0.9, eligible=np.array([1, 1, 0, 0, 0, 0, 0, 0], np.uint8))
+    for o in (opt, again, other):
+        o.close()
+
+
+def test_optimisation_steps_retain_the_best_and_terminate(oracle_lib, small):
+    """Bookkeeping and termination of the optimisation phase (Section 4.1.2, Appendix B.2): step 1
+    scores the uniform pattern, later steps random candidates; each score is the matchness of that
+    candidate on the window; the retained set is the first best so far; the phase ends at the step
+    limit, after max_stale steps without improvement, or when the best matchness exceeds the bound."""
+    s, o, prompt, ar = small
+    seq = _decode_to(o, oracle_lib, prompt, 40)
+    window = seq[-17:]
+    L2 = 2 * s.n_layers
+
+    def run(**kw):
+        opt = oracle_lib.Optimizer(L2, **kw)
+        hist = []
+        while True:
+            r = opt.step(o, window)
+            hist.append(r)
+            if r["finished"]:
+                break
+        with pytest.raises(Exception):
+            opt.step(o, window)                       # finished: no more steps
+        first, cand2 = opt.initial_mask(), opt.candidate(2)
+        opt.close()
+        return hist, first, cand2
+
+    hist, first, cand2 = run(skip_ratio=0.5, max_steps=12, max_stale=100, stop_matchness=2.0, seed=3)
+    assert len(hist) == 12                            # step limit
+    assert np.array_equal(hist[0]["candidate"], first) and np.array_equal(hist[1]["candidate"], cand2)
+    best, best_mask = -1.0, None
+    for r in hist:
+        pred, n_match = o.eval_mask(r["candidate"], window)
+        assert r["score"] == n_match / 16
+        if r["score"] > best:
+            best, best_mask = r["score"], r["candidate"]
+        assert r["best_score"] == best and np.array_equal(r["best"], best_mask)
+    # nothing improves on a perfect first score: stops after max_stale further steps
+    hist, _, _ = run(skip_ratio=0.0, max_steps=50, max_stale=4, stop_matchness=2.0, seed=3)
+    assert hist[0]["score"] == 1.0 and len(hist) == 5 and all(r["best_score"] == 1.0 for r in hist)
+    # matchness above the bound ends the phase at once (the paper's 0.95)
+    hist, _, _ = run(skip_ratio=0.0, max_steps=50, max_stale=4, stop_matchness=0.95, seed=3)
+    assert len(hist) == 1 and hist[0]["finished"]
+    # "exceeds": a score equal to the bound does not stop it
+    hist, _, _ = run(skip_ratio=0.0, max_steps=3, max_stale=100, stop_matchness=1.0, seed=3)
+    assert len(hist) == 3
+
+
 def test_state_and_capacity_errors(oracle_lib, small):
     s, o, prompt, ar = small
     o.reset()
