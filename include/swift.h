@@ -152,6 +152,45 @@ int swift_draft_step(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float 
 int swift_eval_mask(swift_ctx *ctx, const uint8_t *skip_mask, const int32_t *window, int gamma,
                     int32_t *predicted, int *n_match);
 
+/* ---- Optimisation phase on top of swift_eval_mask (Sections 4.1.1 and 4.1.2, Eq. 2; Appendix B.2).
+ * Host logic only.  One swift_opt_step before a decoding step: step 1 scores the uniform initial
+ * skipping pattern (the skipped sublayers spread evenly over the eligible ones), every later step a
+ * random-search candidate with exactly round(skip_ratio * n_sublayers) eligible sublayers skipped;
+ * the candidate replaces the retained set if its matchness on the current window is strictly higher.
+ * The phase is finished when max_steps steps are done, or max_stale steps in a row brought no
+ * improvement, or the best matchness exceeds stop_matchness (the paper: 1000, 300, 0.95).
+ * Random search draws from a counter-based generator keyed by (seed, step): candidates do not depend
+ * on what was evaluated before.  mix64(x): z = x + 0x9E3779B97F4A7C15; z = (z ^ z >> 30) *
+ * 0xBF58476D1CE4E5B9; z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^ z >> 31.  key = mix64(mix64(seed ^
+ * 0x53574946544F5054) + step); draw j = mix64(key + j); partial Fisher-Yates over the eligible list
+ * in index order: entry j is swapped with entry j + draw_j mod (E - j), j < n_skip.
+ * Bayesian optimisation is not built; swift_opt_set_suggester lets a caller take every interval-th
+ * step (the paper's beta = 25) with a candidate of its own (return 0 and fill `candidate`; any other
+ * return falls back to random search). */
+typedef struct {
+    int n_sublayers;        /* 2 * n_layers: attention and MLP sublayers, index order as in skip masks */
+    double skip_ratio;      /* r in [0, 1] */
+    int max_steps;          /* S >= 1 */
+    int max_stale;          /* >= 1 */
+    double stop_matchness;
+    uint64_t seed;
+} swift_opt_config;
+typedef struct swift_opt swift_opt; /* opaque; owned by the library */
+typedef int (*swift_suggest_fn)(void *user, int step, const uint8_t *best_mask, double best_matchness, int n_sublayers,
+                                uint8_t *candidate);
+/* eligible: host, n_sublayers bytes, 1 = may be skipped (NULL: all).  SWIFT_EINVAL if the ratio asks
+ * for more skipped sublayers than are eligible. */
+int swift_opt_create(const swift_opt_config *cfg, const uint8_t *eligible, swift_opt **out);
+int swift_opt_destroy(swift_opt *opt);
+int swift_opt_initial_mask(const swift_opt *opt, uint8_t *mask);          /* mask: host, n_sublayers bytes */
+int swift_opt_candidate(const swift_opt *opt, int step, uint8_t *mask);   /* the random-search candidate of a step */
+int swift_opt_set_suggester(swift_opt *opt, swift_suggest_fn fn, void *user, int interval);
+/* window, gamma: as for swift_eval_mask.  Outputs (host; each may be NULL): the step's candidate and its
+ * matchness, the retained set and its matchness, finished (0/1).  SWIFT_ESTATE once finished; errors of
+ * swift_eval_mask are passed on and leave the optimiser unchanged. */
+int swift_opt_step(swift_ctx *ctx, swift_opt *opt, const int32_t *window, int gamma, uint8_t *candidate,
+                   double *candidate_matchness, uint8_t *best_mask, double *best_matchness, int *finished);
+
 /* Verification (Sections 1, 3.1: drafts are validated in parallel by the full model): the target
  * model over the k+1 rows tokens[0..k] (host; tokens[0] must be the pending token) at positions
  * n..n+k, row i attending slots 0..n+i; target keys/values overwrite slots n..n+k of every layer.

@@ -4,9 +4,9 @@ The work is done by hand-written HIP kernels behind the C ABI in include/swift.h
 (libswift_hip.so, built in-tree by build.py).  This package only marshals
 arguments; PyTorch is used for device memory and streams.
 """
-from .binding import (SwiftError, SwiftModel, check_config, device_bytes, expected_speedup, lib, match_prefix,
+from .binding import (Optimizer, SwiftError, SwiftModel, check_config, device_bytes, expected_speedup, lib, match_prefix,
                       pass_bytes, KERNEL_CLASSES)
 from .decode import generate_ar, generate_swift
 
-__all__ = ["SwiftError", "SwiftModel", "check_config", "device_bytes", "expected_speedup", "lib", "match_prefix",
+__all__ = ["Optimizer", "SwiftError", "SwiftModel", "check_config", "device_bytes", "expected_speedup", "lib", "match_prefix",
            "pass_bytes", "generate_ar", "generate_swift", "KERNEL_CLASSES"]

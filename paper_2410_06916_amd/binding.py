@@ -35,6 +35,14 @@ class Stats(C.Structure):
 _lib = None
 
 
+class OptConfig(C.Structure):
+    _fields_ = [("n_sublayers", C.c_int), ("skip_ratio", C.c_double), ("max_steps", C.c_int), ("max_stale", C.c_int),
+                ("stop_matchness", C.c_double), ("seed", C.c_uint64)]
+
+
+SUGGEST_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int, C.POINTER(C.c_uint8), C.c_double, C.c_int, C.POINTER(C.c_uint8))
+
+
 def lib():
     """Loads the built library.  There is no fallback: if it is missing it is built with
     hipcc, and if that fails the error propagates."""
@@ -65,6 +73,13 @@ def lib():
     L.swift_draft_step.argtypes = [vp, u8p, C.c_int, C.c_float, i32p, f32p, C.POINTER(C.c_int)]
     L.swift_verify.argtypes = [vp, i32p, C.c_int, i32p, f32p]
     L.swift_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int)]
+    L.swift_opt_create.argtypes = [C.POINTER(OptConfig), u8p, C.POINTER(vp)]
+    L.swift_opt_destroy.argtypes = [vp]
+    L.swift_opt_initial_mask.argtypes = [vp, u8p]
+    L.swift_opt_candidate.argtypes = [vp, C.c_int, u8p]
+    L.swift_opt_set_suggester.argtypes = [vp, SUGGEST_FN, vp, C.c_int]
+    L.swift_opt_step.argtypes = [vp, vp, i32p, C.c_int, u8p, C.POINTER(C.c_double), u8p, C.POINTER(C.c_double),
+                                 C.POINTER(C.c_int)]
     L.swift_accept.argtypes = [vp, i32p, C.POINTER(C.c_int)]
     L.swift_rollback.argtypes = [vp, C.c_int, C.c_int32]
     L.swift_get_state.argtypes = [vp, C.POINTER(C.c_int), i32p]
@@ -276,3 +291,55 @@ class SwiftModel:
         n, ms, b = C.c_int64(), C.c_double(), C.c_uint64()
         _chk(lib().swift_profile_read(self._h, C.byref(n), C.byref(ms), C.byref(b)), "swift_profile_read")
         return n.value, ms.value, b.value
+
+
+class Optimizer:
+    """Optimisation phase on top of SwiftModel.eval_mask (argument marshalling only): uniform initial
+    pattern, random-search candidates, best candidate retained, termination rules."""
+
+    def __init__(self, n_sublayers: int, skip_ratio: float, max_steps: int = 1000, max_stale: int = 300,
+                 stop_matchness: float = 0.95, seed: int = 0, eligible: Optional[np.ndarray] = None):
+        self.n = n_sublayers
+        cfg = OptConfig(n_sublayers, skip_ratio, max_steps, max_stale, stop_matchness, seed)
+        el = None if eligible is None else np.ascontiguousarray(eligible, np.uint8)
+        h = C.c_void_p()
+        _chk(lib().swift_opt_create(C.byref(cfg), None if el is None else _p(el, C.c_uint8), C.byref(h)), "swift_opt_create")
+        self._h = h
+        self._cb = None
+
+    def close(self):
+        if self._h:
+            lib().swift_opt_destroy(self._h)
+            self._h = None
+
+    def initial_mask(self) -> np.ndarray:
+        m = np.zeros(self.n, np.uint8)
+        _chk(lib().swift_opt_initial_mask(self._h, _p(m, C.c_uint8)), "swift_opt_initial_mask")
+        return m
+
+    def candidate(self, step: int) -> np.ndarray:
+        m = np.zeros(self.n, np.uint8)
+        _chk(lib().swift_opt_candidate(self._h, step, _p(m, C.c_uint8)), "swift_opt_candidate")
+        return m
+
+    def set_suggester(self, fn, interval: int):
+        """fn(step, best_mask, best_matchness) -> candidate mask or None (None: random search)."""
+        def tramp(_user, step, best, best_score, n, out):
+            r = fn(step, np.ctypeslib.as_array(best, (n,)).copy(), best_score)
+            if r is None:
+                return 1
+            out_arr = np.ctypeslib.as_array(out, (n,))
+            out_arr[:] = np.asarray(r, np.uint8)
+            return 0
+        self._cb = SUGGEST_FN(tramp) if fn else SUGGEST_FN(0)
+        _chk(lib().swift_opt_set_suggester(self._h, self._cb if fn else C.cast(None, SUGGEST_FN), None, interval),
+             "swift_opt_set_suggester")
+
+    def step(self, model: "SwiftModel", window: Sequence[int]):
+        w = np.ascontiguousarray(window, np.int32)
+        cand = np.zeros(self.n, np.uint8)
+        best = np.zeros(self.n, np.uint8)
+        cs, bs, fin = C.c_double(), C.c_double(), C.c_int()
+        _chk(lib().swift_opt_step(model._h, self._h, _p(w, C.c_int32), w.size - 1, _p(cand, C.c_uint8), C.byref(cs),
+                                  _p(best, C.c_uint8), C.byref(bs), C.byref(fin)), "swift_opt_step")
+        return dict(candidate=cand, score=cs.value, best=best, best_score=bs.value, finished=bool(fin.value))

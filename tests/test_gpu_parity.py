@@ -204,6 +204,60 @@ def test_candidate_evaluation_against_oracle(oracle_lib, case):
     g.close()
 
 
+def test_optimisation_phase_follows_the_oracle(oracle_lib):
+    """Sections 4.1.1-4.1.2, Appendix B.2: optimisation steps interleaved with decoding steps give the
+    same candidates, matchness scores, retained sets and termination as the oracle's; the
+    random-search stream is the same on both sides; an external suggester can take every beta-th
+    step."""
+    import paper_2410_06916_amd as P
+    shape = hp.SMALL_GQA_BF16
+    weights = hp.shaped_weights(shape, seed=21)
+    o, g = _pair(oracle_lib, shape, weights, 160, threads=1)
+    prompt = si.uniform_ids(5, 12, shape.vocab)
+    L2 = 2 * shape.n_layers
+    el = np.ones(L2, np.uint8)
+    el[0] = el[-1] = 0
+    kw = dict(skip_ratio=0.5, max_steps=14, max_stale=9, stop_matchness=0.95, seed=11, eligible=el)
+    oo, og = oracle_lib.Optimizer(L2, **kw), P.Optimizer(L2, **kw)
+    assert np.array_equal(oo.initial_mask(), og.initial_mask())
+    for step in (2, 3, 50, 1000):
+        assert np.array_equal(oo.candidate(step), og.candidate(step))
+    seq = list(prompt) + [int(o.prefill(prompt)[0])]
+    assert g.prefill(prompt) == seq[-1]
+    gamma, steps = 16, 0
+    while True:
+        # context accumulation / decoding step (plain greedy here), then one optimisation step
+        to, _ = o.verify([o.pending]); o.accept()
+        tg, _ = g.verify([g.pending]); g.accept()
+        assert int(to[0]) == int(tg[0])
+        seq.append(int(to[0]))
+        if len(seq) - len(prompt) <= gamma:
+            continue
+        window = np.array(seq[-(gamma + 1):], np.int32)
+        ro, rg = oo.step(o, window), og.step(g, window)
+        steps += 1
+        assert np.array_equal(ro["candidate"], rg["candidate"]) and ro["score"] == rg["score"], steps
+        assert np.array_equal(ro["best"], rg["best"]) and ro["best_score"] == rg["best_score"]
+        assert ro["finished"] == rg["finished"]
+        if ro["finished"]:
+            break
+    assert 1 <= steps <= 14
+    with pytest.raises(P.SwiftError):
+        og.step(g, window)
+    # an external suggester takes steps 2, 4, ...; declining (None) falls back to random search
+    og2 = P.Optimizer(L2, skip_ratio=0.5, max_steps=4, max_stale=100, stop_matchness=2.0, seed=11, eligible=el)
+    mine = np.zeros(L2, np.uint8)
+    mine[1] = 1
+    og2.set_suggester(lambda step, best, score: mine if step == 2 else None, 2)
+    r1, r2, r3, r4 = (og2.step(g, window) for _ in range(4))
+    assert np.array_equal(r1["candidate"], og2.initial_mask()) and np.array_equal(r2["candidate"], mine)
+    assert np.array_equal(r3["candidate"], og2.candidate(3)) and np.array_equal(r4["candidate"], og2.candidate(4))
+    assert r4["finished"]
+    for x in (oo, og, og2):
+        x.close()
+    g.close()
+
+
 def test_errors_and_state_machine_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
