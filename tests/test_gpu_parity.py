@@ -258,6 +258,50 @@ def test_optimisation_phase_follows_the_oracle(oracle_lib):
     g.close()
 
 
+_ODD_SHAPES = [
+    # name, layers, hidden, q heads, kv heads, head dim, ffn, vocab, dtype
+    ("mha-d32", 2, 72, 3, 3, 32, 104, 130, "bf16"),          # group 1, nothing a multiple of 32
+    ("gqa4-d64", 2, 200, 8, 2, 64, 328, 514, "bf16"),        # group 4
+    ("gqa8-d16", 3, 88, 8, 1, 16, 40, 66, "bf16"),           # group 8, one kv head, ffn < hidden
+    ("mqa-d128", 1, 264, 2, 1, 128, 520, 1002, "bf16"),      # group 2, head dim 128, one layer
+    ("wide-d128", 2, 1032, 8, 8, 128, 2760, 3002, "bf16"),   # > 1024 wide: several k-tiles per slice, ragged
+    ("f32-gqa2-d32", 2, 136, 4, 2, 32, 88, 250, "fp32"),     # the storage-generic path
+]
+
+
+@pytest.mark.parametrize("spec", _ODD_SHAPES, ids=[s[0] for s in _ODD_SHAPES])
+def test_odd_shapes_against_oracle(oracle_lib, spec):
+    """Shapes whose sizes are ragged against every tile (k-tiles of 32, row groups of 16, gate/up
+    groups of 8, 64-row prefill blocks) and every grouping of query heads per kv head: prefill of a
+    ragged prompt, speculative decoding with a random mask and forced / confidence-stopped drafts,
+    candidate evaluation."""
+    import paper_2410_06916_amd as P
+    name, L, H, nq, nkv, d, F, V, dtype = spec
+    shape = si.ModelShape(name, L, H, nq, nkv, d, F, V, dtype, 1e-5 if dtype == "bf16" else 1e-6)
+    weights = hp.shaped_weights(shape, seed=len(name))
+    n_prompt = 70 if H < 1000 else 23
+    o, g = _pair(oracle_lib, shape, weights, n_prompt + 40, threads=4)
+    prompt = si.uniform_ids(17, n_prompt, V)
+    rng = np.random.default_rng(L * H)
+    mask = (rng.random(2 * L) < 0.5).astype(np.uint8)
+    for max_k, eps in ((6, 0.0), (15, 0.4)):
+        want, to = oracle_lib.generate_swift(o, prompt, 20, mask, max_k, eps, want_logits=True)
+        got, tg = P.generate_swift(g, prompt, 20, mask, max_k, eps, want_logits=True)
+        assert np.array_equal(got, want), (name, max_k, eps)
+        _compare_traces(shape, to, tg)
+    seq = np.concatenate([prompt, want]).astype(np.int32)
+    # the last run left the final emitted tokens uncommitted or truncated: evaluate inside a fresh AR run
+    want = oracle_lib.generate_ar(o, prompt, 20)
+    got = P.generate_ar(g, prompt, 20)
+    assert np.array_equal(got, want)
+    seq = np.concatenate([prompt, want]).astype(np.int32)
+    for gamma in (7, 19):
+        po, mo = o.eval_mask(mask, seq[-(gamma + 1):])
+        pg, mg = g.eval_mask(mask, seq[-(gamma + 1):])
+        assert np.array_equal(pg, po) and mg == mo, (name, gamma)
+    g.close()
+
+
 def test_errors_and_state_machine_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
