@@ -29,6 +29,15 @@
  * biases.  Weights and the key/value cache are stored in `dtype`; the residual
  * stream, normalised activations, queries, attention probabilities, MLP
  * intermediates and logits are fp32 and every accumulation is fp32.
+ *
+ * Guarantee: a token's logits, and the keys and values it leaves in the cache, do
+ * not depend on how many rows share its pass (one-row decoding, a draft pass, a
+ * verify block of 2..16 rows): every kernel adds a row's products in the same
+ * order.  Speculative greedy decoding therefore reproduces plain greedy decoding
+ * of the same context exactly (paper Sections 1 and 3.1), not just up to
+ * rounding.  Prefill blocks use an order of their own; both decoding modes share
+ * the prefill.  The experimental persistent path (swift_debug_persistent) is
+ * outside this guarantee.
  */
 #ifndef SWIFT_H_
 #define SWIFT_H_

@@ -1,6 +1,7 @@
 // gfx950 kernels of the bf16 path: tiled weights streamed once from HBM into MFMA, activations
-// kept in fp32 precision as three bf16 terms.  k_mv1 handles one activation row (draft pass,
-// plain decoding), k_mvN a block of 2..16 rows (verify, prefill).
+// kept in fp32 precision as three bf16 terms.  k_mv1 handles blocks of 1-5 activation rows whose
+// activation fits in LDS (draft pass, plain decoding, short verify blocks), k_mvN blocks of up to
+// 64 rows (longer verify blocks, prefill, candidate evaluation).
 #include <math.h>
 
 #include <hip/hip_ext.h>
