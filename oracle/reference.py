@@ -61,6 +61,14 @@ def lib():
         L.ora_set_tensor.argtypes = [vp, C.c_char_p, vp, C.c_int, C.c_int64]
         L.ora_forward_row.argtypes = [vp, C.c_int32, C.c_int, u8p, f64p]
         L.ora_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int), f64p]
+        L.ora_topk_width.argtypes = [C.c_double]
+        L.ora_topk_width.restype = C.c_int
+        L.ora_topk.argtypes = [f64p, C.c_int, C.c_int, i32p]
+        L.ora_topk.restype = None
+        L.ora_draft_step_topk.argtypes = [vp, u8p, C.c_int, C.c_double, C.c_int, i32p, f64p, C.POINTER(C.c_int),
+                                          C.POINTER(C.c_int)]
+        L.ora_verify_tree.argtypes = [vp, i32p, C.POINTER(C.c_int), C.c_int, i32p, f64p]
+        L.ora_accept_tree.argtypes = [vp, i32p, C.POINTER(C.c_int)]
         L.ora_opt_create.argtypes = [C.POINTER(OptConfig), u8p, C.POINTER(vp)]
         L.ora_opt_destroy.argtypes = [vp]
         L.ora_opt_destroy.restype = None
@@ -287,6 +295,40 @@ class Oracle:
                                  C.byref(nm), _p(lg, C.c_double) if want_logits else None), "ora_eval_mask")
         return (pred, nm.value, lg) if want_logits else (pred, nm.value)
 
+    TREE_ROWS = 16
+    TOPK = 10
+
+    def draft_step_topk(self, skip: np.ndarray, max_k: int, conf_threshold: float, max_width: int = 10):
+        """Drafting with the top candidates of every position kept (Section 4.2, strategy 2).
+        Returns (levels: list of int32 arrays, level j = candidates of draft position j+1, first =
+        the draft token; conf[k])."""
+        skip = np.ascontiguousarray(skip, np.uint8)
+        cap = max(max_k, 1)
+        toks = np.zeros((cap, self.TOPK), np.int32)
+        conf = np.zeros(cap, np.float64)
+        width = np.zeros(cap, np.int32)
+        k = C.c_int(0)
+        _chk(lib().ora_draft_step_topk(self._h, _p(skip, C.c_uint8), max_k, conf_threshold, max_width,
+                                       _p(toks, C.c_int32), _p(conf, C.c_double),
+                                       width.ctypes.data_as(C.POINTER(C.c_int)), C.byref(k)), "ora_draft_step_topk")
+        return [toks[j, :width[j]].copy() for j in range(k.value)], conf[:k.value].copy()
+
+    def verify_tree(self, pending: int, levels, want_logits: bool = False):
+        """levels: list of candidate arrays (first = spine).  Returns (targets[rows], logits or None)."""
+        rows = np.concatenate([[pending]] + [np.asarray(l, np.int32) for l in levels]).astype(np.int32)
+        width = np.array([len(l) for l in levels], np.int32)
+        tgt = np.empty(rows.size, np.int32)
+        lg = np.empty((rows.size, self.vocab), np.float64) if want_logits else None
+        _chk(lib().ora_verify_tree(self._h, _p(rows, C.c_int32), width.ctypes.data_as(C.POINTER(C.c_int)), len(levels),
+                                   _p(tgt, C.c_int32), _p(lg, C.c_double) if want_logits else None), "ora_verify_tree")
+        return tgt, lg
+
+    def accept_tree(self) -> np.ndarray:
+        em = np.empty(self.TREE_ROWS, np.int32)
+        n = C.c_int(0)
+        _chk(lib().ora_accept_tree(self._h, _p(em, C.c_int32), C.byref(n)), "ora_accept_tree")
+        return em[:n.value].copy()
+
     # -- decoding steps
     def reset(self):
         lib().ora_reset(self._h)
@@ -387,3 +429,21 @@ def generate_swift(o: Oracle, prompt: Sequence[int], n_new: int, skip: np.ndarra
         trace.append(dict(n=n0, block=block, draft=d, conf=conf, target=tgt, emitted=em, m=len(em) - 1,
                           logits=lg))
     return np.array(out, np.int32), trace
+
+
+def generate_swift_tree(o: Oracle, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k: int,
+                        conf_threshold: float, max_width: int = 10):
+    """Draft-then-verify greedy decoding with dynamic verification (Section 4.2, strategies 1 and 2):
+    every draft position is widened to its top candidates and the whole token tree is verified in
+    one block.  Returns (tokens, trace)."""
+    out = [int(o.prefill(prompt)[0])]
+    trace = []
+    while len(out) < n_new:
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = o.cache_len
+        levels, conf = o.draft_step_topk(skip, k_cap, conf_threshold, max_width) if k_cap > 0 else ([], np.zeros(0))
+        tgt, _ = o.verify_tree(o.pending, levels)
+        em = o.accept_tree()
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, levels=levels, conf=conf, target=tgt, emitted=em, m=len(em) - 1))
+    return np.array(out[:n_new], np.int32), trace

@@ -25,6 +25,12 @@
  *   - Plain greedy autoregressive decoding (the definition the method must
  *     reproduce token for token), a brute-force forward without any cache,
  *     and the expected-speedup closed form (Appendix B.3, Eq. 6).
+ *   - Dynamic verification (Section 4.2, strategy 2): every draft position is
+ *     widened to its top-k draft predictions, k = 10, 5, 3, 1 for a confidence in
+ *     (0, 0.5], (0.5, 0.8], (0.8, 0.95], (0.95, 1]; all candidates are verified
+ *     in one block whose rows attend the committed context, their ancestors in
+ *     the token tree and themselves; the longest accepted path is kept and its
+ *     keys/values are moved to consecutive cache slots.
  *   - Parallel candidate evaluation of the optimisation phase (Section 4.1.2,
  *     Eq. 3 and Eq. 4): a candidate draft model predicts each of the last
  *     gamma generated tokens from the context before it, reusing the target
@@ -81,6 +87,8 @@
 #define ORA_F32 0
 #define ORA_BF16 1
 #define ORA_MAX_BLOCK 64
+#define ORA_TREE_ROWS 16 /* rows of a token tree block: the pending token + all candidates */
+#define ORA_TOPK 10      /* widest candidate set of one draft position */
 
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, max_seq;
@@ -112,6 +120,10 @@ typedef struct ora_model {
     int k_verify; /* k of the last verify (-1: none) */
     int32_t vtokens[ORA_MAX_BLOCK + 1];
     int32_t target[ORA_MAX_BLOCK + 1];
+    /* token tree of the last dynamic verification (-1: none) */
+    int tree_levels;
+    int tree_width[ORA_TREE_ROWS];
+    int32_t tree_tokens[ORA_TREE_ROWS], tree_target[ORA_TREE_ROWS];
     /* counters (Appendix B.3) */
     int64_t n_draft_passes, n_verify_passes, n_accepted, n_emitted;
 } ora_model;
@@ -273,6 +285,7 @@ int ora_create(const ora_config *c, ora_model **out) {
     m->pending = -1;
     m->k_draft = -1;
     m->k_verify = -1;
+    m->tree_levels = -1;
     *out = m;
     return ORA_OK;
 }
@@ -346,11 +359,30 @@ static float *vslot(const ora_model *m, int l, int pos) {
  * computed and written to cache slot pos before the row attends slots 0..pos.  reuse_kv = 1
  * (candidate evaluation): nothing is written; the row attends the keys and values that slots
  * 0..pos already hold. */
+static int forward_row_general(ora_model *m, int32_t token, int pos, int slot, const int *extra, int n_extra,
+                               int n_base, const uint8_t *skip, double *logits, int reuse_kv);
+
 static int forward_row_impl(ora_model *m, int32_t token, int pos, const uint8_t *skip, double *logits, int reuse_kv) {
+    return forward_row_general(m, token, pos, pos, NULL, 0, pos + 1, skip, logits, reuse_kv);
+}
+
+/* The general row: the token sits at sequence position `pos` (its rotary position), its keys and
+ * values go to cache slot `slot`, and it attends slots 0 .. n_base-1 followed by the n_extra slots
+ * listed in `extra` (in that order).  A plain row has slot = pos, n_base = pos + 1, no extra slots;
+ * a row of a token tree attends the committed slots, then the slots of its ancestors in the block,
+ * then its own. */
+static int forward_row_general(ora_model *m, int32_t token, int pos, int slot, const int *extra, int n_extra,
+                               int n_base, const uint8_t *skip, double *logits, int reuse_kv) {
     const ora_config *c = &m->c;
     if (token < 0 || token >= c->vocab) return ORA_EINVAL;
-    if (pos < 0 || pos >= c->max_seq) return ORA_ECAPACITY;
+    if (pos < 0 || pos >= c->max_seq || slot < 0 || slot >= c->max_seq) return ORA_ECAPACITY;
     const int H = c->hidden, d = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads, F = c->ffn;
+    const int n_att = n_base + n_extra;
+    float *gk = NULL, *gv = NULL; /* gathered keys/values of the attended slots (tree rows only) */
+    if (n_extra > 0) {
+        gk = (float *)malloc(sizeof(float) * (size_t)n_att * (size_t)(nkv * d));
+        gv = (float *)malloc(sizeof(float) * (size_t)n_att * (size_t)(nkv * d));
+    }
     const int Q = nq * d, KV = nkv * d, group = nq / nkv;
     double *x = (double *)malloc(sizeof(double) * (size_t)H);
     double *xh = (double *)malloc(sizeof(double) * (size_t)H);
@@ -374,16 +406,26 @@ static int forward_row_impl(ora_model *m, int32_t token, int pos, const uint8_t 
                 matvec(m, &y->wk, KV, H, xh, k);
                 matvec(m, &y->wv, KV, H, xh, v);
                 for (int h = 0; h < nkv; ++h) ora_rope(k + h * d, d, pos, c->rope_theta);
-                float *ks = kslot(m, l, pos), *vs = vslot(m, l, pos);
+                float *ks = kslot(m, l, slot), *vs = vslot(m, l, slot);
                 for (int i = 0; i < KV; ++i) {
                     ks[i] = round_kv(c, k[i]);
                     vs[i] = round_kv(c, v[i]);
                 }
             }
+            const float *kc = kslot(m, l, 0), *vc = vslot(m, l, 0);
+            if (n_extra > 0) {
+                for (int u = 0; u < n_att; ++u) {
+                    const int src = u < n_base ? u : extra[u - n_base];
+                    memcpy(gk + (size_t)u * KV, kslot(m, l, src), sizeof(float) * (size_t)KV);
+                    memcpy(gv + (size_t)u * KV, vslot(m, l, src), sizeof(float) * (size_t)KV);
+                }
+                kc = gk;
+                vc = gv;
+            }
 #pragma omp parallel for schedule(static) num_threads(m->threads)
             for (int h = 0; h < nq; ++h) {
                 int g = h / group;
-                ora_attend(q + h * d, kslot(m, l, 0) + g * d, vslot(m, l, 0) + g * d, KV, pos + 1, d, att + h * d);
+                ora_attend(q + h * d, kc + g * d, vc + g * d, KV, n_att, d, att + h * d);
             }
             matvec(m, &y->wo, H, Q, att, tmp);
             for (int i = 0; i < H; ++i) x[i] += tmp[i];
@@ -401,6 +443,7 @@ static int forward_row_impl(ora_model *m, int32_t token, int pos, const uint8_t 
     matvec(m, &m->lm_head, c->vocab, H, xh, logits);
 
     free(x); free(xh); free(q); free(k); free(v); free(att); free(tmp); free(hg); free(hu);
+    free(gk); free(gv);
     return ORA_OK;
 }
 
@@ -638,6 +681,7 @@ int ora_reset(ora_model *m) {
     m->pending = -1;
     m->k_draft = -1;
     m->k_verify = -1;
+    m->tree_levels = -1;
     m->n_draft_passes = m->n_verify_passes = m->n_accepted = m->n_emitted = 0;
     return ORA_OK;
 }
@@ -727,6 +771,7 @@ int ora_verify(ora_model *m, const int32_t *tokens, int k, int32_t *target_token
     }
     free(lg);
     m->k_verify = k;
+    m->tree_levels = -1;
     m->n_verify_passes++;
     return ORA_OK;
 }
@@ -748,6 +793,172 @@ int ora_accept(ora_model *m, int32_t *emitted, int *n_emitted) {
     m->n_accepted += acc;
     m->n_emitted += acc + 1;
     m->k_verify = -1;
+    m->k_draft = -1;
+    return ORA_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Dynamic verification (Section 4.2, strategy 2)
+ * ------------------------------------------------------------------------------------------- */
+/* Candidates per draft position from its confidence p (the paper's four bands). */
+int ora_topk_width(double p) {
+    if (p <= 0.5) return 10;
+    if (p <= 0.8) return 5;
+    if (p <= 0.95) return 3;
+    return 1;
+}
+
+/* The k largest logits (compared in fp32, as the arg-max is), largest first; equal values in
+ * index order.  tokens[0] is the arg-max. */
+void ora_topk(const double *logits, int n, int k, int32_t *tokens) {
+    for (int j = 0; j < k; ++j) {
+        int best = -1;
+        float bv = 0.f;
+        for (int i = 0; i < n; ++i) {
+            int taken = 0;
+            for (int t = 0; t < j; ++t) taken |= tokens[t] == i;
+            if (taken) continue;
+            float v = (float)logits[i];
+            if (best < 0 || v > bv) {
+                bv = v;
+                best = i;
+            }
+        }
+        tokens[j] = best;
+    }
+}
+
+/* Drafting as in ora_draft_step, keeping for every draft position j its top candidates
+ * tokens[j][0..width[j]) (tokens[j][0] is the draft token the next position continues from) with
+ * width[j] = min(ora_topk_width(p_j), max_width, rows left), where a block holds at most
+ * ORA_TREE_ROWS rows (the pending token and all candidates); drafting also stops when no row is
+ * left.  tokens: [max_k][ORA_TOPK]. */
+int ora_draft_step_topk(ora_model *m, const uint8_t *skip, int max_k, double conf_threshold, int max_width,
+                        int32_t *tokens, double *draft_conf, int *width, int *k_out) {
+    if (!m || !skip || !tokens || !width || max_k < 0 || max_k > ORA_TREE_ROWS - 1 || max_width < 1) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    if (m->n + ORA_TREE_ROWS > m->c.max_seq) return ORA_ECAPACITY;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)m->c.vocab);
+    int32_t prev = m->pending;
+    int k = 0, rows = 1;
+    for (int j = 1; j <= max_k && rows < ORA_TREE_ROWS; ++j) {
+        int rc = ora_forward_row(m, prev, m->n + j - 1, skip, lg);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+        int32_t tok;
+        double p;
+        ora_argmax_conf(lg, m->c.vocab, &tok, &p);
+        m->n_draft_passes++;
+        int w = ora_topk_width(p);
+        if (w > max_width) w = max_width;
+        if (w > ORA_TREE_ROWS - rows) w = ORA_TREE_ROWS - rows;
+        if (w > m->c.vocab) w = m->c.vocab;
+        ora_topk(lg, m->c.vocab, w, tokens + (size_t)k * ORA_TOPK);
+        width[k] = w;
+        if (draft_conf) draft_conf[k] = p;
+        m->draft[k] = tok;
+        rows += w;
+        ++k;
+        prev = tok;
+        if (p < conf_threshold) break;
+    }
+    free(lg);
+    m->k_draft = k;
+    if (k_out) *k_out = k;
+    return ORA_OK;
+}
+
+/* Verification of a token tree in one block.  Row 0 is the pending token; level j = 1..levels has
+ * width[j-1] rows, the candidates of draft position j, the first of them the draft token itself
+ * (the "spine").  tokens: the rows in order (row 0, level 1, level 2, ...).  A row of level j sits
+ * at sequence position n + j; its keys/values go to cache slot n + row; it attends the committed
+ * slots 0..n-1, row 0, the spine rows of levels 1..j-1, and itself.  target_tokens[row] = arg-max
+ * of the row = the target model's next token after the path that ends in that row. */
+int ora_verify_tree(ora_model *m, const int32_t *tokens, const int *width, int levels, int32_t *target_tokens,
+                    double *logits_out) {
+    if (!m || !tokens || levels < 0 || levels > ORA_TREE_ROWS - 1 || (levels > 0 && !width)) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    int rows = 1;
+    for (int j = 0; j < levels; ++j) {
+        if (width[j] < 1 || width[j] > ORA_TOPK) return ORA_EINVAL;
+        rows += width[j];
+    }
+    if (rows > ORA_TREE_ROWS) return ORA_EINVAL;
+    if (m->n + rows > m->c.max_seq) return ORA_ECAPACITY;
+    const int V = m->c.vocab, n = m->n;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)V);
+    int extra[ORA_TREE_ROWS + 1];
+    int n_spine = 0; /* extra[0..n_spine) = slots of row 0 and of the spine rows of the levels done */
+    int row = 0;
+    for (int j = 0; j <= levels; ++j) {
+        const int w = j == 0 ? 1 : width[j - 1];
+        const int first = row;
+        for (int i = 0; i < w; ++i, ++row) {
+            extra[n_spine] = n + row; /* itself, after its ancestors */
+            int rc = forward_row_general(m, tokens[row], n + j, n + row, extra, n_spine + 1, n, NULL, lg, 0);
+            if (rc) {
+                free(lg);
+                return rc;
+            }
+            int32_t tok;
+            ora_argmax_conf(lg, V, &tok, NULL);
+            m->tree_tokens[row] = tokens[row];
+            m->tree_target[row] = tok;
+            if (target_tokens) target_tokens[row] = tok;
+            if (logits_out) memcpy(logits_out + (int64_t)row * V, lg, sizeof(double) * (size_t)V);
+        }
+        extra[n_spine++] = n + first; /* the first row of the level is the ancestor of the next levels */
+    }
+    free(lg);
+    m->tree_levels = levels;
+    for (int j = 0; j < levels; ++j) m->tree_width[j] = width[j];
+    m->k_verify = -1;
+    m->n_verify_passes++;
+    return ORA_OK;
+}
+
+/* Acceptance on the tree: starting from the target's token after the pending token, a level is
+ * accepted if one of its candidates equals the target's token for the path so far; the path goes on
+ * only through the spine (the other candidates were not extended by the draft model).  Emits the
+ * accepted candidates and the target's own next token, moves the keys/values of the accepted rows to
+ * slots n+1 .. n+m (row 0 already sits in slot n), and sets cache length n + m + 1. */
+int ora_accept_tree(ora_model *m, int32_t *emitted, int *n_emitted) {
+    if (!m) return ORA_EINVAL;
+    if (m->tree_levels < 0) return ORA_ESTATE;
+    const ora_config *c = &m->c;
+    const int KV = c->n_kv_heads * c->head_dim;
+    int32_t cur = m->tree_target[0];
+    int acc = 0, start = 1;
+    for (int j = 1; j <= m->tree_levels; ++j) {
+        const int w = m->tree_width[j - 1];
+        int hit = -1;
+        for (int i = 0; i < w; ++i)
+            if (m->tree_tokens[start + i] == cur) {
+                hit = i;
+                break;
+            }
+        if (hit < 0) break;
+        const int row = start + hit;
+        if (emitted) emitted[acc] = cur;
+        ++acc;
+        if (row != acc) /* accepted row's keys/values to slot n + acc */
+            for (int l = 0; l < c->n_layers; ++l) {
+                memcpy(kslot(m, l, m->n + acc), kslot(m, l, m->n + row), sizeof(float) * (size_t)KV);
+                memcpy(vslot(m, l, m->n + acc), vslot(m, l, m->n + row), sizeof(float) * (size_t)KV);
+            }
+        cur = m->tree_target[row];
+        if (hit != 0) break; /* a candidate beside the spine has no children */
+        start += w;
+    }
+    if (emitted) emitted[acc] = cur;
+    if (n_emitted) *n_emitted = acc + 1;
+    m->n += acc + 1;
+    m->pending = cur;
+    m->n_accepted += acc;
+    m->n_emitted += acc + 1;
+    m->tree_levels = -1;
     m->k_draft = -1;
     return ORA_OK;
 }

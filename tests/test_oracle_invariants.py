@@ -310,6 +310,126 @@ def test_optimisation_steps_retain_the_best_and_terminate(oracle_lib, small):
     assert len(hist) == 3
 
 
+def test_topk_widths_and_selection(oracle_lib):
+    """Section 4.2, strategy 2: k = 10, 5, 3, 1 for a confidence in (0, 0.5], (0.5, 0.8], (0.8, 0.95],
+    (0.95, 1]; the k candidates are the k largest logits, largest first, equal values in index order."""
+    L = oracle_lib.lib()
+    for p, k in ((1e-9, 10), (0.3, 10), (0.5, 10), (0.50001, 5), (0.8, 5), (0.80001, 3), (0.95, 3), (0.950001, 1),
+                 (1.0, 1)):
+        assert L.ora_topk_width(p) == k, p
+    rng = np.random.default_rng(0)
+    import ctypes as C
+    for n in (12, 200, 1000):
+        lg = rng.normal(size=n)
+        lg[rng.integers(0, n, 6)] = lg[3]                   # ties
+        out = np.zeros(10, np.int32)
+        L.ora_topk(lg.ctypes.data_as(C.POINTER(C.c_double)), n, 10, out.ctypes.data_as(C.POINTER(C.c_int32)))
+        want = np.argsort(-lg.astype(np.float32), kind="stable")[:10]
+        assert np.array_equal(out, want)
+
+
+@pytest.mark.parametrize("max_k,eps", [(1, 0.0), (4, 0.0), (8, 0.6), (15, 0.3)])
+def test_dynamic_verification_is_lossless(oracle_lib, small, max_k, eps):
+    """Sections 1 and 3.1: whatever is drafted, and however widely it is verified, the output is the
+    target model's greedy output.  Also: the cache that tree acceptance leaves behind (accepted rows
+    moved to consecutive slots) is the cache plain decoding builds; a block never exceeds 16 rows;
+    the counters add up."""
+    s, o, prompt, ar = small
+    masks = _masks(s.n_layers)
+    ref = oracle_lib.Oracle(s, 96)
+    ref.set_weights(hp.shaped_weights(s, seed=21))
+    leaf_hits = 0
+    for name in ("none", "all", "only1", "only4", "rand0", "rand2"):
+        out, trace = oracle_lib.generate_swift_tree(o, prompt, 40, masks[name], max_k, eps)
+        assert np.array_equal(out, ar), name
+        assert 1 + sum(t["m"] + 1 for t in trace) == 40
+        for t in trace:
+            rows = 1 + sum(len(l) for l in t["levels"])
+            assert rows <= 16 and len(t["levels"]) <= max_k
+            for lev, p in zip(t["levels"], t["conf"]):
+                assert 1 <= len(lev) <= oracle_lib.lib().ora_topk_width(p) and len(set(lev.tolist())) == len(lev)
+            # an accepted candidate beside the spine ends the path
+            path = t["emitted"][:-1]
+            for j, tok in enumerate(path):
+                assert tok in t["levels"][j]
+                if tok != t["levels"][j][0]:
+                    assert j == len(path) - 1
+                    leaf_hits += 1
+        # the cache equals the one plain decoding leaves (same rows, same arithmetic, moved)
+        n = o.cache_len
+        ref.prefill(np.concatenate([prompt, out])[:n])
+        for l in range(s.n_layers):
+            for pos in (n - 1, n - 2, n - 5, n - 9):
+                ko, vo = o.read_kv(l, pos)
+                kr, vr = ref.read_kv(l, pos)
+                assert np.array_equal(ko, kr) and np.array_equal(vo, vr), (name, l, pos)
+    if max_k >= 4:
+        assert leaf_hits > 0          # the widening really rescued some positions
+    ref.close()
+
+
+def test_width_one_tree_is_the_plain_chain(oracle_lib, small):
+    """With one candidate per position the token tree is the draft chain: same drafts, same target
+    tokens, same accepted counts, same logits as ora_verify, step by step."""
+    s, o, prompt, ar = small
+    masks = _masks(s.n_layers)
+    for name in ("rand1", "only3"):
+        out_c, tr_c = oracle_lib.generate_swift(o, prompt, 30, masks[name], 5, 0.4)
+        out_t, tr_t = oracle_lib.generate_swift_tree(o, prompt, 30, masks[name], 5, 0.4, max_width=1)
+        assert np.array_equal(out_c, out_t) and len(tr_c) == len(tr_t)
+        for c, t in zip(tr_c, tr_t):
+            assert np.array_equal(c["draft"], [l[0] for l in t["levels"]])
+            assert np.array_equal(c["target"], t["target"]) and c["m"] == t["m"]
+    # a wider tree never accepts fewer tokens per step at the same state than the chain would
+    o.prefill(prompt)
+    levels, conf = o.draft_step_topk(masks["rand1"], 5, 0.0)
+    tgt, lg_t = o.verify_tree(o.pending, levels, want_logits=True)
+    spine_rows = np.cumsum([1] + [len(l) for l in levels[:-1]])
+    chain = np.array([o.pending] + [l[0] for l in levels], np.int32)
+    o.accept_tree()
+    o.prefill(prompt)
+    tgt_c, lg_c = o.verify(chain, True)
+    assert np.array_equal(lg_c[0], lg_t[0])
+    for j, r in enumerate(spine_rows):
+        assert np.array_equal(lg_c[j + 1], lg_t[r])       # spine rows see exactly the chain's context
+    o.accept()
+
+
+def test_tree_acceptance_by_hand(oracle_lib, small):
+    """Hand-built trees: a candidate beside the spine is accepted and ends the path even when the
+    next level happens to hold the token that follows it (that level continues the spine, not the
+    accepted candidate); a spine hit goes on to the next level; no hit emits only the target's token."""
+    s, o, prompt, ar = small
+    g0, g1, g2 = int(ar[1]), int(ar[2]), int(ar[3])
+    wrong = (g0 + 1) % s.vocab
+    other = (g1 + 7) % s.vocab
+    n0 = len(prompt)
+    # accepted beside the spine at level 1; level 2 (children of `wrong`) contains g1
+    o.prefill(prompt)
+    o.verify_tree(o.pending, [np.array([wrong, g0], np.int32), np.array([g1, other], np.int32)])
+    assert np.array_equal(o.accept_tree(), [g0, g1]) and (o.cache_len, o.pending) == (n0 + 2, g1)
+    # spine hits at both levels, then the target's own token
+    o.prefill(prompt)
+    o.verify_tree(o.pending, [np.array([g0, wrong], np.int32), np.array([g1, other], np.int32)])
+    assert np.array_equal(o.accept_tree(), [g0, g1, g2]) and (o.cache_len, o.pending) == (n0 + 3, g2)
+    # spine hit at level 1, a candidate beside the spine at level 2
+    o.prefill(prompt)
+    o.verify_tree(o.pending, [np.array([g0, wrong], np.int32), np.array([other, g1], np.int32)])
+    assert np.array_equal(o.accept_tree(), [g0, g1, g2]) and o.cache_len == n0 + 3
+    # nothing matches
+    o.prefill(prompt)
+    o.verify_tree(o.pending, [np.array([wrong], np.int32), np.array([g1], np.int32)])
+    assert np.array_equal(o.accept_tree(), [g0]) and (o.cache_len, o.pending) == (n0 + 1, g0)
+    # decoding continues correctly from the compacted cache
+    tgt, _ = o.verify([o.pending])
+    assert int(tgt[0]) == g1
+    o.accept()
+    with pytest.raises(Exception):
+        o.accept_tree()                                # no tree outstanding
+    with pytest.raises(Exception):
+        o.verify_tree(o.pending, [np.arange(10, dtype=np.int32), np.arange(10, dtype=np.int32)])   # 21 rows
+
+
 def test_state_and_capacity_errors(oracle_lib, small):
     s, o, prompt, ar = small
     o.reset()
