@@ -30,8 +30,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None):
-    """One step.  Returns (tokens, prefill_s, decode_s, trace)."""
+def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None, tree_width=0):
+    """One step.  tree_width > 0: dynamic verification with at most that many candidates per draft
+    position.  Returns (tokens, prefill_s, decode_s, trace)."""
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -44,6 +45,13 @@ def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None):
     trace = []
     while len(out) < n_new:
         k_cap = min(max_k, n_new - len(out) - 1)
+        if tree_width > 0:
+            levels = g.draft_step_topk(mask, k_cap, eps, tree_width)[0] if k_cap > 0 else []
+            g.verify_tree(levels)
+            em = g.accept_tree()
+            out.extend(int(t) for t in em)
+            trace.append((len(levels), len(em) - 1))
+            continue
         if k_cap > 0:
             d, conf = g.draft_step(mask, k_cap, eps)
         else:
@@ -205,6 +213,13 @@ def main():
         modes["forced_max_draft_no_skip"] = {"tokens_per_s": round(n_after / dc, 2),
                                              "M": round(s3["emitted_by_verify"] / max(s3["verify_passes"], 1), 3),
                                              "alpha": round(s3["accepted"] / max(s3["draft_passes"], 1), 4)}
+        # dynamic verification (Section 4.2, second strategy): candidate trees instead of chains
+        out_t, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold, tree_width=10)
+        s4 = g.stats()
+        modes["dynamic_verification"] = {"tokens_per_s": round(n_after / dc, 2),
+                                         "M": round(s4["emitted_by_verify"] / max(s4["verify_passes"], 1), 3),
+                                         "alpha": round(s4["accepted"] / max(s4["draft_passes"], 1), 4),
+                                         "same_tokens": bool(np.array_equal(out_t[:w.n_new], ref))}
         log(f"[bench] modes: {modes}")
 
     # ---- per-pass times (host clock around calls that end in a device synchronisation), the

@@ -214,6 +214,45 @@ int swift_verify(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_t
  * the pending token.  Slots at or beyond the new cache length are don't-care from here on. */
 int swift_accept(swift_ctx *ctx, int32_t *emitted, int *n_emitted);
 
+/* ---- dynamic verification (Section 4.2, second strategy of the inference phase) ----------------
+ * Each draft position keeps its top candidates, the fewer the more confident the draft model is, and the
+ * target model verifies all of them in one block whose rows form a token tree.
+ * Readings (the paper gives the bands and the idea, not the tree's shape): only the first candidate of
+ * a position (the greedy draft token) is continued by the draft model, so a position's other candidates
+ * are leaves; a block holds at most SWIFT_MAX_BLOCK rows (pending token + all candidates). */
+#define SWIFT_TOPK 10
+/* Candidates kept for a position drafted with confidence p: 10, 5, 3, 1 for p in (0, 0.5], (0.5, 0.8],
+ * (0.8, 0.95], (0.95, 1]. */
+int swift_topk_width(float p);
+
+/* swift_draft_step that also keeps candidates: position j = 1..*k_out gets width[j-1] =
+ * min(swift_topk_width(p_j), max_width, rows still free in the block) tokens in
+ * tokens[(j-1)*SWIFT_TOPK ..] (host, [max_k][SWIFT_TOPK]; largest logit first, equal logits in id order;
+ * the first is the draft token the next position continues from).  Drafting ends as in swift_draft_step, or
+ * when the block is full.  draft_conf, width: host, max_k entries.  max_width >= 1 (1: the plain chain).
+ * Needs 0 <= max_k <= SWIFT_MAX_BLOCK - 1 and n + SWIFT_MAX_BLOCK <= max_seq (SWIFT_ECAPACITY). */
+int swift_draft_step_topk(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold, int max_width,
+                          int32_t *tokens, float *draft_conf, int *width, int *k_out);
+
+/* Verification of a token tree in one block of the target model.  tokens (host): row 0 = the pending
+ * token, then the width[0] candidates of level 1, the width[1] of level 2, ... (`levels` levels; rows =
+ * 1 + sum width <= SWIFT_MAX_BLOCK; 1 <= width[j] <= SWIFT_TOPK).  A row of level j is computed at sequence
+ * position n + j; it attends the committed slots 0..n-1, row 0, the first rows of levels 1..j-1 and itself;
+ * its keys/values go to cache slot n + (row index).  target_tokens (host, one per row) = arg-max of each
+ * row: the target's next token after the path that ends in that row.  logits_out: NULL, or host fp32
+ * [rows][vocab].  Every row's result equals, bit for bit, that of the same path verified as a chain by
+ * swift_verify.  levels = 0 is one step of plain decoding.  Errors as swift_verify. */
+int swift_verify_tree(swift_ctx *ctx, const int32_t *tokens, const int *width, int levels, int32_t *target_tokens,
+                      float *logits_out);
+
+/* Acceptance after a swift_verify_tree: starting with the target's token after the pending token, a level
+ * is accepted if one of its candidates equals the target's token for the path so far (the path goes on
+ * only through a level's first candidate).  emitted (host, capacity >= levels + 1) receives the m accepted
+ * candidates and the target's own next token; *n_emitted = m + 1.  The accepted rows' keys/values are moved
+ * to slots n+1..n+m of every layer (device copy, stream-ordered), the cache length becomes n + m + 1 and
+ * the last emitted token the pending token.  SWIFT_ESTATE without a preceding swift_verify_tree. */
+int swift_accept_tree(swift_ctx *ctx, int32_t *emitted, int *n_emitted);
+
 /* Sets the cache length to new_cache_len <= current (no data is touched) and makes
  * `pending_token` the pending token.  For callers that manage acceptance themselves. */
 int swift_rollback(swift_ctx *ctx, int new_cache_len, int32_t pending_token);

@@ -6,7 +6,7 @@ arguments; PyTorch is used for device memory and streams.
 """
 from .binding import (Optimizer, SwiftError, SwiftModel, check_config, device_bytes, expected_speedup, lib, match_prefix,
                       pass_bytes, KERNEL_CLASSES)
-from .decode import generate_ar, generate_swift
+from .decode import generate_ar, generate_swift, generate_swift_tree
 
 __all__ = ["Optimizer", "SwiftError", "SwiftModel", "check_config", "device_bytes", "expected_speedup", "lib", "match_prefix",
-           "pass_bytes", "generate_ar", "generate_swift", "KERNEL_CLASSES"]
+           "pass_bytes", "generate_ar", "generate_swift", "generate_swift_tree", "KERNEL_CLASSES"]

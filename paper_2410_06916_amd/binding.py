@@ -11,6 +11,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 MAX_BLOCK = 16
+TOPK = 10
 KERNEL_CLASSES = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lmhead": 5, "other": 6}
 _CODES = {-1: "SWIFT_EINVAL", -2: "SWIFT_ECAPACITY", -3: "SWIFT_ESTATE", -4: "SWIFT_EDEVICE"}
 
@@ -81,6 +82,11 @@ def lib():
     L.swift_opt_step.argtypes = [vp, vp, i32p, C.c_int, u8p, C.POINTER(C.c_double), u8p, C.POINTER(C.c_double),
                                  C.POINTER(C.c_int)]
     L.swift_accept.argtypes = [vp, i32p, C.POINTER(C.c_int)]
+    L.swift_topk_width.argtypes = [C.c_float]
+    L.swift_draft_step_topk.argtypes = [vp, u8p, C.c_int, C.c_float, C.c_int, i32p, f32p, C.POINTER(C.c_int),
+                                        C.POINTER(C.c_int)]
+    L.swift_verify_tree.argtypes = [vp, i32p, C.POINTER(C.c_int), C.c_int, i32p, f32p]
+    L.swift_accept_tree.argtypes = [vp, i32p, C.POINTER(C.c_int)]
     L.swift_rollback.argtypes = [vp, C.c_int, C.c_int32]
     L.swift_get_state.argtypes = [vp, C.POINTER(C.c_int), i32p]
     L.swift_get_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -219,6 +225,38 @@ class SwiftModel:
         out = np.zeros(MAX_BLOCK, np.int32)
         n = C.c_int()
         _chk(lib().swift_accept(self._h, _p(out, C.c_int32), C.byref(n)), "swift_accept")
+        return out[:n.value].copy()
+
+    def draft_step_topk(self, skip: np.ndarray, max_k: int, conf_threshold: float, max_width: int = 10):
+        """Drafting that keeps the top candidates of every position (Section 4.2, second strategy).
+        Returns (levels: one int32 array of candidates per draft position, first = the draft token; conf[k])."""
+        skip = np.ascontiguousarray(skip, np.uint8)
+        cap = max(max_k, 1)
+        toks = np.zeros((cap, TOPK), np.int32)
+        conf = np.zeros(cap, np.float32)
+        width = np.zeros(cap, np.intc)
+        k = C.c_int()
+        _chk(lib().swift_draft_step_topk(self._h, _p(skip, C.c_uint8), max_k, conf_threshold, max_width,
+                                         _p(toks, C.c_int32), _p(conf, C.c_float), _p(width, C.c_int), C.byref(k)),
+             "swift_draft_step_topk")
+        return [toks[j, :width[j]].copy() for j in range(k.value)], conf[:k.value].copy()
+
+    def verify_tree(self, levels, want_logits: bool = False):
+        """levels: candidate arrays per draft position (first = the draft token).  The block is the pending
+        token followed by the levels.  Returns (targets[rows], logits or None)."""
+        rows = np.concatenate([[self.pending]] + [np.asarray(l, np.int32) for l in levels]).astype(np.int32)
+        width = np.array([len(l) for l in levels], np.intc)
+        tgt = np.zeros(rows.size, np.int32)
+        lg = np.empty((rows.size, self.cfg.vocab), np.float32) if want_logits else None
+        _chk(lib().swift_verify_tree(self._h, _p(rows, C.c_int32), _p(width, C.c_int) if len(levels) else None,
+                                     len(levels), _p(tgt, C.c_int32), _p(lg, C.c_float) if want_logits else None),
+             "swift_verify_tree")
+        return tgt, lg
+
+    def accept_tree(self) -> np.ndarray:
+        out = np.zeros(MAX_BLOCK, np.int32)
+        n = C.c_int()
+        _chk(lib().swift_accept_tree(self._h, _p(out, C.c_int32), C.byref(n)), "swift_accept_tree")
         return out[:n.value].copy()
 
     def eval_mask(self, skip: np.ndarray, window: Sequence[int]):

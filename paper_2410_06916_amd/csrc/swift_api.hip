@@ -73,7 +73,7 @@ struct Layout {
     uint64_t embed, lm_head, final_norm;
     std::vector<LayerOff> layers;
     uint64_t cos, sin, kv;
-    uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf;
+    uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf, out_topk;
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
     uint64_t xs, as_, hs, pss, mv_part, mv_counters;
     // persistent stack kernel: cached stage lists, barrier counter + error flag
@@ -133,6 +133,7 @@ Layout make_layout(const swift_model_config &c) {
     L.part_ml = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * 2 * 4);
     L.out_tok = take(kMaxBlockRows * 4);
     L.out_conf = take(kMaxBlockRows * 4);
+    L.out_topk = take(kMaxBlockRows * kTopK * 4);
     L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxBlockRows * 16);
     L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxBlockRows * 16);
     L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxBlockRows * 16);
@@ -232,6 +233,10 @@ struct swift_ctx {
     int32_t pending;  // -1 before prefill
     int k_verify;     // -1: no verify outstanding
     int32_t vtokens[SWIFT_MAX_BLOCK], targets[SWIFT_MAX_BLOCK];
+    int tree_levels;  // -1: no tree verification outstanding
+    int tree_width[SWIFT_MAX_BLOCK];
+    bool want_topk;   // the next pass with logits also keeps the top candidates of its rows
+    int32_t *h_topk;  // pinned, [kTopK]
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
     int tune_ks[SWIFT_KC_COUNT], tune_wg[SWIFT_KC_COUNT];
@@ -296,11 +301,19 @@ char *kv_base(swift_ctx *x, int layer, int which) {
     return x->base + x->L.kv + ((uint64_t)layer * 2 + which) * per;
 }
 
+// The rows of a token tree: level of each block row, block row of the first candidate of each level
+// (the only one with children), both also packed as 4-bit fields for the kernels.
+struct TreeRows {
+    int depth[kMaxRows], spine[kMaxRows];
+    uint64_t depth4, spine4;
+};
+
 // ---- storage-generic path: one token through the network at position `pos`; row = which row of
 // the activation / logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM
-// head and the arg-max for this row.
+// head and the arg-max for this row.  tree: the row is block row `row` of a token tree whose first row
+// sits in slot tree_base; `pos` is then the row's cache slot and it is rotated for its level's position.
 int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int row, bool want_logits,
-                bool reuse_kv = false) {
+                bool reuse_kv = false, const TreeRows *tree = nullptr, int tree_base = 0) {
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -325,8 +338,9 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
         if (epi == EPI_QKV) {
             g.kcache = kv_base(x, layer, 0);
             g.vcache = kv_base(x, layer, 1);
-            g.cos_row = dptr<float>(x, L.cos) + (size_t)pos * (d / 2);
-            g.sin_row = dptr<float>(x, L.sin) + (size_t)pos * (d / 2);
+            const int rope_pos = tree ? tree_base + tree->depth[row] : pos;
+            g.cos_row = dptr<float>(x, L.cos) + (size_t)rope_pos * (d / 2);
+            g.sin_row = dptr<float>(x, L.sin) + (size_t)rope_pos * (d / 2);
         }
         g.pos = pos;
         g.max_seq = c.max_seq;
@@ -361,6 +375,13 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.max_split = L.n_split_max;
             a.out = ar;
             a.out_s = nullptr;
+            if (tree) {
+                a.tree = 1;
+                a.n_base = tree_base;
+                a.row_base = row;
+                a.depth4 = tree->depth4;
+                a.spine4 = tree->spine4;
+            }
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
                           [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
             if ((rc = linear(SWIFT_KC_OPROJ, EPI_RESID, y.wo, H, Q, ar, nullptr, xr, l))) return rc;
@@ -372,7 +393,8 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
     }
     if (want_logits) {
         if ((rc = linear(SWIFT_KC_LMHEAD, EPI_LOGITS, L.lm_head, V, H, xr, dptr<float>(x, L.final_norm), lr, 0))) return rc;
-        ArgmaxArgs m{lr, V, 1, dptr<int32_t>(x, L.out_tok) + row, dptr<float>(x, L.out_conf) + row};
+        ArgmaxArgs m{lr, V, 1, dptr<int32_t>(x, L.out_tok) + row, dptr<float>(x, L.out_conf) + row,
+                     x->want_topk ? dptr<int32_t>(x, L.out_topk) + (size_t)row * kTopK : nullptr, kTopK};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)V * 4, [&] { return launch_argmax_conf(m, s); }));
     }
     return SWIFT_OK;
@@ -380,8 +402,10 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
 
 // ---- tiled bf16 path: a block of R rows (tokens[0..R) at positions pos0..pos0+R-1) through the
 // network in one sweep over the weights.  Row r attends cache slots [0, pos0 + r].
+// tree: the rows are those of a token tree (R <= 16): row r goes to slot pos0 + r, is rotated for position
+// pos0 + its level, and attends the committed slots and the rows on its path from the root.
 int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
-                        bool reuse_kv = false) {
+                        bool reuse_kv = false, const TreeRows *tree = nullptr) {
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -458,6 +482,10 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.ld_out = Q;
             m.kcache = kv_base(x, l, 0);
             m.vcache = kv_base(x, l, 1);
+            if (tree) {
+                m.tree = 1;
+                m.depth4 = tree->depth4;
+            }
             push_mv(SWIFT_KC_QKV, EPI_QKV, m, 0);
 
             StackStage at{};
@@ -478,6 +506,13 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.max_split = L.n_split_max;
             a.out = nullptr;
             a.out_s = as_;
+            if (tree) {
+                a.tree = 1;
+                a.n_base = pos0;
+                a.row_base = 0;
+                a.depth4 = tree->depth4;
+                a.spine4 = tree->spine4;
+            }
             list.push_back(at);
             classes.push_back(SWIFT_KC_ATTN);
 
@@ -535,7 +570,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     const int group = c.n_q_heads / c.n_kv_heads;
     const int max_T = (std::max(std::max(H, Q), F) + 31) / 32;
     const size_t stack_lds = stack_lds_bytes(max_T, R, d, group, (int)list.size());
-    const bool use_stack = x->stack_on && !reuse_kv && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
+    const bool use_stack = x->stack_on && !reuse_kv && !tree && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
                            pos0 + R <= 1536 && n_att <= x->n_cu / 2 && (int)list.size() <= L.stack_max_stages &&
                            (group == 1 || group == 2 || group == 4 || group == 8);
     if (use_stack) {
@@ -593,6 +628,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                     AttnArgs a = list[i].at;
                     a.q += (size_t)row0 * Q;
                     a.n_ctx += row0;
+                    a.row_base = row0;  // (a tree has at most 16 rows: one part)
                     a.rows = std::min(per_launch, R - row0);
                     a.out_s += 24 * row0;  // first of this part's 3 * rows term columns
                     a.out_rows = R <= kMaxRows ? R : kMaxBlockRows;
@@ -608,7 +644,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         }
     }
     if (want_logits) {
-        ArgmaxArgs am{dptr<float>(x, L.logits), V, R, dptr<int32_t>(x, L.out_tok), dptr<float>(x, L.out_conf)};
+        ArgmaxArgs am{dptr<float>(x, L.logits), V, R, dptr<int32_t>(x, L.out_tok), dptr<float>(x, L.out_conf),
+                      x->want_topk ? dptr<int32_t>(x, L.out_topk) : nullptr, kTopK};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * V * 4, [&] { return launch_argmax_conf(am, s); }));
     }
     return SWIFT_OK;
@@ -618,10 +655,11 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
 // reuse_kv: the rows' keys and values are not computed; every row attends what the cache already holds
 // for slots up to its own position (candidate evaluation).
 int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
-                  bool reuse_kv = false) {
-    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits, reuse_kv);
+                  bool reuse_kv = false, const TreeRows *tree = nullptr) {
+    if (tree && R > kMaxRows) return fail(SWIFT_EINVAL, "a token tree has at most 16 rows");
+    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits, reuse_kv, tree);
     for (int r = 0; r < R; ++r) {
-        int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits, reuse_kv);
+        int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits, reuse_kv, tree, pos0);
         if (rc) return rc;
     }
     return SWIFT_OK;
@@ -740,6 +778,9 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->n = 0;
     x->pending = -1;
     x->k_verify = -1;
+    x->tree_levels = -1;
+    x->want_topk = false;
+    x->h_topk = nullptr;
     memset(&x->st, 0, sizeof(x->st));
     x->prof_class = -1;
     memset(x->tune_ks, 0, sizeof(x->tune_ks));
@@ -754,7 +795,7 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->stack_used = false;
     x->stack_keys.assign(kStackTables, StackKey());
     x->h_err = nullptr;
-    hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxBlockRows + 4) * 4, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxBlockRows + 4 + kTopK) * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete x;
         return fail(SWIFT_EDEVICE, std::string("hipHostMalloc: ") + hipGetErrorString(e));
@@ -762,6 +803,7 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->h_conf = (float *)(x->h_tok + kMaxBlockRows);
     x->h_err = x->h_tok + 2 * kMaxBlockRows;
     x->h_err[0] = 0;
+    x->h_topk = x->h_tok + 2 * kMaxBlockRows + 4;
 
     // rotary tables: angle = pos * theta^(-2i/d) in fp64, cos/sin rounded to fp32
     const int half = cfg->head_dim / 2;
@@ -869,6 +911,7 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     x->n = n_prompt;
     x->pending = x->h_tok[last_rows - 1];
     x->k_verify = -1;
+    x->tree_levels = -1;
     memset(&x->st, 0, sizeof(x->st));
     x->st.emitted_total = 1;
     *first_token = x->pending;
@@ -944,6 +987,7 @@ extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t 
         target_tokens[i] = x->h_tok[i];
     }
     x->k_verify = k;
+    x->tree_levels = -1;
     x->st.verify_passes++;
     return SWIFT_OK;
 }
@@ -965,6 +1009,134 @@ extern "C" int swift_accept(swift_ctx *x, int32_t *emitted, int *n_emitted) {
     return SWIFT_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// dynamic verification (Section 4.2, second strategy): top-k candidates per draft position, verified as a
+// token tree
+// ------------------------------------------------------------------------------------------
+extern "C" int swift_topk_width(float p) { return p <= 0.5f ? 10 : p <= 0.8f ? 5 : p <= 0.95f ? 3 : 1; }
+
+extern "C" int swift_draft_step_topk(swift_ctx *x, const uint8_t *skip_mask, int max_k, float conf_threshold, int max_width,
+                                     int32_t *tokens, float *draft_conf, int *width, int *k_out) {
+    if (!x || !skip_mask || !k_out) return fail(SWIFT_EINVAL, "null argument");
+    if (max_k < 0 || max_k > SWIFT_MAX_BLOCK - 1) return fail(SWIFT_EINVAL, "max_k out of range");
+    if (max_width < 1) return fail(SWIFT_EINVAL, "max_width must be at least 1");
+    if (max_k > 0 && (!tokens || !draft_conf || !width)) return fail(SWIFT_EINVAL, "null output array");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "draft before prefill");
+    if (x->n + SWIFT_MAX_BLOCK > x->c.max_seq) return fail(SWIFT_ECAPACITY, "a full tree block would run past the cache capacity");
+    int32_t prev = x->pending;
+    int k = 0, rows = 1;
+    for (int j = 1; j <= max_k && rows < SWIFT_MAX_BLOCK; ++j) {
+        x->want_topk = true;
+        int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
+        x->want_topk = false;
+        if (rc) return rc;
+        HIP_TRY(hipMemcpyAsync(x->h_topk, dptr<int32_t>(x, x->L.out_topk), kTopK * 4, hipMemcpyDeviceToHost, x->stream));
+        rc = read_results(x, 1);
+        if (rc) return rc;
+        const float p = x->h_conf[0];
+        int w = swift_topk_width(p);
+        w = std::min(w, max_width);
+        w = std::min(w, SWIFT_MAX_BLOCK - rows);
+        w = std::min(w, x->c.vocab);
+        for (int i = 0; i < w; ++i) tokens[(size_t)k * SWIFT_TOPK + i] = x->h_topk[i];
+        width[k] = w;
+        draft_conf[k] = p;
+        prev = x->h_tok[0];
+        rows += w;
+        ++k;
+        x->st.draft_passes++;
+        if (p < conf_threshold) break;
+    }
+    *k_out = k;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_verify_tree(swift_ctx *x, const int32_t *tokens, const int *width, int levels, int32_t *target_tokens,
+                                 float *logits_out) {
+    if (!x || !tokens || !target_tokens) return fail(SWIFT_EINVAL, "null argument");
+    if (levels < 0 || levels > SWIFT_MAX_BLOCK - 1 || (levels > 0 && !width)) return fail(SWIFT_EINVAL, "levels out of range");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "verify before prefill");
+    if (tokens[0] != x->pending) return fail(SWIFT_EINVAL, "tokens[0] must be the pending token");
+    TreeRows t{};
+    int rows = 1;
+    for (int j = 1; j <= levels; ++j) {
+        const int w = width[j - 1];
+        if (w < 1 || w > SWIFT_TOPK) return fail(SWIFT_EINVAL, "level width out of range (1..10)");
+        if (rows + w > SWIFT_MAX_BLOCK) return fail(SWIFT_EINVAL, "more than 16 rows in the tree");
+        t.spine[j] = rows;
+        for (int i = 0; i < w; ++i) t.depth[rows++] = j;
+    }
+    for (int r = 0; r < rows; ++r) {
+        if (tokens[r] < 0 || tokens[r] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
+        t.depth4 |= (uint64_t)t.depth[r] << (4 * r);
+    }
+    for (int j = 0; j <= levels; ++j) t.spine4 |= (uint64_t)t.spine[j] << (4 * j);
+    if (x->n + rows > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
+    int rc = forward_block(x, tokens, rows, x->n, nullptr, true, false, &t);
+    if (rc) return rc;
+    rc = read_results(x, rows);
+    if (rc) return rc;
+    if (logits_out) {
+        HIP_TRY(hipMemcpyAsync(logits_out, dptr<float>(x, x->L.logits), (size_t)rows * x->c.vocab * 4, hipMemcpyDeviceToHost,
+                               x->stream));
+        HIP_TRY(hipStreamSynchronize(x->stream));
+    }
+    for (int r = 0; r < rows; ++r) {
+        x->vtokens[r] = tokens[r];
+        x->targets[r] = x->h_tok[r];
+        target_tokens[r] = x->h_tok[r];
+    }
+    x->tree_levels = levels;
+    for (int j = 0; j < levels; ++j) x->tree_width[j] = width[j];
+    x->k_verify = -1;
+    x->st.verify_passes++;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_accept_tree(swift_ctx *x, int32_t *emitted, int *n_emitted) {
+    if (!x || !emitted || !n_emitted) return fail(SWIFT_EINVAL, "null argument");
+    if (x->tree_levels < 0) return fail(SWIFT_ESTATE, "accept without a preceding tree verification");
+    const swift_model_config &c = x->c;
+    KvMoveArgs mv{};
+    int32_t cur = x->targets[0];
+    int acc = 0, start = 1;
+    for (int j = 1; j <= x->tree_levels; ++j) {
+        const int w = x->tree_width[j - 1];
+        int hit = -1;
+        for (int i = 0; i < w && hit < 0; ++i)
+            if (x->vtokens[start + i] == cur) hit = i;
+        if (hit < 0) break;
+        const int row = start + hit;
+        emitted[acc++] = cur;
+        if (row != acc) {  // the accepted row's keys/values to slot n + acc
+            mv.src[mv.n_moves] = x->n + row;
+            mv.dst[mv.n_moves] = x->n + acc;
+            ++mv.n_moves;
+        }
+        cur = x->targets[row];
+        if (hit != 0) break;  // a candidate beside the first has no children
+        start += w;
+    }
+    if (mv.n_moves > 0) {
+        mv.kv = x->base + x->L.kv;
+        mv.plane_elems = (int64_t)c.n_kv_heads * c.max_seq * c.head_dim;
+        mv.n_planes = 2 * c.n_layers;
+        mv.n_kv_heads = c.n_kv_heads;
+        mv.max_seq = c.max_seq;
+        mv.head_dim = c.head_dim;
+        HIP_TRY(launch_kv_move(c.dtype, mv, x->stream));
+    }
+    emitted[acc] = cur;
+    *n_emitted = acc + 1;
+    x->n += acc + 1;
+    x->pending = cur;
+    x->tree_levels = -1;
+    x->st.accepted += acc;
+    x->st.emitted_by_verify += acc + 1;
+    x->st.emitted_total += acc + 1;
+    return SWIFT_OK;
+}
+
 extern "C" int swift_rollback(swift_ctx *x, int new_cache_len, int32_t pending_token) {
     if (!x) return fail(SWIFT_EINVAL, "null context");
     if (x->pending < 0) return fail(SWIFT_ESTATE, "rollback before prefill");
@@ -973,6 +1145,7 @@ extern "C" int swift_rollback(swift_ctx *x, int new_cache_len, int32_t pending_t
     x->n = new_cache_len;
     x->pending = pending_token;
     x->k_verify = -1;
+    x->tree_levels = -1;
     return SWIFT_OK;
 }
 

@@ -75,11 +75,34 @@ __device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], 
     }
 }
 
+// Cache slots launch row `row` attends (it walks logical slots [0, this value)).
+template <bool TREE>
+__device__ inline int attn_row_ctx(const AttnArgs &a, int row) {
+    if constexpr (TREE)
+        return a.n_base + (int)((a.depth4 >> (4 * ((a.row_base + row) & 15))) & 15) + 1;
+    else
+        return a.n_ctx + row;
+}
+// Where logical slot p of launch row `row` lives in the cache (p < attn_row_ctx).  A chain row's logical
+// slots are the physical ones; a tree row's slots beyond the committed prefix are those of the rows on
+// its path from the root.
+template <bool TREE>
+__device__ inline int attn_phys_slot(const AttnArgs &a, int row, int p) {
+    if constexpr (TREE) {
+        const int lvl = p - a.n_base;
+        if (lvl < 0) return p;
+        const int depth = (int)((a.depth4 >> (4 * ((a.row_base + row) & 15))) & 15);
+        return a.n_base + (lvl < depth ? (int)((a.spine4 >> (4 * (lvl & 15))) & 15) : a.row_base + row);
+    } else {
+        return p;
+    }
+}
+
 // One workgroup of 16 wavefronts (1024 threads, all of them call this) computes the attention of
-// block row `row` for the GROUP query heads that share kv head g over the whole cache range
-// [0, n_ctx + row).  Step s of wavefront w covers slots (16 s + w) * SPW ..; the loads of NB steps
+// block row `row` for the GROUP query heads that share kv head g over the row's whole range of
+// attn_row_ctx slots.  Step s of wavefront w covers slots (16 s + w) * SPW ..; the loads of NB steps
 // are issued together.  sh: LDS, [16*GROUP] max, [16*GROUP] sum, [16*GROUP*d] weighted values.
-template <typename T, int GROUP>
+template <typename T, int GROUP, bool TREE = false>
 __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *sh) {
     constexpr int VEC = T::VEC;
     constexpr int NB = GROUP <= 2 ? 4 : 1;
@@ -87,7 +110,7 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
     const int LPP = d / VEC, SPW = 64 / LPP;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lj = lane & (LPP - 1), lg = lane / LPP;
-    const int n_ctx = a.n_ctx + row;
+    const int n_ctx = attn_row_ctx<TREE>(a, row);
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
     float *sm = sh, *sl = sh + 16 * GROUP, *so = sh + 32 * GROUP;
@@ -118,7 +141,7 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = ((s0 + b) * 16 + wave) * SPW + lg;
-            const int pc = min(p, n_ctx - 1);
+            const int pc = attn_phys_slot<TREE>(a, row, min(p, n_ctx - 1));
             pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);

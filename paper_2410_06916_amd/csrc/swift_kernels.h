@@ -36,7 +36,7 @@ struct GemvArgs {
     // EPI_QKV only
     void *kcache, *vcache;           // this layer's [n_kv][max_seq][d]
     const float *cos_row, *sin_row;  // rotary table rows for `pos`: [d/2] each
-    int pos, max_seq, head_dim, n_q_heads, n_kv_heads;
+    int pos, max_seq, head_dim, n_q_heads, n_kv_heads;  // pos: the cache slot the keys/values go to
 };
 hipError_t launch_gemv(int dtype, int epilogue, const GemvArgs &a, int n_cu, hipStream_t s);
 
@@ -61,6 +61,14 @@ struct AttnArgs {
     uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*out_rows][8], or nullptr
     int out_rows;                 // rows of the block out_s belongs to (0: rows); a launch may cover a
                                   // 16-row part of a larger block: out_s then points at its first column
+    // Token tree instead of a chain (tree != 0; at most 16 block rows).  Launch row r is block row
+    // row_base + r and sits at level depth(row) of the tree (nibble `row` of depth4); the block's
+    // keys/values sit in slots n_base + block row.  The row attends, in this order, the committed slots
+    // [0, n_base), then for level i = 0 .. depth-1 the slot of block row spine(i) (nibble i of spine4;
+    // spine(0) = 0, the block's first row), then its own slot: the same sequence of keys/values, batched
+    // the same way, as a chain row at position n_base + depth, so the result is the chain's bit for bit.
+    int tree, n_base, row_base;
+    uint64_t depth4, spine4;
 };
 // True when the attention of a block runs on the one-workgroup-per-(kv head, row) kernel (no partial
 // buffers: one launch may then cover any number of rows); false: the split kernel, at most kMaxRows
@@ -68,13 +76,27 @@ struct AttnArgs {
 inline bool attn_uses_head_kernel(int max_seq, int n_kv_heads) { return max_seq <= 1600 && n_kv_heads >= 24; }
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
 
+constexpr int kTopK = 10;  // candidates kept per row (SWIFT_TOPK)
 struct ArgmaxArgs {
     const float *logits;  // [rows][V]
     int V, rows;
     int32_t *tokens;      // [rows]
     float *conf;          // [rows]
+    int32_t *topk;        // nullptr, or [rows][kTopK]: the n_topk largest logits' indices, largest first,
+    int n_topk;           //   equal values in index order (topk[0] is the arg-max)
 };
 hipError_t launch_argmax_conf(const ArgmaxArgs &a, hipStream_t s);
+
+// Copies cache slots src[i] -> dst[i], i = 0 .. n_moves-1 in this order, for every kv head of every plane
+// (a plane: the keys or the values of one layer, [n_kv][max_seq][d]; planes are plane_elems apart).
+struct KvMoveArgs {
+    void *kv;
+    int64_t plane_elems;
+    int n_planes, n_kv_heads, max_seq, head_dim;
+    int n_moves;
+    int src[16], dst[16];
+};
+hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s);
 
 hipError_t launch_fill_nan(int dtype, void *p, int64_t n_elems, hipStream_t s);
 
@@ -132,6 +154,10 @@ struct MvArgs {
     void *kcache, *vcache;   // QKV: this layer's [n_kv][max_seq][d]
     const float *cos_tab, *sin_tab;  // QKV: [max_seq][d/2]
     int pos0, max_seq, head_dim, n_q_heads, n_kv_heads;
+    // QKV: row r's keys/values go to slot pos0 + r; it is rotated for position pos0 + r, or, for the rows
+    // of a token tree (tree != 0, R <= 16), for position pos0 + nibble r of depth4 (the row's level)
+    int tree;
+    uint64_t depth4;
     // multi-row kernel only: split-K scratch
     float *part;           // [k splits][row group][R][16] fp32 partial results
     int *counters;         // one per 8-row-group block, zero between launches
@@ -139,6 +165,10 @@ struct MvArgs {
     int S;                 // set by the launcher
     int kgroup;            // set by the launcher: K slices whose sums are added first (see mv_slice_group)
 };
+// position block row r of a QKV pass is rotated for
+__host__ __device__ inline int mv_rope_pos(const MvArgs &a, int r) {
+    return a.pos0 + (a.tree ? (int)((a.depth4 >> (4 * (r & 15))) & 15) : r);
+}
 constexpr size_t kMvMaxLds = 150 * 1024;
 // Rows the LDS-resident kernel takes (3R term columns must fit one MFMA column block)
 constexpr int kMvSmallRows = 5;

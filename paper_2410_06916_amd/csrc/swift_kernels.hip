@@ -191,8 +191,11 @@ hipError_t launch_embed(int dtype, const EmbedArgs &a, hipStream_t s) {
 // the first chunk is normalised and written directly; otherwise the workgroup writes the row's partial
 // and k_attn_combine merges the partials in split order.  What a row's result is does not depend on
 // which other rows share its workgroup: slots beyond a row's range leave its running values untouched.
-template <typename T, int GROUP, int RB>
+// TREE: the rows are those of a token tree (attn_row_ctx, attn_phys_slot); each row then has a slot of its
+// own inside its range, so rows do not share loads (RB = 1).
+template <typename T, int GROUP, int RB, bool TREE = false>
 __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
+    static_assert(!TREE || RB == 1, "tree rows do not share key/value loads");
     constexpr int VEC = T::VEC;
     constexpr int NB = GROUP <= 2 ? 4 : 1;
     constexpr int M = GROUP * RB;  // members: (row rr, head h) -> rr * GROUP + h
@@ -205,7 +208,8 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
     const int lj = lane & (LPP - 1), lg = lane / LPP;
     const int lo = sp * chunk;
     const int n_rows = min(RB, a.rows - row0);
-    const int hi_max = min(a.n_ctx + row0 + n_rows - 1, lo + chunk);  // end of the longest row's range here
+    // end of the longest row's range here
+    const int hi_max = min(TREE ? attn_row_ctx<TREE>(a, row0) : a.n_ctx + row0 + n_rows - 1, lo + chunk);
     if (hi_max <= lo) return;  // no row of this block reaches this chunk
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
         const int rr = mm / GROUP, h = mm - rr * GROUP;
         const int row = min(row0 + rr, a.rows - 1);
         // block row r sees the cache up to its own slot; rows past the block take part in nothing
-        lim[mm] = rr < n_rows ? min(a.n_ctx + row0 + rr, lo + chunk) : 0;
+        lim[mm] = rr < n_rows ? min(attn_row_ctx<TREE>(a, row0 + rr), lo + chunk) : 0;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) q[mm][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
     }
@@ -241,7 +245,8 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = lo + ((s0 + b) * 4 + wave) * SPW + lg;
-            const int pc = min(p, hi_max - 1);  // clamp: slots past the range are loaded and discarded
+            // clamp: slots past the range are loaded and discarded
+            const int pc = attn_phys_slot<TREE>(a, row0, min(p, hi_max - 1));
             pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
@@ -289,8 +294,9 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
         const int mm = idx / d, j = idx - mm * d;
         const int rr = mm / GROUP, h = mm - rr * GROUP;
         const int row = row0 + rr;
-        const int n_ctx = a.n_ctx + row;
-        if (rr >= n_rows || lo >= n_ctx) continue;       // no such row, or the row ends before this chunk
+        if (rr >= n_rows) continue;                      // no such row
+        const int n_ctx = attn_row_ctx<TREE>(a, row);
+        if (lo >= n_ctx) continue;                       // the row ends before this chunk
         const int ns_row = (n_ctx + chunk - 1) / chunk;  // splits this row really has
         const float mn = fmaxf(fmaxf(sm[0][mm], sm[1][mm]), fmaxf(sm[2][mm], sm[3][mm]));
         float ls = 0.f, os = 0.f;
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
 // at 7600 cache slots).
 __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
     const int head = blockIdx.x, row = blockIdx.y, d = a.head_dim;
-    const int ns = (a.n_ctx + row + chunk - 1) / chunk;
+    const int ns = ((a.tree ? attn_row_ctx<true>(a, row) : attn_row_ctx<false>(a, row)) + chunk - 1) / chunk;
     if (ns == 1) return;  // written directly by the split kernel
     const size_t base = ((size_t)row * a.n_q_heads + head) * n_split;
     float M = -INFINITY;
@@ -357,30 +363,36 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
 
 // Short contexts: one workgroup of 16 wavefronts per (kv head, block row) walks the whole cache
 // range (attn_head_unit), so nothing goes through global memory and one launch suffices.
-template <typename T, int GROUP>
+template <typename T, int GROUP, bool TREE>
 __global__ __launch_bounds__(1024) void k_attn_head(AttnArgs a) {
     extern __shared__ __align__(16) float sh[];
-    attn_head_unit<T, GROUP>(a, blockIdx.x, blockIdx.y, sh);
+    attn_head_unit<T, GROUP, TREE>(a, blockIdx.x, blockIdx.y, sh);
 }
 
-template <typename T, int GROUP>
-static hipError_t launch_attn_head_t(const AttnArgs &a, hipStream_t s) {
+template <typename T, int GROUP, bool TREE>
+static hipError_t launch_attn_head_tt(const AttnArgs &a, hipStream_t s) {
     const size_t lds = (size_t)(32 * GROUP + 16 * GROUP * a.head_dim) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn_head<T, GROUP>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_head<T, GROUP, TREE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn_head<T, GROUP>), dim3(a.n_kv_heads, a.rows), dim3(1024), lds, s, a);
+    hipLaunchKernelGGL((k_attn_head<T, GROUP, TREE>), dim3(a.n_kv_heads, a.rows), dim3(1024), lds, s, a);
     return hipGetLastError();
+}
+template <typename T, int GROUP>
+static hipError_t launch_attn_head_t(const AttnArgs &a, hipStream_t s) {
+    return a.tree ? launch_attn_head_tt<T, GROUP, true>(a, s) : launch_attn_head_tt<T, GROUP, false>(a, s);
 }
 
 template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int group = a.n_q_heads / a.n_kv_heads;
-    const int ctx = a.n_ctx + a.rows - 1;          // longest row of the block
+    // longest row of the block (a tree: an upper bound; workgroups beyond a row's range leave at once)
+    const int ctx = a.tree ? a.n_base + a.row_base + a.rows : a.n_ctx + a.rows - 1;
+    if (a.tree && (a.row_base < 0 || a.row_base + a.rows > 16)) return hipErrorInvalidValue;
     // Which kernel runs, and where the cache range is cut, depends on the cache capacity and the head
     // count only, never on the rows of the block or the current length: a row's result is then the
     // same bit for bit whether it is computed alone or inside a block.
@@ -406,9 +418,16 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
     // block rows that share their key/value loads in one workgroup (the more, the less cache traffic;
     // bounded by registers: members = heads per kv head x rows)
-    const int rb = group == 1 ? 4 : group == 2 ? 2 : 1;
+    const int rb = a.tree ? 1 : group == 1 ? 4 : group == 2 ? 2 : 1;
     dim3 grid(a.n_kv_heads, n_split, (a.rows + rb - 1) / rb), block(256);
-    switch (group) {
+    if (a.tree) switch (group) {
+        case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 1, true>), grid, block, 0, s, a, chunk); break;
+        case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 1, true>), grid, block, 0, s, a, chunk); break;
+        case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1, true>), grid, block, 0, s, a, chunk); break;
+        case 8: hipLaunchKernelGGL((k_attn_split<T, 8, 1, true>), grid, block, 0, s, a, chunk); break;
+        default: return hipErrorInvalidValue;
+    }
+    else switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 4>), grid, block, 0, s, a, chunk); break;
         case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 2>), grid, block, 0, s, a, chunk); break;
         case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1>), grid, block, 0, s, a, chunk); break;
@@ -429,6 +448,7 @@ hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_
 // ------------------------------------------------------------------------------------------
 // greedy choice + confidence:  token = first arg-max, conf = 1 / sum exp(l - max)
 // ------------------------------------------------------------------------------------------
+template <bool TOPK>
 __global__ __launch_bounds__(1024) void k_argmax_conf(ArgmaxArgs a) {
     const float *lg = a.logits + (size_t)blockIdx.x * a.V;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -500,10 +520,116 @@ __global__ __launch_bounds__(1024) void k_argmax_conf(ArgmaxArgs a) {
         a.tokens[blockIdx.x] = bi;
         a.conf[blockIdx.x] = 1.0f / t;
     }
+    if (!TOPK) return;
+    // the next largest logits, one per round: strike the last winner out, find the first maximum again
+    __shared__ int taken[kTopK];
+    if (tid == 0) {
+        taken[0] = bi;
+        a.topk[(size_t)blockIdx.x * kTopK] = bi;
+    }
+    for (int j = 1; j < a.n_topk; ++j) {
+        __syncthreads();  // taken[j-1] is written; the previous round's reads of smax/sidx are done
+        best = -INFINITY;
+        bi = 0x7fffffff;
+        if (in_regs) {
+            const int last = taken[j - 1];
+#pragma unroll
+            for (int k = 0; k < PT; ++k) {
+                if (tid + 1024 * k == last) v[k] = -INFINITY;
+                if (v[k] > best) {
+                    best = v[k];
+                    bi = tid + 1024 * k;
+                }
+            }
+            // (a struck-out logit and a real -inf logit look alike: real ones are told apart below)
+        } else {
+            for (int i = tid; i < a.V; i += 1024) {
+                bool free_ = true;
+                for (int t = 0; t < j; ++t) free_ &= taken[t] != i;
+                const float x = lg[i];
+                if (free_ && x > best) {
+                    best = x;
+                    bi = i;
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(best, off, 64);
+            const int oi = __shfl_xor(bi, off, 64);
+            if (ov > best || (ov == best && oi < bi)) {
+                best = ov;
+                bi = oi;
+            }
+        }
+        if (lane == 0) {
+            smax[wave] = best;
+            sidx[wave] = bi;
+        }
+        __syncthreads();
+        best = smax[0];
+        bi = sidx[0];
+        for (int w = 1; w < 16; ++w)
+            if (smax[w] > best || (smax[w] == best && sidx[w] < bi)) {
+                best = smax[w];
+                bi = sidx[w];
+            }
+        if (bi == 0x7fffffff) {
+            // only -inf logits are left: the lowest index not taken yet
+            int i = 0;
+            for (bool again = true; again;) {
+                again = false;
+                for (int t = 0; t < j; ++t)
+                    if (taken[t] == i) {
+                        ++i;
+                        again = true;
+                    }
+            }
+            bi = i;
+        }
+        if (tid == 0) {
+            taken[j] = bi;
+            a.topk[(size_t)blockIdx.x * kTopK + j] = bi;
+        }
+    }
 }
 
 hipError_t launch_argmax_conf(const ArgmaxArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(k_argmax_conf, dim3(a.rows), dim3(1024), 0, s, a);
+    if (a.topk) {
+        if (a.n_topk < 1 || a.n_topk > kTopK) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k_argmax_conf<true>, dim3(a.rows), dim3(1024), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(k_argmax_conf<false>, dim3(a.rows), dim3(1024), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// cache compaction after acceptance on a token tree
+// ------------------------------------------------------------------------------------------
+// Workgroup (kv head, plane) carries out the moves in order; element e of every move is handled by the
+// same thread, so a move that overwrites the source of an earlier one comes after that one's read.
+template <typename T>
+__global__ void k_kv_move(KvMoveArgs a) {
+    typename T::elem *p = (typename T::elem *)a.kv + (size_t)blockIdx.y * a.plane_elems +
+                          (size_t)blockIdx.x * a.max_seq * a.head_dim;
+    for (int i = 0; i < a.n_moves; ++i) {
+        const typename T::elem *src = p + (size_t)a.src[i] * a.head_dim;
+        typename T::elem *dst = p + (size_t)a.dst[i] * a.head_dim;
+        for (int e = threadIdx.x; e < a.head_dim; e += blockDim.x) dst[e] = src[e];
+    }
+}
+
+hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s) {
+    if (a.n_moves <= 0) return hipSuccess;
+    if (a.n_moves > 16) return hipErrorInvalidValue;
+    for (int i = 0; i < a.n_moves; ++i)
+        if (a.src[i] < 0 || a.src[i] >= a.max_seq || a.dst[i] < 0 || a.dst[i] >= a.max_seq) return hipErrorInvalidValue;
+    dim3 grid(a.n_kv_heads, a.n_planes), block(a.head_dim < 64 ? 64 : a.head_dim > 256 ? 256 : a.head_dim);
+    if (dtype == F32)
+        hipLaunchKernelGGL(k_kv_move<F32T>, grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL(k_kv_move<BF16T>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -63,10 +63,10 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
             } else {
                 const int d = a.head_dim, half = d >> 1, gph = half >> 3;
                 const int hh = rg / gph, i = 8 * (rg - hh * gph) + j;
-                const int nq = a.n_q_heads, nkv = a.n_kv_heads, pos = a.pos0 + r;
+                const int nq = a.n_q_heads, nkv = a.n_kv_heads, pos = a.pos0 + r, rpos = mv_rope_pos(a, r);
                 if (hh < nq + nkv) {
-                    const float c = rot ? rot[r * d + i] : a.cos_tab[(size_t)pos * half + i];
-                    const float s = rot ? rot[r * d + half + i] : a.sin_tab[(size_t)pos * half + i];
+                    const float c = rot ? rot[r * d + i] : a.cos_tab[(size_t)rpos * half + i];
+                    const float s = rot ? rot[r * d + half + i] : a.sin_tab[(size_t)rpos * half + i];
                     const float qa = ya * c - yb * s, qb = yb * c + ya * s;
                     if (hh < nq) {
                         float *qp = a.out_f32 + (size_t)r * a.ld_out + hh * d + i;

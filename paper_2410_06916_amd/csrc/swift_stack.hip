@@ -71,6 +71,8 @@ __device__ inline MvArgs uni(const MvArgs &g) {
     m.head_dim = uni(g.head_dim);
     m.n_q_heads = uni(g.n_q_heads);
     m.n_kv_heads = uni(g.n_kv_heads);
+    m.tree = 0;  // token trees do not run on this kernel
+    m.depth4 = 0;
     m.part = nullptr;
     m.counters = nullptr;
     m.part_capacity = 0;
@@ -94,6 +96,11 @@ __device__ inline AttnArgs uni(const AttnArgs &g) {
     t.out = uni(g.out);
     t.out_s = uni(g.out_s);
     t.out_rows = uni(g.out_rows);
+    t.tree = 0;
+    t.n_base = 0;
+    t.row_base = 0;
+    t.depth4 = 0;
+    t.spine4 = 0;
     return t;
 }
 

@@ -285,8 +285,8 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
                 const int d = a.head_dim, half = d >> 1;
                 for (int i = tid; i < R * half; i += 512) {
                     const int r = i / half, e = i - r * half;
-                    rot[r * d + e] = a.cos_tab[(size_t)(a.pos0 + r) * half + e];
-                    rot[r * d + half + e] = a.sin_tab[(size_t)(a.pos0 + r) * half + e];
+                    rot[r * d + e] = a.cos_tab[(size_t)mv_rope_pos(a, r) * half + e];
+                    rot[r * d + half + e] = a.sin_tab[(size_t)mv_rope_pos(a, r) * half + e];
                 }
             }
         };

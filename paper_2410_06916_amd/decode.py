@@ -44,3 +44,26 @@ def generate_swift(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k
         out.extend(int(t) for t in em)
         trace.append(dict(n=n0, block=block, draft=d, conf=conf, target=tgt, emitted=em, m=len(em) - 1, logits=lg))
     return np.array(out, np.int32), trace
+
+
+def generate_swift_tree(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k: int, conf_threshold: float,
+                        max_width: int = 10, poison: bool = False, want_logits: bool = False):
+    """Draft-then-verify greedy decoding with dynamic verification (paper Section 4.2, both strategies):
+    every draft position keeps its top candidates and the token tree is verified in one block.
+    Returns (tokens, trace); the last step may emit past n_new, the tokens are cut to n_new."""
+    out: List[int] = [m.prefill(prompt)]
+    trace: List[dict] = []
+    while len(out) < n_new:
+        if poison:
+            m.poison_kv()
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = m.cache_len
+        if k_cap > 0:
+            levels, conf = m.draft_step_topk(skip, k_cap, conf_threshold, max_width)
+        else:
+            levels, conf = [], np.zeros(0, np.float32)
+        tgt, lg = m.verify_tree(levels, want_logits)
+        em = m.accept_tree()
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, levels=levels, conf=conf, target=tgt, emitted=em, m=len(em) - 1, logits=lg))
+    return np.array(out[:n_new], np.int32), trace

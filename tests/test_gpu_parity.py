@@ -302,6 +302,146 @@ def test_odd_shapes_against_oracle(oracle_lib, spec):
     g.close()
 
 
+def _compare_tree_traces(shape, to, tg):
+    tol = TOL[shape.dtype]
+    assert len(to) == len(tg)
+    for so, sg in zip(to, tg):
+        assert so["n"] == sg["n"]
+        assert len(so["levels"]) == len(sg["levels"])
+        for lo, lg in zip(so["levels"], sg["levels"]):
+            assert np.array_equal(lo, lg), (lo, lg)
+        assert np.array_equal(so["target"], sg["target"])
+        assert so["m"] == sg["m"] and np.array_equal(so["emitted"], sg["emitted"])
+        if len(so["conf"]):
+            assert np.allclose(sg["conf"], so["conf"], rtol=max(tol, 1e-4) * 5, atol=1e-7)
+
+
+_TREE_CASES = {
+    # name: (shape, max_seq, n_prompt)
+    "small-gqa": (hp.SMALL_GQA, 96, 12),                       # fp32 storage: the row-at-a-time kernels
+    "small-gqa-bf16": (hp.SMALL_GQA_BF16, 96, 12),             # tiled kernels, one-workgroup attention
+    "small-gqa-bf16-long-cache": (hp.SMALL_GQA_BF16, 1700, 70),  # split attention
+    "mha-d32": (si.ModelShape("mha-d32", 2, 72, 3, 3, 32, 104, 130, "bf16", 1e-5), 96, 12),
+    "big-vocab": (si.ModelShape("big-vocab", 1, 64, 2, 1, 32, 96, 33002, "bf16", 1e-5), 80, 9),  # > 32 logits per thread
+}
+
+
+@pytest.mark.parametrize("case", list(_TREE_CASES))
+def test_dynamic_verification_against_oracle(oracle_lib, case):
+    """Section 4.2, second strategy: top-k candidates per draft position by confidence band, the token
+    tree verified in one block, acceptance along the tree with the accepted rows' keys/values moved into
+    place.  Candidates, widths, targets, emitted tokens, logits and the cache contents afterwards against
+    the oracle, with slots beyond the cache length NaN-filled before every step."""
+    import paper_2410_06916_amd as P
+    shape, max_seq, n_prompt = _TREE_CASES[case]
+    weights = hp.shaped_weights(shape, seed=21)
+    o, g = _pair(oracle_lib, shape, weights, max_seq, threads=4)
+    prompt = si.uniform_ids(11, n_prompt, shape.vocab)
+    rng = np.random.default_rng(5)
+    L2 = 2 * shape.n_layers
+    masks = [np.ones(L2, np.uint8)] + [(rng.random(L2) < 0.5).astype(np.uint8) for _ in range(2)]
+    n_new = 30 if shape.vocab < 1000 else 12
+    beside = moved = 0
+    for i, mask in enumerate(masks):
+        for max_k, eps, max_width in ((4, 0.5, 10), (7, 0.0, 3), (15, 0.3, 10), (6, 0.0, 1)):
+            want, to = oracle_lib.generate_swift_tree(o, prompt, n_new, mask, max_k, eps, max_width)
+            got, tg = P.generate_swift_tree(g, prompt, n_new, mask, max_k, eps, max_width, poison=True)
+            assert np.array_equal(got, want), (case, i, max_k, eps, max_width)
+            _compare_tree_traces(shape, to, tg)
+            assert g.cache_len == o.cache_len and g.pending == o.pending
+            for t in tg:
+                # steps whose last accepted token was not its level's first candidate / that moved cache slots
+                beside += int(t["m"] > 0 and len(t["levels"][t["m"] - 1]) > 1 and
+                              t["emitted"][t["m"] - 1] != t["levels"][t["m"] - 1][0])
+                moved += int(t["m"] > 1 and len(t["levels"][0]) > 1)
+            if max_width == 1:
+                assert all(len(l) == 1 for t in tg for l in t["levels"])
+            # the compacted cache: every committed slot of every layer
+            for layer in range(shape.n_layers):
+                for pos in range(n_prompt, g.cache_len):
+                    ko, vo = o.read_kv(layer, pos)
+                    kg, vg = g.read_kv(layer, pos)
+                    tol = 1e-5 if shape.dtype == "fp32" else 1e-2
+                    assert np.allclose(kg, ko, rtol=tol, atol=tol) and np.allclose(vg, vo, rtol=tol, atol=tol), \
+                        (case, layer, pos)
+    assert moved > 0 and (beside > 0 or not case.startswith("small-gqa")), (beside, moved)
+    # logits of one tree block
+    mask = masks[1]
+    assert g.prefill(prompt) == o.prefill(prompt)[0]
+    lo, _ = o.draft_step_topk(mask, 6, 0.0, 10)
+    lg_, _ = g.draft_step_topk(mask, 6, 0.0, 10)
+    assert all(np.array_equal(a, b) for a, b in zip(lo, lg_)) and len(lo) == len(lg_)
+    to_, wl = o.verify_tree(o.pending, lo, want_logits=True)
+    tg_, gl = g.verify_tree(lg_, want_logits=True)
+    assert np.array_equal(to_, tg_)
+    assert np.all(hp.rel_err_rowmax(gl, wl) <= TOL[shape.dtype])
+    assert np.array_equal(o.accept_tree(), g.accept_tree())
+    g.close()
+
+
+@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers"])
+def test_tree_rows_equal_chain_rows_bit_for_bit(case):
+    """A row of a token tree gives, bit for bit, the logits the same path gives when it is verified as a
+    chain (which in turn equal those of one-token-at-a-time decoding): dynamic verification then cannot
+    change the output.  Trees with several wide levels; after acceptance the moved keys/values serve the
+    next steps exactly like those a chain would have written."""
+    import paper_2410_06916_amd as P
+    if case == "7b-width-2-layers":
+        shape, weights, max_seq, n_prompt = si.LLAMA2_7B.with_layers(2), None, 64, 20
+    else:
+        shape = hp.SMALL_GQA_BF16
+        weights = hp.shaped_weights(shape, seed=3)
+        max_seq, n_prompt = (1700, 70) if case.endswith("long-cache") else (96, 12)
+    g = P.SwiftModel(shape, max_seq)
+    if weights is None:
+        for nm, t in _gpu_weights(shape, 0):
+            g.load_tensor(nm, t)
+    else:
+        g.load_weights(weights)
+    g.prefill(si.uniform_ids(4, n_prompt, shape.vocab))
+    n0, t0 = g.cache_len, g.pending
+    rng = np.random.default_rng(8)
+    for widths in ((3, 1, 5, 2), (10, 5), (1, 1, 1, 1, 1, 1, 1), (2, 2, 2, 2, 2, 2, 2, 1), (4,)):
+        g.rollback(n0, t0)
+        levels = [rng.integers(0, shape.vocab, w).astype(np.int32) for w in widths]
+        tgt, lg = g.verify_tree(levels, True)
+        row, spine = 1, [t0]
+        for j, lv in enumerate(levels):
+            for i, tok in enumerate(lv):
+                g.rollback(n0, t0)
+                ctgt, clg = g.verify(spine + [int(tok)], True)
+                assert int(ctgt[-1]) == int(tgt[row + i])
+                assert np.array_equal(clg[-1], lg[row + i]), (case, widths, j, i)
+            row += len(lv)
+            spine.append(int(lv[0]))
+    # acceptance on the tree, then plain decoding: same tokens and logits as a chain all the way
+    g.rollback(n0, t0)
+    ref_toks, ref_rows = [], []
+    for _ in range(10):
+        tgt, lg = g.verify([g.pending], True)
+        g.accept()
+        ref_toks.append(int(tgt[0]))
+        ref_rows.append(lg[0].copy())
+    g.rollback(n0, t0)
+    other = lambda t: (t + 1) % shape.vocab
+    # level 1: right token second; level 2: right token first; level 3: right token third (ends the path)
+    levels = [np.array([other(ref_toks[0]), ref_toks[0]], np.int32), np.array([ref_toks[1]], np.int32),
+              np.array([other(ref_toks[2]), other(other(ref_toks[2])), ref_toks[2]], np.int32)]
+    g.verify_tree(levels)
+    em = g.accept_tree()
+    assert [int(t) for t in em] == ref_toks[:1] + [ref_toks[1]]      # a hit beside the first candidate ends the path
+    g.rollback(n0, t0)
+    levels[0] = levels[0][::-1].copy()
+    g.verify_tree(levels)
+    em = g.accept_tree()
+    assert [int(t) for t in em] == ref_toks[:4] and g.cache_len == n0 + 4
+    for i in range(4, 10):
+        tgt, lg = g.verify([g.pending], True)
+        g.accept()
+        assert int(tgt[0]) == ref_toks[i] and np.array_equal(lg[0], ref_rows[i]), (case, i)
+    g.close()
+
+
 def test_errors_and_state_machine_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
@@ -499,6 +639,10 @@ def test_full_size_workloads_are_lossless_on_gpu(name, n_prompt, n_new):
         assert st["emitted_total"] == n_new and st["verify_passes"] == len(trace)
         assert st["accepted"] == sum(t["m"] for t in trace)
         assert 1 + sum(t["m"] + 1 for t in trace) == n_new
+    # dynamic verification: candidate trees instead of chains
+    out, trace = P.generate_swift_tree(g, prompt, n_new, mask, w.max_k, w.conf_threshold)
+    assert np.array_equal(out, ar), (name, "tree")
+    assert 1 + sum(t["m"] + 1 for t in trace) == n_new
     # no-skip mask: the draft model is the target model, every draft is accepted
     out, trace = P.generate_swift(g, prompt, n_new, np.zeros_like(mask), w.max_k, 0.0)
     assert np.array_equal(out, ar) and all(t["m"] == len(t["draft"]) for t in trace)
