@@ -69,6 +69,18 @@ def lib():
                                           C.POINTER(C.c_int)]
         L.ora_verify_tree.argtypes = [vp, i32p, C.POINTER(C.c_int), C.c_int, i32p, f64p]
         L.ora_accept_tree.argtypes = [vp, i32p, C.POINTER(C.c_int)]
+        L.ora_warp.argtypes = [f64p, C.c_int, C.c_double, C.c_double, f64p, f64p]
+        L.ora_warp.restype = None
+        L.ora_sample.argtypes = [f64p, C.c_int, C.c_double, f64p]
+        L.ora_spec_keep.argtypes = [C.c_double, C.c_double, C.c_double, f64p]
+        L.ora_spec_resample.argtypes = [f64p, f64p, C.c_int, C.c_double, f64p]
+        L.ora_spec_first_token_batch.argtypes = [f64p, f64p, C.c_int, f64p, C.c_int64, i32p]
+        L.ora_spec_first_token_batch.restype = None
+        L.ora_prefill_sample.argtypes = [vp, i32p, C.c_int, C.c_double, C.c_double, C.c_double, i32p, f64p]
+        L.ora_draft_step_sample.argtypes = [vp, u8p, C.c_int, C.c_double, C.c_double, C.c_double, f64p, i32p, f64p,
+                                            C.POINTER(C.c_int), f64p]
+        L.ora_verify_sample.argtypes = [vp, i32p, C.c_int, C.c_double, C.c_double, f64p, C.c_double, i32p,
+                                        C.POINTER(C.c_int), f64p, f64p]
         L.ora_opt_create.argtypes = [C.POINTER(OptConfig), u8p, C.POINTER(vp)]
         L.ora_opt_destroy.argtypes = [vp]
         L.ora_opt_destroy.restype = None
@@ -83,6 +95,7 @@ def lib():
         L.ora_draft_step.argtypes = [vp, u8p, C.c_int, C.c_double, i32p, f64p, C.POINTER(C.c_int)]
         L.ora_verify.argtypes = [vp, i32p, C.c_int, i32p, f64p]
         L.ora_accept.argtypes = [vp, i32p, C.POINTER(C.c_int)]
+        L.ora_rollback.argtypes = [vp, C.c_int, C.c_int32]
         L.ora_cache_len.argtypes = [vp]
         L.ora_pending.argtypes = [vp]
         L.ora_get_stats.argtypes = [vp, C.POINTER(C.c_int64)]
@@ -130,6 +143,41 @@ def rmsnorm(x, g, eps):
     g = np.ascontiguousarray(g, np.float64)
     out = np.empty_like(x)
     lib().ora_rmsnorm(_p(x, C.c_double), _p(g, C.c_double), x.size, eps, _p(out, C.c_double))
+    return out
+
+
+def warp(logits, temperature, top_p):
+    """(probabilities, margin) of the distribution tokens are sampled from."""
+    lg = np.ascontiguousarray(logits, np.float64)
+    out = np.empty_like(lg)
+    mg = C.c_double()
+    lib().ora_warp(_p(lg, C.c_double), lg.size, temperature, top_p, _p(out, C.c_double), C.byref(mg))
+    return out, mg.value
+
+
+def sample(weights, u):
+    w = np.ascontiguousarray(weights, np.float64)
+    mg = C.c_double()
+    return lib().ora_sample(_p(w, C.c_double), w.size, u, C.byref(mg)), mg.value
+
+
+def spec_keep(p_x, q_x, u):
+    return bool(lib().ora_spec_keep(p_x, q_x, u, None))
+
+
+def spec_resample(p, q, u):
+    p = np.ascontiguousarray(p, np.float64)
+    q = np.ascontiguousarray(q, np.float64)
+    return lib().ora_spec_resample(_p(p, C.c_double), _p(q, C.c_double), p.size, u, None)
+
+
+def spec_first_token_batch(p, q, u):
+    p = np.ascontiguousarray(p, np.float64)
+    q = np.ascontiguousarray(q, np.float64)
+    u = np.ascontiguousarray(u, np.float64).reshape(-1, 3)
+    out = np.empty(u.shape[0], np.int32)
+    lib().ora_spec_first_token_batch(_p(p, C.c_double), _p(q, C.c_double), p.size, _p(u, C.c_double), u.shape[0],
+                                     _p(out, C.c_int32))
     return out
 
 
@@ -323,6 +371,51 @@ class Oracle:
                                    _p(tgt, C.c_int32), _p(lg, C.c_double) if want_logits else None), "ora_verify_tree")
         return tgt, lg
 
+    def rollback(self, new_cache_len: int, pending: int):
+        _chk(lib().ora_rollback(self._h, new_cache_len, pending), "ora_rollback")
+
+    # -- speculative sampling
+    def prefill_sample(self, prompt: Sequence[int], temperature: float, top_p: float, u: float):
+        """Returns (first token, margin)."""
+        p = np.ascontiguousarray(prompt, np.int32)
+        tok = C.c_int32()
+        mg = C.c_double()
+        _chk(lib().ora_prefill_sample(self._h, _p(p, C.c_int32), p.size, temperature, top_p, u, C.byref(tok),
+                                      C.byref(mg)), "ora_prefill_sample")
+        return tok.value, mg.value
+
+    def draft_step_sample(self, skip: np.ndarray, max_k: int, conf_threshold: float, temperature: float, top_p: float,
+                          u: Sequence[float]):
+        """Returns (draft tokens, conf, margin)."""
+        skip = np.ascontiguousarray(skip, np.uint8)
+        u = np.ascontiguousarray(u, np.float64)
+        assert u.size >= max_k
+        cap = max(max_k, 1)
+        toks = np.zeros(cap, np.int32)
+        conf = np.zeros(cap, np.float64)
+        k = C.c_int(0)
+        mg = C.c_double()
+        _chk(lib().ora_draft_step_sample(self._h, _p(skip, C.c_uint8), max_k, conf_threshold, temperature, top_p,
+                                         _p(u, C.c_double), _p(toks, C.c_int32), _p(conf, C.c_double), C.byref(k),
+                                         C.byref(mg)), "ora_draft_step_sample")
+        return toks[:k.value].copy(), conf[:k.value].copy(), mg.value
+
+    def verify_sample(self, tokens: Sequence[int], temperature: float, top_p: float, u_accept: Sequence[float],
+                      u_final: float, want_probs: bool = False):
+        """Returns (emitted tokens, probs or None, margin)."""
+        t = np.ascontiguousarray(tokens, np.int32)
+        k = t.size - 1
+        ua = np.ascontiguousarray(u_accept, np.float64)
+        assert ua.size >= k
+        em = np.zeros(k + 1, np.int32)
+        n = C.c_int(0)
+        mg = C.c_double()
+        pr = np.empty((k + 1, self.vocab), np.float64) if want_probs else None
+        _chk(lib().ora_verify_sample(self._h, _p(t, C.c_int32), k, temperature, top_p, _p(ua, C.c_double), u_final,
+                                     _p(em, C.c_int32), C.byref(n), _p(pr, C.c_double) if want_probs else None,
+                                     C.byref(mg)), "ora_verify_sample")
+        return em[:n.value].copy(), pr, mg.value
+
     def accept_tree(self) -> np.ndarray:
         em = np.empty(self.TREE_ROWS, np.int32)
         n = C.c_int(0)
@@ -446,4 +539,33 @@ def generate_swift_tree(o: Oracle, prompt: Sequence[int], n_new: int, skip: np.n
         em = o.accept_tree()
         out.extend(int(t) for t in em)
         trace.append(dict(n=n0, levels=levels, conf=conf, target=tgt, emitted=em, m=len(em) - 1))
+    return np.array(out[:n_new], np.int32), trace
+
+
+SAMPLE_U_PER_STEP = 31  # uniforms one decoding step may use: 15 draws, 15 acceptance tests, 1 final draw
+
+
+def generate_swift_sample(o: Oracle, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k: int,
+                          conf_threshold: float, temperature: float, top_p: float, u0: float, U: np.ndarray):
+    """Draft-then-verify decoding with speculative sampling.  u0: the uniform of the first token;
+    U[s]: the uniforms of decoding step s ([0:15] draft draws, [15:30] acceptance tests, [30] the
+    final draw).  Returns (tokens, trace); trace[s]["margin"] says how far the step's decisions
+    were from falling differently."""
+    tok, mg0 = o.prefill_sample(prompt, temperature, top_p, u0)
+    out = [int(tok)]
+    trace = []
+    s = 0
+    while len(out) < n_new:
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = o.cache_len
+        if k_cap > 0:
+            d, conf, m1 = o.draft_step_sample(skip, k_cap, conf_threshold, temperature, top_p, U[s, 0:15])
+        else:
+            d, conf, m1 = np.zeros(0, np.int32), np.zeros(0), 1.0
+        block = np.concatenate([[o.pending], d]).astype(np.int32)
+        em, _, m2 = o.verify_sample(block, temperature, top_p, U[s, 15:30], float(U[s, 30]))
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, draft=d, conf=conf, emitted=em, m=len(em) - 1, margin=min(m1, m2),
+                          first_margin=mg0))
+        s += 1
     return np.array(out[:n_new], np.int32), trace

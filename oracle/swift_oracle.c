@@ -124,6 +124,9 @@ typedef struct ora_model {
     int tree_levels;
     int tree_width[ORA_TREE_ROWS];
     int32_t tree_tokens[ORA_TREE_ROWS], tree_target[ORA_TREE_ROWS];
+    /* speculative sampling: the draft distributions of the current step, [ORA_TREE_ROWS][vocab] */
+    double *qdist;
+    int k_sampled; /* draft tokens drawn by the last ora_draft_step_sample (-1: none) */
     /* counters (Appendix B.3) */
     int64_t n_draft_passes, n_verify_passes, n_accepted, n_emitted;
 } ora_model;
@@ -286,6 +289,7 @@ int ora_create(const ora_config *c, ora_model **out) {
     m->k_draft = -1;
     m->k_verify = -1;
     m->tree_levels = -1;
+    m->k_sampled = -1;
     *out = m;
     return ORA_OK;
 }
@@ -295,6 +299,7 @@ void ora_destroy(ora_model *m) {
     free(m->layers);
     free(m->kcache);
     free(m->vcache);
+    free(m->qdist);
     free(m);
 }
 
@@ -682,6 +687,7 @@ int ora_reset(ora_model *m) {
     m->k_draft = -1;
     m->k_verify = -1;
     m->tree_levels = -1;
+    m->k_sampled = -1;
     m->n_draft_passes = m->n_verify_passes = m->n_accepted = m->n_emitted = 0;
     return ORA_OK;
 }
@@ -744,6 +750,7 @@ int ora_draft_step(ora_model *m, const uint8_t *skip, int max_k, double conf_thr
     }
     free(lg);
     m->k_draft = k;
+    m->k_sampled = -1;
     if (k_out) *k_out = k;
     return ORA_OK;
 }
@@ -866,6 +873,7 @@ int ora_draft_step_topk(ora_model *m, const uint8_t *skip, int max_k, double con
     }
     free(lg);
     m->k_draft = k;
+    m->k_sampled = -1;
     if (k_out) *k_out = k;
     return ORA_OK;
 }
@@ -960,6 +968,273 @@ int ora_accept_tree(ora_model *m, int32_t *emitted, int *n_emitted) {
     m->n_emitted += acc + 1;
     m->tree_levels = -1;
     m->k_draft = -1;
+    return ORA_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Speculative sampling (Section 5.1 and Appendix B.2: acceptance by speculative sampling,
+ * temperature 0.6 and top-p 0.95 for the sampled runs)
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    double p;
+    int i;
+} prob_idx;
+static int by_prob_desc(const void *a, const void *b) {
+    const prob_idx *x = (const prob_idx *)a, *y = (const prob_idx *)b;
+    if (x->p != y->p) return x->p > y->p ? -1 : 1;
+    return x->i - y->i;
+}
+
+/* The distribution tokens are drawn from: softmax(logits / temperature), restricted to the nucleus
+ * and renormalised.  Nucleus: walk the tokens from the most to the least probable and stop at the
+ * first one with which the probabilities add up to top_p or more; every token as probable as that
+ * last one belongs to it too.  top_p >= 1 keeps everything.
+ * margin (may be NULL): how far the cut was from falling elsewhere: the smaller of (sum with the
+ * cut's ties - top_p), (top_p - sum before the cut's probability value) and the relative gap to
+ * the next smaller probability. */
+void ora_warp(const double *logits, int n, double temperature, double top_p, double *probs, double *margin) {
+    double mx = logits[0];
+    for (int i = 1; i < n; ++i)
+        if (logits[i] > mx) mx = logits[i];
+    double z = 0.0;
+    for (int i = 0; i < n; ++i) {
+        probs[i] = exp((logits[i] - mx) / temperature);
+        z += probs[i];
+    }
+    for (int i = 0; i < n; ++i) probs[i] /= z;
+    if (margin) *margin = 1.0;
+    if (top_p >= 1.0) return;
+    prob_idx *o = (prob_idx *)malloc(sizeof(prob_idx) * (size_t)n);
+    for (int i = 0; i < n; ++i) {
+        o[i].p = probs[i];
+        o[i].i = i;
+    }
+    qsort(o, (size_t)n, sizeof(prob_idx), by_prob_desc);
+    double cum = 0.0;
+    int j = 0;
+    for (; j < n; ++j) {
+        cum += o[j].p;
+        if (cum >= top_p) break;
+    }
+    if (j == n) j = n - 1; /* rounding left the total a hair below top_p: everything stays */
+    const double cut = o[j].p;
+    double before = 0.0, with_ties = 0.0;
+    int last = j;
+    for (int t = 0; t < n; ++t) {
+        if (o[t].p > cut) before += o[t].p;
+        if (o[t].p >= cut) {
+            with_ties += o[t].p;
+            last = t;
+        }
+    }
+    if (margin) {
+        double mg = with_ties - top_p;
+        if (top_p - before < mg) mg = top_p - before;
+        if (last + 1 < n && (cut - o[last + 1].p) / cut < mg) mg = (cut - o[last + 1].p) / cut;
+        *margin = mg;
+    }
+    for (int i = 0; i < n; ++i)
+        if (probs[i] < cut) probs[i] = 0.0;
+    for (int i = 0; i < n; ++i) probs[i] /= with_ties;
+    free(o);
+}
+
+/* Inverse-CDF draw in token-id order from non-negative weights w (need not be normalised):
+ * the first token j with w_0 + .. + w_j > u * total, u in [0, 1).  margin (may be NULL): distance
+ * of u from the two ends of the chosen token's interval, on the normalised scale. */
+int ora_sample(const double *w, int n, double u, double *margin) {
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) total += w[i];
+    double c = 0.0;
+    int last = -1;
+    for (int j = 0; j < n; ++j) {
+        if (w[j] <= 0.0) continue;
+        last = j;
+        const double c0 = c;
+        c += w[j];
+        if (c > u * total) {
+            if (margin) {
+                double a = c / total - u, b = u - c0 / total;
+                *margin = a < b ? a : b;
+            }
+            return j;
+        }
+    }
+    if (margin) *margin = 0.0;
+    return last; /* u * total reached the total through rounding */
+}
+
+/* One acceptance decision: draft token x drawn from q is kept iff u < min(1, p[x] / q[x]). */
+int ora_spec_keep(double p_x, double q_x, double u, double *margin) {
+    if (margin) *margin = fabs(p_x - u * q_x) / (q_x > 0.0 ? q_x : 1.0);
+    return u * q_x < p_x;
+}
+
+/* The replacement token after a rejection: drawn from max(0, p - q) renormalised (from p itself
+ * if p == q everywhere). */
+int ora_spec_resample(const double *p, const double *q, int n, double u, double *margin) {
+    double *r = (double *)malloc(sizeof(double) * (size_t)n);
+    double tot = 0.0;
+    for (int i = 0; i < n; ++i) {
+        r[i] = p[i] > q[i] ? p[i] - q[i] : 0.0;
+        tot += r[i];
+    }
+    int tok = tot > 0.0 ? ora_sample(r, n, u, margin) : ora_sample(p, n, u, margin);
+    free(r);
+    return tok;
+}
+
+/* Test helper: the first token a speculative step with one draft token emits, given target and
+ * draft distributions p, q over n tokens and the three uniforms (draw, acceptance, replacement);
+ * out[i] for triples u[3i..3i+2]. */
+void ora_spec_first_token_batch(const double *p, const double *q, int n, const double *u, int64_t count, int32_t *out) {
+    for (int64_t i = 0; i < count; ++i) {
+        const int x = ora_sample(q, n, u[3 * i], NULL);
+        out[i] = ora_spec_keep(p[x], q[x], u[3 * i + 1], NULL) ? x : ora_spec_resample(p, q, n, u[3 * i + 2], NULL);
+    }
+}
+
+/* Prefill whose first token is drawn from the warped distribution of the last prompt row. */
+int ora_prefill_sample(ora_model *m, const int32_t *prompt, int P, double temperature, double top_p, double u,
+                       int32_t *first_token, double *min_margin) {
+    if (!m || temperature <= 0.0 || top_p <= 0.0 || u < 0.0 || u >= 1.0) return ORA_EINVAL;
+    const int V = m->c.vocab;
+    double *lg = (double *)malloc(sizeof(double) * (size_t)V * 2), *pr = lg + V;
+    int32_t greedy;
+    int rc = ora_prefill(m, prompt, P, &greedy, lg);
+    if (rc) {
+        free(lg);
+        return rc;
+    }
+    double m1, m2;
+    ora_warp(lg, V, temperature, top_p, pr, &m1);
+    const int tok = ora_sample(pr, V, u, &m2);
+    free(lg);
+    m->pending = tok;
+    if (first_token) *first_token = tok;
+    if (min_margin) *min_margin = m1 < m2 ? m1 : m2;
+    return ORA_OK;
+}
+
+/* Drafting with sampling: as ora_draft_step, but draft token j is drawn with u[j-1] from the warped
+ * distribution q_j of the draft model's logits, which is kept for the acceptance test.  The
+ * confidence that ends drafting early stays the top-1 probability of the plain softmax. */
+int ora_draft_step_sample(ora_model *m, const uint8_t *skip, int max_k, double conf_threshold, double temperature,
+                          double top_p, const double *u, int32_t *draft_tokens, double *draft_conf, int *k_out,
+                          double *min_margin) {
+    if (!m || !skip || max_k < 0 || max_k > ORA_TREE_ROWS - 1 || temperature <= 0.0 || top_p <= 0.0) return ORA_EINVAL;
+    if (max_k > 0 && !u) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    if (m->n + max_k + 1 > m->c.max_seq) return ORA_ECAPACITY;
+    const int V = m->c.vocab;
+    if (!m->qdist) m->qdist = (double *)malloc(sizeof(double) * (size_t)V * ORA_TREE_ROWS);
+    double *lg = (double *)malloc(sizeof(double) * (size_t)V);
+    int32_t prev = m->pending;
+    int k = 0;
+    double mm = 1.0;
+    for (int j = 1; j <= max_k; ++j) {
+        if (u[j - 1] < 0.0 || u[j - 1] >= 1.0) {
+            free(lg);
+            return ORA_EINVAL;
+        }
+        int rc = ora_forward_row(m, prev, m->n + j - 1, skip, lg);
+        if (rc) {
+            free(lg);
+            return rc;
+        }
+        int32_t top;
+        double p, m1, m2;
+        ora_argmax_conf(lg, V, &top, &p);
+        double *q = m->qdist + (size_t)k * V;
+        ora_warp(lg, V, temperature, top_p, q, &m1);
+        const int tok = ora_sample(q, V, u[j - 1], &m2);
+        if (m1 < mm) mm = m1;
+        if (m2 < mm) mm = m2;
+        m->n_draft_passes++;
+        m->draft[k] = tok;
+        if (draft_tokens) draft_tokens[k] = tok;
+        if (draft_conf) draft_conf[k] = p;
+        ++k;
+        prev = tok;
+        if (p < conf_threshold) break;
+    }
+    free(lg);
+    m->k_draft = k;
+    m->k_sampled = k;
+    if (k_out) *k_out = k;
+    if (min_margin) *min_margin = mm;
+    return ORA_OK;
+}
+
+/* Verification and acceptance with sampling: the target model over [pending, x_1..x_k] (the tokens
+ * of the last ora_draft_step_sample); p_i = warped distribution of row i-1.  x_i is kept iff
+ * u_accept[i-1] < min(1, p_i(x_i) / q_i(x_i)); the first rejected position gets a token drawn with
+ * u_final from max(0, p_i - q_i) renormalised and ends the step; if all k are kept, one more token is
+ * drawn with u_final from p_{k+1}.  State afterwards as after ora_accept.  k = 0: one step of plain
+ * sampling.  probs_out: NULL or [k+1][vocab], the target's warped distributions. */
+int ora_verify_sample(ora_model *m, const int32_t *tokens, int k, double temperature, double top_p, const double *u_accept,
+                      double u_final, int32_t *emitted, int *n_emitted, double *probs_out, double *min_margin) {
+    if (!m || !tokens || k < 0 || k > ORA_TREE_ROWS - 1 || temperature <= 0.0 || top_p <= 0.0) return ORA_EINVAL;
+    if (u_final < 0.0 || u_final >= 1.0 || (k > 0 && !u_accept)) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    if (tokens[0] != m->pending) return ORA_EINVAL;
+    if (k > 0 && (m->k_sampled < k || !m->qdist)) return ORA_ESTATE;
+    for (int i = 0; i < k; ++i)
+        if (tokens[1 + i] != m->draft[i]) return ORA_EINVAL;
+    const int V = m->c.vocab;
+    double *lgs = (double *)malloc(sizeof(double) * (size_t)V * (size_t)(k + 2));
+    double *pr = lgs + (size_t)V * (size_t)(k + 1);
+    int rc = ora_verify(m, tokens, k, NULL, lgs);
+    if (rc) {
+        free(lgs);
+        return rc;
+    }
+    double mm = 1.0, mg;
+    int acc = 0;
+    int32_t last = -1;
+    for (int i = 0; i <= k; ++i) {
+        ora_warp(lgs + (size_t)i * V, V, temperature, top_p, pr, &mg);
+        if (mg < mm) mm = mg;
+        if (probs_out) memcpy(probs_out + (size_t)i * V, pr, sizeof(double) * (size_t)V);
+        if (i == k) {
+            last = ora_sample(pr, V, u_final, &mg);
+            if (mg < mm) mm = mg;
+            break;
+        }
+        const double *q = m->qdist + (size_t)i * V;
+        const int x = tokens[1 + i];
+        const int keep = ora_spec_keep(pr[x], q[x], u_accept[i], &mg);
+        if (mg < mm) mm = mg;
+        if (!keep) {
+            last = ora_spec_resample(pr, q, V, u_final, &mg);
+            if (mg < mm) mm = mg;
+            break;
+        }
+        if (emitted) emitted[acc] = x;
+        ++acc;
+    }
+    free(lgs);
+    if (emitted) emitted[acc] = last;
+    if (n_emitted) *n_emitted = acc + 1;
+    m->n += acc + 1;
+    m->pending = last;
+    m->n_accepted += acc;
+    m->n_emitted += acc + 1;
+    m->k_verify = -1;
+    m->k_draft = -1;
+    m->k_sampled = -1;
+    if (min_margin) *min_margin = mm;
+    return ORA_OK;
+}
+
+/* Sets the cache length to new_len <= current and the pending token; no data is touched. */
+int ora_rollback(ora_model *m, int new_len, int32_t pending) {
+    if (!m || new_len < 0 || new_len > m->n || pending < 0 || pending >= m->c.vocab) return ORA_EINVAL;
+    if (m->pending < 0) return ORA_ESTATE;
+    m->n = new_len;
+    m->pending = pending;
+    m->k_draft = m->k_verify = m->k_sampled = -1;
+    m->tree_levels = -1;
     return ORA_OK;
 }
 
