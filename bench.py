@@ -30,13 +30,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None, tree_width=0):
+def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None, tree_width=0, sampling=None):
     """One step.  tree_width > 0: dynamic verification with at most that many candidates per draft
-    position.  Returns (tokens, prefill_s, decode_s, trace)."""
+    position.  sampling = (temperature, top_p, U): speculative sampling with the uniforms U[step][31].
+    Returns (tokens, prefill_s, decode_s, trace)."""
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    out = [g.prefill(prompt)]
+    out = [g.prefill_sample(prompt, sampling[0], sampling[1], 0.5) if sampling else g.prefill(prompt)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     if after_prefill:
@@ -45,6 +46,14 @@ def run_generation(P, g, prompt, n_new, mask, max_k, eps, after_prefill=None, tr
     trace = []
     while len(out) < n_new:
         k_cap = min(max_k, n_new - len(out) - 1)
+        if sampling:
+            T, top_p, U = sampling
+            u = U[len(trace)]
+            d = g.draft_step_sample(mask, k_cap, eps, T, top_p, u[:15])[0] if k_cap > 0 else np.zeros(0, np.int32)
+            em, _ = g.verify_sample(np.concatenate([[g.pending], d]).astype(np.int32), T, top_p, u[15:30], float(u[30]))
+            out.extend(int(t) for t in em)
+            trace.append((len(d), len(em) - 1))
+            continue
         if tree_width > 0:
             levels = g.draft_step_topk(mask, k_cap, eps, tree_width)[0] if k_cap > 0 else []
             g.verify_tree(levels)
@@ -220,6 +229,16 @@ def main():
                                          "M": round(s4["emitted_by_verify"] / max(s4["verify_passes"], 1), 3),
                                          "alpha": round(s4["accepted"] / max(s4["draft_passes"], 1), 4),
                                          "same_tokens": bool(np.array_equal(out_t[:w.n_new], ref))}
+        # speculative sampling (Section 5.1, Appendix B.2: temperature 0.6, top-p 0.95), seeded uniforms
+        U = np.random.default_rng(0).random((w.n_new + 1, 31), dtype=np.float32)
+        _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold, sampling=(0.6, 0.95, U))
+        s5 = g.stats()
+        n_s = s5["emitted_total"] - 1
+        modes["speculative_sampling"] = {"tokens_per_s": round(n_s / dc, 2),
+                                         "M": round(s5["emitted_by_verify"] / max(s5["verify_passes"], 1), 3),
+                                         "alpha": round(s5["accepted"] / max(s5["draft_passes"], 1), 4)}
+        _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, 0, 0.0, sampling=(0.6, 0.95, U))
+        modes["plain_sampling"] = {"tokens_per_s": round((g.stats()["emitted_total"] - 1) / dc, 2)}
         log(f"[bench] modes: {modes}")
 
     # ---- per-pass times (host clock around calls that end in a device synchronisation), the

@@ -253,6 +253,40 @@ int swift_verify_tree(swift_ctx *ctx, const int32_t *tokens, const int *width, i
  * the last emitted token the pending token.  SWIFT_ESTATE without a preceding swift_verify_tree. */
 int swift_accept_tree(swift_ctx *ctx, int32_t *emitted, int *n_emitted);
 
+/* ---- speculative sampling (Section 5.1 and Appendix B.2: speculative sampling is the acceptance rule;
+ * the sampled runs use temperature 0.6 and top-p 0.95) --------------------------------------------
+ * Tokens are drawn from W(logits) = softmax(logits / temperature) cut to its nucleus and renormalised.
+ * Nucleus: the tokens whose probability is at least t*, the largest probability value t for which the
+ * tokens with probability >= t together reach top_p (tokens as probable as the last one needed all stay;
+ * top_p >= 1 keeps everything).  A draw with the uniform u in [0, 1) takes the first token id j with
+ * W_0 + .. + W_j > u * (W_0 + .. + W_{V-1}).  The library draws no random numbers: the caller passes the
+ * uniforms (SWIFT_EINVAL outside [0, 1)), so a run is reproducible and testable against other code.
+ * Arithmetic in fp32; temperature > 0 and top_p > 0. */
+
+/* swift_prefill, then the first token is drawn with u from W of the last prompt row's logits. */
+int swift_prefill_sample(swift_ctx *ctx, const int32_t *prompt, int n_prompt, float temperature, float top_p, float u,
+                         int32_t *first_token);
+
+/* swift_draft_step with sampled draft tokens: draft token j is drawn with u[j-1] (host, max_k entries) from
+ * q_j = W(draft logits of position j), which stays on the device for the acceptance test.  draft_conf and
+ * the early stop use the top-1 probability of the plain softmax, as in swift_draft_step (the paper does not
+ * say what the confidence is when sampling). */
+int swift_draft_step_sample(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold,
+                            float temperature, float top_p, const float *u, int32_t *draft_tokens, float *draft_conf,
+                            int *k_out);
+
+/* Verification and acceptance in one call.  tokens[0..k] (host): the pending token and the first k draft
+ * tokens of the preceding swift_draft_step_sample (SWIFT_ESTATE / SWIFT_EINVAL otherwise).  The target
+ * model runs over the block as in swift_verify; p_i = W(logits of row i-1).  Draft token x_i is kept iff
+ * u_accept[i-1] * q_i(x_i) < p_i(x_i), i.e. with probability min(1, p_i(x_i) / q_i(x_i)); the first token not
+ * kept is replaced by a draw with u_final from max(0, p_i - q_i) renormalised and ends the step; if all k
+ * are kept, one more token is drawn with u_final from p_{k+1}.  emitted (host, capacity >= k+1), *n_emitted
+ * = kept + 1; cache length, pending token and statistics change as after swift_accept.  k = 0: one step
+ * of plain sampling.  probs_out: NULL, or host fp32 [k+1][vocab] = p_1 .. p_{k+1}.
+ * u_accept: host, k entries. */
+int swift_verify_sample(swift_ctx *ctx, const int32_t *tokens, int k, float temperature, float top_p,
+                        const float *u_accept, float u_final, int32_t *emitted, int *n_emitted, float *probs_out);
+
 /* Sets the cache length to new_cache_len <= current (no data is touched) and makes
  * `pending_token` the pending token.  For callers that manage acceptance themselves. */
 int swift_rollback(swift_ctx *ctx, int new_cache_len, int32_t pending_token);

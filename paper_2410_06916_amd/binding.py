@@ -82,6 +82,11 @@ def lib():
     L.swift_opt_step.argtypes = [vp, vp, i32p, C.c_int, u8p, C.POINTER(C.c_double), u8p, C.POINTER(C.c_double),
                                  C.POINTER(C.c_int)]
     L.swift_accept.argtypes = [vp, i32p, C.POINTER(C.c_int)]
+    L.swift_prefill_sample.argtypes = [vp, i32p, C.c_int, C.c_float, C.c_float, C.c_float, i32p]
+    L.swift_draft_step_sample.argtypes = [vp, u8p, C.c_int, C.c_float, C.c_float, C.c_float, f32p, i32p, f32p,
+                                          C.POINTER(C.c_int)]
+    L.swift_verify_sample.argtypes = [vp, i32p, C.c_int, C.c_float, C.c_float, f32p, C.c_float, i32p,
+                                      C.POINTER(C.c_int), f32p]
     L.swift_topk_width.argtypes = [C.c_float]
     L.swift_draft_step_topk.argtypes = [vp, u8p, C.c_int, C.c_float, C.c_int, i32p, f32p, C.POINTER(C.c_int),
                                         C.POINTER(C.c_int)]
@@ -258,6 +263,42 @@ class SwiftModel:
         n = C.c_int()
         _chk(lib().swift_accept_tree(self._h, _p(out, C.c_int32), C.byref(n)), "swift_accept_tree")
         return out[:n.value].copy()
+
+    def prefill_sample(self, prompt: Sequence[int], temperature: float, top_p: float, u: float) -> int:
+        p = np.ascontiguousarray(prompt, np.int32)
+        tok = C.c_int32()
+        _chk(lib().swift_prefill_sample(self._h, _p(p, C.c_int32), p.size, temperature, top_p, u, C.byref(tok)),
+             "swift_prefill_sample")
+        return tok.value
+
+    def draft_step_sample(self, skip: np.ndarray, max_k: int, conf_threshold: float, temperature: float, top_p: float,
+                          u: Sequence[float]):
+        """Sampled drafting (speculative sampling): u = the uniforms of the draws.  Returns (tokens, conf)."""
+        skip = np.ascontiguousarray(skip, np.uint8)
+        u = np.ascontiguousarray(u, np.float32)
+        assert u.size >= max_k
+        toks = np.zeros(max(max_k, 1), np.int32)
+        conf = np.zeros(max(max_k, 1), np.float32)
+        k = C.c_int()
+        _chk(lib().swift_draft_step_sample(self._h, _p(skip, C.c_uint8), max_k, conf_threshold, temperature, top_p,
+                                           _p(u, C.c_float), _p(toks, C.c_int32), _p(conf, C.c_float), C.byref(k)),
+             "swift_draft_step_sample")
+        return toks[:k.value].copy(), conf[:k.value].copy()
+
+    def verify_sample(self, tokens: Sequence[int], temperature: float, top_p: float, u_accept: Sequence[float],
+                      u_final: float, want_probs: bool = False):
+        """Verification + acceptance by speculative sampling.  Returns (emitted, probs or None)."""
+        t = np.ascontiguousarray(tokens, np.int32)
+        k = t.size - 1
+        ua = np.ascontiguousarray(u_accept, np.float32)
+        assert ua.size >= k
+        em = np.zeros(k + 1, np.int32)
+        n = C.c_int()
+        pr = np.empty((k + 1, self.cfg.vocab), np.float32) if want_probs else None
+        _chk(lib().swift_verify_sample(self._h, _p(t, C.c_int32), k, temperature, top_p,
+                                       _p(ua, C.c_float) if k else None, u_final, _p(em, C.c_int32), C.byref(n),
+                                       _p(pr, C.c_float) if want_probs else None), "swift_verify_sample")
+        return em[:n.value].copy(), pr
 
     def eval_mask(self, skip: np.ndarray, window: Sequence[int]):
         """Candidate evaluation (Section 4.1.2): window = last gamma committed tokens + the pending

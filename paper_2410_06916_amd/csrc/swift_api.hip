@@ -74,6 +74,7 @@ struct Layout {
     std::vector<LayerOff> layers;
     uint64_t cos, sin, kv;
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf, out_topk;
+    uint64_t samp_q, samp_p, samp_out;  // speculative sampling: draft and target distributions [16][V], results
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
     uint64_t xs, as_, hs, pss, mv_part, mv_counters;
     // persistent stack kernel: cached stage lists, barrier counter + error flag
@@ -134,6 +135,9 @@ Layout make_layout(const swift_model_config &c) {
     L.out_tok = take(kMaxBlockRows * 4);
     L.out_conf = take(kMaxBlockRows * 4);
     L.out_topk = take(kMaxBlockRows * kTopK * 4);
+    L.samp_q = take((uint64_t)kMaxRows * V * 4);
+    L.samp_p = take((uint64_t)kMaxRows * V * 4);
+    L.samp_out = take(256);
     L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxBlockRows * 16);
     L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxBlockRows * 16);
     L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxBlockRows * 16);
@@ -235,6 +239,8 @@ struct swift_ctx {
     int32_t vtokens[SWIFT_MAX_BLOCK], targets[SWIFT_MAX_BLOCK];
     int tree_levels;  // -1: no tree verification outstanding
     int tree_width[SWIFT_MAX_BLOCK];
+    int k_sampled;    // draft tokens of the last swift_draft_step_sample whose distributions are kept (-1: none)
+    int32_t sampled[SWIFT_MAX_BLOCK];
     bool want_topk;   // the next pass with logits also keeps the top candidates of its rows
     int32_t *h_topk;  // pinned, [kTopK]
     swift_stats st;
@@ -779,6 +785,7 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->pending = -1;
     x->k_verify = -1;
     x->tree_levels = -1;
+    x->k_sampled = -1;
     x->want_topk = false;
     x->h_topk = nullptr;
     memset(&x->st, 0, sizeof(x->st));
@@ -912,6 +919,7 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     x->pending = x->h_tok[last_rows - 1];
     x->k_verify = -1;
     x->tree_levels = -1;
+    x->k_sampled = -1;
     memset(&x->st, 0, sizeof(x->st));
     x->st.emitted_total = 1;
     *first_token = x->pending;
@@ -948,6 +956,7 @@ extern "C" int swift_draft_step(swift_ctx *x, const uint8_t *skip_mask, int max_
     if (x->n + max_k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "draft would run past the cache capacity");
     int32_t prev = x->pending;
     int k = 0;
+    x->k_sampled = -1;
     for (int j = 1; j <= max_k; ++j) {
         int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
         if (rc) return rc;
@@ -988,6 +997,7 @@ extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t 
     }
     x->k_verify = k;
     x->tree_levels = -1;
+    x->k_sampled = -1;
     x->st.verify_passes++;
     return SWIFT_OK;
 }
@@ -1025,6 +1035,7 @@ extern "C" int swift_draft_step_topk(swift_ctx *x, const uint8_t *skip_mask, int
     if (x->n + SWIFT_MAX_BLOCK > x->c.max_seq) return fail(SWIFT_ECAPACITY, "a full tree block would run past the cache capacity");
     int32_t prev = x->pending;
     int k = 0, rows = 1;
+    x->k_sampled = -1;
     for (int j = 1; j <= max_k && rows < SWIFT_MAX_BLOCK; ++j) {
         x->want_topk = true;
         int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
@@ -1089,6 +1100,7 @@ extern "C" int swift_verify_tree(swift_ctx *x, const int32_t *tokens, const int 
     x->tree_levels = levels;
     for (int j = 0; j < levels; ++j) x->tree_width[j] = width[j];
     x->k_verify = -1;
+    x->k_sampled = -1;
     x->st.verify_passes++;
     return SWIFT_OK;
 }
@@ -1137,6 +1149,148 @@ extern "C" int swift_accept_tree(swift_ctx *x, int32_t *emitted, int *n_emitted)
     return SWIFT_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// speculative sampling (Section 5.1, Appendix B.2)
+// ------------------------------------------------------------------------------------------
+namespace {
+int check_sampling(float temperature, float top_p) {
+    if (!(temperature > 0.f) || !(top_p > 0.f)) return fail(SWIFT_EINVAL, "temperature and top_p must be positive");
+    return SWIFT_OK;
+}
+bool is_uniform(float u) { return u >= 0.f && u < 1.f; }
+// probs row `dst_row` of buffer `dst` <- warped logits rows [row0, row0 + rows)
+int warp_rows(swift_ctx *x, int row0, int rows, float temperature, float top_p, uint64_t dst, int dst_row) {
+    WarpArgs w{};
+    w.logits = dptr<float>(x, x->L.logits) + (size_t)row0 * x->c.vocab;
+    w.ld_logits = x->c.vocab;
+    w.V = x->c.vocab;
+    w.rows = rows;
+    w.temperature = temperature;
+    w.top_p = top_p;
+    w.probs = dptr<float>(x, dst) + (size_t)dst_row * x->c.vocab;
+    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)rows * x->c.vocab * 8, [&] { return launch_warp(w, x->stream); }));
+    return SWIFT_OK;
+}
+}  // namespace
+
+extern "C" int swift_prefill_sample(swift_ctx *x, const int32_t *prompt, int n_prompt, float temperature, float top_p,
+                                    float u, int32_t *first_token) {
+    if (!first_token) return fail(SWIFT_EINVAL, "null argument");
+    int rc = check_sampling(temperature, top_p);
+    if (rc) return rc;
+    if (!is_uniform(u)) return fail(SWIFT_EINVAL, "uniforms must lie in [0, 1)");
+    int32_t greedy;
+    rc = swift_prefill(x, prompt, n_prompt, &greedy);
+    if (rc) return rc;
+    // the last prompt row's logits are still in place
+    const int block = x->L.tiled ? kMaxBlockRows : kMaxRows;
+    const int last_row = (n_prompt - 1) % block;
+    rc = warp_rows(x, last_row, 1, temperature, top_p, x->L.samp_p, 0);
+    if (rc) return rc;
+    HIP_TRY(launch_draw(dptr<float>(x, x->L.samp_p), x->c.vocab, u, dptr<int32_t>(x, x->L.samp_out), x->stream));
+    HIP_TRY(hipMemcpyAsync(x->h_topk, dptr<int32_t>(x, x->L.samp_out), 4, hipMemcpyDeviceToHost, x->stream));
+    HIP_TRY(hipStreamSynchronize(x->stream));
+    x->pending = x->h_topk[0];
+    *first_token = x->pending;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_draft_step_sample(swift_ctx *x, const uint8_t *skip_mask, int max_k, float conf_threshold,
+                                       float temperature, float top_p, const float *u, int32_t *draft_tokens,
+                                       float *draft_conf, int *k_out) {
+    if (!x || !skip_mask || !k_out) return fail(SWIFT_EINVAL, "null argument");
+    if (max_k < 0 || max_k > SWIFT_MAX_BLOCK - 1) return fail(SWIFT_EINVAL, "max_k out of range");
+    if (max_k > 0 && (!draft_tokens || !draft_conf || !u)) return fail(SWIFT_EINVAL, "null array");
+    int rc = check_sampling(temperature, top_p);
+    if (rc) return rc;
+    for (int j = 0; j < max_k; ++j)
+        if (!is_uniform(u[j])) return fail(SWIFT_EINVAL, "uniforms must lie in [0, 1)");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "draft before prefill");
+    if (x->n + max_k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "draft would run past the cache capacity");
+    int32_t prev = x->pending;
+    int k = 0;
+    x->k_sampled = -1;
+    for (int j = 1; j <= max_k; ++j) {
+        rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
+        if (rc) return rc;
+        rc = warp_rows(x, 0, 1, temperature, top_p, x->L.samp_q, k);
+        if (rc) return rc;
+        HIP_TRY(launch_draw(dptr<float>(x, x->L.samp_q) + (size_t)k * x->c.vocab, x->c.vocab, u[j - 1],
+                            dptr<int32_t>(x, x->L.samp_out), x->stream));
+        HIP_TRY(hipMemcpyAsync(x->h_topk, dptr<int32_t>(x, x->L.samp_out), 4, hipMemcpyDeviceToHost, x->stream));
+        rc = read_results(x, 1);
+        if (rc) return rc;
+        prev = x->h_topk[0];
+        draft_tokens[k] = prev;
+        draft_conf[k] = x->h_conf[0];
+        x->sampled[k] = prev;
+        ++k;
+        x->st.draft_passes++;
+        if (x->h_conf[0] < conf_threshold) break;
+    }
+    x->k_sampled = k;
+    *k_out = k;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_verify_sample(swift_ctx *x, const int32_t *tokens, int k, float temperature, float top_p,
+                                   const float *u_accept, float u_final, int32_t *emitted, int *n_emitted,
+                                   float *probs_out) {
+    if (!x || !tokens || !emitted || !n_emitted) return fail(SWIFT_EINVAL, "null argument");
+    if (k < 0 || k > SWIFT_MAX_BLOCK - 1) return fail(SWIFT_EINVAL, "k out of range");
+    if (k > 0 && !u_accept) return fail(SWIFT_EINVAL, "null array");
+    int rc = check_sampling(temperature, top_p);
+    if (rc) return rc;
+    if (!is_uniform(u_final)) return fail(SWIFT_EINVAL, "uniforms must lie in [0, 1)");
+    for (int i = 0; i < k; ++i)
+        if (!is_uniform(u_accept[i])) return fail(SWIFT_EINVAL, "uniforms must lie in [0, 1)");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "verify before prefill");
+    if (tokens[0] != x->pending) return fail(SWIFT_EINVAL, "tokens[0] must be the pending token");
+    if (k > 0 && x->k_sampled < k) return fail(SWIFT_ESTATE, "no draft distributions for these tokens (swift_draft_step_sample first)");
+    for (int i = 0; i < k; ++i)
+        if (tokens[1 + i] != x->sampled[i]) return fail(SWIFT_EINVAL, "tokens differ from the last sampled draft");
+    if (x->n + k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
+    rc = forward_block(x, tokens, k + 1, x->n, nullptr, true);
+    if (rc) return rc;
+    rc = warp_rows(x, 0, k + 1, temperature, top_p, x->L.samp_p, 0);
+    if (rc) return rc;
+    SpecAcceptArgs sa{};
+    sa.p = dptr<float>(x, x->L.samp_p);
+    sa.q = dptr<float>(x, x->L.samp_q);
+    sa.V = x->c.vocab;
+    sa.k = k;
+    for (int i = 0; i < k; ++i) {
+        sa.x[i] = tokens[1 + i];
+        sa.u_accept[i] = u_accept[i];
+    }
+    sa.u_final = u_final;
+    sa.out = dptr<int32_t>(x, x->L.samp_out);
+    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)x->c.vocab * 8, [&] { return launch_spec_accept(sa, x->stream); }));
+    HIP_TRY(hipMemcpyAsync(x->h_topk, dptr<int32_t>(x, x->L.samp_out), 8, hipMemcpyDeviceToHost, x->stream));
+    rc = read_results(x, k + 1);
+    if (rc) return rc;
+    if (probs_out) {
+        HIP_TRY(hipMemcpyAsync(probs_out, dptr<float>(x, x->L.samp_p), (size_t)(k + 1) * x->c.vocab * 4, hipMemcpyDeviceToHost,
+                               x->stream));
+        HIP_TRY(hipStreamSynchronize(x->stream));
+    }
+    const int m = x->h_topk[0];
+    if (m < 0 || m > k) return fail(SWIFT_EDEVICE, "acceptance kernel returned an impossible count");
+    for (int i = 0; i < m; ++i) emitted[i] = tokens[1 + i];
+    emitted[m] = x->h_topk[1];
+    *n_emitted = m + 1;
+    x->n += m + 1;
+    x->pending = x->h_topk[1];
+    x->k_verify = -1;
+    x->tree_levels = -1;
+    x->k_sampled = -1;
+    x->st.verify_passes++;
+    x->st.accepted += m;
+    x->st.emitted_by_verify += m + 1;
+    x->st.emitted_total += m + 1;
+    return SWIFT_OK;
+}
+
 extern "C" int swift_rollback(swift_ctx *x, int new_cache_len, int32_t pending_token) {
     if (!x) return fail(SWIFT_EINVAL, "null context");
     if (x->pending < 0) return fail(SWIFT_ESTATE, "rollback before prefill");
@@ -1146,6 +1300,7 @@ extern "C" int swift_rollback(swift_ctx *x, int new_cache_len, int32_t pending_t
     x->pending = pending_token;
     x->k_verify = -1;
     x->tree_levels = -1;
+    x->k_sampled = -1;
     return SWIFT_OK;
 }
 

@@ -87,6 +87,31 @@ struct ArgmaxArgs {
 };
 hipError_t launch_argmax_conf(const ArgmaxArgs &a, hipStream_t s);
 
+// ------------------------------------------------------------------------------------------
+// speculative sampling
+// ------------------------------------------------------------------------------------------
+// probs[r] = softmax(logits[r] / temperature) restricted to its nucleus (top_p) and renormalised
+struct WarpArgs {
+    const float *logits;  // [rows][ld_logits]
+    int ld_logits, V, rows;
+    float temperature, top_p;
+    float *probs;         // [rows][V]
+};
+hipError_t launch_warp(const WarpArgs &a, hipStream_t s);
+// out[0] = the first token j with probs[0] + .. + probs[j] > u * (sum of probs), 0 <= u < 1
+hipError_t launch_draw(const float *probs, int V, float u, int32_t *out, hipStream_t s);
+// Keep / replace rule over a verified block of k draft tokens x[i] drawn from q[i] (rows of [.][V]), target
+// distributions p[0..k]: out[0] = number of tokens kept, out[1] = the token that follows them.
+struct SpecAcceptArgs {
+    const float *p, *q;
+    int V, k;
+    int32_t x[kMaxRows];
+    float u_accept[kMaxRows];
+    float u_final;
+    int32_t *out;
+};
+hipError_t launch_spec_accept(const SpecAcceptArgs &a, hipStream_t s);
+
 // Copies cache slots src[i] -> dst[i], i = 0 .. n_moves-1 in this order, for every kv head of every plane
 // (a plane: the keys or the values of one layer, [n_kv][max_seq][d]; planes are plane_elems apart).
 struct KvMoveArgs {

@@ -67,3 +67,29 @@ def generate_swift_tree(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, 
         out.extend(int(t) for t in em)
         trace.append(dict(n=n0, levels=levels, conf=conf, target=tgt, emitted=em, m=len(em) - 1, logits=lg))
     return np.array(out[:n_new], np.int32), trace
+
+
+SAMPLE_U_PER_STEP = 31  # uniforms one decoding step may use: 15 draws, 15 acceptance tests, 1 final draw
+
+
+def generate_swift_sample(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, max_k: int, conf_threshold: float,
+                          temperature: float, top_p: float, u0: float, U: np.ndarray, want_probs: bool = False):
+    """Draft-then-verify decoding with speculative sampling (paper Section 5.1, Appendix B.2).  The caller
+    supplies the uniforms: u0 for the first token, U[s] for decoding step s ([0:15] the draft draws,
+    [15:30] the acceptance tests, [30] the final draw).  Returns (tokens, trace)."""
+    out: List[int] = [m.prefill_sample(prompt, temperature, top_p, u0)]
+    trace: List[dict] = []
+    s = 0
+    while len(out) < n_new:
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = m.cache_len
+        if k_cap > 0:
+            d, conf = m.draft_step_sample(skip, k_cap, conf_threshold, temperature, top_p, U[s, 0:15])
+        else:
+            d, conf = np.zeros(0, np.int32), np.zeros(0, np.float32)
+        block = np.concatenate([[m.pending], d]).astype(np.int32)
+        em, pr = m.verify_sample(block, temperature, top_p, U[s, 15:30], float(U[s, 30]), want_probs)
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, draft=d, conf=conf, emitted=em, m=len(em) - 1, probs=pr))
+        s += 1
+    return np.array(out[:n_new], np.int32), trace
