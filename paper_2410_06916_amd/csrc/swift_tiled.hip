@@ -127,7 +127,7 @@ hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s) {
 // threads load (thread = (partial p mod 32, row r)); mv_norm_load issues the first eight loads per
 // thread (enough for 256 partials, hidden <= 4096) so that the caller can put them ahead of the
 // weight loads; mv_norm_finish adds the rest, then 16 threads add the 32 per-lane sums in order:
-// the summation order is fixed.  Ends with a barrier.
+// the summation order is fixed.  Ends with a barrier (both barriers order LDS traffic only).
 struct NormPart {
     float v[8];
 };
@@ -160,14 +160,14 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
         }
         scratch[q * 16 + r] = ss;
     }
-    __syncthreads();
+    lds_barrier();  // (LDS traffic only: the caller's weight loads stay in flight)
     if (tid < 16) {
         float ss = 0.f;
         if (a.pss)
             for (int q2 = 0; q2 < 32; ++q2) ss += scratch[q2 * 16 + tid];
         rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 // The same for blocks of up to 64 rows (row pitch 64): thread = (partial p mod 8, row r), then 64
@@ -341,21 +341,26 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 
         const int nb16 = (n + NS - 1) / NS;
+        // (the scheduling barriers keep every reload right behind the MFMA that frees its slot: left
+        // alone, the scheduler moves all NS loads behind the last MFMA and the window drains once per block)
         for (int b = 0; b + 1 < nb16; ++b) {
 #pragma unroll
             for (int u = 0; u < NS; ++u) {
                 mma_slot(b * NS + u, buf[u], acc, live_mask);
                 buf[u] = load_slot((b + 1) * NS + u);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if (seg + 1 < a.S) {
             // the window rolls on into the next round's row group: the stream never drains
             const int rgn = min(((seg + 1) * W + (int)blockIdx.x) * G + g, last_rg);
             base = Wt + ((size_t)rgn * T + t0) * 64 + lane;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NS; ++u) {
                 mma_slot((nb16 - 1) * NS + u, buf[u], acc, live_mask);
                 buf[u] = load_slot(u);
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma unroll
