@@ -487,6 +487,62 @@ def test_errors_and_state_machine_on_device(oracle_lib):
     g.close()
 
 
+def test_tree_errors_and_degenerate_trees_on_device(oracle_lib):
+    """Error paths and degenerate shapes of the dynamic-verification calls: the oracle and the library reject
+    and accept the same things; a tree without levels is one step of plain decoding; a failed call
+    leaves the state untouched."""
+    import paper_2410_06916_amd as P
+    shape = hp.SMALL_GQA
+    weights = hp.shaped_weights(shape, seed=1)
+    o, g = _pair(oracle_lib, shape, weights, 40, threads=1)
+    mask = np.zeros(2 * shape.n_layers, np.uint8)
+    with pytest.raises(P.SwiftError) as e:
+        g.draft_step_topk(mask, 3, 0.0)                        # before prefill
+    assert e.value.code == -3
+    prompt = si.uniform_ids(3, 8, shape.vocab)
+    t = g.prefill(prompt)
+    assert t == o.prefill(prompt)[0]
+    with pytest.raises(P.SwiftError) as e:
+        g.accept_tree()                                        # nothing verified
+    assert e.value.code == -3
+    with pytest.raises(oracle_lib.OracleError):
+        o.accept_tree()
+    for bad in ([np.arange(11)], [np.arange(10), np.arange(6)], [np.array([], np.int32)],
+                [np.array([shape.vocab])]):                    # too wide, too many rows, empty level, bad id
+        with pytest.raises(P.SwiftError) as e:
+            g.verify_tree([np.asarray(b, np.int32) for b in bad])
+        assert e.value.code == -1
+    with pytest.raises(P.SwiftError) as e:
+        g.draft_step_topk(mask, 3, 0.0, 0)                     # max_width < 1
+    assert e.value.code == -1
+    n0 = g.cache_len
+    assert g.pending == t and n0 == 8
+    # a tree without levels is one step of plain decoding
+    tg, _ = g.verify_tree([])
+    to, _ = o.verify_tree(o.pending, [])
+    assert np.array_equal(tg, to)
+    eg, eo = g.accept_tree(), o.accept_tree()
+    assert np.array_equal(eg, eo) and len(eg) == 1 and g.cache_len == n0 + 1
+    # a verify in between cancels an outstanding tree, and the other way round
+    g.verify_tree([[1, 2]])
+    g.verify([g.pending])
+    with pytest.raises(P.SwiftError):
+        g.accept_tree()
+    g.accept()
+    g.verify([g.pending])
+    g.verify_tree([[3]])
+    with pytest.raises(P.SwiftError):
+        g.accept()
+    g.accept_tree()
+    # capacity: a tree step needs room for a full block
+    while g.cache_len + 16 <= 40:
+        g.verify([g.pending]); g.accept()
+    with pytest.raises(P.SwiftError) as e:
+        g.draft_step_topk(mask, 3, 0.0)
+    assert e.value.code == -2
+    g.close()
+
+
 @pytest.mark.parametrize("base,n_layers", [(si.LLAMA2_7B, 2)], ids=["7b-width-2-layers"])
 def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     """Same widths, heads, FFN, vocab and dtype as the 7B workload, two layers deep."""
