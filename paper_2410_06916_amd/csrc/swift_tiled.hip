@@ -341,26 +341,23 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 
         const int nb16 = (n + NS - 1) / NS;
-        // (the scheduling barriers keep every reload right behind the MFMA that frees its slot: left
-        // alone, the scheduler moves all NS loads behind the last MFMA and the window drains once per block)
+        // (As compiled, the NS reloads of a block go out together behind its last MFMA.  Pinning each
+        // reload behind the MFMA that frees its slot with scheduling barriers measured the same.)
         for (int b = 0; b + 1 < nb16; ++b) {
 #pragma unroll
             for (int u = 0; u < NS; ++u) {
                 mma_slot(b * NS + u, buf[u], acc, live_mask);
                 buf[u] = load_slot((b + 1) * NS + u);
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if (seg + 1 < a.S) {
             // the window rolls on into the next round's row group: the stream never drains
             const int rgn = min(((seg + 1) * W + (int)blockIdx.x) * G + g, last_rg);
             base = Wt + ((size_t)rgn * T + t0) * 64 + lane;
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NS; ++u) {
                 mma_slot((nb16 - 1) * NS + u, buf[u], acc, live_mask);
                 buf[u] = load_slot(u);
-                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma unroll
