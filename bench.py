@@ -229,6 +229,22 @@ def main():
                                          "M": round(s4["emitted_by_verify"] / max(s4["verify_passes"], 1), 3),
                                          "alpha": round(s4["accepted"] / max(s4["draft_passes"], 1), 4),
                                          "same_tokens": bool(np.array_equal(out_t[:w.n_new], ref))}
+        # the whole method (Section 4): context accumulation, then an optimisation step (random-search
+        # candidate scored on the last 32 generated tokens) before every decoding step, as the paper's
+        # settings have it for a run of this length (the phase would go on for up to 1000 steps)
+        el = np.zeros(mask.size, np.uint8)
+        el[4:-4] = 1
+        opt = P.Optimizer(mask.size, skip_ratio=0.5, max_steps=1000, max_stale=300, stop_matchness=0.95, seed=1,
+                          eligible=el)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out_f, tr_f = P.generate_swift_on_the_fly(g, opt, prompt, w.n_new, w.max_k, w.conf_threshold, gamma=32)
+        torch.cuda.synchronize()
+        t_f = time.perf_counter() - t0
+        opt.close()
+        n_opt = sum(t["opt"] is not None for t in tr_f)
+        modes["on_the_fly"] = {"tokens_per_s_incl_prefill": round(w.n_new / t_f, 2), "optimisation_steps": n_opt,
+                               "decoding_steps": len(tr_f), "same_tokens": bool(np.array_equal(out_f, ref))}
         # speculative sampling (Section 5.1, Appendix B.2: temperature 0.6, top-p 0.95), seeded uniforms
         U = np.random.default_rng(0).random((w.n_new + 1, 31), dtype=np.float32)
         _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, w.max_k, w.conf_threshold, sampling=(0.6, 0.95, U))

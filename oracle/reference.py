@@ -542,6 +542,40 @@ def generate_swift_tree(o: Oracle, prompt: Sequence[int], n_new: int, skip: np.n
     return np.array(out[:n_new], np.int32), trace
 
 
+def generate_swift_on_the_fly(o: Oracle, opt, prompt: Sequence[int], n_new: int, max_k: int, conf_threshold: float,
+                              gamma: int = 32, tree_width: int = 0):
+    """Section 4 as a whole for one input: context accumulation with the uniform initial pattern, then
+    an optimisation step before every decoding step until the optimiser terminates, then acceleration
+    with the retained layer set.  An optimisation step needs gamma committed generated tokens; its
+    window is those plus the pending token.  Returns (tokens, trace)."""
+    out = [int(o.prefill(prompt)[0])]
+    mask = opt.initial_mask()
+    done = False
+    trace = []
+    while len(out) < n_new:
+        info = None
+        if (not done) and len(out) >= gamma + 1:
+            window = np.array(out[len(out) - gamma - 1:], np.int32)
+            info = opt.step(o, window)
+            mask = info["best"]
+            done = info["finished"]
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = o.cache_len
+        if tree_width > 0:
+            levels = o.draft_step_topk(mask, k_cap, conf_threshold, tree_width)[0] if k_cap > 0 else []
+            o.verify_tree(o.pending, levels)
+            em = o.accept_tree()
+            n_draft = len(levels)
+        else:
+            d = o.draft_step(mask, k_cap, conf_threshold)[0] if k_cap > 0 else np.zeros(0, np.int32)
+            o.verify(np.concatenate([[o.pending], d]).astype(np.int32))
+            em = o.accept()
+            n_draft = len(d)
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, mask=np.array(mask, np.uint8), opt=info, n_draft=n_draft, emitted=em, m=len(em) - 1))
+    return np.array(out[:n_new], np.int32), trace
+
+
 SAMPLE_U_PER_STEP = 31  # uniforms one decoding step may use: 15 draws, 15 acceptance tests, 1 final draw
 
 

@@ -6,7 +6,7 @@ arguments; PyTorch is used for device memory and streams.
 """
 from .binding import (Optimizer, SwiftError, SwiftModel, check_config, device_bytes, expected_speedup, lib, match_prefix,
                       pass_bytes, KERNEL_CLASSES)
-from .decode import generate_ar, generate_swift, generate_swift_tree, generate_swift_sample, SAMPLE_U_PER_STEP
+from .decode import generate_ar, generate_swift, generate_swift_tree, generate_swift_sample, generate_swift_on_the_fly, SAMPLE_U_PER_STEP
 
 __all__ = ["Optimizer", "SwiftError", "SwiftModel", "check_config", "device_bytes", "expected_speedup", "lib", "match_prefix",
-           "pass_bytes", "generate_ar", "generate_swift", "generate_swift_tree", "generate_swift_sample", "SAMPLE_U_PER_STEP", "KERNEL_CLASSES"]
+           "pass_bytes", "generate_ar", "generate_swift", "generate_swift_tree", "generate_swift_sample", "generate_swift_on_the_fly", "SAMPLE_U_PER_STEP", "KERNEL_CLASSES"]

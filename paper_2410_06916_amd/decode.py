@@ -69,6 +69,39 @@ def generate_swift_tree(m, prompt: Sequence[int], n_new: int, skip: np.ndarray, 
     return np.array(out[:n_new], np.int32), trace
 
 
+def generate_swift_on_the_fly(m, opt, prompt: Sequence[int], n_new: int, max_k: int, conf_threshold: float,
+                              gamma: int = 32, tree_width: int = 0):
+    """The whole method for one input (paper Section 4): prefill; context accumulation with the uniform
+    initial pattern until gamma generated tokens are committed (Section 4.1.1); then one optimisation step before
+    every decoding step (a candidate from `opt` scored on the last gamma generated tokens, the best one retained
+    and used to draft this step, Section 4.1.2) until `opt` terminates; then plain acceleration with the retained
+    set (Section 4.2).  tree_width > 0 adds dynamic verification.  Returns (tokens, trace)."""
+    out: List[int] = [m.prefill(prompt)]
+    mask = opt.initial_mask()
+    finished = False
+    trace: List[dict] = []
+    while len(out) < n_new:
+        info = None
+        if not finished and len(out) - 1 >= gamma:
+            info = opt.step(m, out[-(gamma + 1):])
+            mask, finished = info["best"], info["finished"]
+        k_cap = min(max_k, n_new - len(out) - 1)
+        n0 = m.cache_len
+        if tree_width > 0:
+            levels = m.draft_step_topk(mask, k_cap, conf_threshold, tree_width)[0] if k_cap > 0 else []
+            m.verify_tree(levels)
+            em = m.accept_tree()
+            n_draft = len(levels)
+        else:
+            d = m.draft_step(mask, k_cap, conf_threshold)[0] if k_cap > 0 else np.zeros(0, np.int32)
+            m.verify(np.concatenate([[m.pending], d]).astype(np.int32))
+            em = m.accept()
+            n_draft = len(d)
+        out.extend(int(t) for t in em)
+        trace.append(dict(n=n0, mask=np.array(mask, np.uint8), opt=info, n_draft=n_draft, emitted=em, m=len(em) - 1))
+    return np.array(out[:n_new], np.int32), trace
+
+
 SAMPLE_U_PER_STEP = 31  # uniforms one decoding step may use: 15 draws, 15 acceptance tests, 1 final draw
 
 

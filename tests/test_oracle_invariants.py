@@ -430,6 +430,38 @@ def test_tree_acceptance_by_hand(oracle_lib, small):
         o.verify_tree(o.pending, [np.arange(10, dtype=np.int32), np.arange(10, dtype=np.int32)])   # 21 rows
 
 
+@pytest.mark.parametrize("tree_width", [0, 10])
+def test_whole_method_phases_and_losslessness(oracle_lib, small, tree_width):
+    """Section 4 end to end: context accumulation with the uniform pattern, one optimisation step before
+    every decoding step once gamma generated tokens are committed, acceleration with the retained set
+    after termination; the output equals plain greedy decoding throughout."""
+    s, o, prompt, ar = small
+    L2 = 2 * s.n_layers
+    gamma = 6
+    opt = oracle_lib.Optimizer(L2, skip_ratio=0.5, max_steps=4, max_stale=100, stop_matchness=2.0, seed=3)
+    toks, tr = oracle_lib.generate_swift_on_the_fly(o, opt, prompt, 40, 5, 0.3, gamma=gamma, tree_width=tree_width)
+    assert np.array_equal(toks, ar)
+    emitted = 1
+    steps = []
+    for t in tr:
+        if t["opt"] is None:
+            # no optimisation step: either the window is not full yet, or the phase is over
+            assert emitted - 1 < gamma or len(steps) == 4
+            if emitted - 1 < gamma:
+                assert np.array_equal(t["mask"], opt.initial_mask())
+        else:
+            assert emitted - 1 >= gamma and len(steps) < 4
+            steps.append(t["opt"])
+            assert np.array_equal(t["mask"], t["opt"]["best"])       # the retained set drafts this very step
+        emitted += len(t["emitted"])
+    assert len(steps) == 4 and steps[-1]["finished"] and not steps[-2]["finished"]
+    assert np.array_equal(steps[0]["candidate"], opt.initial_mask())
+    best = max(x["score"] for x in steps)
+    assert steps[-1]["best_score"] == best
+    assert all(np.array_equal(t["mask"], steps[-1]["best"]) for t in tr[-3:])   # acceleration phase
+    opt.close()
+
+
 def test_state_and_capacity_errors(oracle_lib, small):
     s, o, prompt, ar = small
     o.reset()
