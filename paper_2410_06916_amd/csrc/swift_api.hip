@@ -444,7 +444,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.T = (K + 31) / 32;
         m.n_rg = n_rg;
         m.R = R;
-        m.RL = R <= kMaxRows ? R : kMaxBlockRows;
+        m.RL = block_row_layout(R);
         m.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
         m.eps = c.rms_eps;
         m.norm_dim = H;
@@ -569,7 +569,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     ea.gain_next = gain_of(0);
     ea.pss = pss;
     ea.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
-    ea.RL = R <= kMaxRows ? R : kMaxBlockRows;
+    ea.RL = block_row_layout(R);
     HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
 
     // ---- one persistent launch where the block qualifies, else one launch per stage
@@ -637,7 +637,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                     a.row_base = row0;  // (a tree has at most 16 rows: one part)
                     a.rows = std::min(per_launch, R - row0);
                     a.out_s += 24 * row0;  // first of this part's 3 * rows term columns
-                    a.out_rows = R <= kMaxRows ? R : kMaxBlockRows;
+                    a.out_rows = block_row_layout(R);
                     HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
                                   [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
                 }

@@ -10,6 +10,9 @@ namespace swift {
 
 constexpr int kMaxRows = 16;       // rows of one verify block (SWIFT_MAX_BLOCK)
 constexpr int kMaxBlockRows = 64;  // rows of one prefill block
+// Rows the split-activation layouts of a block of R rows are pitched for: R itself up to 16 rows (verify
+// blocks), else 32 or 64 (prefill blocks, candidate evaluation windows).
+inline int block_row_layout(int R) { return R <= kMaxRows ? R : R <= 32 ? 32 : kMaxBlockRows; }
 constexpr int kAttnMaxSplit = 64;  // most cache-length splits of one (row, kv head)
 constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
@@ -164,7 +167,7 @@ struct MvArgs {
     const void *Wt;        // tiled weights
     int O, K, T, n_rg;     // real rows / depth, k-tiles, row groups
     int R;                 // activation rows, 1..64
-    int RL;                // rows the split layouts (in_s, out_s) are pitched for: R up to 16 rows, else 64
+    int RL;                // rows the split layouts (in_s, out_s) are pitched for: block_row_layout(R)
                            // (columns of rows that do not exist hold garbage that no result depends on)
     const uint16_t *in_s;  // split input [K/8][3 RL][8]
     const float *pss;      // [n_pss][rp] partial sums of squares of the producer, or nullptr: no norm
@@ -212,7 +215,7 @@ hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_o
 struct EmbedRowsArgs {
     const uint16_t *E;  // [V][H] bf16 row-major
     int H, R;
-    int RL;             // rows the split layout xs is pitched for (R, or 64 for blocks of more than 16 rows)
+    int RL;             // rows the split layout xs is pitched for: block_row_layout(R)
     int32_t tokens[kMaxBlockRows];
     float *x;           // [R][H]
     uint16_t *xs;       // [H/8][3 RL][8]

@@ -512,12 +512,12 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 // zero tile by tile, a workgroup covers a group of 8, 4, 2 or 1 whole slices (mv_slice_group: a
 // function of the matrix alone, not of the row count) and adds their sums per term in slice order,
 // combines the three terms, and the last workgroup adds the group results in order.  The
-// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 12 (prefill) keeps its own
+// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 6 / 12 (blocks of 17-32 / 33-64 rows) keep their own
 // fixed order.
 template <int EPI, int NCB, int CT, int RG>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int R = a.R, NC = 3 * a.RL;  // NC: columns of the split input as laid out (= 16 NCB when NCB = 12)
+    const int R = a.R, NC = 3 * a.RL;  // NC: columns of the split input as laid out (= 16 NCB when NCB is 6 or 12)
     const int buf_bytes = 4 * CT * NC * 16;
     // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
     const int main_bytes = max(2 * buf_bytes, NCB * 8192);
@@ -532,7 +532,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     const int tb = (int)blockIdx.y * TS;
     const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
     const int col = lane & 15, kg = lane >> 4;
-    constexpr bool kCanon = NCB <= 3;  // verify blocks; the 12-column-block prefill variant keeps its own order
+    constexpr bool kCanon = NCB <= 3;  // verify blocks; the variants for more than 16 rows keep their own order
     // A slice is walked in chunks of CT tiles that do not run over its end (the last chunk of a slice
     // may be partial), so that slices end between chunks.  The prefill variant has one "slice": its
     // whole K range.
@@ -758,20 +758,21 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
     if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp ||
-        a.RL != (a.R <= kMaxRows ? a.R : kMaxBlockRows))
+        a.RL != block_row_layout(a.R))
         return hipErrorInvalidValue;
     // small blocks whose whole activation fits in LDS take the single-pass kernel
     if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
-    // up to 16 rows: 1-3 column blocks, K chunks of 8 tiles; 17-64 rows (prefill): 12 column
-    // blocks, K chunks of 4 tiles (48 KB of split activation per chunk)
-    const int ncb = a.R > kMaxRows ? 12 : (3 * a.R + 15) / 16;
+    // up to 16 rows: 1-3 column blocks, K chunks of 8 tiles; 17-32 / 33-64 rows (prefill, candidate
+    // evaluation): 6 / 12 column blocks, K chunks of 8 / 4 tiles (48 KB of split activation per chunk)
+    const int ncb = (3 * a.RL + 15) / 16;
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
         switch (ncb) {                                                  \
             case 1: return launch_mvN_t<E, 1, 8, 1>(a, n_cu, s);          \
             case 2: return launch_mvN_t<E, 2, 8, 1>(a, n_cu, s);          \
             case 3: return launch_mvN_t<E, 3, 8, 1>(a, n_cu, s);          \
+            case 6: return launch_mvN_t<E, 6, 8, 1>(a, n_cu, s);          \
             default: return launch_mvN_t<E, 12, 4, 1>(a, n_cu, s);         \
         }
     switch (epi) {
