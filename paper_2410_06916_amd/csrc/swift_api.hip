@@ -492,6 +492,13 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                 m.tree = 1;
                 m.depth4 = tree->depth4;
             }
+            // the committed keys/values the attention launch will read: warmed into L2 by spare workgroups of
+            // this launch (one-workgroup-per-head attention only: its workgroup-to-head mapping is what the
+            // warm-up relies on)
+            if (!reuse_kv && attn_uses_head_kernel(c.max_seq, c.n_kv_heads)) {
+                m.pf_heads = c.n_kv_heads;
+                m.pf_rows = pos0;
+            }
             push_mv(SWIFT_KC_QKV, EPI_QKV, m, 0);
 
             StackStage at{};

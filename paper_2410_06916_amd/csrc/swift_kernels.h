@@ -192,6 +192,10 @@ struct MvArgs {
     int part_capacity;     // row-group-splits the scratch can hold
     int S;                 // set by the launcher
     int kgroup;            // set by the launcher: K slices whose sums are added first (see mv_slice_group)
+    // QKV, LDS-resident kernel only: cache lines to pull into the L2 of the die that will run the attention of
+    // kv head g right after this launch (rows [0, pf_rows) of head g's keys and values); pf_heads = 0: none.
+    // n_wg: workgroups that do the projection (set by the launcher; the grid holds pf_heads more, plus padding)
+    int pf_rows, pf_heads, n_wg, pf_first;
 };
 // position block row r of a QKV pass is rotated for
 __host__ __device__ inline int mv_rope_pos(const MvArgs &a, int r) {

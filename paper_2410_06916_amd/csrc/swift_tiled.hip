@@ -246,7 +246,27 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     const int nv = max(0, min(n, T - ks * n)); // ... of which exist
     const int nvm1 = max(nv - 1, 0);
     const u32x4 *Wt = (const u32x4 *)a.Wt;
-    const int W = gridDim.x;
+    const int W = a.n_wg;
+    if (EPI == EPI_QKV && (int)blockIdx.x >= W) {
+        // Cache warm-up for the attention launch that follows: workgroup pf_first + g reads kv head g's
+        // committed keys and values.  Workgroups go to the dies round-robin by index, and the attention
+        // kernel's workgroup for head g has index g (+ a multiple of 8 per further row), so with pf_first a
+        // multiple of 8 the lines land in the L2 that kernel's loads will ask.  No result; no barrier.
+        const int gh = (int)blockIdx.x - a.pf_first;
+        if (gh < 0 || gh >= a.pf_heads) return;
+        const size_t head_units = (size_t)a.max_seq * a.head_dim / 8;  // 16-byte units of one head
+        const int n_units = a.pf_rows * a.head_dim / 8;
+        const u32x4 *kp = (const u32x4 *)a.kcache + (size_t)gh * head_units;
+        const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * head_units;
+        u32x4 x = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < n_units; i += 512) {
+            x ^= kp[i];
+            x ^= vp[i];
+        }
+        // (keeps the loads alive; the flag word is never all ones)
+        if ((x.x & x.y & x.z & x.w) == 0xffffffffu && a.pf_rows < 0) ((volatile uint32_t *)smem)[0] = x.x;
+        return;
+    }
     const int last_rg = a.n_rg - 1;
     const int col = lane & 15, kg = lane >> 4;
     // byte address of this lane's B chunk for tile t: boff + t * bstride; lanes of columns >= NC
@@ -451,6 +471,15 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
         best_s = (a.n_rg + G * best_w - 1) / (G * best_w);
     }
     a.S = best_s;
+    a.n_wg = best_w;
+    int grid = best_w;
+    // (the warm-up workgroups only pay while they run beside the projection: they need free slots)
+    if (epi == EPI_QKV && a.pf_heads > 0 && a.pf_rows > 0 && (best_w + 7) / 8 * 8 + a.pf_heads <= max_wg) {
+        a.pf_first = (best_w + 7) / 8 * 8;
+        grid = a.pf_first + a.pf_heads;
+    } else {
+        a.pf_heads = 0;
+    }
     a.kgroup = best_ks == 8 ? mv_slice_group(a, n_cu) : best_ks;
     // Slots per block of the load window (= loads in flight per wavefront): 16 unless another depth
     // cuts a slice of n tiles with fewer wasted slots (n = 43: 3 x 15 instead of 3 x 16; n = 20:
@@ -470,18 +499,18 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 #define SWIFT_MV_CASE(E)                                                                   \
     case E:                                                                                \
         switch (best_ks) {                                                                 \
-            case 1: return launch_mv1_t<E, 1, 16>(a, best_w, lds, s);                      \
-            case 2: return launch_mv1_t<E, 2, 16>(a, best_w, lds, s);                      \
-            case 4: return launch_mv1_t<E, 4, 16>(a, best_w, lds, s);                      \
+            case 1: return launch_mv1_t<E, 1, 16>(a, grid, lds, s);                      \
+            case 2: return launch_mv1_t<E, 2, 16>(a, grid, lds, s);                      \
+            case 4: return launch_mv1_t<E, 4, 16>(a, grid, lds, s);                      \
             default:                                                                       \
                 switch (ns) {                                                              \
-                    case 10: return launch_mv1_t<E, 8, 10>(a, best_w, lds, s);             \
-                    case 11: return launch_mv1_t<E, 8, 11>(a, best_w, lds, s);             \
-                    case 12: return launch_mv1_t<E, 8, 12>(a, best_w, lds, s);             \
-                    case 13: return launch_mv1_t<E, 8, 13>(a, best_w, lds, s);             \
-                    case 14: return launch_mv1_t<E, 8, 14>(a, best_w, lds, s);             \
-                    case 15: return launch_mv1_t<E, 8, 15>(a, best_w, lds, s);             \
-                    default: return launch_mv1_t<E, 8, 16>(a, best_w, lds, s);             \
+                    case 10: return launch_mv1_t<E, 8, 10>(a, grid, lds, s);             \
+                    case 11: return launch_mv1_t<E, 8, 11>(a, grid, lds, s);             \
+                    case 12: return launch_mv1_t<E, 8, 12>(a, grid, lds, s);             \
+                    case 13: return launch_mv1_t<E, 8, 13>(a, grid, lds, s);             \
+                    case 14: return launch_mv1_t<E, 8, 14>(a, grid, lds, s);             \
+                    case 15: return launch_mv1_t<E, 8, 15>(a, grid, lds, s);             \
+                    default: return launch_mv1_t<E, 8, 16>(a, grid, lds, s);             \
                 }                                                                          \
         }
     switch (epi) {
