@@ -120,3 +120,26 @@ def test_null_and_range_arguments_are_rejected_without_a_device(P):
     assert L.swift_create(C.byref(cfg), vp(4096 + 8), 1 << 40, None, C.byref(out)) == -1   # misaligned arena
     assert L.swift_create(C.byref(cfg), vp(4096), 16, None, C.byref(out)) == -2  # arena too small
     assert b"arena" in L.swift_last_error()
+
+
+def test_new_entry_points_reject_null_contexts_without_a_device(P):
+    """Dynamic verification, speculative sampling, candidate evaluation: argument checks come first."""
+    L = P.lib()
+    assert L.swift_eval_mask(None, None, None, 4, None, None) == -1
+    assert L.swift_draft_step_topk(None, None, 1, 0.5, 10, None, None, None, None) == -1
+    assert L.swift_verify_tree(None, None, None, 0, None, None) == -1
+    assert L.swift_accept_tree(None, None, None) == -1
+    assert L.swift_prefill_sample(None, None, 0, 0.6, 0.95, 0.5, None) == -1
+    assert L.swift_draft_step_sample(None, None, 1, 0.5, 0.6, 0.95, None, None, None, None) == -1
+    assert L.swift_verify_sample(None, None, 0, 0.6, 0.95, None, 0.5, None, None, None) == -1
+    # the band table of dynamic verification (Section 4.2) is host arithmetic
+    assert [L.swift_topk_width(p) for p in (0.01, 0.5, 0.51, 0.8, 0.81, 0.95, 0.96, 1.0)] == [10, 10, 5, 5, 3, 3, 1, 1]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
