@@ -194,8 +194,9 @@ struct MvArgs {
     int kgroup;            // set by the launcher: K slices whose sums are added first (see mv_slice_group)
     // QKV, LDS-resident kernel only: cache lines to pull into the L2 of the die that will run the attention of
     // kv head g right after this launch (rows [0, pf_rows) of head g's keys and values); pf_heads = 0: none.
-    // n_wg: workgroups that do the projection (set by the launcher; the grid holds pf_heads more, plus padding)
-    int pf_rows, pf_heads, n_wg, pf_first;
+    // n_wg: workgroups that do the projection; pf_first, pf_wgs: first warm-up workgroup and how many (all set by
+    // the launcher)
+    int pf_rows, pf_heads, n_wg, pf_first, pf_wgs;
 };
 // position block row r of a QKV pass is rotated for
 __host__ __device__ inline int mv_rope_pos(const MvArgs &a, int r) {

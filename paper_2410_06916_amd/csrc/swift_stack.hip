@@ -73,7 +73,7 @@ __device__ inline MvArgs uni(const MvArgs &g) {
     m.n_kv_heads = uni(g.n_kv_heads);
     m.tree = 0;  // token trees do not run on this kernel
     m.depth4 = 0;
-    m.pf_rows = m.pf_heads = m.n_wg = m.pf_first = 0;
+    m.pf_rows = m.pf_heads = m.n_wg = m.pf_first = m.pf_wgs = 0;
     m.part = nullptr;
     m.counters = nullptr;
     m.part_capacity = 0;

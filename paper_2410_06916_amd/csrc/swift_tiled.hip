@@ -4,6 +4,8 @@
 // 64 rows (longer verify blocks, prefill, candidate evaluation).
 #include <math.h>
 
+#include <algorithm>
+
 #include <hip/hip_ext.h>
 
 #include "swift_device.h"
@@ -248,20 +250,24 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
     const u32x4 *Wt = (const u32x4 *)a.Wt;
     const int W = a.n_wg;
     if (EPI == EPI_QKV && (int)blockIdx.x >= W) {
-        // Cache warm-up for the attention launch that follows: workgroup pf_first + g reads kv head g's
-        // committed keys and values.  Workgroups go to the dies round-robin by index, and the attention
-        // kernel's workgroup for head g has index g (+ a multiple of 8 per further row), so with pf_first a
-        // multiple of 8 the lines land in the L2 that kernel's loads will ask.  No result; no barrier.
-        const int gh = (int)blockIdx.x - a.pf_first;
-        if (gh < 0 || gh >= a.pf_heads) return;
+        // Cache warm-up for the attention launch that follows: warm-up workgroup p reads the committed keys
+        // and values of the kv heads congruent to p.  Workgroups go to the dies round-robin by index, and the
+        // attention kernel's workgroup for head g has index g (+ a multiple of 8 per further row), so with
+        // pf_first and the number of warm-up workgroups multiples of 8 the lines land in the L2
+        // that kernel's loads will ask.  No result; no barrier.
+        // (pf_wgs warm-up workgroups, a multiple of 8: workgroup p takes the heads congruent to p modulo pf_wgs)
+        const int p = (int)blockIdx.x - a.pf_first;
+        if (p < 0) return;
         const size_t head_units = (size_t)a.max_seq * a.head_dim / 8;  // 16-byte units of one head
         const int n_units = a.pf_rows * a.head_dim / 8;
-        const u32x4 *kp = (const u32x4 *)a.kcache + (size_t)gh * head_units;
-        const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * head_units;
         u32x4 x = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < n_units; i += 512) {
-            x ^= kp[i];
-            x ^= vp[i];
+        for (int gh = p; gh < a.pf_heads; gh += a.pf_wgs) {
+            const u32x4 *kp = (const u32x4 *)a.kcache + (size_t)gh * head_units;
+            const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * head_units;
+            for (int i = tid; i < n_units; i += 512) {
+                x ^= kp[i];
+                x ^= vp[i];
+            }
         }
         // (keeps the loads alive; the flag word is never all ones)
         if ((x.x & x.y & x.z & x.w) == 0xffffffffu && a.pf_rows < 0) ((volatile uint32_t *)smem)[0] = x.x;
@@ -473,12 +479,23 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
     a.S = best_s;
     a.n_wg = best_w;
     int grid = best_w;
-    // (the warm-up workgroups only pay while they run beside the projection: they need free slots)
-    if (epi == EPI_QKV && a.pf_heads > 0 && a.pf_rows > 0 && (best_w + 7) / 8 * 8 + a.pf_heads <= max_wg) {
-        a.pf_first = (best_w + 7) / 8 * 8;
-        grid = a.pf_first + a.pf_heads;
+    // (the warm-up workgroups only pay while they run beside the projection: they take free slots only)
+    a.pf_first = (best_w + 7) / 8 * 8;
+    a.pf_wgs = std::min((max_wg - a.pf_first) / 8 * 8, (a.pf_heads + 7) / 8 * 8);
+    // Only with one workgroup per head, the compute units clearly under-filled (measured with 480 of 512 slots
+    // taken: the extra workgroups slow the projection down by more than the attention gains), and a context
+    // short enough for a workgroup to read its whole head well before the projection ends: one compute unit
+    // takes in about 37 GB/s and the weights stream at about 5 TB/s, so a head may hold 0.6 of what can be
+    // read in that time (7B shape: up to about 860 slots; warming only part of a longer head measured worse
+    // than not warming at all).
+    const double t_us = (double)a.n_rg * a.T * 1024.0 / 5.0e6;
+    const double head_bytes = (double)a.pf_rows * a.head_dim * 4.0;  // keys and values, bf16
+    if (epi == EPI_QKV && a.pf_heads > 0 && a.pf_rows > 0 && a.pf_wgs >= a.pf_heads &&
+        a.pf_first + a.pf_wgs <= max_wg * 85 / 100 && head_bytes <= 0.6 * 37.0e3 * t_us) {
+        grid = a.pf_first + a.pf_wgs;
     } else {
         a.pf_heads = 0;
+        a.pf_wgs = 0;
     }
     a.kgroup = best_ks == 8 ? mv_slice_group(a, n_cu) : best_ks;
     // Slots per block of the load window (= loads in flight per wavefront): 16 unless another depth
