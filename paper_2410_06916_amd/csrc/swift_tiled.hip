@@ -561,7 +561,7 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 // LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 6 / 12 (blocks of 17-32 / 33-64 rows) keep their own
 // fixed order.
 template <int EPI, int NCB, int CT, int RG>
-__global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
+__global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int R = a.R, NC = 3 * a.RL;  // NC: columns of the split input as laid out (= 16 NCB when NCB is 6 or 12)
     const int buf_bytes = 4 * CT * NC * 16;
@@ -574,7 +574,10 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = a.T;
-    const int rg0 = ((int)blockIdx.x * 8 + wave) * RG;  // first row group of this wavefront
+    // rpw <= 8 wavefronts of a workgroup own row groups (the launcher's choice: as many as spread the matrix
+    // evenly over the compute units); the others only help with the copies and the barriers
+    const bool active = wave < rpw;
+    const int rg0 = ((int)blockIdx.x * rpw + min(wave, rpw - 1)) * RG;  // first row group of this wavefront
     const int tb = (int)blockIdx.y * TS;
     const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
     const int col = lane & 15, kg = lane >> 4;
@@ -627,7 +630,8 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
         for (int g = 0; g < RG; ++g)
 #pragma unroll
             for (int u = 0; u < CT; ++u)
-                A[g][u] = __builtin_nontemporal_load(base[g] + (size_t)min(t0 + u, nt - 1) * 64);
+                A[g][u] = active ? __builtin_nontemporal_load(base[g] + (size_t)min(t0 + u, nt - 1) * 64)
+                                 : u32x4{0u, 0u, 0u, 0u};
     };
     auto loadB = [&](int c, u32x4(&tmp)[NQ]) {
         const int gu0 = 4 * (tb + chunk_t0(c)) * NC;
@@ -724,7 +728,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
 #pragma unroll
     for (int g = 0; g < RG; ++g) {
         const int rg = rg0 + g;
-        const bool live = rg < a.n_rg;
+        const bool live = active && rg < a.n_rg;
         if constexpr (kCanon)
             dump_regs(ssum);  // (RG = 1) the sum of this workgroup's slices, per term
         else
@@ -756,7 +760,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS) {
 #pragma unroll
     for (int g = 0; g < RG; ++g) {
         const int rg = rg0 + g;
-        if (rg >= a.n_rg) continue;
+        if (!active || rg >= a.n_rg) continue;
         const float *p0 = a.part + (size_t)rg * (16 * R);
         const size_t sstride = (size_t)a.n_rg * (16 * R);
         mv_epilogue<EPI>(a, rg, lane, rs, nullptr, [&](int r, int j) {
@@ -799,7 +803,17 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
         TS = (a.T + ksp - 1) / ksp;
     }
     ksp = (a.T + TS - 1) / TS;  // workgroups whose K range holds tiles
-    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG>, dim3(n_rb, ksp), dim3(512), lds, s, a, TS);
+    // Without a K split and with fewer 8-row-group blocks than compute units, a workgroup takes fewer row
+    // groups, so that every compute unit gets about the same share: what bounds these launches is what ONE
+    // compute unit can take in (weights plus its copy of the activation), not the chip's HBM rate.
+    int rpw = 8, grid_x = n_rb;
+    if (ksp == 1 && n_rb < n_cu) {
+        rpw = (a.n_rg + RG * n_cu - 1) / (RG * n_cu);
+        if (rpw < 4) rpw = 4;
+        if (rpw > 8) rpw = 8;
+        grid_x = (a.n_rg + rpw * RG - 1) / (rpw * RG);
+    }
+    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
