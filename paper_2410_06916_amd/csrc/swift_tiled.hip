@@ -803,12 +803,12 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
         TS = (a.T + ksp - 1) / ksp;
     }
     ksp = (a.T + TS - 1) / TS;  // workgroups whose K range holds tiles
-    // Without a K split and with fewer 8-row-group blocks than compute units, a workgroup takes fewer row
-    // groups, so that every compute unit gets about the same share: what bounds these launches is what ONE
-    // compute unit can take in (weights plus its copy of the activation), not the chip's HBM rate.
+    // With fewer workgroups than compute units, a workgroup takes fewer row groups, so that every compute unit
+    // gets about the same share: what bounds these launches is what ONE compute unit can take in (weights plus
+    // its copy of the activation), not the chip's HBM rate.
     int rpw = 8, grid_x = n_rb;
-    if (ksp == 1 && n_rb < n_cu) {
-        rpw = (a.n_rg + RG * n_cu - 1) / (RG * n_cu);
+    if (n_rb * ksp < n_cu) {
+        rpw = (a.n_rg * ksp + RG * n_cu - 1) / (RG * n_cu);
         if (rpw < 4) rpw = 4;
         if (rpw > 8) rpw = 8;
         grid_x = (a.n_rg + rpw * RG - 1) / (rpw * RG);
