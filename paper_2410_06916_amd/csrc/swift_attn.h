@@ -102,38 +102,47 @@ __device__ inline int attn_phys_slot(const AttnArgs &a, int row, int p) {
 // block row `row` for the GROUP query heads that share kv head g over the row's whole range of
 // attn_row_ctx slots.  Step s of wavefront w covers slots (16 s + w) * SPW ..; the loads of NB steps
 // are issued together.  sh: LDS, [16*GROUP] max, [16*GROUP] sum, [16*GROUP*d] weighted values.
-template <typename T, int GROUP, bool TREE = false>
-__device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *sh) {
+template <typename T, int GROUP, bool TREE = false, int RB = 1>
+__device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float *sh) {
+    // RB consecutive block rows share every key/value load (chain rows only: a tree row has a slot of its
+    // own inside its range).  Members: (row rr, head h) -> rr * GROUP + h.  What a row's result is does not
+    // depend on the rows that share its workgroup: slots beyond a row's range leave its running values
+    // untouched.
+    static_assert(!TREE || RB == 1, "tree rows do not share key/value loads");
     constexpr int VEC = T::VEC;
-    constexpr int NB = GROUP <= 2 ? 4 : 1;
+    constexpr int M = GROUP * RB;
+    constexpr int NB = M <= 2 ? 4 : 1;
     const int d = a.head_dim;
     const int LPP = d / VEC, SPW = 64 / LPP;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lj = lane & (LPP - 1), lg = lane / LPP;
-    const int n_ctx = attn_row_ctx<TREE>(a, row);
+    const int n_rows = min(RB, a.rows - row0);
+    const int n_ctx = attn_row_ctx<TREE>(a, row0 + n_rows - 1);  // the longest row's range
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
-    float *sm = sh, *sl = sh + 16 * GROUP, *so = sh + 32 * GROUP;
+    float *sm = sh, *sl = sh + 16 * M, *so = sh + 32 * M;
 
-    float q[GROUP][VEC];
+    float q[M][VEC];
+    int lim[M];
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h)
+    for (int mm = 0; mm < M; ++mm) {
+        const int rr = mm / GROUP, h = mm - rr * GROUP;
+        const int row = min(row0 + rr, a.rows - 1);
+        lim[mm] = rr < n_rows ? attn_row_ctx<TREE>(a, row0 + rr) : 0;  // rows past the block take part in nothing
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) q[h][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
-    float m[GROUP], l[GROUP], o[GROUP][VEC];
+        for (int j = 0; j < VEC; ++j) q[mm][j] = a.q[((size_t)row * nq + g * GROUP + h) * d + lj * VEC + j];
+    }
+    float m[M], l[M], o[M][VEC];
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h) {
-        m[h] = -INFINITY;
-        l[h] = 0.f;
+    for (int mm = 0; mm < M; ++mm) {
+        m[mm] = -INFINITY;
+        l[mm] = 0.f;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) o[h][j] = 0.f;
+        for (int j = 0; j < VEC; ++j) o[mm][j] = 0.f;
     }
     const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
     const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
     const int steps = (n_ctx + 16 * SPW - 1) / (16 * SPW);
-    int lim[GROUP];
-#pragma unroll
-    for (int h = 0; h < GROUP; ++h) lim[h] = n_ctx;
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
@@ -141,16 +150,16 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int p = ((s0 + b) * 16 + wave) * SPW + lg;
-            const int pc = attn_phys_slot<TREE>(a, row, min(p, n_ctx - 1));
+            const int pc = attn_phys_slot<TREE>(a, row0, min(p, n_ctx - 1));
             pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
             vv[b] = *(const u32x4 *)(vc + (size_t)pc * d + lj * VEC);
         }
-        attn_batch<T, GROUP, NB>(kv, vv, pos, lim, q, scale, LPP, m, l, o);
+        attn_batch<T, M, NB>(kv, vv, pos, lim, q, scale, LPP, m, l, o);
     }
     // merge the lane groups of a wavefront
 #pragma unroll
-    for (int h = 0; h < GROUP; ++h) {
+    for (int h = 0; h < M; ++h) {
         for (int off = LPP; off < 64; off <<= 1) {
             const float m2 = __shfl_xor(m[h], off, 64);
             const float l2 = __shfl_xor(l[h], off, 64);
@@ -168,27 +177,30 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row, float *
     }
     if (lg == 0) {
 #pragma unroll
-        for (int h = 0; h < GROUP; ++h) {
+        for (int h = 0; h < M; ++h) {
             if (lj == 0) {
-                sm[wave * GROUP + h] = m[h];
-                sl[wave * GROUP + h] = l[h];
+                sm[wave * M + h] = m[h];
+                sl[wave * M + h] = l[h];
             }
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) so[((size_t)wave * GROUP + h) * d + lj * VEC + j] = o[h][j];
+            for (int j = 0; j < VEC; ++j) so[((size_t)wave * M + h) * d + lj * VEC + j] = o[h][j];
         }
     }
     __syncthreads();
     // merge the 16 wavefronts, normalise, write
-    for (int idx = tid; idx < GROUP * d; idx += 1024) {
-        const int h = idx / d, j = idx - h * d;
+    for (int idx = tid; idx < M * d; idx += 1024) {
+        const int mm = idx / d, j = idx - mm * d;
+        const int rr = mm / GROUP, h = mm - rr * GROUP;
+        if (rr >= n_rows) continue;
+        const int row = row0 + rr;
         float mn = -INFINITY;
-        for (int w = 0; w < 16; ++w) mn = fmaxf(mn, sm[w * GROUP + h]);
+        for (int w = 0; w < 16; ++w) mn = fmaxf(mn, sm[w * M + mm]);
         float ls = 0.f, os = 0.f;
         for (int w = 0; w < 16; ++w) {
-            const float mw = sm[w * GROUP + h];
+            const float mw = sm[w * M + mm];
             const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mn);
-            ls += sl[w * GROUP + h] * c;
-            os += so[((size_t)w * GROUP + h) * d + j] * c;
+            ls += sl[w * M + mm] * c;
+            os += so[((size_t)w * M + mm) * d + j] * c;
         }
         const float y = os / ls;
         const int e = (g * GROUP + h) * d + j;
