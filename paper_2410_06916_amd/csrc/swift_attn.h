@@ -98,11 +98,11 @@ __device__ inline int attn_phys_slot(const AttnArgs &a, int row, int p) {
     }
 }
 
-// One workgroup of 16 wavefronts (1024 threads, all of them call this) computes the attention of
+// One workgroup of NW wavefronts (64 NW threads, all of them call this) computes the attention of
 // block row `row` for the GROUP query heads that share kv head g over the row's whole range of
-// attn_row_ctx slots.  Step s of wavefront w covers slots (16 s + w) * SPW ..; the loads of NB steps
-// are issued together.  sh: LDS, [16*GROUP] max, [16*GROUP] sum, [16*GROUP*d] weighted values.
-template <typename T, int GROUP, bool TREE = false, int RB = 1>
+// attn_row_ctx slots.  Step s of wavefront w covers slots (NW s + w) * SPW ..; the loads of NB steps
+// are issued together.  sh: LDS, [NW*M] max, [NW*M] sum, [NW*M*d] weighted values (M members).
+template <typename T, int GROUP, bool TREE = false, int RB = 1, int NW = 16>
 __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float *sh) {
     // RB consecutive block rows share every key/value load (chain rows only: a tree row has a slot of its
     // own inside its range).  Members: (row rr, head h) -> rr * GROUP + h.  What a row's result is does not
@@ -120,7 +120,7 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float 
     const int n_ctx = attn_row_ctx<TREE>(a, row0 + n_rows - 1);  // the longest row's range
     const float scale = 1.0f / sqrtf((float)d);
     const int nq = a.n_q_heads;
-    float *sm = sh, *sl = sh + 16 * M, *so = sh + 32 * M;
+    float *sm = sh, *sl = sh + NW * M, *so = sh + 2 * NW * M;
 
     float q[M][VEC];
     int lim[M];
@@ -142,14 +142,14 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float 
     }
     const typename T::elem *kc = (const typename T::elem *)a.kcache + (size_t)g * a.max_seq * d;
     const typename T::elem *vc = (const typename T::elem *)a.vcache + (size_t)g * a.max_seq * d;
-    const int steps = (n_ctx + 16 * SPW - 1) / (16 * SPW);
+    const int steps = (n_ctx + NW * SPW - 1) / (NW * SPW);
 
     for (int s0 = 0; s0 < steps; s0 += NB) {
         u32x4 kv[NB], vv[NB];
         int pos[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const int p = ((s0 + b) * 16 + wave) * SPW + lg;
+            const int p = ((s0 + b) * NW + wave) * SPW + lg;
             const int pc = attn_phys_slot<TREE>(a, row0, min(p, n_ctx - 1));
             pos[b] = p;
             kv[b] = *(const u32x4 *)(kc + (size_t)pc * d + lj * VEC);
@@ -187,16 +187,16 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float 
         }
     }
     __syncthreads();
-    // merge the 16 wavefronts, normalise, write
-    for (int idx = tid; idx < M * d; idx += 1024) {
+    // merge the wavefronts, normalise, write
+    for (int idx = tid; idx < M * d; idx += 64 * NW) {
         const int mm = idx / d, j = idx - mm * d;
         const int rr = mm / GROUP, h = mm - rr * GROUP;
         if (rr >= n_rows) continue;
         const int row = row0 + rr;
         float mn = -INFINITY;
-        for (int w = 0; w < 16; ++w) mn = fmaxf(mn, sm[w * M + mm]);
+        for (int w = 0; w < NW; ++w) mn = fmaxf(mn, sm[w * M + mm]);
         float ls = 0.f, os = 0.f;
-        for (int w = 0; w < 16; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float mw = sm[w * M + mm];
             const float c = (mw == -INFINITY) ? 0.f : __expf(mw - mn);
             ls += sl[w * M + mm] * c;

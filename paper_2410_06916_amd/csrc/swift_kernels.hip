@@ -363,16 +363,17 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
 
 // Short contexts: one workgroup of 16 wavefronts per (kv head, block row) walks the whole cache
 // range (attn_head_unit), so nothing goes through global memory and one launch suffices.
+constexpr int kAttnHeadWaves = 8;  // wavefronts of a one-workgroup-per-head attention workgroup
 template <typename T, int GROUP, bool TREE, int RB>
-__global__ __launch_bounds__(1024) void k_attn_head(AttnArgs a) {
+__global__ __launch_bounds__(64 * kAttnHeadWaves) void k_attn_head(AttnArgs a) {
     extern __shared__ __align__(16) float sh[];
-    attn_head_unit<T, GROUP, TREE, RB>(a, blockIdx.x, blockIdx.y * RB, sh);
+    attn_head_unit<T, GROUP, TREE, RB, kAttnHeadWaves>(a, blockIdx.x, blockIdx.y * RB, sh);
 }
 
 template <typename T, int GROUP, bool TREE, int RB>
 static hipError_t launch_attn_head_tt(const AttnArgs &a, hipStream_t s) {
     constexpr int M = GROUP * RB;
-    const size_t lds = (size_t)(32 * M + 16 * M * a.head_dim) * sizeof(float);
+    const size_t lds = (size_t)(2 * kAttnHeadWaves * M + kAttnHeadWaves * M * a.head_dim) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k_attn_head<T, GROUP, TREE, RB>,
@@ -380,7 +381,8 @@ static hipError_t launch_attn_head_tt(const AttnArgs &a, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn_head<T, GROUP, TREE, RB>), dim3(a.n_kv_heads, (a.rows + RB - 1) / RB), dim3(1024), lds, s, a);
+    hipLaunchKernelGGL((k_attn_head<T, GROUP, TREE, RB>), dim3(a.n_kv_heads, (a.rows + RB - 1) / RB),
+                       dim3(64 * kAttnHeadWaves), lds, s, a);
     return hipGetLastError();
 }
 template <typename T, int GROUP>
