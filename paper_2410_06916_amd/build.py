@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswift_hip.so")
-SOURCES = ["swift_api.hip", "swift_kernels.hip", "swift_tiled.hip", "swift_stack.hip", "swift_opt.hip", "swift_sample.hip"]
+SOURCES = ["swift_api.hip", "swift_kernels.hip", "swift_tiled.hip", "swift_stack.hip", "swift_opt.hip", "swift_sample.hip",
+           "swift_attn_block.hip"]
 HEADERS = ["swift_kernels.h", "swift_device.h", "swift_attn.h", "swift_mv.h", os.path.join("..", "..", "include", "swift.h")]
 
 # packed-fp32 instruction selection is switched off for all device code

@@ -634,7 +634,12 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     } else {
         for (size_t i = 0; i < list.size(); ++i) {
             const int kc = classes[i];
-            if (list[i].type == ST_ATTN) {
+            if (list[i].type == ST_ATTN && attn_block_applies(c.dtype, list[i].at)) {
+                AttnArgs a = list[i].at;
+                a.out_rows = block_row_layout(R);
+                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
+                              [&] { return launch_attn_block(a, x->n_cu, s); }));
+            } else if (list[i].type == ST_ATTN) {
                 // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
                 const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
                 for (int row0 = 0; row0 < R; row0 += per_launch) {

@@ -78,6 +78,12 @@ struct AttnArgs {
 // rows per launch.  Depends on the cache capacity and the head count only.
 inline bool attn_uses_head_kernel(int max_seq, int n_kv_heads) { return max_seq <= 1600 && n_kv_heads >= 24; }
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
+// Merges the partial results of n_split cache ranges of `chunk` slots, per (row, query head), in range order.
+hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s);
+// Blocks of 17..64 chain rows over a bf16 cache with head_dim 64 or 128: the whole block in one launch on the
+// matrix cores (all rows share every key/value load).  `a` describes the whole block (rows, out_rows).
+bool attn_block_applies(int dtype, const AttnArgs &a);
+hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s);
 
 constexpr int kTopK = 10;  // candidates kept per row (SWIFT_TOPK)
 struct ArgmaxArgs {

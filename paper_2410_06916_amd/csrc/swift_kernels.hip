@@ -451,6 +451,12 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     return hipGetLastError();
 }
 
+hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s) {
+    hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads, a.rows), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a, chunk,
+                       n_split);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s) {
     return dtype == F32 ? launch_attn_t<F32T>(a, n_cu, s) : launch_attn_t<BF16T>(a, n_cu, s);
 }

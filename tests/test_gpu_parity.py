@@ -159,6 +159,65 @@ def test_prefill_block_sizes_against_oracle(oracle_lib):
     g.close()
 
 
+BLOCK_ATTN_SHAPES = {
+    # head_dim 64, two query heads per kv head
+    "d64-gqa2": si.ModelShape("d64-gqa2", 2, 256, 4, 2, 64, 344, 384, "bf16", 1e-5),
+    # head_dim 128, four query heads on one kv head
+    "d128-gqa4": si.ModelShape("d128-gqa4", 2, 512, 4, 1, 128, 344, 384, "bf16", 1e-5),
+    # head_dim 128, one kv head per query head
+    "d128-mha": si.ModelShape("d128-mha", 2, 256, 2, 2, 128, 344, 384, "bf16", 1e-5),
+}
+
+
+@pytest.mark.parametrize("case", sorted(BLOCK_ATTN_SHAPES))
+def test_block_attention_on_matrix_cores_against_oracle(oracle_lib, case):
+    """Blocks of 17..64 rows over a bf16 cache with heads of 64 or 128 take the matrix-core attention
+    kernel (Section 3.1: the rows of a prefill or verify pass form one causal block).  Prompt lengths that
+    give ragged blocks, full blocks, a 64-row block followed by one row, and contexts cut into one to five
+    cache ranges; checked through what depends on the attention output of every prompt row: the keys and
+    values of the second layer, the logits of the next pass, the greedy continuation.  Then the blocks of
+    candidate evaluation (Section 4.1.2) over the same cache."""
+    import paper_2410_06916_amd as P
+    shape = BLOCK_ATTN_SHAPES[case]
+    weights = hp.shaped_weights(shape, seed=12)
+    o, g = _pair(oracle_lib, shape, weights, 640, threads=8)
+    for n_prompt in (17, 33, 63, 64, 65, 129, 200, 600):
+        prompt = si.uniform_ids(70 + n_prompt, n_prompt, shape.vocab)
+        fo = o.prefill(prompt)[0]
+        fg = g.prefill(prompt)
+        for pos in sorted({0, 15, 16, n_prompt // 2, n_prompt - 2, n_prompt - 1}):
+            ko, vo = o.read_kv(1, pos)
+            kg, vg = g.read_kv(1, pos)
+            # (a first-layer slot that rounds to the neighbouring bf16 value on one side shifts every later
+            # row a little, so single rounding steps are not the bound here: the bf16 tolerance is)
+            assert hp.rel_err_rowmax(kg, ko)[0] <= TOL["bf16"] / 2, (case, n_prompt, pos)
+            assert hp.rel_err_rowmax(vg, vo)[0] <= TOL["bf16"] / 2, (case, n_prompt, pos)
+        to, lo_ = o.verify([o.pending], True)
+        tg, lg = g.verify([g.pending], True)
+        assert np.all(hp.rel_err_rowmax(lg, lo_) <= TOL["bf16"]), (case, n_prompt)
+        top2 = np.sort(lo_[0])[-2:]
+        if top2[1] - top2[0] > 1e-3 * np.abs(lo_[0]).max():   # the arg-max is not a near tie
+            assert fg == fo and int(tg[0]) == int(to[0]), (case, n_prompt)
+    # candidate evaluation over the 600-token cache: blocks of 18..64 rows that reuse the target's cache
+    prompt = si.uniform_ids(70 + 600, 600, shape.vocab)
+    o.prefill(prompt)
+    g.prefill(prompt)
+    window_src = np.concatenate([prompt, [o.pending]]).astype(np.int32)
+    masks = [np.zeros(4, np.uint8), np.array([0, 1, 0, 0], np.uint8), np.array([0, 0, 1, 1], np.uint8)]
+    for gamma in (17, 40, 64):
+        for mi, mask in enumerate(masks):
+            po, mo, lgo = o.eval_mask(mask, window_src[-(gamma + 1):], want_logits=True)
+            pg, mg = g.eval_mask(mask, window_src[-(gamma + 1):])
+            # rows whose arg-max is a near tie may differ; everything else must agree
+            srt = np.sort(lgo, axis=1)
+            clear = (srt[:, -1] - srt[:, -2]) > 1e-3 * np.abs(lgo).max(axis=1)
+            assert clear.mean() > 0.8, (case, gamma, mi)
+            assert np.array_equal(np.asarray(pg)[clear], np.asarray(po)[clear]), (case, gamma, mi)
+            if clear.all():
+                assert mg == mo
+    g.close()
+
+
 @pytest.mark.parametrize("case", ["small-gqa", "small-gqa-bf16", "7b-width-2-layers"])
 def test_candidate_evaluation_against_oracle(oracle_lib, case):
     """Section 4.1.2, Eq. 3-4: predictions of candidate draft models over the last gamma generated
