@@ -648,7 +648,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                     a.n_ctx += row0;
                     a.row_base = row0;  // (a tree has at most 16 rows: one part)
                     a.rows = std::min(per_launch, R - row0);
-                    a.out_s += 24 * row0;  // first of this part's 3 * rows term columns
+                    a.out_s += 8 * block_terms(block_row_layout(R)) * row0;  // first of this part's term columns
                     a.out_rows = block_row_layout(R);
                     HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
                                   [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));

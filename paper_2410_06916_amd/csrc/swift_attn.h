@@ -208,10 +208,11 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float 
         if (a.out_s) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
-            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * (a.out_rows ? a.out_rows : a.rows)) + 3 * row) * 8 + (e & 7);
+            const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;
-            p[16] = lo;
+            if (nt == 3) p[16] = lo;
         }
     }
 }

@@ -189,12 +189,13 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
                 split3(y, hi[i], mid[i], lw[i]);
             }
             if (a.out_s) {
-                uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * (a.out_rows ? a.out_rows : a.rows)) + 3 * row) * 8 + (e & 7);
+                const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+                uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     p[i] = hi[i];
                     p[8 + i] = mid[i];
-                    p[16 + i] = lw[i];
+                    if (nt == 3) p[16 + i] = lw[i];
                 }
             }
         }

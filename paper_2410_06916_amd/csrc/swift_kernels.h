@@ -13,6 +13,12 @@ constexpr int kMaxBlockRows = 64;  // rows of one prefill block
 // Rows the split-activation layouts of a block of R rows are pitched for: R itself up to 16 rows (verify
 // blocks), else 32 or 64 (prefill blocks, candidate evaluation windows).
 inline int block_row_layout(int R) { return R <= kMaxRows ? R : R <= 32 ? 32 : kMaxBlockRows; }
+// bf16 terms an fp32 activation is split into, by the layout's row count RL.  Up to 16 rows: three
+// (hi + mid + lo is the value exactly), so that a row's result does not depend on the rows it shares
+// a pass with.  Blocks of more than 16 rows (prefill, candidate evaluation) make no such promise and
+// carry the first two terms only (relative error 2^-17 per element): a third less to stage, read and
+// multiply.  Term t of row r is column terms * r + t.
+__host__ __device__ inline int block_terms(int RL) { return RL > kMaxRows ? 2 : 3; }
 constexpr int kAttnMaxSplit = 64;  // most cache-length splits of one (row, kv head)
 constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
@@ -61,7 +67,7 @@ struct AttnArgs {
     float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
     int max_split;                // splits the partial buffers can hold
     float *out;                   // fp32 [rows][n_q][d], or nullptr
-    uint16_t *out_s;              // three-term bf16 split [n_q*d/8][3*out_rows][8], or nullptr
+    uint16_t *out_s;              // bf16 term split [n_q*d/8][block_terms(out_rows)*out_rows][8], or nullptr
     int out_rows;                 // rows of the block out_s belongs to (0: rows); a launch may cover a
                                   // 16-row part of a larger block: out_s then points at its first column
     // Token tree instead of a chain (tree != 0; at most 16 block rows).  Launch row r is block row

@@ -313,10 +313,11 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
             if (a.out_s) {
                 uint16_t hi16, mid16, lo16;
                 split3(y, hi16, mid16, lo16);
-                uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * orows) + 3 * row) * 8 + (e & 7);
+                const int nt = block_terms(orows);
+                uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
                 p[0] = hi16;
                 p[8] = mid16;
-                p[16] = lo16;
+                if (nt == 3) p[16] = lo16;
             }
         } else {
             const size_t slot = ((size_t)row * nq + g * GROUP + h) * n_split + sp;
@@ -353,10 +354,11 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
         if (a.out_s) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
-            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (3 * (a.out_rows ? a.out_rows : a.rows)) + 3 * row) * 8 + (e & 7);
+            const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;
-            p[16] = lo;
+            if (nt == 3) p[16] = lo;
         }
     }
 }

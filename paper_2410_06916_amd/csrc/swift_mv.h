@@ -14,7 +14,7 @@ namespace swift {
 // (no loop around the loads and stores below).
 template <int EPI, bool ONE_PASS = false, typename YF>
 __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, const float *rot, YF Y) {
-    const int R = a.R, NC = 3 * a.RL;  // NC: column pitch of the split outputs
+    const int R = a.R, NT = block_terms(a.RL), NC = NT * a.RL;  // NC: column pitch of the split outputs
     if (EPI == EPI_RESID || EPI == EPI_LOGITS) {
         const int iters = ONE_PASS ? 1 : (16 * R + 63) >> 6;
         for (int it = 0; it < iters; ++it) {
@@ -32,10 +32,10 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                     *xp = xn;
                     uint16_t hi, mid, lo;
                     split3(xn * a.gain_next[row], hi, mid, lo);
-                    uint16_t *p = a.out_s + ((size_t)(row >> 3) * NC + 3 * r) * 8 + (row & 7);
+                    uint16_t *p = a.out_s + ((size_t)(row >> 3) * NC + NT * r) * 8 + (row & 7);
                     p[0] = hi;
                     p[8] = mid;
-                    p[16] = lo;
+                    if (NT == 3) p[16] = lo;
                 }
                 float ss = xn * xn;
 #pragma unroll
@@ -55,10 +55,10 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                 if (2 * (8 * rg + j) < a.O) {
                     uint16_t hi, mid, lo;
                     split3(ya / (1.0f + expf(-ya)) * yb, hi, mid, lo);
-                    uint16_t *p = a.out_s + ((size_t)rg * NC + 3 * r) * 8 + j;
+                    uint16_t *p = a.out_s + ((size_t)rg * NC + NT * r) * 8 + j;
                     p[0] = hi;
                     p[8] = mid;
-                    p[16] = lo;
+                    if (NT == 3) p[16] = lo;
                 }
             } else {
                 const int d = a.head_dim, half = d >> 1, gph = half >> 3;

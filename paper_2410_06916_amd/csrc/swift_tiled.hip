@@ -90,7 +90,7 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
     // one thread per (row r, element i); 16 consecutive lanes share a 16-element group
-    const int NC = 3 * a.RL;
+    const int NT = block_terms(a.RL), NC = NT * a.RL;
     const int Hp = (a.H + 15) & ~15;
     const int total = a.R * Hp;
     for (int idx0 = blockIdx.x * 256; idx0 < total; idx0 += gridDim.x * 256) {
@@ -103,10 +103,10 @@ __global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
             a.x[(size_t)r * a.H + i] = v;
             uint16_t hi, mid, lo;
             split3(v * a.gain_next[i], hi, mid, lo);
-            uint16_t *p = a.xs + ((size_t)(i >> 3) * NC + 3 * r) * 8 + (i & 7);
+            uint16_t *p = a.xs + ((size_t)(i >> 3) * NC + NT * r) * 8 + (i & 7);
             p[0] = hi;
             p[8] = mid;
-            p[16] = lo;
+            if (NT == 3) p[16] = lo;
         }
         float ss = v * v;
 #pragma unroll
@@ -559,12 +559,12 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 // zero tile by tile, a workgroup covers a group of 8, 4, 2 or 1 whole slices (mv_slice_group: a
 // function of the matrix alone, not of the row count) and adds their sums per term in slice order,
 // combines the three terms, and the last workgroup adds the group results in order.  The
-// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 6 / 12 (blocks of 17-32 / 33-64 rows) keep their own
+// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 4 / 8 (blocks of 17-32 / 33-64 rows, two-term columns) keep their own
 // fixed order.
 template <int EPI, int NCB, int CT, int RG>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int R = a.R, NC = 3 * a.RL;  // NC: columns of the split input as laid out (= 16 NCB when NCB is 6 or 12)
+    const int R = a.R, NT = block_terms(a.RL), NC = NT * a.RL;  // NC: columns of the split input as laid out (= 16 NCB beyond 16 rows)
     const int buf_bytes = 4 * CT * NC * 16;
     // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
     const int main_bytes = max(2 * buf_bytes, NCB * 8192);
@@ -717,7 +717,10 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     // ---- per row group of the wavefront: results to LDS (dump[wave][column][tile row]), then the
     // epilogue, or with split K the partial
     float *dw = dump + (size_t)wave * (NCB * 256);
-    auto y_local = [&](int r, int j) { return (dw[(3 * r) * 16 + j] + dw[(3 * r + 1) * 16 + j]) + dw[(3 * r + 2) * 16 + j]; };
+    auto y_local = [&](int r, int j) {
+        const float y2 = dw[(NT * r) * 16 + j] + dw[(NT * r + 1) * 16 + j];
+        return NT == 3 ? y2 + dw[(3 * r + 2) * 16 + j] : y2;
+    };
     auto dump_regs = [&](const f32x4(&v)[NCB]) {
         __syncthreads();  // the B buffers / the previous dump are no longer read
 #pragma unroll
@@ -786,7 +789,7 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int NC = 3 * a.RL;
+    const int NC = block_terms(a.RL) * a.RL;
     const size_t buf2 = 2 * (size_t)4 * CT * NC * 16;
     const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 320 + 2048;
     const int n_rb = (a.n_rg + 8 * RG - 1) / (8 * RG);
@@ -824,17 +827,18 @@ hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_overri
     // small blocks whose whole activation fits in LDS take the single-pass kernel
     if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
-    // up to 16 rows: 1-3 column blocks, K chunks of 8 tiles; 17-32 / 33-64 rows (prefill, candidate
-    // evaluation): 6 / 12 column blocks, K chunks of 8 / 4 tiles (48 KB of split activation per chunk)
-    const int ncb = (3 * a.RL + 15) / 16;
+    // up to 16 rows: 1-3 column blocks of three-term columns, K chunks of 8 tiles; 17-32 / 33-64 rows
+    // (prefill, candidate evaluation): 4 / 8 column blocks of two-term columns
+    const int ncb = (block_terms(a.RL) * a.RL + 15) / 16;
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
         switch (ncb) {                                                  \
             case 1: return launch_mvN_t<E, 1, 8, 1>(a, n_cu, s);          \
             case 2: return launch_mvN_t<E, 2, 8, 1>(a, n_cu, s);          \
             case 3: return launch_mvN_t<E, 3, 8, 1>(a, n_cu, s);          \
-            case 6: return launch_mvN_t<E, 6, 8, 1>(a, n_cu, s);          \
-            default: return launch_mvN_t<E, 12, 4, 1>(a, n_cu, s);         \
+            case 4: return launch_mvN_t<E, 4, 8, 1>(a, n_cu, s);          \
+            case 8: return launch_mvN_t<E, 8, 8, 1>(a, n_cu, s);          \
+            default: return hipErrorInvalidValue;                        \
         }
     switch (epi) {
         SWIFT_MVN_CASE(EPI_QKV)

@@ -155,7 +155,8 @@ def test_prefill_block_sizes_against_oracle(oracle_lib):
                 # a value next to a bf16 rounding boundary may land on the other side
                 assert np.allclose(kg, ko, rtol=2 ** -7, atol=1e-6), (n_prompt, layer, pos)
                 assert np.allclose(vg, vo, rtol=2 ** -7, atol=1e-6), (n_prompt, layer, pos)
-                assert (kg != ko).mean() < 0.05 and (vg != vo).mean() < 0.05
+                # (blocks of more than 16 rows carry two of the three bf16 terms of an activation: 2^-17)
+                assert (kg != ko).mean() < 0.1 and (vg != vo).mean() < 0.1
     g.close()
 
 
