@@ -561,7 +561,7 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 // combines the three terms, and the last workgroup adds the group results in order.  The
 // LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 4 / 8 (blocks of 17-32 / 33-64 rows, two-term columns) keep their own
 // fixed order.
-template <int EPI, int NCB, int CT, int RG>
+template <int EPI, int NCB, int CT, int RG, bool DMA>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int R = a.R, NT = block_terms(a.RL), NC = NT * a.RL;  // NC: columns of the split input as laid out (= 16 NCB beyond 16 rows)
@@ -651,6 +651,25 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
             if (i < chunk_units) dst[i] = tmp[q];
         }
     };
+    // DMA variants: B chunk c -> LDS buffer bi straight from global memory (no registers, no LDS write
+    // instructions: the data lands while the wavefronts run MFMAs).  A wavefront's 64 lanes fill 64
+    // consecutive 16-byte units from a wavefront-uniform base; lanes past the chunk take no part.  Units
+    // past the real K range (a ragged last tile) are zeroed with ordinary writes.
+    auto dmaB = [&](int c, int bi) {
+        const int gu0 = 4 * (tb + chunk_t0(c)) * NC;
+        u32x4 *dst = (u32x4 *)(smem + 16 + (size_t)bi * buf_bytes);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int i = tid + 512 * q;
+            if (i < chunk_units) {
+                if (gu0 + i < real_units)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(bsrc + gu0 + i),
+                                                     (__attribute__((address_space(3))) void *)(dst + 512 * q + 64 * wave), 16, 0, 0);
+                else
+                    dst[i] = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
     // The B operands of a tile (NCB LDS reads) are requested one tile ahead of the MFMAs that use
     // them.  Slots past the chunk's tiles multiply a zero A operand.
     auto mfmas = [&](int c, const u32x4(&A)[RG][CT], int bi) {
@@ -685,33 +704,60 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
         if (kCanon && ((c + 1) % nchs == 0 || c + 1 == nch)) slice_end();
     };
 
-    // Pipeline: while the MFMAs of chunk c run, the A tiles of chunk c + 1 and the B operand of
-    // chunk c + 2 are on their way from memory, and the B operand of chunk c + 1 (loaded during
-    // the previous step) is copied into the other LDS buffer.  One LDS-only barrier per step: it
-    // does not wait for the loads in flight.
-    u32x4 A0[RG][CT], A1[RG][CT], tmp[NQ];
-    loadB(0, tmp);
-    loadA(0, A0);
-    if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
-    storeB(0, tmp);
-    if (nch > 1) loadB(1, tmp);
-    if (a.rp == 16)
-        mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
-    else
-        mv_norm_rows64(a, rs, nscratch);
-
-    auto step = [&](int c, const u32x4(&Ac)[RG][CT], int bc, u32x4(&An)[RG][CT], int bn) {
-        lds_barrier();  // chunk c's B is visible; nobody reads buffer bn any more
-        if (c + 1 < nch) {
-            storeB(bn, tmp);
-            if (c + 2 < nch) loadB(c + 2, tmp);
-            loadA(c + 1, An);
+    u32x4 A0[RG][CT], A1[RG][CT];
+    if constexpr (DMA) {
+        // Pipeline: while the MFMAs of chunk c run, the B operand and the A tiles of chunk c + 1 are on their
+        // way, the former straight into the other LDS buffer.  Per step: wait for this wavefront's own loads
+        // of chunk c, then one barrier (everybody's part of B(c) has landed; nobody reads the other buffer).
+        if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+        dmaB(0, 0);
+        loadA(0, A0);
+        if (a.rp == 16)
+            mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+        else
+            mv_norm_rows64(a, rs, nscratch);
+        auto step = [&](int c, const u32x4(&Ac)[RG][CT], int bc, u32x4(&An)[RG][CT], int bn) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            lds_barrier();
+            if (c + 1 < nch) {
+                dmaB(c + 1, bn);
+                loadA(c + 1, An);
+            }
+            mfmas(c, Ac, bc);
+        };
+        for (int c = 0; c < nch; c += 2) {
+            step(c, A0, 0, A1, 1);
+            if (c + 1 < nch) step(c + 1, A1, 1, A0, 0);
         }
-        mfmas(c, Ac, bc);
-    };
-    for (int c = 0; c < nch; c += 2) {
-        step(c, A0, 0, A1, 1);
-        if (c + 1 < nch) step(c + 1, A1, 1, A0, 0);
+    } else {
+        // Pipeline: while the MFMAs of chunk c run, the A tiles of chunk c + 1 and the B operand of
+        // chunk c + 2 are on their way from memory, and the B operand of chunk c + 1 (loaded during
+        // the previous step) is copied into the other LDS buffer.  One LDS-only barrier per step: it
+        // does not wait for the loads in flight.
+        u32x4 tmp[NQ];
+        loadB(0, tmp);
+        loadA(0, A0);
+        if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
+        storeB(0, tmp);
+        if (nch > 1) loadB(1, tmp);
+        if (a.rp == 16)
+            mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+        else
+            mv_norm_rows64(a, rs, nscratch);
+
+        auto step = [&](int c, const u32x4(&Ac)[RG][CT], int bc, u32x4(&An)[RG][CT], int bn) {
+            lds_barrier();  // chunk c's B is visible; nobody reads buffer bn any more
+            if (c + 1 < nch) {
+                storeB(bn, tmp);
+                if (c + 2 < nch) loadB(c + 2, tmp);
+                loadA(c + 1, An);
+            }
+            mfmas(c, Ac, bc);
+        };
+        for (int c = 0; c < nch; c += 2) {
+            step(c, A0, 0, A1, 1);
+            if (c + 1 < nch) step(c + 1, A1, 1, A0, 0);
+        }
     }
 
     // ---- per row group of the wavefront: results to LDS (dump[wave][column][tile row]), then the
@@ -780,11 +826,11 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     if (tid == 0) a.counters[blockIdx.x] = 0;
 }
 
-template <int EPI, int NCB, int CT, int RG>
+template <int EPI, int NCB, int CT, int RG, bool DMA>
 static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT, RG>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT, RG, DMA>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMvMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -817,7 +863,7 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
         if (rpw > 8) rpw = 8;
         grid_x = (a.n_rg + rpw * RG - 1) / (rpw * RG);
     }
-    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
+    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG, DMA>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
@@ -833,11 +879,11 @@ hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_overri
 #define SWIFT_MVN_CASE(E)                                               \
     case E:                                                             \
         switch (ncb) {                                                  \
-            case 1: return launch_mvN_t<E, 1, 8, 1>(a, n_cu, s);          \
-            case 2: return launch_mvN_t<E, 2, 8, 1>(a, n_cu, s);          \
-            case 3: return launch_mvN_t<E, 3, 8, 1>(a, n_cu, s);          \
-            case 4: return launch_mvN_t<E, 4, 8, 1>(a, n_cu, s);          \
-            case 8: return launch_mvN_t<E, 8, 8, 1>(a, n_cu, s);          \
+            case 1: return launch_mvN_t<E, 1, 8, 1, false>(a, n_cu, s);          \
+            case 2: return launch_mvN_t<E, 2, 8, 1, false>(a, n_cu, s);          \
+            case 3: return launch_mvN_t<E, 3, 8, 1, false>(a, n_cu, s);          \
+            case 4: return launch_mvN_t<E, 4, 8, 1, true>(a, n_cu, s);          \
+            case 8: return launch_mvN_t<E, 8, 8, 1, true>(a, n_cu, s);          \
             default: return hipErrorInvalidValue;                        \
         }
     switch (epi) {
