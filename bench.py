@@ -322,7 +322,7 @@ def main():
         seq = np.concatenate([prompt, toks]).astype(np.int32)
         cand = {"note": "draft-model block pass over the last gamma generated tokens with the workload's skip mask, "
                         "target cache reused; median of 8 calls, host clock"}
-        for gamma in (16, 32, 64):
+        for gamma in (16, 32, 64, 128):
             ts = []
             for _ in range(8):
                 t0 = time.perf_counter()

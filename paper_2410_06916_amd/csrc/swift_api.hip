@@ -941,19 +941,24 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
 extern "C" int swift_eval_mask(swift_ctx *x, const uint8_t *skip_mask, const int32_t *window, int gamma,
                                int32_t *predicted, int *n_match) {
     if (!x || !skip_mask || !window || !n_match) return fail(SWIFT_EINVAL, "null argument");
-    if (gamma < 1 || gamma > kMaxBlockRows) return fail(SWIFT_EINVAL, "gamma out of range (1..64)");
+    if (gamma < 1 || gamma > SWIFT_MAX_WINDOW) return fail(SWIFT_EINVAL, "gamma out of range (1..128)");
     if (x->pending < 0) return fail(SWIFT_ESTATE, "candidate evaluation before prefill");
     if (gamma > x->n) return fail(SWIFT_ESTATE, "window longer than the cache");
     for (int i = 0; i <= gamma; ++i)
         if (window[i] < 0 || window[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
-    int rc = forward_block(x, window, gamma, x->n - gamma, skip_mask, true, true);
-    if (rc) return rc;
-    rc = read_results(x, gamma);
-    if (rc) return rc;
+    // Rows read the target's cache and write nothing, so a window longer than a block is evaluated
+    // block by block.
     int m = 0;
-    for (int i = 0; i < gamma; ++i) {
-        if (predicted) predicted[i] = x->h_tok[i];
-        if (x->h_tok[i] == window[i + 1]) ++m;
+    for (int r0 = 0; r0 < gamma; r0 += kMaxBlockRows) {
+        const int rows = std::min(kMaxBlockRows, gamma - r0);
+        int rc = forward_block(x, window + r0, rows, x->n - gamma + r0, skip_mask, true, true);
+        if (rc) return rc;
+        rc = read_results(x, rows);
+        if (rc) return rc;
+        for (int i = 0; i < rows; ++i) {
+            if (predicted) predicted[r0 + i] = x->h_tok[i];
+            if (x->h_tok[i] == window[r0 + i + 1]) ++m;
+        }
     }
     *n_match = m;
     return SWIFT_OK;

@@ -223,7 +223,7 @@ def test_block_attention_on_matrix_cores_against_oracle(oracle_lib, case):
 def test_candidate_evaluation_against_oracle(oracle_lib, case):
     """Section 4.1.2, Eq. 3-4: predictions of candidate draft models over the last gamma generated
     tokens (block pass with the skip mask, target cache reused, nothing written) and the match
-    count, for windows of 1..64 tokens; the decoding state is untouched."""
+    count, for windows of 1..128 tokens (more than 64: two blocks); the decoding state is untouched."""
     import paper_2410_06916_amd as P
     if case == "7b-width-2-layers":
         shape = si.LLAMA2_7B.with_layers(2)
@@ -233,7 +233,7 @@ def test_candidate_evaluation_against_oracle(oracle_lib, case):
     else:
         shape = hp.SMALL_GQA if case == "small-gqa" else hp.SMALL_GQA_BF16
         weights = hp.shaped_weights(shape, seed=21)
-        n_prompt, n_gen, gammas, threads = 12, 70, (1, 4, 6, 16, 32, 64), 1
+        n_prompt, n_gen, gammas, threads = 12, 140, (1, 4, 6, 16, 32, 64, 65, 100, 128), 1
         rng = np.random.default_rng(2)
         L2 = 2 * shape.n_layers
         masks = [np.zeros(L2, np.uint8), np.ones(L2, np.uint8)] + [(rng.random(L2) < 0.5).astype(np.uint8)
@@ -260,7 +260,7 @@ def test_candidate_evaluation_against_oracle(oracle_lib, case):
     with pytest.raises(P.SwiftError):
         g.eval_mask(masks[0], np.zeros(g.cache_len + 2, np.int32))
     with pytest.raises(P.SwiftError):
-        g.eval_mask(masks[0], np.zeros(66, np.int32))       # gamma 65 > 64
+        g.eval_mask(masks[0], np.zeros(130, np.int32))      # gamma 129 > 128
     g.close()
 
 
