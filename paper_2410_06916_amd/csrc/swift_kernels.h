@@ -170,7 +170,8 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s);
 
 // Activations between the tiled kernels.  An fp32 activation vector of R rows (tokens) that
 // feeds a projection is kept as three bf16 terms per value (value = hi + mid + lo exactly), laid
-// out as the MFMA B operand: [K/8 chunks][NC = 3R columns][8 k] bf16, column 3r + term.  The
+// out as the MFMA B operand: [K/8 chunks][NC = 3R columns][8 k] bf16, column 3r + term (blocks of
+// more than 16 rows: the first two terms, NC = 2 RL columns, column 2r + term; block_terms).  The
 // residual stream itself stays fp32 [R][H]; the kernel that updates it also writes the split of
 // (x * gain of the next consumer) and, per 16-row group, the partial sums of squares of x, so the
 // consumer only adds up the partials (fixed order) to get the RMSNorm scale 1/sqrt(mean x^2 + eps)

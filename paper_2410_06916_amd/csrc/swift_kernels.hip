@@ -363,7 +363,7 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
     }
 }
 
-// Short contexts: one workgroup of 16 wavefronts per (kv head, block row) walks the whole cache
+// Short contexts: one workgroup of kAttnHeadWaves wavefronts per (kv head, block row) walks the whole cache
 // range (attn_head_unit), so nothing goes through global memory and one launch suffices.
 constexpr int kAttnHeadWaves = 8;  // wavefronts of a one-workgroup-per-head attention workgroup
 template <typename T, int GROUP, bool TREE, int RB>

@@ -1,5 +1,5 @@
 // gfx950 kernels of the bf16 path: tiled weights streamed once from HBM into MFMA, activations
-// kept in fp32 precision as three bf16 terms.  k_mv1 handles blocks of 1-5 activation rows whose
+// kept in fp32 precision as three bf16 terms (two in blocks of more than 16 rows).  k_mv1 handles blocks of 1-5 activation rows whose
 // activation fits in LDS (draft pass, plain decoding, short verify blocks), k_mvN blocks of up to
 // 64 rows (longer verify blocks, prefill, candidate evaluation).
 #include <math.h>
