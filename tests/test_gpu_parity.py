@@ -219,6 +219,29 @@ def test_block_attention_on_matrix_cores_against_oracle(oracle_lib, case):
     g.close()
 
 
+def test_block_attention_at_7b_width_against_oracle(oracle_lib):
+    """The same kernel with the 7B workload's 32 heads of 128, two layers deep: a 200-token prompt (three
+    64-row blocks, the third over two cache ranges, and an 8-row tail on the row-at-a-time kernel)."""
+    shape = si.LLAMA2_7B.with_layers(2)
+    weights = si.make_weights(shape, 0)
+    o, g = _pair(oracle_lib, shape, weights, 224, threads=16)
+    prompt = si.uniform_ids(9, 200, shape.vocab)
+    fo = o.prefill(prompt)[0]
+    fg = g.prefill(prompt)
+    for pos in (0, 63, 64, 130, 191, 192, 199):
+        ko, vo = o.read_kv(1, pos)
+        kg, vg = g.read_kv(1, pos)
+        assert hp.rel_err_rowmax(kg, ko)[0] <= TOL["bf16"] / 2, pos
+        assert hp.rel_err_rowmax(vg, vo)[0] <= TOL["bf16"] / 2, pos
+    to, lo_ = o.verify([o.pending], True)
+    tg, lg = g.verify([g.pending], True)
+    assert np.all(hp.rel_err_rowmax(lg, lo_) <= TOL["bf16"])
+    top2 = np.sort(lo_[0])[-2:]
+    if top2[1] - top2[0] > 1e-3 * np.abs(lo_[0]).max():
+        assert fg == fo and int(tg[0]) == int(to[0])
+    g.close()
+
+
 @pytest.mark.parametrize("case", ["small-gqa", "small-gqa-bf16", "7b-width-2-layers"])
 def test_candidate_evaluation_against_oracle(oracle_lib, case):
     """Section 4.1.2, Eq. 3-4: predictions of candidate draft models over the last gamma generated
