@@ -129,7 +129,7 @@ hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s) {
 // threads load (thread = (partial p mod 32, row r)); mv_norm_load issues the first eight loads per
 // thread (enough for 256 partials, hidden <= 4096) so that the caller can put them ahead of the
 // weight loads; mv_norm_finish adds the rest, then 16 threads add the 32 per-lane sums in order:
-// the summation order is fixed.  Ends with a barrier.  (Full barriers: LDS-only ones, which would leave the
+// the summation order is fixed.  One barrier, before the final sums.  (Full barriers: LDS-only ones, which would leave the
 // caller's first weight loads in flight, measured 0.3 us slower per launch.)
 struct NormPart {
     float v[8];
@@ -144,6 +144,7 @@ __device__ inline NormPart mv_norm_load(const MvArgs &a) {
     }
     return np;
 }
+template <bool LDS_ONLY = false>
 __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float *rs /* LDS [16] */,
                                       float *scratch /* LDS [512] */) {
     const int tid = threadIdx.x, r = tid & 15, q = tid >> 4;
@@ -163,18 +164,22 @@ __device__ inline void mv_norm_finish(const MvArgs &a, const NormPart &np, float
         }
         scratch[q * 16 + r] = ss;
     }
-    __syncthreads();
+    if (LDS_ONLY)
+        lds_barrier();
+    else
+        __syncthreads();
     if (tid < 16) {
         float ss = 0.f;
         if (a.pss)
             for (int q2 = 0; q2 < 32; ++q2) ss += scratch[q2 * 16 + tid];
         rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
     }
-    __syncthreads();
+    // (no barrier here: the scales are read by the epilogue only, and every caller has a barrier between
+    // this point and its epilogue)
 }
 
 // The same for blocks of up to 64 rows (row pitch 64): thread = (partial p mod 8, row r), then 64
-// threads add the 8 per-thread sums in order.  Ends with a barrier.  scratch: LDS [512].
+// threads add the 8 per-thread sums in order.  One barrier, before the final sums.  scratch: LDS [512].
 __device__ inline void mv_norm_rows64(const MvArgs &a, float *rs /* LDS [64] */, float *scratch) {
     const int tid = threadIdx.x, r = tid & 63, q = tid >> 6;
     if (a.pss) {
@@ -198,7 +203,8 @@ __device__ inline void mv_norm_rows64(const MvArgs &a, float *rs /* LDS [64] */,
             for (int q2 = 0; q2 < 8; ++q2) ss += scratch[q2 * 64 + tid];
         rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
     }
-    __syncthreads();
+    // (no barrier here: the scales are read by the epilogue only, and every caller has a barrier between
+    // this point and its epilogue)
 }
 
 // Slices (of the 8 K slices of a row group) whose sums are added first, in slice order, before the
@@ -306,6 +312,12 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         u32x4 *dst = (u32x4 *)(smem + 16);
         const int n_units = T * 4 * NC, real_units = (a.K >> 3) * NC;
         const u32x4 zero = {0u, 0u, 0u, 0u};
+        // The residual projections read their norm partials ahead of the weight window and wait for them
+        // with an LDS-only barrier, so that the MFMAs start on the first tiles while the rest of the window
+        // is still on its way (o_proj 10.7 -> 10.4 us, down_proj 19.0 -> 18.2 us); the other epilogues measured
+        // slower that way (q|k|v by 2.7 us) and keep the full barrier.
+        constexpr bool kEarlyNorm = EPI == EPI_RESID;
+        NormPart np;
         auto side_loads = [&]() {
             if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
             if (EPI == EPI_QKV) {
@@ -324,6 +336,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
                 const int i = tid + 512 * q;
                 tmp[q] = i < real_units ? src[i] : zero;
             }
+            if (kEarlyNorm) np = mv_norm_load(a);
             prime(0);
             side_loads();
 #pragma unroll
@@ -338,6 +351,7 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
                 const int i = tid + 512 * q;
                 tmp[q] = i < real_units ? src[i] : zero;
             }
+            if (kEarlyNorm) np = mv_norm_load(a);
             prime(0);
             side_loads();
 #pragma unroll
@@ -358,7 +372,8 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
                 }
             }
         }
-        mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+        if (!kEarlyNorm) np = mv_norm_load(a);
+        mv_norm_finish<kEarlyNorm>(a, np, rs, nscratch);
     }
 
     for (int seg = 0; seg < a.S; ++seg) {
