@@ -430,7 +430,12 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
     // block rows that share their key/value loads in one workgroup (the more, the less cache traffic;
     // bounded by registers: members = heads per kv head x rows)
-    const int rb = a.tree ? 1 : group == 1 ? 4 : group == 2 ? 2 : 1;
+    // (one or two rows take the instance with as many members: the same arithmetic per row -- a row's result
+    // does not depend on the rows that share its workgroup -- without the idle members' share of the vector
+    // arithmetic)
+    const bool one_row = !a.tree && a.rows == 1 && group <= 2;
+    const bool two_rows = !a.tree && a.rows == 2 && group == 1;
+    const int rb = a.tree || one_row ? 1 : two_rows ? 2 : group == 1 ? 4 : group == 2 ? 2 : 1;
     dim3 grid(a.n_kv_heads, n_split, (a.rows + rb - 1) / rb), block(256);
     if (a.tree) switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 1, true>), grid, block, 0, s, a, chunk); break;
@@ -439,7 +444,14 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
         case 8: hipLaunchKernelGGL((k_attn_split<T, 8, 1, true>), grid, block, 0, s, a, chunk); break;
         default: return hipErrorInvalidValue;
     }
-    else switch (group) {
+    else if (one_row) {
+        if (group == 1)
+            hipLaunchKernelGGL((k_attn_split<T, 1, 1>), grid, block, 0, s, a, chunk);
+        else
+            hipLaunchKernelGGL((k_attn_split<T, 2, 1>), grid, block, 0, s, a, chunk);
+    } else if (two_rows) {
+        hipLaunchKernelGGL((k_attn_split<T, 1, 2>), grid, block, 0, s, a, chunk);
+    } else switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 4>), grid, block, 0, s, a, chunk); break;
         case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 2>), grid, block, 0, s, a, chunk); break;
         case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1>), grid, block, 0, s, a, chunk); break;
