@@ -75,3 +75,66 @@ def test_random_shapes_against_oracle(oracle_lib, first_seed):
         o.close()
         n_done += 1
     assert n_done >= 20
+
+
+def _random_loop_case(seed, dtype):
+    rng = np.random.default_rng(seed + 7000)
+    d = int(rng.choice([16, 32, 64, 128]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    while n_kv * group * d > 512:
+        if group > 1:
+            group //= 2
+        elif n_kv > 1:
+            n_kv //= 2
+        else:
+            d //= 2
+    n_q = n_kv * group
+    ffn = int(rng.integers(8, 40)) * 8
+    vocab = int(rng.integers(50, 300)) * 2
+    n_layers = int(rng.integers(2, 5))
+    max_seq = int(rng.choice([128, 1700]))
+    n_prompt = int(rng.integers(1, 60))
+    n_new = int(rng.integers(4, 30))
+    shape = si.ModelShape(f"loop-{seed}", n_layers, n_q * d, n_q, n_kv, d, ffn, vocab, dtype,
+                          1e-6 if dtype == "fp32" else 1e-5)
+    mask = (rng.random(2 * n_layers) < 0.35).astype(np.uint8)
+    max_k = int(rng.integers(1, 16))
+    eps = float(rng.choice([0.0, 0.3, 0.8]))
+    width = int(rng.choice([1, 3, 10]))
+    return shape, max_seq, n_prompt, n_new, mask, max_k, eps, width
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_random_decoding_loops_are_lossless(oracle_lib, dtype):
+    """Plain greedy decoding, draft-then-verify decoding and decoding with dynamic verification (Sections 3.1
+    and 4.2) on seeded random shapes, masks, draft lengths and thresholds.  fp32 storage: every loop's tokens
+    equal the oracle's.  bf16 storage (where a near tie may fall the other way than in the oracle): the
+    speculative loops on the GPU reproduce the GPU's own plain decoding exactly, and so do the oracle's."""
+    import paper_2410_06916_amd as P
+    n_done = 0
+    for seed in range(24):
+        shape, max_seq, n_prompt, n_new, mask, max_k, eps, width = _random_loop_case(seed, dtype)
+        if shape.hidden % 32:
+            continue
+        what = (seed, shape, max_seq, n_prompt, n_new, max_k, eps, width)
+        weights = hp.shaped_weights(shape, seed=seed)
+        o = oracle_lib.Oracle(shape, max_seq, threads=8)
+        o.set_weights(weights)
+        g = P.SwiftModel(shape, max_seq)
+        g.load_weights(weights)
+        prompt = si.uniform_ids(2000 + seed, n_prompt, shape.vocab)
+        want = oracle_lib.generate_ar(o, prompt, n_new)
+        plain = P.generate_ar(g, prompt, n_new)
+        w1, _ = oracle_lib.generate_swift(o, prompt, n_new, mask, max_k, eps)
+        g1, _ = P.generate_swift(g, prompt, n_new, mask, max_k, eps)
+        w2, _ = oracle_lib.generate_swift_tree(o, prompt, n_new, mask, min(max_k, 8), eps, width)
+        g2, _ = P.generate_swift_tree(g, prompt, n_new, mask, min(max_k, 8), eps, width)
+        assert np.array_equal(w1, want) and np.array_equal(w2, want), what
+        assert np.array_equal(g1, plain) and np.array_equal(g2, plain), what
+        if dtype == "fp32":
+            assert np.array_equal(plain, want), what
+        g.close()
+        o.close()
+        n_done += 1
+    assert n_done >= 16
