@@ -194,3 +194,47 @@ def test_sampling_errors_on_device(oracle_lib):
     with pytest.raises(P.SwiftError):
         g.verify_sample([g.pending, int(d[0])], 0.6, 0.9, [0.5], 0.5)     # the distributions are spent
     g.close()
+
+
+def test_sampled_decoding_on_random_shapes(oracle_lib):
+    """The same lockstep comparison on seeded random shapes, temperatures, nucleus sizes, masks and draft
+    lengths (head sizes 16..128, vocabularies up to 4000, both storage types)."""
+    compared = run = n_done = 0
+    for seed in range(30):
+        rng = np.random.default_rng(seed + 9000)
+        d = int(rng.choice([16, 32, 64, 128]))
+        group = int(rng.choice([1, 2, 4]))
+        n_kv = int(rng.choice([1, 2]))
+        while n_kv * group * d > 512:
+            if group > 1:
+                group //= 2
+            elif n_kv > 1:
+                n_kv //= 2
+            else:
+                d //= 2
+        n_q = n_kv * group
+        if (n_q * d) % 32:
+            continue
+        ffn = int(rng.integers(8, 40)) * 8
+        vocab = int(rng.integers(50, 2000)) * 2
+        dtype = "bf16" if rng.random() < 0.6 else "fp32"
+        n_layers = int(rng.integers(1, 4))
+        max_seq = int(rng.choice([128, 1700]))
+        shape = si.ModelShape(f"random-{seed}", n_layers, n_q * d, n_q, n_kv, d, ffn, vocab, dtype, 1e-5)
+        weights = hp.shaped_weights(shape, seed=seed, head_scale=float(rng.choice([20.0, 60.0, 150.0])))
+        o, g = _pair(oracle_lib, shape, weights, max_seq)
+        prompt = si.uniform_ids(3000 + seed, int(rng.integers(1, 50)), vocab)
+        mask = (rng.random(2 * n_layers) < 0.4).astype(np.uint8)
+        T = float(rng.choice([0.6, 1.0, 1.5]))
+        top_p = float(rng.choice([0.5, 0.9, 0.95, 1.0]))
+        max_k = int(rng.integers(1, 15))
+        eps = float(rng.choice([0.0, 0.3]))
+        U = rng.random((64, 31))
+        u0 = float(rng.random())
+        c, r, _, _ = _lockstep(o, g, shape, prompt, int(rng.integers(5, 30)), mask, max_k, eps, T, top_p, u0, U)
+        compared += c
+        run += r
+        n_done += 1
+        g.close()
+        o.close()
+    assert n_done >= 20 and compared >= run // 2, (n_done, compared, run)
