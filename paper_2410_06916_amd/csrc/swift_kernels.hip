@@ -430,12 +430,13 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
     // block rows that share their key/value loads in one workgroup (the more, the less cache traffic;
     // bounded by registers: members = heads per kv head x rows)
-    // (one or two rows take the instance with as many members: the same arithmetic per row -- a row's result
+    // (one to three rows take the instance with as many members: the same arithmetic per row -- a row's result
     // does not depend on the rows that share its workgroup -- without the idle members' share of the vector
     // arithmetic)
     const bool one_row = !a.tree && a.rows == 1 && group <= 2;
     const bool two_rows = !a.tree && a.rows == 2 && group == 1;
-    const int rb = a.tree || one_row ? 1 : two_rows ? 2 : group == 1 ? 4 : group == 2 ? 2 : 1;
+    const bool three_rows = !a.tree && a.rows == 3 && group == 1;
+    const int rb = a.tree || one_row ? 1 : two_rows ? 2 : three_rows ? 3 : group == 1 ? 4 : group == 2 ? 2 : 1;
     dim3 grid(a.n_kv_heads, n_split, (a.rows + rb - 1) / rb), block(256);
     if (a.tree) switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 1, true>), grid, block, 0, s, a, chunk); break;
@@ -451,6 +452,8 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
             hipLaunchKernelGGL((k_attn_split<T, 2, 1>), grid, block, 0, s, a, chunk);
     } else if (two_rows) {
         hipLaunchKernelGGL((k_attn_split<T, 1, 2>), grid, block, 0, s, a, chunk);
+    } else if (three_rows) {
+        hipLaunchKernelGGL((k_attn_split<T, 1, 3>), grid, block, 0, s, a, chunk);
     } else switch (group) {
         case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 4>), grid, block, 0, s, a, chunk); break;
         case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 2>), grid, block, 0, s, a, chunk); break;

@@ -471,6 +471,11 @@ def test_tree_rows_equal_chain_rows_bit_for_bit(case):
     import paper_2410_06916_amd as P
     if case == "7b-width-2-layers":
         shape, weights, max_seq, n_prompt = si.LLAMA2_7B.with_layers(2), None, 64, 20
+    elif case == "d128-mha":
+        # one kv head per query head and too few heads for the one-workgroup-per-head kernel: the split
+        # kernel's one-, two-, three- and four-row instances
+        shape = BLOCK_ATTN_SHAPES[case]
+        weights, max_seq, n_prompt = hp.shaped_weights(shape, seed=3), 1700, 70
     else:
         shape = hp.SMALL_GQA_BF16
         weights = hp.shaped_weights(shape, seed=3)
@@ -676,7 +681,7 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     g.close()
 
 
-@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers"])
+@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers", "d128-mha"])
 def test_block_rows_equal_single_rows_bit_for_bit(case):
     """What makes speculative output equal plain greedy output exactly rather than up to rounding
     (Sections 1 and 3.1: verification leaves the output unchanged): the logits of a token do not
@@ -704,7 +709,7 @@ def test_block_rows_equal_single_rows_bit_for_bit(case):
         g.accept()
         toks.append(int(tgt[0]))
         rows.append(lg[0].copy())
-    for R in (2, 5, 6, 9, 16):
+    for R in (2, 3, 5, 6, 9, 16):
         g.rollback(n0, t0)
         tgt, lg = g.verify(toks[:R], True)
         assert [int(x) for x in tgt] == toks[1:R + 1]
