@@ -36,8 +36,7 @@
  * order.  Speculative greedy decoding therefore reproduces plain greedy decoding
  * of the same context exactly (paper Sections 1 and 3.1), not just up to
  * rounding.  Prefill blocks use an order of their own; both decoding modes share
- * the prefill.  The experimental persistent path (swift_debug_persistent) is
- * outside this guarantee.
+ * the prefill.
  */
 #ifndef SWIFT_H_
 #define SWIFT_H_
@@ -144,6 +143,8 @@ int swift_prefill(swift_ctx *ctx, const int32_t *prompt, int n_prompt, int32_t *
  * skip_mask: host, uint8[2*n_layers], entry 2l = attention sublayer of layer l, 2l+1 = its MLP,
  * non-zero = skipped.  A skipped sublayer leaves the residual stream unchanged and writes no
  * key/value.  Draft keys/values go to slots n.. of the non-skipped attention sublayers.
+ * A verification that has not been accepted yet is cancelled (its swift_accept then fails with
+ * SWIFT_ESTATE): the draft overwrites cache slots that verification wrote.
  * draft_tokens / draft_conf: host arrays of max_k entries; *k_out in [0, max_k].
  * Needs 0 <= max_k <= SWIFT_MAX_BLOCK - 1 and n + max_k + 1 <= max_seq (SWIFT_ECAPACITY). */
 int swift_draft_step(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold,
@@ -198,8 +199,9 @@ int swift_opt_initial_mask(const swift_opt *opt, uint8_t *mask);          /* mas
 int swift_opt_candidate(const swift_opt *opt, int step, uint8_t *mask);   /* the random-search candidate of a step */
 int swift_opt_set_suggester(swift_opt *opt, swift_suggest_fn fn, void *user, int interval);
 /* window, gamma: as for swift_eval_mask.  Outputs (host; each may be NULL): the step's candidate and its
- * matchness, the retained set and its matchness, finished (0/1).  SWIFT_ESTATE once finished; errors of
- * swift_eval_mask are passed on and leave the optimiser unchanged. */
+ * matchness, the retained set and its matchness, finished (0/1).  SWIFT_ESTATE once finished; SWIFT_EINVAL
+ * if the optimiser's n_sublayers is not twice the context's layer count; errors of swift_eval_mask are
+ * passed on and leave the optimiser unchanged. */
 int swift_opt_step(swift_ctx *ctx, swift_opt *opt, const int32_t *window, int gamma, uint8_t *candidate,
                    double *candidate_matchness, uint8_t *best_mask, double *best_matchness, int *finished);
 
@@ -295,6 +297,8 @@ int swift_verify_sample(swift_ctx *ctx, const int32_t *tokens, int k, float temp
 int swift_rollback(swift_ctx *ctx, int new_cache_len, int32_t pending_token);
 
 int swift_get_state(swift_ctx *ctx, int *cache_len, int32_t *pending_token);
+/* The configuration the context was created with. */
+int swift_get_config(swift_ctx *ctx, swift_model_config *out);
 int swift_get_stats(swift_ctx *ctx, swift_stats *out);
 
 /* ---- test and measurement hooks -------------------------------------------------------------- */
@@ -305,6 +309,12 @@ int swift_debug_poison_kv(swift_ctx *ctx);
 int swift_debug_read_logits(swift_ctx *ctx, int row, float *out);
 /* Copies slot `pos` of layer `layer` to k_out / v_out (host fp32 [n_kv_heads*head_dim] each). */
 int swift_debug_read_kv(swift_ctx *ctx, int layer, int pos, float *k_out, float *v_out);
+
+/* Names the attention kernel instance a block of `rows` rows would take in this context at its present
+ * cache length (tree != 0: the rows of a token tree), e.g. "split<bf16, group 1, rows 3>": kernel family,
+ * storage type, query heads per key/value head, block rows that share a workgroup's key/value loads.
+ * out: host, capacity bytes, NUL-terminated.  Host only; for tests that must know what they covered. */
+int swift_debug_attn_path(swift_ctx *ctx, int rows, int tree, char *out, int capacity);
 
 /* Kernel classes for per-kernel timing. */
 #define SWIFT_KC_QKV 0      /* RMSNorm + fused Q/K/V projection + rotation + cache append */
@@ -320,23 +330,6 @@ int swift_debug_read_kv(swift_ctx *ctx, int layer, int pos, float *k_out, float 
  * that share a 16-row group (0 = automatic, else 1, 2, 4 or 8) and workgroups (0 = automatic).
  * Results do not depend on it bit for bit only within one setting; it exists for tuning runs. */
 int swift_debug_tune(swift_ctx *ctx, int kernel_class, int waves_per_row_group, int workgroups);
-
-/* Experimental path, off by default.  on = 1: blocks of up to four rows of a bf16 model whose
- * deepest activation fits one workgroup's LDS, at positions below 1536, run as ONE persistent launch
- * (decoder stack + LM head; stages separated by grid-wide barriers with bounded polling, the weight
- * stream kept going across them) instead of one launch per projection / attention.  Results match
- * the launch-per-stage path within rounding (the k-slices are summed in a different grouping).  It
- * is measured slower than the default on MI355X and exists for that comparison.  Per-class timing
- * (swift_profile_class) selects the launch-per-stage path while it is on.  If a grid-wide wait ever
- * runs out, the call that was running returns SWIFT_EDEVICE, its results are invalid, and the
- * context continues launch per stage. */
-int swift_debug_persistent(swift_ctx *ctx, int on);
-/* With swift_debug_persistent(ctx, 2) every persistent launch also records, for its first and its
- * last workgroup, the device's 100 MHz clock after each stage's grid-wide wait and at the end of the
- * workgroup's share of the stage (a measurement hook: a profiler sees the launch as one kernel).
- * Returns the readings of the last such launch: ticks[((w * n_stages) + s) * 2 + {0, 1}], w = 0
- * (first workgroup) or 1 (last); capacity = elements of `ticks`, at least 4 * n_stages. */
-int swift_debug_read_stack_trace(swift_ctx *ctx, uint64_t *ticks, int capacity, int *n_stages);
 
 /* Turns per-launch timing of one kernel class on (kernel_class in [0, SWIFT_KC_COUNT)) or off (-1).
  * While on, every launch of that class is bracketed by HIP events on the context's stream. */

@@ -52,7 +52,8 @@ def lib():
     if _lib is not None:
         return _lib
     path = _build.lib_path()
-    if not os.path.exists(path):
+    if _build.is_stale():
+        # no library yet, or its sources have changed since it was built: never run an old binary
         _build.build()
     # PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  It has to be in the process
     # before this library is loaded so that both resolve to that one runtime; two HIP runtimes in
@@ -96,12 +97,12 @@ def lib():
     L.swift_rollback.argtypes = [vp, C.c_int, C.c_int32]
     L.swift_get_state.argtypes = [vp, C.POINTER(C.c_int), i32p]
     L.swift_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    L.swift_get_config.argtypes = [vp, cfgp]
     L.swift_debug_poison_kv.argtypes = [vp]
     L.swift_debug_read_logits.argtypes = [vp, C.c_int, f32p]
     L.swift_debug_read_kv.argtypes = [vp, C.c_int, C.c_int, f32p, f32p]
     L.swift_debug_tune.argtypes = [vp, C.c_int, C.c_int, C.c_int]
-    L.swift_debug_persistent.argtypes = [vp, C.c_int]
-    L.swift_debug_read_stack_trace.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int, C.POINTER(C.c_int)]
+    L.swift_debug_attn_path.argtypes = [vp, C.c_int, C.c_int, C.c_char_p, C.c_int]
     L.swift_profile_class.argtypes = [vp, C.c_int]
     L.swift_profile_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     _lib = L
@@ -149,6 +150,8 @@ def pass_bytes(cfg: ModelConfig, skip: Optional[np.ndarray], n_ctx: int, rows: i
     sp = None
     if skip is not None:
         skip = np.ascontiguousarray(skip, np.uint8)
+        if skip.size != 2 * cfg.n_layers:
+            raise ValueError(f"skip mask must have {2 * cfg.n_layers} entries")
         sp = _p(skip, C.c_uint8)
     _chk(lib().swift_pass_bytes(C.byref(cfg), sp, n_ctx, rows, C.byref(n)), "swift_pass_bytes")
     return n.value
@@ -202,6 +205,13 @@ class SwiftModel:
         for name, t in (weights.items() if hasattr(weights, "items") else weights):
             self.load_tensor(name, t)
 
+    def _mask(self, skip) -> np.ndarray:
+        """A skip mask as the library reads it: uint8[2 * n_layers]."""
+        skip = np.ascontiguousarray(skip, np.uint8)
+        if skip.ndim != 1 or skip.size != 2 * self.cfg.n_layers:
+            raise ValueError(f"skip mask must have {2 * self.cfg.n_layers} entries, got {skip.shape}")
+        return skip
+
     # -- decoding path
     def prefill(self, prompt: Sequence[int]) -> int:
         p = np.ascontiguousarray(prompt, np.int32)
@@ -210,7 +220,7 @@ class SwiftModel:
         return tok.value
 
     def draft_step(self, skip: np.ndarray, max_k: int, conf_threshold: float):
-        skip = np.ascontiguousarray(skip, np.uint8)
+        skip = self._mask(skip)
         toks = np.zeros(max(max_k, 1), np.int32)
         conf = np.zeros(max(max_k, 1), np.float32)
         k = C.c_int()
@@ -236,7 +246,7 @@ class SwiftModel:
     def draft_step_topk(self, skip: np.ndarray, max_k: int, conf_threshold: float, max_width: int = 10):
         """Drafting that keeps the top candidates of every position (Section 4.2, second strategy).
         Returns (levels: one int32 array of candidates per draft position, first = the draft token; conf[k])."""
-        skip = np.ascontiguousarray(skip, np.uint8)
+        skip = self._mask(skip)
         cap = max(max_k, 1)
         toks = np.zeros((cap, TOPK), np.int32)
         conf = np.zeros(cap, np.float32)
@@ -275,7 +285,7 @@ class SwiftModel:
     def draft_step_sample(self, skip: np.ndarray, max_k: int, conf_threshold: float, temperature: float, top_p: float,
                           u: Sequence[float]):
         """Sampled drafting (speculative sampling): u = the uniforms of the draws.  Returns (tokens, conf)."""
-        skip = np.ascontiguousarray(skip, np.uint8)
+        skip = self._mask(skip)
         u = np.ascontiguousarray(u, np.float32)
         assert u.size >= max_k
         toks = np.zeros(max(max_k, 1), np.int32)
@@ -306,7 +316,7 @@ class SwiftModel:
         token.  Returns (predicted[gamma], n_match)."""
         w = np.ascontiguousarray(window, np.int32)
         gamma = w.size - 1
-        skip = np.ascontiguousarray(skip, np.uint8)
+        skip = self._mask(skip)
         pred = np.empty(max(gamma, 0), np.int32)
         nm = C.c_int(0)
         _chk(lib().swift_eval_mask(self._h, _p(skip, C.c_uint8), _p(w, C.c_int32), gamma, _p(pred, C.c_int32),
@@ -349,17 +359,11 @@ class SwiftModel:
         _chk(lib().swift_debug_read_kv(self._h, layer, pos, _p(k, C.c_float), _p(v, C.c_float)), "swift_debug_read_kv")
         return k, v
 
-    def persistent(self, on: bool, trace: bool = False):
-        _chk(lib().swift_debug_persistent(self._h, (2 if trace else 1) if on else 0), "swift_debug_persistent")
-
-    def stack_trace(self) -> np.ndarray:
-        """Clock readings (100 MHz ticks) of the last traced persistent launch: [2 workgroups][stages][2]."""
-        cap = 4 * (5 * self.cfg.n_layers + 1)
-        buf = np.zeros(cap, np.uint64)
-        n = C.c_int(0)
-        _chk(lib().swift_debug_read_stack_trace(self._h, buf.ctypes.data_as(C.POINTER(C.c_uint64)), cap, C.byref(n)),
-             "swift_debug_read_stack_trace")
-        return buf[:4 * n.value].reshape(2, n.value, 2)
+    def attn_path(self, rows: int, tree: bool = False) -> str:
+        """Name of the attention kernel instance a block of `rows` rows takes in this context."""
+        buf = C.create_string_buffer(96)
+        _chk(lib().swift_debug_attn_path(self._h, rows, 1 if tree else 0, buf, 96), "swift_debug_attn_path")
+        return buf.value.decode()
 
     def tune(self, name: str, waves_per_row_group: int = 0, workgroups: int = 0):
         _chk(lib().swift_debug_tune(self._h, KERNEL_CLASSES[name], waves_per_row_group, workgroups), "swift_debug_tune")

@@ -63,8 +63,6 @@ extern "C" int swift_check_config(const swift_model_config *c) {
 
 namespace {
 
-constexpr int kStackTables = 4;  // stage lists kept on the device (draft mask, verify, plain decoding, ...)
-
 struct LayerOff {
     uint64_t attn_norm, wqkv, wo, mlp_norm, wgu, wd;
 };
@@ -77,9 +75,6 @@ struct Layout {
     uint64_t samp_q, samp_p, samp_out;  // speculative sampling: draft and target distributions [16][V], results
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
     uint64_t xs, as_, hs, pss, mv_part, mv_counters;
-    // persistent stack kernel: cached stage lists, barrier counter + error flag
-    uint64_t stack_tab, stack_sync, stack_trace;
-    int stack_max_stages;
     int mv_part_capacity;
     uint64_t stage, stage_bytes;  // staging for host tensors that are re-tiled on the device
     uint64_t total;
@@ -145,10 +140,6 @@ Layout make_layout(const swift_model_config &c) {
     L.mv_part_capacity = 8192;
     L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxBlockRows * 4);
     L.mv_counters = take(4096 * 4);
-    L.stack_max_stages = 5 * c.n_layers + 1;
-    L.stack_tab = take((uint64_t)kStackTables * L.stack_max_stages * sizeof(StackStage));
-    L.stack_sync = take(256);
-    L.stack_trace = take((uint64_t)2 * L.stack_max_stages * 2 * 8);
     L.stage_bytes = bf ? std::max(std::max(V * H, F * H), std::max(Q * H, KV * H)) * eb : 0;
     L.stage = take(L.stage_bytes);
     L.total = off;
@@ -209,13 +200,6 @@ extern "C" int swift_pass_bytes(const swift_model_config *cfg, const uint8_t *sk
 // ------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------
-// identifies a cached stage list: rows, LM head included or not, skip mask (empty = none)
-struct StackKey {
-    int R = 0, n_stages = 0;
-    bool logits = false, valid = false;
-    std::vector<uint8_t> mask;
-};
-
 struct ProfRec {
     hipEvent_t a, b;
     uint64_t bytes;
@@ -246,15 +230,6 @@ struct swift_ctx {
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
     int tune_ks[SWIFT_KC_COUNT], tune_wg[SWIFT_KC_COUNT];
-    // persistent stack kernel
-    bool stack_on;              // use it where a block qualifies
-    bool stack_trace;           // record per-stage clock readings of the next persistent launches
-    int stack_trace_stages;     // stages of the last traced launch
-    unsigned stack_base;        // value of the device barrier counter before the next launch
-    int stack_next;             // table slot to overwrite next
-    std::vector<StackKey> stack_keys;  // what each device table slot holds
-    int32_t *h_err;             // pinned: the kernel's error flag after a pass
-    bool stack_used;            // a persistent launch happened since the flag was last read
     // profiling
     int prof_class;
     std::vector<ProfRec> prof;
@@ -460,20 +435,22 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.part_capacity = L.mv_part_capacity;
         return m;
     };
-    // ---- the pass as a list of stages
-    std::vector<StackStage> list;
-    std::vector<int> classes;  // kernel class of each stage (profiling, launch-shape overrides)
+    // ---- the pass as a list of launches
+    struct Launch {
+        int kc;       // kernel class (profiling, launch-shape overrides)
+        int epi;      // projections: Epilogue; attention: -1
+        MvArgs mv;
+        AttnArgs at;
+    };
+    std::vector<Launch> list;
     list.reserve(5 * stages.size() + 1);
-    auto push_mv = [&](int kc, int epi, const MvArgs &m, int wg_first) {
-        StackStage st{};
-        st.type = ST_MV;
+    auto push_mv = [&](int kc, int epi, const MvArgs &m) {
+        Launch st{};
+        st.kc = kc;
         st.epi = epi;
-        st.wg_first = wg_first;
         st.mv = m;
         list.push_back(st);
-        classes.push_back(kc);
     };
-    const int n_att = c.n_kv_heads * R;  // workgroups busy with attention (persistent kernel)
     for (size_t i = 0; i < stages.size(); ++i) {
         const int l = stages[i].layer;
         const LayerOff &y = L.layers[l];
@@ -499,11 +476,11 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                 m.pf_heads = c.n_kv_heads;
                 m.pf_rows = pos0;
             }
-            push_mv(SWIFT_KC_QKV, EPI_QKV, m, 0);
+            push_mv(SWIFT_KC_QKV, EPI_QKV, m);
 
-            StackStage at{};
-            at.type = ST_ATTN;
-            at.n_units = n_att;
+            Launch at{};
+            at.kc = SWIFT_KC_ATTN;
+            at.epi = -1;
             AttnArgs &a = at.at;
             a.q = qf;
             a.kcache = kv_base(x, l, 0);
@@ -527,7 +504,6 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                 a.spine4 = tree->spine4;
             }
             list.push_back(at);
-            classes.push_back(SWIFT_KC_ATTN);
 
             MvArgs o = base_args(y.wo, H, Q, (H + 15) / 16);
             o.in_s = as_;
@@ -536,16 +512,14 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             o.out_s = xs;
             o.gain_next = gnext;
             o.pss_out = pss;
-            // (persistent kernel: the workgroups that computed the attention sit this one out, so
-            // that their cold start after the attention falls into the stage after it)
-            push_mv(SWIFT_KC_OPROJ, EPI_RESID, o, n_att);
+            push_mv(SWIFT_KC_OPROJ, EPI_RESID, o);
         } else {
             MvArgs m = base_args(y.wgu, 2 * F, H, (F + 7) / 8);
             m.in_s = xs;
             m.pss = pss;
             m.n_pss = n_pss;
             m.out_s = hs;
-            push_mv(SWIFT_KC_GATEUP, EPI_SWIGLU, m, 0);
+            push_mv(SWIFT_KC_GATEUP, EPI_SWIGLU, m);
             MvArgs w = base_args(y.wd, H, F, (H + 15) / 16);
             w.in_s = hs;
             w.out_f32 = xf;
@@ -553,7 +527,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             w.out_s = xs;
             w.gain_next = gnext;
             w.pss_out = pss;
-            push_mv(SWIFT_KC_DOWN, EPI_RESID, w, 0);
+            push_mv(SWIFT_KC_DOWN, EPI_RESID, w);
         }
     }
     if (want_logits) {
@@ -563,7 +537,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.n_pss = n_pss;
         m.out_f32 = dptr<float>(x, L.logits);
         m.ld_out = V;
-        push_mv(SWIFT_KC_LMHEAD, EPI_LOGITS, m, 0);
+        push_mv(SWIFT_KC_LMHEAD, EPI_LOGITS, m);
     }
 
     EmbedRowsArgs ea{};
@@ -579,86 +553,33 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     ea.RL = block_row_layout(R);
     HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
 
-    // ---- one persistent launch where the block qualifies, else one launch per stage
-    const int group = c.n_q_heads / c.n_kv_heads;
-    const int max_T = (std::max(std::max(H, Q), F) + 31) / 32;
-    const size_t stack_lds = stack_lds_bytes(max_T, R, d, group, (int)list.size());
-    const bool use_stack = x->stack_on && !reuse_kv && !tree && x->prof_class < 0 && !list.empty() && R <= 4 && stack_lds <= kStackMaxLds &&
-                           pos0 + R <= 1536 && n_att <= x->n_cu / 2 && (int)list.size() <= L.stack_max_stages &&
-                           (group == 1 || group == 2 || group == 4 || group == 8);
-    if (use_stack) {
-        // find or upload the stage list (pointers and shapes only; the position is a launch argument)
-        int slot = -1;
-        const size_t mask_len = skip ? (size_t)2 * c.n_layers : 0;
-        for (int t = 0; t < kStackTables; ++t) {
-            const StackKey &k = x->stack_keys[t];
-            if (k.valid && k.R == R && k.logits == want_logits && k.mask.size() == mask_len &&
-                (mask_len == 0 || memcmp(k.mask.data(), skip, mask_len) == 0)) {
-                slot = t;
-                break;
-            }
-        }
-        StackStage *tab = nullptr;
-        if (slot < 0) {
-            slot = x->stack_next;
-            x->stack_next = (x->stack_next + 1) % kStackTables;
-            tab = dptr<StackStage>(x, L.stack_tab) + (size_t)slot * L.stack_max_stages;
-            HIP_TRY(hipStreamSynchronize(s));  // an earlier launch may still read this slot
-            HIP_TRY(hipMemcpyAsync(tab, list.data(), list.size() * sizeof(StackStage), hipMemcpyHostToDevice, s));
-            HIP_TRY(hipStreamSynchronize(s));  // `list` goes out of scope
-            StackKey &k = x->stack_keys[slot];
-            k.valid = true;
-            k.R = R;
-            k.logits = want_logits;
-            k.n_stages = (int)list.size();
-            k.mask.assign(skip ? skip : nullptr, skip ? skip + mask_len : nullptr);
-        } else {
-            tab = dptr<StackStage>(x, L.stack_tab) + (size_t)slot * L.stack_max_stages;
-        }
-        StackArgs sa{};
-        sa.stages = tab;
-        sa.n_stages = (int)list.size();
-        sa.pos0 = pos0;
-        sa.R = R;
-        sa.head_dim = d;
-        sa.act_bytes = (int)stack_act_bytes(max_T, R, d, group);
-        sa.barrier = dptr<unsigned>(x, L.stack_sync);
-        sa.barrier_base = x->stack_base;
-        sa.spin_limit = 1 << 20;
-        sa.error = dptr<int>(x, L.stack_sync) + 16;
-        sa.trace = x->stack_trace ? dptr<uint64_t>(x, L.stack_trace) : nullptr;
-        if (x->stack_trace) x->stack_trace_stages = (int)list.size();
-        HIP_TRY(launch_stack(sa, group, stack_lds, x->n_cu, s));
-        x->stack_base += (unsigned)(list.size() - 1) * (unsigned)x->n_cu;
-        x->stack_used = true;
-    } else {
-        for (size_t i = 0; i < list.size(); ++i) {
-            const int kc = classes[i];
-            if (list[i].type == ST_ATTN && attn_block_applies(c.dtype, list[i].at)) {
+    // ---- one launch per stage
+    for (size_t i = 0; i < list.size(); ++i) {
+        const int kc = list[i].kc;
+        if (list[i].epi < 0 && attn_block_applies(c.dtype, list[i].at)) {
+            AttnArgs a = list[i].at;
+            a.out_rows = block_row_layout(R);
+            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
+                          [&] { return launch_attn_block(a, x->n_cu, s); }));
+        } else if (list[i].epi < 0) {
+            // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
+            const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
+            for (int row0 = 0; row0 < R; row0 += per_launch) {
                 AttnArgs a = list[i].at;
+                a.q += (size_t)row0 * Q;
+                a.n_ctx += row0;
+                a.row_base = row0;  // (a tree has at most 16 rows: one part)
+                a.rows = std::min(per_launch, R - row0);
+                a.out_s += 8 * block_terms(block_row_layout(R)) * row0;  // first of this part's term columns
                 a.out_rows = block_row_layout(R);
-                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
-                              [&] { return launch_attn_block(a, x->n_cu, s); }));
-            } else if (list[i].type == ST_ATTN) {
-                // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
-                const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
-                for (int row0 = 0; row0 < R; row0 += per_launch) {
-                    AttnArgs a = list[i].at;
-                    a.q += (size_t)row0 * Q;
-                    a.n_ctx += row0;
-                    a.row_base = row0;  // (a tree has at most 16 rows: one part)
-                    a.rows = std::min(per_launch, R - row0);
-                    a.out_s += 8 * block_terms(block_row_layout(R)) * row0;  // first of this part's term columns
-                    a.out_rows = block_row_layout(R);
-                    HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
-                                  [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
-                }
-            } else {
-                const MvArgs &m = list[i].mv;
-                const int epi = list[i].epi;
-                HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
-                              [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }, true));
+                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
+                              [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
             }
+        } else {
+            const MvArgs &m = list[i].mv;
+            const int epi = list[i].epi;
+            HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2,
+                          [&] { return launch_mv(epi, m, x->n_cu, x->tune_ks[kc], x->tune_wg[kc], s); }, true));
         }
     }
     if (want_logits) {
@@ -687,22 +608,11 @@ int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const ui
 int read_results(swift_ctx *x, int rows) {
     HIP_TRY(hipMemcpyAsync(x->h_tok, dptr<int32_t>(x, x->L.out_tok), rows * 4, hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipMemcpyAsync(x->h_conf, dptr<float>(x, x->L.out_conf), rows * 4, hipMemcpyDeviceToHost, x->stream));
-    if (x->stack_used)
-        HIP_TRY(hipMemcpyAsync(x->h_err, dptr<int>(x, x->L.stack_sync) + 16, 4, hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipStreamSynchronize(x->stream));
-    if (x->stack_used) {
-        x->stack_used = false;
-        if (x->h_err[0] != 0) {
-            // a grid-wide wait of the persistent kernel ran out: its results are invalid and the
-            // barrier counter no longer matches the host's count.  Start over without it.
-            x->h_err[0] = 0;
-            x->stack_on = false;
-            x->stack_base = 0;
-            HIP_TRY(hipMemsetAsync(x->base + x->L.stack_sync, 0, 256, x->stream));
-            HIP_TRY(hipStreamSynchronize(x->stream));
-            return fail(SWIFT_EDEVICE, "persistent kernel: a grid-wide wait ran out; the pass is invalid (persistent path now off)");
-        }
-    }
+    // a token id is fed back as an embedding row index: never pass on one outside the vocabulary
+    for (int i = 0; i < rows; ++i)
+        if (x->h_tok[i] < 0 || x->h_tok[i] >= x->c.vocab)
+            return fail(SWIFT_EDEVICE, "the arg-max kernel returned a token id outside the vocabulary");
     return SWIFT_OK;
 }
 
@@ -806,22 +716,12 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     memset(x->tune_wg, 0, sizeof(x->tune_wg));
     x->h_tok = nullptr;
     x->h_conf = nullptr;
-    x->stack_on = false;
-    x->stack_trace = false;
-    x->stack_trace_stages = 0;
-    x->stack_base = 0;
-    x->stack_next = 0;
-    x->stack_used = false;
-    x->stack_keys.assign(kStackTables, StackKey());
-    x->h_err = nullptr;
     hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxBlockRows + 4 + kTopK) * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
         delete x;
         return fail(SWIFT_EDEVICE, std::string("hipHostMalloc: ") + hipGetErrorString(e));
     }
     x->h_conf = (float *)(x->h_tok + kMaxBlockRows);
-    x->h_err = x->h_tok + 2 * kMaxBlockRows;
-    x->h_err[0] = 0;
     x->h_topk = x->h_tok + 2 * kMaxBlockRows + 4;
 
     // rotary tables: angle = pos * theta^(-2i/d) in fp64, cos/sin rounded to fp32
@@ -836,7 +736,6 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
         }
     }
     e = hipMemsetAsync(x->base + L.mv_counters, 0, 4096 * 4, x->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(x->base + L.stack_sync, 0, 256, x->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.cos, ct.data(), ct.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(x->base + L.sin, stb.data(), stb.size() * 4, hipMemcpyHostToDevice, x->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(x->stream);
@@ -973,6 +872,8 @@ extern "C" int swift_draft_step(swift_ctx *x, const uint8_t *skip_mask, int max_
     if (x->n + max_k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "draft would run past the cache capacity");
     int32_t prev = x->pending;
     int k = 0;
+    x->k_verify = -1;     // the draft overwrites slots an outstanding verification wrote: its accept must fail
+    x->tree_levels = -1;
     x->k_sampled = -1;
     for (int j = 1; j <= max_k; ++j) {
         int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
@@ -1052,6 +953,8 @@ extern "C" int swift_draft_step_topk(swift_ctx *x, const uint8_t *skip_mask, int
     if (x->n + SWIFT_MAX_BLOCK > x->c.max_seq) return fail(SWIFT_ECAPACITY, "a full tree block would run past the cache capacity");
     int32_t prev = x->pending;
     int k = 0, rows = 1;
+    x->k_verify = -1;     // the draft overwrites slots an outstanding verification wrote: its accept must fail
+    x->tree_levels = -1;
     x->k_sampled = -1;
     for (int j = 1; j <= max_k && rows < SWIFT_MAX_BLOCK; ++j) {
         x->want_topk = true;
@@ -1226,6 +1129,8 @@ extern "C" int swift_draft_step_sample(swift_ctx *x, const uint8_t *skip_mask, i
     if (x->n + max_k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "draft would run past the cache capacity");
     int32_t prev = x->pending;
     int k = 0;
+    x->k_verify = -1;     // the draft overwrites slots an outstanding verification wrote: its accept must fail
+    x->tree_levels = -1;
     x->k_sampled = -1;
     for (int j = 1; j <= max_k; ++j) {
         rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
@@ -1328,6 +1233,12 @@ extern "C" int swift_get_state(swift_ctx *x, int *cache_len, int32_t *pending_to
     return SWIFT_OK;
 }
 
+extern "C" int swift_get_config(swift_ctx *x, swift_model_config *out) {
+    if (!x || !out) return fail(SWIFT_EINVAL, "null argument");
+    *out = x->c;
+    return SWIFT_OK;
+}
+
 extern "C" int swift_get_stats(swift_ctx *x, swift_stats *out) {
     if (!x || !out) return fail(SWIFT_EINVAL, "null argument");
     *out = x->st;
@@ -1379,20 +1290,24 @@ extern "C" int swift_debug_read_kv(swift_ctx *x, int layer, int pos, float *k_ou
     return SWIFT_OK;
 }
 
-extern "C" int swift_debug_persistent(swift_ctx *x, int on) {
-    if (!x) return fail(SWIFT_EINVAL, "null context");
-    x->stack_on = on != 0;
-    x->stack_trace = on == 2;
-    return SWIFT_OK;
-}
-
-extern "C" int swift_debug_read_stack_trace(swift_ctx *x, uint64_t *ticks, int capacity, int *n_stages) {
-    if (!x || !ticks || !n_stages) return fail(SWIFT_EINVAL, "null argument");
-    const int n = x->stack_trace_stages;
-    if (capacity < 4 * n) return fail(SWIFT_EINVAL, "capacity < 4 * stages of the last traced launch");
-    HIP_TRY(hipStreamSynchronize(x->stream));
-    if (n > 0) HIP_TRY(hipMemcpy(ticks, x->base + x->L.stack_trace, (size_t)4 * n * 8, hipMemcpyDeviceToHost));
-    *n_stages = n;
+extern "C" int swift_debug_attn_path(swift_ctx *x, int rows, int tree, char *out, int capacity) {
+    if (!x || !out || capacity < 1 || rows < 1 || rows > kMaxBlockRows || (tree && rows > kMaxRows))
+        return fail(SWIFT_EINVAL, "bad argument");
+    const swift_model_config &c = x->c;
+    AttnArgs a{};
+    a.n_ctx = x->n + 1;
+    a.rows = rows;
+    a.max_seq = c.max_seq;
+    a.head_dim = c.head_dim;
+    a.n_q_heads = c.n_q_heads;
+    a.n_kv_heads = c.n_kv_heads;
+    a.max_split = x->L.n_split_max;
+    a.tree = tree ? 1 : 0;
+    a.n_base = x->n;
+    if (x->L.tiled && attn_block_applies(c.dtype, a))
+        snprintf(out, (size_t)capacity, "block<bf16, d %d>", c.head_dim);
+    else
+        attn_path_name(c.dtype, a, x->n_cu, out, capacity);
     return SWIFT_OK;
 }
 

@@ -1,4 +1,4 @@
-// Attention device code shared by the attention kernels and the persistent decoder-stack kernel.
+// Attention device code of the row-at-a-time attention kernels.
 #pragma once
 #include <math.h>
 

@@ -84,6 +84,9 @@ struct AttnArgs {
 // rows per launch.  Depends on the cache capacity and the head count only.
 inline bool attn_uses_head_kernel(int max_seq, int n_kv_heads) { return max_seq <= 1600 && n_kv_heads >= 24; }
 hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_t s);
+// Writes the name of the kernel instance launch_attn_decode would take for `a` (e.g. "split<bf16, group 1,
+// rows 3>") into out; returns the length snprintf reports.  Host only.
+int attn_path_name(int dtype, const AttnArgs &a, int n_cu, char *out, int capacity);
 // Merges the partial results of n_split cache ranges of `chunk` slots, per (row, query head), in range order.
 hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s);
 // Blocks of 17..64 chain rows over a bf16 cache with head_dim 64 or 128: the whole block in one launch on the
@@ -242,52 +245,5 @@ struct EmbedRowsArgs {
     int rp;             // row pitch of pss (16 or 64)
 };
 hipError_t launch_embed_rows(const EmbedRowsArgs &a, hipStream_t s);
-
-// ------------------------------------------------------------------------------------------
-// persistent decoder-stack kernel (tiled bf16 path, blocks of few rows)
-// ------------------------------------------------------------------------------------------
-// One launch runs a list of stages (the projections and attentions of the non-skipped sublayers,
-// then the LM head) on one workgroup of 1024 threads per compute unit.  Stages are separated by a
-// grid-wide barrier on a counter in device memory; every wavefront keeps its window of weight-tile
-// loads rolling across stage boundaries, so the weight stream does not stop while the barrier and
-// the staging of the next activation take place.
-enum StackStageType : int { ST_MV = 0, ST_ATTN = 1 };
-struct StackStage {
-    int type;      // StackStageType
-    int epi;       // ST_MV: Epilogue
-    int wg_first;  // ST_MV: workgroups [wg_first, grid) share the row groups (round-robin)
-    int n_units;   // ST_ATTN: (kv head, row) pairs; workgroup u < n_units takes pair (u % n_kv, u / n_kv)
-    MvArgs mv;     // ST_MV (pos0 is replaced by StackArgs::pos0; part/counters/S unused)
-    AttnArgs at;   // ST_ATTN (n_ctx is replaced by StackArgs::pos0 + 1; partial buffers unused)
-};
-struct StackArgs {
-    const StackStage *stages;  // device memory
-    int n_stages;
-    int pos0;                  // position of block row 0
-    int R, head_dim;           // rows of the block (the same in every stage), head dimension
-    int act_bytes;             // LDS bytes of the activation area (stack_act_bytes)
-    unsigned *barrier;         // arrival counter; keeps counting over the launches of a context
-    unsigned barrier_base;     // its value when this launch starts
-    int spin_limit;            // polls of one wait before a workgroup gives up
-    int *error;                // set to 1 by a workgroup that gave up (the results are then invalid)
-    uint64_t *trace;           // nullptr, or [2 workgroups (first, last)][n_stages][2]: 100 MHz clock after the
-                               // stage's grid-wide wait and at the end of the workgroup's share of the stage
-};
-constexpr int kStackThreads = 1024;
-constexpr size_t kStackMaxLds = 158 * 1024;
-// LDS bytes of the activation area / of the whole workgroup for stages whose deepest matrix has
-// max_T k-tiles, R rows
-inline size_t stack_act_bytes(int max_T, int R, int head_dim, int group) {
-    const size_t act = (size_t)max_T * 64 * 3 * (size_t)R;
-    const size_t att = (size_t)(32 * group + 16 * group * head_dim) * 4;
-    return act > att ? act : att;
-}
-inline size_t stack_lds_bytes(int max_T, int R, int head_dim, int group, int n_stages) {
-    const size_t NC = 3 * (size_t)R;
-    return 16 + stack_act_bytes(max_T, R, head_dim, group) + 2 * 16 * 16 * NC * 4 + 64 + 4096 +
-           (size_t)R * head_dim * 4 + 16 + (size_t)n_stages * 32;
-}
-// group = query heads per kv head (1, 2, 4, 8); n_wg = workgroups = compute units of the device
-hipError_t launch_stack(const StackArgs &a, int group, size_t lds, int n_wg, hipStream_t s);
 
 }  // namespace swift

@@ -11,6 +11,7 @@
 #include "swift_attn.h"
 
 #include <math.h>
+#include <stdio.h>
 
 #include "swift_device.h"
 
@@ -387,85 +388,104 @@ static hipError_t launch_attn_head_tt(const AttnArgs &a, hipStream_t s) {
                        dim3(64 * kAttnHeadWaves), lds, s, a);
     return hipGetLastError();
 }
-template <typename T, int GROUP>
-static hipError_t launch_attn_head_t(const AttnArgs &a, int n_cu, hipStream_t s) {
-    if (a.tree) return launch_attn_head_tt<T, GROUP, true, 1>(a, s);
-    // Blocks with more (head, row) pairs than compute units: two rows share every key/value load where the
-    // registers allow it, so that a compute unit does not read a head's cache twice (7B, 9 rows: 19 -> 15 us
-    // per layer; with fewer pairs the one-row workgroups are faster: 13 against 15.5 us at 4 rows).
-    if constexpr (GROUP == 1) {
-        if (a.rows * a.n_kv_heads > n_cu) return launch_attn_head_tt<T, GROUP, false, 2>(a, s);
+// Which attention kernel instance a launch takes.  Which kernel runs, and where the cache range is cut,
+// depends on the cache capacity and the head count only, never on the current length; the number of block
+// rows only decides how many rows share a workgroup's key/value loads, which changes no row's result.
+struct AttnPlan {
+    bool head;     // one workgroup per (kv head, row block) over the whole range; else split over the cache length
+    int group;     // query heads per kv head
+    int rb;        // block rows that share a workgroup's loads
+    int chunk;     // split kernel: cache slots per workgroup
+    int n_split;   // split kernel: ranges the longest row reaches
+};
+template <typename T>
+static AttnPlan attn_plan(const AttnArgs &a, int n_cu) {
+    AttnPlan p{};
+    p.group = a.n_q_heads / a.n_kv_heads;
+    // The one-workgroup-per-head kernel needs enough kv heads to occupy the chip with a single row.
+    p.head = attn_uses_head_kernel(a.max_seq, a.n_kv_heads);
+    if (p.head) {
+        // Blocks with more (head, row) pairs than compute units: two rows share every key/value load where the
+        // registers allow it, so that a compute unit does not read a head's cache twice (7B, 9 rows: 19 -> 15 us
+        // per layer; with fewer pairs the one-row workgroups are faster: 13 against 15.5 us at 4 rows).
+        p.rb = (!a.tree && p.group == 1 && a.rows * a.n_kv_heads > n_cu) ? 2 : 1;
+        return p;
     }
-    return launch_attn_head_tt<T, GROUP, false, 1>(a, s);
+    // longest row of the block (a tree: an upper bound; workgroups beyond a row's range leave at once)
+    const int ctx = a.tree ? a.n_base + a.row_base + a.rows : a.n_ctx + a.rows - 1;
+    const int d = a.head_dim, VEC = T::VEC, SPW = 64 / (d / VEC);
+    const int gran = 4 * SPW;  // slots one workgroup step covers
+    // chunk length: a full cache cut into enough pieces for about two workgroups per compute unit with one row
+    int want = (2 * n_cu + a.n_kv_heads - 1) / a.n_kv_heads;
+    if (want > a.max_split) want = a.max_split;
+    if (want < 1) want = 1;
+    p.chunk = (a.max_seq + want - 1) / want;
+    p.chunk = (p.chunk + gran - 1) / gran * gran;
+    p.n_split = (ctx + p.chunk - 1) / p.chunk;  // <= want <= max_split
+    // Block rows that share their key/value loads in one workgroup (the more, the less cache traffic; bounded
+    // by registers: members = heads per kv head x rows).  One to three rows take the instance with as many
+    // members: the same arithmetic per row without the idle members' share of the vector arithmetic.
+    if (a.tree)
+        p.rb = 1;
+    else if (p.group == 1)
+        p.rb = a.rows < 4 ? a.rows : 4;
+    else if (p.group == 2)
+        p.rb = a.rows == 1 ? 1 : 2;
+    else
+        p.rb = 1;
+    return p;
 }
 
 template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
-    const int group = a.n_q_heads / a.n_kv_heads;
-    // longest row of the block (a tree: an upper bound; workgroups beyond a row's range leave at once)
-    const int ctx = a.tree ? a.n_base + a.row_base + a.rows : a.n_ctx + a.rows - 1;
     if (a.tree && (a.row_base < 0 || a.row_base + a.rows > 16)) return hipErrorInvalidValue;
-    // Which kernel runs, and where the cache range is cut, depends on the cache capacity and the head
-    // count only, never on the rows of the block or the current length: a row's result is then the
-    // same bit for bit whether it is computed alone or inside a block.
-    // The one-workgroup-per-head kernel needs enough kv heads to occupy the chip with a single row.
-    if (attn_uses_head_kernel(a.max_seq, a.n_kv_heads)) {
-        switch (group) {
-            case 1: return launch_attn_head_t<T, 1>(a, n_cu, s);
-            case 2: return launch_attn_head_t<T, 2>(a, n_cu, s);
-            case 4: return launch_attn_head_t<T, 4>(a, n_cu, s);
-            case 8: return launch_attn_head_t<T, 8>(a, n_cu, s);
+    const AttnPlan p = attn_plan<T>(a, n_cu);
+    if (p.head) {
+#define SWIFT_HEAD_CASE(G)                                                            \
+    case G:                                                                           \
+        if (a.tree) return launch_attn_head_tt<T, G, true, 1>(a, s);                  \
+        if (G == 1 && p.rb == 2) return launch_attn_head_tt<T, 1, false, 2>(a, s);    \
+        return launch_attn_head_tt<T, G, false, 1>(a, s);
+        switch (p.group) {
+            SWIFT_HEAD_CASE(1)
+            SWIFT_HEAD_CASE(2)
+            SWIFT_HEAD_CASE(4)
+            SWIFT_HEAD_CASE(8)
             default: return hipErrorInvalidValue;
         }
+#undef SWIFT_HEAD_CASE
     }
-    const int d = a.head_dim, VEC = T::VEC, SPW = 64 / (d / VEC);
-    const int gran = 4 * SPW;                      // slots one workgroup step covers
-    // chunk length: a full cache cut into enough pieces for about two workgroups per compute unit
-    // with one row
-    int want = (2 * n_cu + a.n_kv_heads - 1) / a.n_kv_heads;
-    if (want > a.max_split) want = a.max_split;
-    if (want < 1) want = 1;
-    int chunk = (a.max_seq + want - 1) / want;
-    chunk = (chunk + gran - 1) / gran * gran;
-    const int n_split = (ctx + chunk - 1) / chunk;  // <= want <= max_split
-    // block rows that share their key/value loads in one workgroup (the more, the less cache traffic;
-    // bounded by registers: members = heads per kv head x rows)
-    // (one to three rows take the instance with as many members: the same arithmetic per row -- a row's result
-    // does not depend on the rows that share its workgroup -- without the idle members' share of the vector
-    // arithmetic)
-    const bool one_row = !a.tree && a.rows == 1 && group <= 2;
-    const bool two_rows = !a.tree && a.rows == 2 && group == 1;
-    const bool three_rows = !a.tree && a.rows == 3 && group == 1;
-    const int rb = a.tree || one_row ? 1 : two_rows ? 2 : three_rows ? 3 : group == 1 ? 4 : group == 2 ? 2 : 1;
-    dim3 grid(a.n_kv_heads, n_split, (a.rows + rb - 1) / rb), block(256);
-    if (a.tree) switch (group) {
-        case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 1, true>), grid, block, 0, s, a, chunk); break;
-        case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 1, true>), grid, block, 0, s, a, chunk); break;
-        case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1, true>), grid, block, 0, s, a, chunk); break;
-        case 8: hipLaunchKernelGGL((k_attn_split<T, 8, 1, true>), grid, block, 0, s, a, chunk); break;
+    const int chunk = p.chunk, n_split = p.n_split;
+    dim3 grid(a.n_kv_heads, n_split, (a.rows + p.rb - 1) / p.rb), block(256);
+#define SWIFT_SPLIT(G, RB, TREE) hipLaunchKernelGGL((k_attn_split<T, G, RB, TREE>), grid, block, 0, s, a, chunk)
+    const int key = p.group * 100 + p.rb * 10 + (a.tree ? 1 : 0);
+    switch (key) {
+        case 111: SWIFT_SPLIT(1, 1, true); break;
+        case 211: SWIFT_SPLIT(2, 1, true); break;
+        case 411: SWIFT_SPLIT(4, 1, true); break;
+        case 811: SWIFT_SPLIT(8, 1, true); break;
+        case 110: SWIFT_SPLIT(1, 1, false); break;
+        case 120: SWIFT_SPLIT(1, 2, false); break;
+        case 130: SWIFT_SPLIT(1, 3, false); break;
+        case 140: SWIFT_SPLIT(1, 4, false); break;
+        case 210: SWIFT_SPLIT(2, 1, false); break;
+        case 220: SWIFT_SPLIT(2, 2, false); break;
+        case 410: SWIFT_SPLIT(4, 1, false); break;
+        case 810: SWIFT_SPLIT(8, 1, false); break;
         default: return hipErrorInvalidValue;
     }
-    else if (one_row) {
-        if (group == 1)
-            hipLaunchKernelGGL((k_attn_split<T, 1, 1>), grid, block, 0, s, a, chunk);
-        else
-            hipLaunchKernelGGL((k_attn_split<T, 2, 1>), grid, block, 0, s, a, chunk);
-    } else if (two_rows) {
-        hipLaunchKernelGGL((k_attn_split<T, 1, 2>), grid, block, 0, s, a, chunk);
-    } else if (three_rows) {
-        hipLaunchKernelGGL((k_attn_split<T, 1, 3>), grid, block, 0, s, a, chunk);
-    } else switch (group) {
-        case 1: hipLaunchKernelGGL((k_attn_split<T, 1, 4>), grid, block, 0, s, a, chunk); break;
-        case 2: hipLaunchKernelGGL((k_attn_split<T, 2, 2>), grid, block, 0, s, a, chunk); break;
-        case 4: hipLaunchKernelGGL((k_attn_split<T, 4, 1>), grid, block, 0, s, a, chunk); break;
-        case 8: hipLaunchKernelGGL((k_attn_split<T, 8, 1>), grid, block, 0, s, a, chunk); break;
-        default: return hipErrorInvalidValue;
-    }
+#undef SWIFT_SPLIT
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_split == 1) return e;
     hipLaunchKernelGGL(k_attn_combine, dim3(a.n_q_heads, a.rows), dim3(a.head_dim < 64 ? 64 : a.head_dim), 0, s, a, chunk,
                        n_split);
     return hipGetLastError();
+}
+
+int attn_path_name(int dtype, const AttnArgs &a, int n_cu, char *out, int capacity) {
+    const AttnPlan p = dtype == F32 ? attn_plan<F32T>(a, n_cu) : attn_plan<BF16T>(a, n_cu);
+    return snprintf(out, (size_t)capacity, "%s<%s, group %d, rows %d%s>", p.head ? "head" : "split",
+                    dtype == F32 ? "f32" : "bf16", p.group, p.rb, a.tree ? ", tree" : "");
 }
 
 hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s) {
@@ -536,6 +556,9 @@ __global__ __launch_bounds__(1024) void k_argmax_conf(ArgmaxArgs a) {
             best = smax[w];
             bi = sidx[w];
         }
+    // nothing compared greater than -inf (a row of NaN or -inf only): token 0, like a scan that starts
+    // from index 0 and moves on strict improvement only
+    if (bi == 0x7fffffff) bi = 0;
     float sum = 0.f;
     if (in_regs) {
 #pragma unroll

@@ -1,4 +1,4 @@
-// Epilogue of the tiled projection kernels, shared with the persistent decoder-stack kernel.
+// Epilogue of the tiled projection kernels.
 #pragma once
 #include <math.h>
 

@@ -113,6 +113,9 @@ extern "C" int swift_opt_step(swift_ctx *ctx, swift_opt *o, const int32_t *windo
     if (!ctx || !o || !window) return SWIFT_EINVAL;
     if (o->finished) return SWIFT_ESTATE;
     const int n = o->c.n_sublayers;
+    // the candidate is indexed as a skip mask of the context's model: one entry per sublayer
+    swift_model_config mc;
+    if (swift_get_config(ctx, &mc) != SWIFT_OK || n != 2 * mc.n_layers) return SWIFT_EINVAL;
     std::vector<uint8_t> cand((size_t)n, 0);
     const int step = o->step + 1;
     bool have = false;
@@ -126,7 +129,7 @@ extern "C" int swift_opt_step(swift_ctx *ctx, swift_opt *o, const int32_t *windo
     if (!have) random_candidate(o, step, cand.data());
     int n_match = 0;
     const int rc = swift_eval_mask(ctx, cand.data(), window, gamma, nullptr, &n_match);
-    if (rc != SWIFT_OK) return rc;  // (also catches a mask length that does not fit the model)
+    if (rc != SWIFT_OK) return rc;
     o->step = step;
     const double score = (double)n_match / (double)gamma;
     if (score > o->best_score) {

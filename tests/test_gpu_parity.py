@@ -462,7 +462,7 @@ def test_dynamic_verification_against_oracle(oracle_lib, case):
     g.close()
 
 
-@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers"])
+@pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers", "d128-mha"])
 def test_tree_rows_equal_chain_rows_bit_for_bit(case):
     """A row of a token tree gives, bit for bit, the logits the same path gives when it is verified as a
     chain (which in turn equal those of one-token-at-a-time decoding): dynamic verification then cannot
@@ -565,6 +565,15 @@ def test_errors_and_state_machine_on_device(oracle_lib):
         g.verify([t] * 14)
     assert e.value.code == -2
     assert g.cache_len == n0 and g.pending == t     # state untouched by failed calls
+    # a draft step after a verification that was not accepted cancels it (its slots are overwritten)
+    g.verify([g.pending])
+    g.draft_step(np.ones(2 * shape.n_layers, np.uint8), 2, 0.0)
+    with pytest.raises(P.SwiftError) as e:
+        g.accept()
+    assert e.value.code == -3
+    assert g.cache_len == n0 and g.pending == t
+    with pytest.raises(ValueError):
+        g.draft_step(np.zeros(3, np.uint8), 1, 0.5)            # a mask of the wrong length never reaches the library
     # explicit roll-back: decode two tokens, rewind, decode them again
     a1, _ = g.verify([g.pending]); g.accept()
     a2, _ = g.verify([g.pending]); g.accept()
@@ -681,6 +690,53 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     g.close()
 
 
+_WIDTHS = {"13b": si.LLAMA2_13B, "70b": si.LLAMA2_70B}
+
+
+@pytest.mark.parametrize("width", ["13b", "70b"])
+@pytest.mark.parametrize("scenario", ["short-cache", "long-cache"])
+def test_other_widths_narrow_depth_against_oracle(oracle_lib, width, scenario):
+    """The 13B and the 70B (64 query heads on 8 kv heads) workloads' widths, heads, FFN, vocabulary and dtype,
+    two layers deep, against the oracle step by step (Section 4.2, Eq. 5): drafts, stop decisions, verify
+    targets exact -- a differing token must be a near tie of the oracle's own logits -- and every verify row's
+    logits within the bf16 tolerance.  short-cache: 12-token prompt, drafts of up to 3 tokens, the attention
+    sublayer of layer 1 and the MLP of layer 0 skipped.  long-cache: a cache capacity beyond the short-context
+    attention kernel's, a 70-token prompt (a 64-row prefill block and a tail), drafts of up to 12 tokens
+    (13-row verify blocks), both sublayers of layer 0 skipped."""
+    import paper_2410_06916_amd as P
+    shape = _WIDTHS[width].with_layers(2)
+    if scenario == "short-cache":
+        max_seq, n_prompt, n_new, mask, max_k = 48, 12, 10, np.array([0, 1, 1, 0], np.uint8), 3
+    else:
+        max_seq, n_prompt, n_new, mask, max_k = 1700, 70, 15, np.array([1, 1, 0, 0], np.uint8), 12
+    g = P.SwiftModel(shape, max_seq)
+    o = oracle_lib.Oracle(shape, max_seq, threads=16)
+    for name, t in _gpu_weights(shape, 0):
+        g.load_tensor(name, t)
+        o.set_tensor(name, t.cpu())
+    prompt = si.uniform_ids(1, n_prompt, shape.vocab)
+    res = hp.lockstep_swift(o, g, prompt, n_new, mask, max_k, 0.0, TOL["bf16"])
+    assert len(res["tokens"]) == n_new and res["rows_checked"] >= n_new
+    # with forced-length drafts the verify blocks really had max_k + 1 rows
+    assert res["max_rows"] == max_k + 1
+    assert sum(res["ties"].values()) <= 2, res["ties"]
+    g.close()
+    o.close()
+
+
+# attention kernel instance per block size that each case of the bit-for-bit test is meant to reach
+_EXPECTED_ATTN_PATHS = {
+    "small-gqa-bf16": {1: "split<bf16, group 2, rows 1>", 2: "split<bf16, group 2, rows 2>",
+                       16: "split<bf16, group 2, rows 2>"},
+    "small-gqa-bf16-long-cache": {1: "split<bf16, group 2, rows 1>", 9: "split<bf16, group 2, rows 2>"},
+    "7b-width-2-layers": {1: "head<bf16, group 1, rows 1>", 5: "head<bf16, group 1, rows 1>",
+                          9: "head<bf16, group 1, rows 2>", 16: "head<bf16, group 1, rows 2>"},
+    "d128-mha": {1: "split<bf16, group 1, rows 1>", 2: "split<bf16, group 1, rows 2>",
+                 3: "split<bf16, group 1, rows 3>", 5: "split<bf16, group 1, rows 4>",
+                 16: "split<bf16, group 1, rows 4>"},
+}
+
+
 @pytest.mark.parametrize("case", ["small-gqa-bf16", "small-gqa-bf16-long-cache", "7b-width-2-layers", "d128-mha"])
 def test_block_rows_equal_single_rows_bit_for_bit(case):
     """What makes speculative output equal plain greedy output exactly rather than up to rounding
@@ -691,11 +747,19 @@ def test_block_rows_equal_single_rows_bit_for_bit(case):
     import paper_2410_06916_amd as P
     if case == "7b-width-2-layers":
         shape, weights, max_seq, n_prompt = si.LLAMA2_7B.with_layers(2), None, 64, 20
+    elif case == "d128-mha":
+        # heads of 128, one kv head per query head, a cache beyond the short-context kernel's capacity
+        shape = BLOCK_ATTN_SHAPES[case]
+        weights, max_seq, n_prompt = hp.shaped_weights(shape, seed=3), 1700, 70
     else:
         shape = hp.SMALL_GQA_BF16
         weights = hp.shaped_weights(shape, seed=3)
         max_seq, n_prompt = (1700, 70) if case.endswith("long-cache") else (96, 12)
     g = P.SwiftModel(shape, max_seq)
+    # the attention kernel each block size takes is the one the case is meant to cover
+    want_path = _EXPECTED_ATTN_PATHS[case]
+    for R, name in want_path.items():
+        assert g.attn_path(R) == name, (case, R, g.attn_path(R))
     if weights is None:
         for nm, t in _gpu_weights(shape, 0):
             g.load_tensor(nm, t)
@@ -715,38 +779,6 @@ def test_block_rows_equal_single_rows_bit_for_bit(case):
         assert [int(x) for x in tgt] == toks[1:R + 1]
         for r in range(R):
             assert np.array_equal(lg[r], rows[r]), (case, R, r, np.abs(lg[r] - rows[r]).max())
-    g.close()
-
-
-@pytest.mark.parametrize("case", ["small-gqa-bf16", "7b-width-2-layers"])
-def test_persistent_stack_kernel_matches_oracle(oracle_lib, case):
-    """The opt-in one-launch-per-pass path (grid-wide barriers between stages, bounded polling):
-    same tokens, drafts, acceptance and logits as the oracle, for skip masks that remove whole
-    attention / MLP stages, blocks of 1-4 rows, and GQA."""
-    import paper_2410_06916_amd as P
-    if case == "small-gqa-bf16":
-        shape = hp.SMALL_GQA_BF16
-        weights = hp.shaped_weights(shape, seed=21)
-        max_seq, n_prompt, n_new, threads = 96, 12, 40, 1
-        rng = np.random.default_rng(9)
-        L2 = 2 * shape.n_layers
-        masks = [np.zeros(L2, np.uint8), np.ones(L2, np.uint8), (rng.random(L2) < 0.5).astype(np.uint8)]
-        settings = ((3, 0.0), (3, 0.5), (1, 2.0))
-    else:
-        shape = si.LLAMA2_7B.with_layers(2)
-        weights = si.make_weights(shape, 0)
-        max_seq, n_prompt, n_new, threads = 48, 12, 10, 8
-        masks = [np.array([0, 1, 1, 0], np.uint8)]
-        settings = ((3, 0.0),)
-    o, g = _pair(oracle_lib, shape, weights, max_seq, threads=threads)
-    g.persistent(True)
-    prompt = si.uniform_ids(11, n_prompt, shape.vocab)
-    for mask in masks:
-        for max_k, eps in settings:
-            want, to = oracle_lib.generate_swift(o, prompt, n_new, mask, max_k, eps, want_logits=True)
-            got, tg = P.generate_swift(g, prompt, n_new, mask, max_k, eps, want_logits=True)
-            assert np.array_equal(got, want), (case, max_k, eps)
-            _compare_traces(shape, to, tg)
     g.close()
 
 

@@ -73,6 +73,18 @@ def test_argmax_decided_in_fp32(oracle_lib):
     assert oracle_lib.argmax_conf(lg)[0] == 2
 
 
+def test_argmax_of_a_row_without_a_maximum_is_token_zero(oracle_lib):
+    """A row of NaN or of -inf only has no element that compares greater than another: the scan that starts at
+    index 0 and moves on strict improvement stays at 0 (the rule the library's kernel follows too, so that
+    no out-of-range id is ever fed back as an embedding index)."""
+    assert oracle_lib.argmax_conf(np.full(40, np.nan))[0] == 0
+    assert oracle_lib.argmax_conf(np.full(40, -np.inf))[0] == 0
+    lg = np.full(40, np.nan)
+    lg[0] = -np.inf
+    lg[5] = -3.0            # the first element that compares greater than index 0's wins
+    assert oracle_lib.argmax_conf(lg)[0] == 5
+
+
 # ---------------------------------------------------------------- RMSNorm
 def test_rmsnorm_properties(oracle_lib):
     rng = np.random.default_rng(1)
