@@ -213,6 +213,22 @@ int swift_opt_step(swift_ctx *ctx, swift_opt *opt, const int32_t *window, int ga
  * Needs 0 <= k <= SWIFT_MAX_BLOCK - 1 and n + k + 1 <= max_seq. */
 int swift_verify(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out);
 
+/* swift_verify for callers that must not allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels and the same results bit for bit, but their scratch
+ * memory (arrival counters and partial sums of projections that split K over workgroups, partial results
+ * of attention split over the cache length) lies in a device array of SWIFT_STATIC_SCRATCH_BYTES that is
+ * part of the library's code object instead of in the context's arena.  The call allocates and frees
+ * nothing, on the device or the pinned host side, and creates no events (per-class timing is off
+ * during it).  Every GPU the library runs on holds that array from the first use until the process ends.
+ * A block whose partial results do not fit (many query heads times many block rows times many cache
+ * ranges: e.g. more than 7 rows of a 64-head model with a cache of thousands of slots) is refused with
+ * SWIFT_ECAPACITY and a message that says so, before anything is launched; swift_verify takes it.
+ * All contexts of a process share one array per GPU, and it keeps the last call's contents: calls that
+ * overlap on one GPU (two streams, two threads) race; one call at a time per GPU.
+ * State changes, errors and the following swift_accept are exactly those of swift_verify. */
+#define SWIFT_STATIC_SCRATCH_BYTES (24u << 20)
+int swift_verify_static(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out);
+
 /* Acceptance + roll-back after a swift_verify: m = swift_match_prefix(tokens[1..k], targets);
  * emitted (host, capacity >= k+1) receives the m accepted draft tokens followed by the target's own
  * token; *n_emitted = m + 1; the cache length becomes n + m + 1 and the last emitted token becomes

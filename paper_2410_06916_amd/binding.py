@@ -75,6 +75,7 @@ def lib():
     L.swift_prefill.argtypes = [vp, i32p, C.c_int, i32p]
     L.swift_draft_step.argtypes = [vp, u8p, C.c_int, C.c_float, i32p, f32p, C.POINTER(C.c_int)]
     L.swift_verify.argtypes = [vp, i32p, C.c_int, i32p, f32p]
+    L.swift_verify_static.argtypes = [vp, i32p, C.c_int, i32p, f32p]
     L.swift_eval_mask.argtypes = [vp, u8p, i32p, C.c_int, i32p, C.POINTER(C.c_int)]
     L.swift_opt_create.argtypes = [C.POINTER(OptConfig), u8p, C.POINTER(vp)]
     L.swift_opt_destroy.argtypes = [vp]
@@ -235,6 +236,16 @@ class SwiftModel:
         lg = np.empty((k + 1, self.cfg.vocab), np.float32) if want_logits else None
         _chk(lib().swift_verify(self._h, _p(t, C.c_int32), k, _p(tgt, C.c_int32),
                                 _p(lg, C.c_float) if want_logits else None), "swift_verify")
+        return tgt, lg
+
+    def verify_static(self, tokens: Sequence[int], want_logits: bool = False):
+        """swift_verify_static: verification whose kernels' scratch lies in the library's static device array."""
+        t = np.ascontiguousarray(tokens, np.int32)
+        k = t.size - 1
+        tgt = np.zeros(k + 1, np.int32)
+        lg = np.empty((k + 1, self.cfg.vocab), np.float32) if want_logits else None
+        _chk(lib().swift_verify_static(self._h, _p(t, C.c_int32), k, _p(tgt, C.c_int32),
+                                       _p(lg, C.c_float) if want_logits else None), "swift_verify_static")
         return tgt, lg
 
     def accept(self) -> np.ndarray:

@@ -198,8 +198,48 @@ extern "C" int swift_pass_bytes(const swift_model_config *cfg, const uint8_t *sk
 }
 
 // ------------------------------------------------------------------------------------------
+// static scratch of the allocation-free entry point (swift_verify_static)
+// ------------------------------------------------------------------------------------------
+// Layout of the array: [arrival counters][split-K partial sums][attention partials: part_ml | part_o].
+constexpr size_t kStaticCounterBytes = 4096 * 4;
+constexpr int kStaticPartSlots = 8192;  // row-group-splits of kMaxRows rows, as the arena's area holds for such blocks
+constexpr size_t kStaticPartBytes = (size_t)kStaticPartSlots * 16 * kMaxRows * 4;            // 8 MiB
+constexpr size_t kStaticAttnBytes = SWIFT_STATIC_SCRATCH_BYTES - kStaticCounterBytes - kStaticPartBytes;
+static __device__ __align__(256) unsigned char scratch[SWIFT_STATIC_SCRATCH_BYTES];
+// The array's address on each device (every GPU holds its own copy at its own address); set once per device.
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+
+namespace {
+// Resolves the array's device address for the current device (first call on a device only).
+int static_scratch(char **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SWIFT_EDEVICE, "device ordinal out of range");
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SWIFT_EDEVICE, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (char *)g_scratch_ptr[dev];
+    return SWIFT_OK;
+}
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------
+// Device memory the kernels use beyond their inputs and outputs: split-K partial sums and arrival
+// counters of the block projection kernel, partial results of attention split over the cache length.
+struct Scratch {
+    float *mv_part;
+    int *mv_counters;
+    int mv_part_capacity;  // row-group-splits mv_part holds for a block of kMaxBlockRows rows (arena) / kMaxRows rows (static)
+    float *part_o, *part_ml;
+    size_t part_o_floats;  // capacity of part_o (part_ml holds 2 floats per head_dim floats of part_o)
+};
+
 struct ProfRec {
     hipEvent_t a, b;
     uint64_t bytes;
@@ -211,6 +251,9 @@ struct swift_ctx {
     char *base;
     hipStream_t stream;
     int n_cu;
+    Scratch arena_scr;  // the scratch buffers inside the arena
+    Scratch scr;        // the ones the kernels of the current call use
+    bool no_events;     // the current call must not create HIP events (allocation-free entry point)
     std::vector<bool> loaded;  // per tensor slot
     int n_loaded;
     // pinned host staging for results
@@ -249,7 +292,7 @@ int n_tensors(const swift_model_config &c) { return 3 + 9 * c.n_layers; }
 // itself; otherwise the launch is bracketed by two event records on the stream.
 template <typename F>
 hipError_t timed(swift_ctx *x, int kc, uint64_t bytes, F &&f, bool kernel_events = false) {
-    if (x->prof_class != kc) return f();
+    if (x->prof_class != kc || x->no_events) return f();
     hipEvent_t ev[2];
     for (auto &e : ev) {
         if (!x->pool.empty()) {
@@ -351,8 +394,8 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
             a.head_dim = d;
             a.n_q_heads = c.n_q_heads;
             a.n_kv_heads = c.n_kv_heads;
-            a.part_o = dptr<float>(x, L.part_o);
-            a.part_ml = dptr<float>(x, L.part_ml);
+            a.part_o = x->scr.part_o;
+            a.part_ml = x->scr.part_ml;
             a.max_split = L.n_split_max;
             a.out = ar;
             a.out_s = nullptr;
@@ -430,9 +473,9 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.n_kv_heads = c.n_kv_heads;
         m.cos_tab = dptr<float>(x, L.cos);
         m.sin_tab = dptr<float>(x, L.sin);
-        m.part = dptr<float>(x, L.mv_part);
-        m.counters = dptr<int>(x, L.mv_counters);
-        m.part_capacity = L.mv_part_capacity;
+        m.part = x->scr.mv_part;
+        m.counters = x->scr.mv_counters;
+        m.part_capacity = L.mv_part_capacity;  // (decides the K split, hence the summation order: one value everywhere)
         return m;
     };
     // ---- the pass as a list of launches
@@ -491,8 +534,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.head_dim = d;
             a.n_q_heads = c.n_q_heads;
             a.n_kv_heads = c.n_kv_heads;
-            a.part_o = dptr<float>(x, L.part_o);
-            a.part_ml = dptr<float>(x, L.part_ml);
+            a.part_o = x->scr.part_o;
+            a.part_ml = x->scr.part_ml;
             a.max_split = L.n_split_max;
             a.out = nullptr;
             a.out_s = as_;
@@ -695,6 +738,11 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     int dev = 0, n_cu = 0;
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    // the static scratch array's address on this device (needed by swift_verify_static only; resolved here
+    // so that that call has nothing left to set up)
+    char *static_base = nullptr;
+    rc = static_scratch(&static_base);
+    if (rc) return rc;
     swift_ctx *x = new swift_ctx();
     x->c = *cfg;
     x->L = L;
@@ -711,6 +759,10 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->want_topk = false;
     x->h_topk = nullptr;
     memset(&x->st, 0, sizeof(x->st));
+    x->arena_scr = Scratch{dptr<float>(x, L.mv_part), dptr<int>(x, L.mv_counters), L.mv_part_capacity, dptr<float>(x, L.part_o),
+                           dptr<float>(x, L.part_ml), (size_t)kMaxRows * cfg->n_q_heads * L.n_split_max * cfg->head_dim};
+    x->scr = x->arena_scr;
+    x->no_events = false;
     x->prof_class = -1;
     memset(x->tune_ks, 0, sizeof(x->tune_ks));
     memset(x->tune_wg, 0, sizeof(x->tune_wg));
@@ -891,14 +943,8 @@ extern "C" int swift_draft_step(swift_ctx *x, const uint8_t *skip_mask, int max_
     return SWIFT_OK;
 }
 
-extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out) {
-    if (!x || !tokens || !target_tokens) return fail(SWIFT_EINVAL, "null argument");
-    if (k < 0 || k > SWIFT_MAX_BLOCK - 1) return fail(SWIFT_EINVAL, "k out of range");
-    if (x->pending < 0) return fail(SWIFT_ESTATE, "verify before prefill");
-    if (tokens[0] != x->pending) return fail(SWIFT_EINVAL, "tokens[0] must be the pending token");
-    for (int i = 0; i <= k; ++i)
-        if (tokens[i] < 0 || tokens[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
-    if (x->n + k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
+namespace {
+int verify_impl(swift_ctx *x, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out) {
     int rc = forward_block(x, tokens, k + 1, x->n, nullptr, true);
     if (rc) return rc;
     rc = read_results(x, k + 1);
@@ -918,6 +964,93 @@ extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t 
     x->k_sampled = -1;
     x->st.verify_passes++;
     return SWIFT_OK;
+}
+
+int check_verify_args(swift_ctx *x, const int32_t *tokens, int k, int32_t *target_tokens) {
+    if (!x || !tokens || !target_tokens) return fail(SWIFT_EINVAL, "null argument");
+    if (k < 0 || k > SWIFT_MAX_BLOCK - 1) return fail(SWIFT_EINVAL, "k out of range");
+    if (x->pending < 0) return fail(SWIFT_ESTATE, "verify before prefill");
+    if (tokens[0] != x->pending) return fail(SWIFT_EINVAL, "tokens[0] must be the pending token");
+    for (int i = 0; i <= k; ++i)
+        if (tokens[i] < 0 || tokens[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
+    if (x->n + k + 1 > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
+    return SWIFT_OK;
+}
+}  // namespace
+
+extern "C" int swift_verify(swift_ctx *x, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out) {
+    int rc = check_verify_args(x, tokens, k, target_tokens);
+    if (rc) return rc;
+    return verify_impl(x, tokens, k, target_tokens, logits_out);
+}
+
+// ------------------------------------------------------------------------------------------
+// verification without any allocation: the kernels' scratch in a file-scope device array
+// ------------------------------------------------------------------------------------------
+extern "C" int swift_verify_static(swift_ctx *x, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out) {
+    int rc = check_verify_args(x, tokens, k, target_tokens);
+    if (rc) return rc;
+    const swift_model_config &c = x->c;
+    const int R = k + 1, d = c.head_dim, H = c.hidden, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
+    // ---- what this block needs of the array, checked before anything is launched
+    size_t attn_floats = 0;
+    {
+        AttnArgs a{};
+        a.rows = R;
+        a.n_ctx = x->n + 1;
+        a.max_seq = c.max_seq;
+        a.head_dim = d;
+        a.n_q_heads = c.n_q_heads;
+        a.n_kv_heads = c.n_kv_heads;
+        a.max_split = x->L.n_split_max;
+        attn_floats = attn_partial_floats(c.dtype, a, x->n_cu);
+    }
+    // part_o then holds attn_floats floats and part_ml two per head_dim of them
+    const size_t ml_bytes = align_up(attn_floats / d * 2 * 4);
+    if (ml_bytes + attn_floats * 4 > kStaticAttnBytes)
+        return fail(SWIFT_ECAPACITY, "swift_verify_static: the attention partials of a block of " + std::to_string(R) +
+                                         " rows of this model need " + std::to_string(ml_bytes + attn_floats * 4) +
+                                         " bytes, the static scratch holds " + std::to_string(kStaticAttnBytes) +
+                                         "; use swift_verify");
+    if (x->L.tiled) {
+        const struct { int O, K, n_rg; } mats[5] = {{Q + 2 * KV, H, (Q + 2 * KV) / 16}, {H, Q, (H + 15) / 16},
+                                                    {2 * F, H, (F + 7) / 8},             {H, F, (H + 15) / 16},
+                                                    {V, H, (V + 15) / 16}};
+        for (const auto &mt : mats) {
+            MvArgs m{};
+            m.O = mt.O;
+            m.K = mt.K;
+            m.T = (mt.K + 31) / 32;
+            m.n_rg = mt.n_rg;
+            m.R = R;
+            m.RL = block_row_layout(R);
+            m.head_dim = d;
+            m.part_capacity = x->L.mv_part_capacity;
+            const int slots = mv_split_slots(m, x->n_cu);
+            if (slots > kStaticPartSlots || (mt.n_rg + 7) / 8 > (int)(kStaticCounterBytes / 4))
+                return fail(SWIFT_ECAPACITY, "swift_verify_static: a projection of this model needs more split-K scratch "
+                                             "than the static array holds; use swift_verify");
+        }
+    }
+    char *base = nullptr;
+    rc = static_scratch(&base);
+    if (rc) return rc;
+    Scratch st{};
+    st.mv_counters = (int *)base;
+    st.mv_part = (float *)(base + kStaticCounterBytes);
+    st.mv_part_capacity = kStaticPartSlots;
+    st.part_ml = (float *)(base + kStaticCounterBytes + kStaticPartBytes);
+    st.part_o = (float *)(base + kStaticCounterBytes + kStaticPartBytes + ml_bytes);
+    st.part_o_floats = attn_floats;
+    // The array keeps what the last call left (of any context on this device): the arrival counters must
+    // start at zero.  A fill kernel, not a memset: the caller may be capturing the stream into a graph.
+    HIP_TRY(launch_fill_u32(st.mv_counters, 0u, (int64_t)(kStaticCounterBytes / 4), x->stream));
+    x->scr = st;
+    x->no_events = true;
+    rc = verify_impl(x, tokens, k, target_tokens, logits_out);
+    x->scr = x->arena_scr;
+    x->no_events = false;
+    return rc;
 }
 
 extern "C" int swift_accept(swift_ctx *x, int32_t *emitted, int *n_emitted) {

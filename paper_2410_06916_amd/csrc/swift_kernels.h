@@ -87,6 +87,9 @@ hipError_t launch_attn_decode(int dtype, const AttnArgs &a, int n_cu, hipStream_
 // Writes the name of the kernel instance launch_attn_decode would take for `a` (e.g. "split<bf16, group 1,
 // rows 3>") into out; returns the length snprintf reports.  Host only.
 int attn_path_name(int dtype, const AttnArgs &a, int n_cu, char *out, int capacity);
+// Floats of part_o the attention launches of a block described by `a` may write at any cache length up to
+// max_seq (part_ml: 2 floats per head_dim floats of part_o); 0: the kernel keeps everything on chip.
+size_t attn_partial_floats(int dtype, const AttnArgs &a, int n_cu);
 // Merges the partial results of n_split cache ranges of `chunk` slots, per (row, query head), in range order.
 hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s);
 // Blocks of 17..64 chain rows over a bf16 cache with head_dim 64 or 128: the whole block in one launch on the
@@ -142,6 +145,8 @@ struct KvMoveArgs {
 hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s);
 
 hipError_t launch_fill_nan(int dtype, void *p, int64_t n_elems, hipStream_t s);
+// p[i] = v for n 32-bit words (a kernel rather than a memset, so that the call may be captured into a graph)
+hipError_t launch_fill_u32(void *p, uint32_t v, int64_t n, hipStream_t s);
 
 // dst[i] (fp32) = src[i] (dtype)
 hipError_t launch_to_f32(int dtype, const void *src, float *dst, int64_t n, hipStream_t s);
@@ -231,6 +236,9 @@ inline size_t mv1_lds_bytes(int K, int R, int head_dim) {
 void set_launch_events(hipEvent_t start, hipEvent_t stop);
 // ks_override / wg_override: 0 = choose automatically (LDS-resident kernel only).
 hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s);
+// Row-group-splits of `part` (16 * R floats each) that launch_mv writes for a block of up to 16 rows
+// described by `a` (0: the launch splits K inside workgroups only and uses neither `part` nor `counters`).
+int mv_split_slots(const MvArgs &a, int n_cu);
 
 // x[r] = E[token r] (fp32), split of x * gain_next, partial sums of squares per 16 elements.
 struct EmbedRowsArgs {

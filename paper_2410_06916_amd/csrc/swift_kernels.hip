@@ -482,6 +482,13 @@ static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
     return hipGetLastError();
 }
 
+size_t attn_partial_floats(int dtype, const AttnArgs &a, int n_cu) {
+    const AttnPlan p = dtype == F32 ? attn_plan<F32T>(a, n_cu) : attn_plan<BF16T>(a, n_cu);
+    if (p.head) return 0;
+    const int max_splits = (a.max_seq + p.chunk - 1) / p.chunk;
+    return (size_t)a.rows * a.n_q_heads * max_splits * a.head_dim;
+}
+
 int attn_path_name(int dtype, const AttnArgs &a, int n_cu, char *out, int capacity) {
     const AttnPlan p = dtype == F32 ? attn_plan<F32T>(a, n_cu) : attn_plan<BF16T>(a, n_cu);
     return snprintf(out, (size_t)capacity, "%s<%s, group %d, rows %d%s>", p.head ? "head" : "split",
@@ -705,6 +712,17 @@ hipError_t launch_fill_nan(int dtype, void *p, int64_t n, hipStream_t s) {
         hipLaunchKernelGGL(k_fill_nan<F32T>, dim3(grid), dim3(256), 0, s, (float *)p, n);
     else
         hipLaunchKernelGGL(k_fill_nan<BF16T>, dim3(grid), dim3(256), 0, s, (uint16_t *)p, n);
+    return hipGetLastError();
+}
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, int64_t n) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+hipError_t launch_fill_u32(void *p, uint32_t v, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    int grid = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, s, (uint32_t *)p, v, n);
     return hipGetLastError();
 }
 

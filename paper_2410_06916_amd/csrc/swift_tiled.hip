@@ -881,6 +881,14 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG, DMA>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
 }
 
+int mv_split_slots(const MvArgs &a, int n_cu) {
+    if (a.R <= kMvSmallRows && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds) return 0;  // LDS-resident kernel
+    if (block_terms(a.RL) * a.RL > 48) return a.part_capacity;  // the variants for more than 16 rows: not needed by callers
+    const int TS = ((a.T + 7) / 8) * mv_slice_group(a, n_cu);
+    const int ksp = (a.T + TS - 1) / TS;
+    return ksp > 1 ? ksp * a.n_rg : 0;
+}
+
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
     if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp ||
         a.RL != block_row_layout(a.R))
