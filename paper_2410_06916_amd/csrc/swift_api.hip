@@ -71,6 +71,9 @@ struct Layout {
     uint64_t embed, lm_head, final_norm;
     std::vector<LayerOff> layers;
     uint64_t cos, sin, kv;
+    uint64_t kv_k_bytes, kv_v_bytes;  // one layer's key plane, value plane (the value plane follows the key plane)
+    int nb32;                         // > 0: values transposed in blocks of 32 slots, nb32 blocks per kv head
+    bool mfma_attn;                   // decode / draft / verify attention on the matrix cores (bf16, heads of 64 or 128)
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf, out_topk;
     uint64_t samp_q, samp_p, samp_out;  // speculative sampling: draft and target distributions [16][V], results
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
@@ -118,7 +121,11 @@ Layout make_layout(const swift_model_config &c) {
     }
     L.cos = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
     L.sin = take((uint64_t)c.max_seq * (c.head_dim / 2) * 4);
-    L.kv = take((uint64_t)c.n_layers * 2 * KV * c.max_seq * eb);
+    L.mfma_attn = attn_mfma_applies(c.dtype, c.head_dim);
+    L.nb32 = L.mfma_attn ? (c.max_seq + 31) / 32 : 0;
+    L.kv_k_bytes = align_up(KV * c.max_seq * eb);
+    L.kv_v_bytes = align_up(L.mfma_attn ? KV * (uint64_t)L.nb32 * 32 * eb : KV * c.max_seq * eb);
+    L.kv = take((uint64_t)c.n_layers * (L.kv_k_bytes + L.kv_v_bytes));
     L.n_split_max = kAttnMaxSplit;
     L.x = take(kMaxBlockRows * H * 4);
     L.q = take(kMaxBlockRows * Q * 4);
@@ -320,9 +327,7 @@ hipError_t timed(swift_ctx *x, int kc, uint64_t bytes, F &&f, bool kernel_events
 }
 
 char *kv_base(swift_ctx *x, int layer, int which) {
-    const uint64_t eb = elem_bytes(x->c.dtype);
-    const uint64_t per = (uint64_t)x->c.n_kv_heads * x->c.max_seq * x->c.head_dim * eb;
-    return x->base + x->L.kv + ((uint64_t)layer * 2 + which) * per;
+    return x->base + x->L.kv + (uint64_t)layer * (x->L.kv_k_bytes + x->L.kv_v_bytes) + (which ? x->L.kv_k_bytes : 0);
 }
 
 // The rows of a token tree: level of each block row, block row of the first candidate of each level
@@ -508,6 +513,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.ld_out = Q;
             m.kcache = kv_base(x, l, 0);
             m.vcache = kv_base(x, l, 1);
+            m.nb32 = L.nb32;
             if (tree) {
                 m.tree = 1;
                 m.depth4 = tree->depth4;
@@ -537,6 +543,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.part_o = x->scr.part_o;
             a.part_ml = x->scr.part_ml;
             a.max_split = L.n_split_max;
+            a.nb32 = L.nb32;
             a.out = nullptr;
             a.out_s = as_;
             if (tree) {
@@ -604,6 +611,10 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.out_rows = block_row_layout(R);
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
                           [&] { return launch_attn_block(a, x->n_cu, s); }));
+        } else if (list[i].epi < 0 && L.mfma_attn) {
+            AttnArgs a = list[i].at;
+            a.out_rows = block_row_layout(R);
+            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R), [&] { return launch_attn_mfma(a, x->n_cu, s); }));
         } else if (list[i].epi < 0) {
             // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
             const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
@@ -1003,7 +1014,8 @@ extern "C" int swift_verify_static(swift_ctx *x, const int32_t *tokens, int k, i
         a.n_q_heads = c.n_q_heads;
         a.n_kv_heads = c.n_kv_heads;
         a.max_split = x->L.n_split_max;
-        attn_floats = attn_partial_floats(c.dtype, a, x->n_cu);
+        a.nb32 = x->L.nb32;
+        attn_floats = x->L.mfma_attn ? attn_mfma_partial_floats(a, x->n_cu) : attn_partial_floats(c.dtype, a, x->n_cu);
     }
     // part_o then holds attn_floats floats and part_ml two per head_dim of them
     const size_t ml_bytes = align_up(attn_floats / d * 2 * 4);
@@ -1184,8 +1196,10 @@ extern "C" int swift_accept_tree(swift_ctx *x, int32_t *emitted, int *n_emitted)
     }
     if (mv.n_moves > 0) {
         mv.kv = x->base + x->L.kv;
-        mv.plane_elems = (int64_t)c.n_kv_heads * c.max_seq * c.head_dim;
-        mv.n_planes = 2 * c.n_layers;
+        mv.layer_elems = (int64_t)((x->L.kv_k_bytes + x->L.kv_v_bytes) / elem_bytes(c.dtype));
+        mv.v_offset = (int64_t)(x->L.kv_k_bytes / elem_bytes(c.dtype));
+        mv.n_layers = c.n_layers;
+        mv.nb32 = x->L.nb32;
         mv.n_kv_heads = c.n_kv_heads;
         mv.max_seq = c.max_seq;
         mv.head_dim = c.head_dim;
@@ -1387,11 +1401,16 @@ extern "C" int swift_debug_poison_kv(swift_ctx *x) {
     const uint64_t eb = elem_bytes(c.dtype);
     const int64_t tail = (int64_t)(c.max_seq - x->n) * c.head_dim;
     for (int l = 0; l < c.n_layers; ++l)
-        for (int w = 0; w < 2; ++w)
+        for (int w = 0; w < 2; ++w) {
+            if (w == 1 && x->L.nb32 > 0) {
+                HIP_TRY(launch_vt_poison(kv_base(x, l, 1), c.n_kv_heads, x->L.nb32, c.head_dim, x->n, x->stream));
+                continue;
+            }
             for (int g = 0; g < c.n_kv_heads; ++g) {
                 char *p = kv_base(x, l, w) + ((uint64_t)g * c.max_seq + x->n) * c.head_dim * eb;
                 HIP_TRY(launch_fill_nan(c.dtype, p, tail, x->stream));
             }
+        }
     HIP_TRY(hipStreamSynchronize(x->stream));
     return SWIFT_OK;
 }
@@ -1412,9 +1431,13 @@ extern "C" int swift_debug_read_kv(swift_ctx *x, int layer, int pos, float *k_ou
     // stage through the attention output buffer (fp32, >= n_q*d elements, idle between passes)
     float *tmp = dptr<float>(x, x->L.att);
     for (int w = 0; w < 2; ++w) {
-        for (int g = 0; g < c.n_kv_heads; ++g) {
-            const char *src = kv_base(x, layer, w) + ((uint64_t)g * c.max_seq + pos) * c.head_dim * eb;
-            HIP_TRY(launch_to_f32(c.dtype, src, tmp + (size_t)g * c.head_dim, c.head_dim, x->stream));
+        if (w == 1 && x->L.nb32 > 0) {
+            HIP_TRY(launch_vt_read(kv_base(x, layer, 1), c.n_kv_heads, x->L.nb32, c.head_dim, pos, tmp, x->stream));
+        } else {
+            for (int g = 0; g < c.n_kv_heads; ++g) {
+                const char *src = kv_base(x, layer, w) + ((uint64_t)g * c.max_seq + pos) * c.head_dim * eb;
+                HIP_TRY(launch_to_f32(c.dtype, src, tmp + (size_t)g * c.head_dim, c.head_dim, x->stream));
+            }
         }
         HIP_TRY(hipMemcpyAsync(w == 0 ? k_out : v_out, tmp, (size_t)c.n_kv_heads * c.head_dim * 4, hipMemcpyDeviceToHost,
                                x->stream));
@@ -1437,8 +1460,13 @@ extern "C" int swift_debug_attn_path(swift_ctx *x, int rows, int tree, char *out
     a.max_split = x->L.n_split_max;
     a.tree = tree ? 1 : 0;
     a.n_base = x->n;
+    a.nb32 = x->L.nb32;
+    if (tree)  // (a chain of `rows` levels: the deepest tree of that many rows)
+        for (int r = 0; r < rows; ++r) a.depth4 |= (uint64_t)r << (4 * r);
     if (x->L.tiled && attn_block_applies(c.dtype, a))
         snprintf(out, (size_t)capacity, "block<bf16, d %d>", c.head_dim);
+    else if (x->L.mfma_attn)
+        attn_mfma_path_name(a, x->n_cu, out, capacity);
     else
         attn_path_name(c.dtype, a, x->n_cu, out, capacity);
     return SWIFT_OK;

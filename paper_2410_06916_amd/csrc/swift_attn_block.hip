@@ -2,7 +2,8 @@
 // the blocks of candidate evaluation; paper Section 3.1: the verify / prefill pass processes its rows as
 // one causal block).  One workgroup per (query head, range of cache slots): its four wavefronts take 16
 // block rows each and share every 64-slot chunk of keys and values through LDS, so a chunk is read once
-// for all 64 rows instead of once per group of rows.
+// for all 64 rows instead of once per group of rows.  The values come from a cache that stores them transposed
+// in blocks of 32 slots, so they reach LDS as V^T with plain 16-byte copies.
 //
 // Arithmetic.  Scores: S^T = K Q^T with the fp32 query rows as three bf16 terms (the products are
 // exact, the sums fp32).  The transposed form leaves a row's scores in one lane column, so its
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
     const int hi_all = min(a.n_ctx + a.rows - 1, lo + chunk);  // end of the longest row's range here
     if (hi_all <= lo) return;
     const uint16_t *kc = (const uint16_t *)a.kcache + (size_t)kvh * a.max_seq * D;
-    const uint16_t *vc = (const uint16_t *)a.vcache + (size_t)kvh * a.max_seq * D;
+    const uint16_t *vt = (const uint16_t *)a.vcache + (size_t)kvh * a.nb32 * D * 32;
     const int row = 16 * wave + col;
     const int lim = row < a.rows ? a.n_ctx + row : 0;  // rows past the block take part in nothing
     const int tile_lim = a.n_ctx + min(16 * wave + 15, a.rows - 1);
@@ -73,15 +74,27 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
     }
 
     u32x4 kr[NPC], vr[NPC];
-    // Slots past the longest row's range are replaced by its last slot: a slot that has been written
-    // (never-written slots may hold anything, and 0 x NaN is NaN in the second product).
+    // Keys: piece p = (slot p / PPR, 8 elements).  Slots past the longest row's range are replaced by its last
+    // slot (an unwritten slot may hold anything).  Values come from the transposed cache (blocks of 32 slots,
+    // kv_vt_index): piece p = (element p / 8, 8 slots of the chunk); slots past the range are zeroed in the
+    // registers (0 x NaN is NaN in the second product).
     auto load_chunk = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < NPC; ++u) {
             const int p = tid + 256 * u, key = p / PPR, dj = p - key * PPR;
-            const size_t off = (size_t)min(k0 + key, hi_all - 1) * D + 8 * dj;
-            kr[u] = *(const u32x4 *)(kc + off);
-            vr[u] = *(const u32x4 *)(vc + off);
+            kr[u] = *(const u32x4 *)(kc + (size_t)min(k0 + key, hi_all - 1) * D + 8 * dj);
+            const int dd = p >> 3, sg = p & 7;
+            const int blk = min((k0 >> 5) + (sg >> 2), a.nb32 - 1);
+            u32x4 v = *(const u32x4 *)(vt + ((size_t)blk * D + dd) * 32 + 8 * (sg & 3));
+            const int n_ok = hi_all - (k0 + 8 * sg);  // slots of this piece inside the range
+            if (n_ok < 8) {
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (j >= n_ok) w[j >> 1] &= (j & 1) ? 0x0000ffffu : 0xffff0000u;
+                v = u32x4{w[0], w[1], w[2], w[3]};
+            }
+            vr[u] = v;
         }
     };
     // V^T in LDS: element (dd, key) at row dd, column 8 ((key / 8) ^ (dd / 8 & 7)) + key % 8
@@ -90,10 +103,8 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
         for (int u = 0; u < NPC; ++u) {
             const int p = tid + 256 * u, key = p / PPR, dj = p - key * PPR;
             *(u32x4 *)(Ks + key * KP + 8 * dj) = kr[u];
-            const int kcol = 8 * ((key >> 3) ^ (dj & 7)) + (key & 7);
-            const uint32_t w[4] = {vr[u].x, vr[u].y, vr[u].z, vr[u].w};
-#pragma unroll
-            for (int j = 0; j < 8; ++j) Vt[(8 * dj + j) * VP + kcol] = (uint16_t)(w[j >> 1] >> (16 * (j & 1)));
+            const int dd = p >> 3, sg = p & 7;
+            *(u32x4 *)(Vt + dd * VP + 8 * (sg ^ ((dd >> 3) & 7))) = vr[u];
         }
     };
 
@@ -221,6 +232,7 @@ bool attn_block_applies(int dtype, const AttnArgs &a) {
 hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s) {
     if (a.tree || a.rows < 1 || a.rows > 64 || (a.head_dim != 64 && a.head_dim != 128) || a.n_ctx < 1 ||
         a.n_kv_heads < 1 || a.n_q_heads % a.n_kv_heads != 0 || a.n_ctx + a.rows - 1 > a.max_seq || (!a.out && !a.out_s) ||
+        a.nb32 < (a.max_seq + 31) / 32 ||
         !a.part_o || !a.part_ml)
         return hipErrorInvalidValue;
     const int ctx = a.n_ctx + a.rows - 1;

@@ -78,7 +78,27 @@ struct AttnArgs {
     // the same way, as a chain row at position n_base + depth, so the result is the chain's bit for bit.
     int tree, n_base, row_base;
     uint64_t depth4, spine4;
+    // Matrix-core attention (bf16 cache, heads of 64 or 128; attn_mfma_applies): the values are stored
+    // transposed in blocks of 32 slots (see kv_vt_index), nb32 blocks per kv head.
+    int nb32;
 };
+// ------------------------------------------------------------------------------------------
+// key/value cache layouts
+// ------------------------------------------------------------------------------------------
+// Keys: [kv head][slot][d].  Values: the same, except for bf16 caches with heads of 64 or 128, whose
+// attention runs on the matrix cores and wants eight consecutive slots of one value element in one 16-byte
+// load: there the values are stored transposed in blocks of 32 slots, [kv head][slot / 32][element][slot % 32]
+// (nb32 = ceil(max_seq / 32) blocks per head).
+inline bool attn_mfma_applies(int dtype, int head_dim) { return dtype == 1 /* BF16 */ && (head_dim == 64 || head_dim == 128); }
+__host__ __device__ inline size_t kv_vt_index(int kv_head, int nb32, int d, int slot, int elem) {
+    return (((size_t)kv_head * nb32 + (slot >> 5)) * d + elem) * 32 + (slot & 31);
+}
+// Rows one launch of the matrix-core attention kernel takes (two tiles of 16 members for one kv head per
+// workgroup; more members go to further workgroups)
+constexpr int kAttnMfmaMaxRows = 32;
+hipError_t launch_attn_mfma(const AttnArgs &a, int n_cu, hipStream_t s);
+int attn_mfma_path_name(const AttnArgs &a, int n_cu, char *out, int capacity);
+size_t attn_mfma_partial_floats(const AttnArgs &a, int n_cu);
 // True when the attention of a block runs on the one-workgroup-per-(kv head, row) kernel (no partial
 // buffers: one launch may then cover any number of rows); false: the split kernel, at most kMaxRows
 // rows per launch.  Depends on the cache capacity and the head count only.
@@ -133,17 +153,20 @@ struct SpecAcceptArgs {
 };
 hipError_t launch_spec_accept(const SpecAcceptArgs &a, hipStream_t s);
 
-// Copies cache slots src[i] -> dst[i], i = 0 .. n_moves-1 in this order, for every kv head of every plane
-// (a plane: the keys or the values of one layer, [n_kv][max_seq][d]; planes are plane_elems apart).
+// Copies cache slots src[i] -> dst[i], i = 0 .. n_moves-1 in this order, for every kv head of the key plane and
+// the value plane of every layer.  Layer l's keys start at kv + l * layer_elems ([n_kv][max_seq][d]), its values
+// v_offset elements later ([n_kv][max_seq][d], or transposed in blocks with nb32 > 0: kv_vt_index).
 struct KvMoveArgs {
     void *kv;
-    int64_t plane_elems;
-    int n_planes, n_kv_heads, max_seq, head_dim;
+    int64_t layer_elems, v_offset;
+    int n_layers, n_kv_heads, max_seq, head_dim, nb32;
     int n_moves;
-    int src[16], dst[16];
+    int src[32], dst[32];
 };
 hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s);
 
+hipError_t launch_vt_poison(void *plane, int n_kv, int nb32, int d, int first_slot, hipStream_t s);
+hipError_t launch_vt_read(const void *plane, int n_kv, int nb32, int d, int slot, float *dst, hipStream_t s);
 hipError_t launch_fill_nan(int dtype, void *p, int64_t n_elems, hipStream_t s);
 // p[i] = v for n 32-bit words (a kernel rather than a memset, so that the call may be captured into a graph)
 hipError_t launch_fill_u32(void *p, uint32_t v, int64_t n, hipStream_t s);
@@ -207,6 +230,7 @@ struct MvArgs {
     // of a token tree (tree != 0, R <= 16), for position pos0 + nibble r of depth4 (the row's level)
     int tree;
     uint64_t depth4;
+    int nb32;              // QKV: > 0: the values go to the transposed layout (kv_vt_index) with nb32 blocks per head
     // multi-row kernel only: split-K scratch
     float *part;           // [k splits][row group][R][16] fp32 partial results
     int *counters;         // one per 8-row-group block, zero between launches

@@ -674,25 +674,60 @@ hipError_t launch_argmax_conf(const ArgmaxArgs &a, hipStream_t s) {
 // same thread, so a move that overwrites the source of an earlier one comes after that one's read.
 template <typename T>
 __global__ void k_kv_move(KvMoveArgs a) {
-    typename T::elem *p = (typename T::elem *)a.kv + (size_t)blockIdx.y * a.plane_elems +
-                          (size_t)blockIdx.x * a.max_seq * a.head_dim;
+    const int layer = blockIdx.y >> 1, is_v = blockIdx.y & 1, d = a.head_dim;
+    typename T::elem *plane = (typename T::elem *)a.kv + (size_t)layer * a.layer_elems + (is_v ? a.v_offset : 0);
+    if (is_v && a.nb32 > 0) {
+        for (int i = 0; i < a.n_moves; ++i)
+            for (int e = threadIdx.x; e < d; e += blockDim.x)
+                plane[kv_vt_index(blockIdx.x, a.nb32, d, a.dst[i], e)] = plane[kv_vt_index(blockIdx.x, a.nb32, d, a.src[i], e)];
+        return;
+    }
+    typename T::elem *p = plane + (size_t)blockIdx.x * a.max_seq * d;
     for (int i = 0; i < a.n_moves; ++i) {
-        const typename T::elem *src = p + (size_t)a.src[i] * a.head_dim;
-        typename T::elem *dst = p + (size_t)a.dst[i] * a.head_dim;
-        for (int e = threadIdx.x; e < a.head_dim; e += blockDim.x) dst[e] = src[e];
+        const typename T::elem *src = p + (size_t)a.src[i] * d;
+        typename T::elem *dst = p + (size_t)a.dst[i] * d;
+        for (int e = threadIdx.x; e < d; e += blockDim.x) dst[e] = src[e];
     }
 }
 
 hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s) {
     if (a.n_moves <= 0) return hipSuccess;
-    if (a.n_moves > 16) return hipErrorInvalidValue;
+    if (a.n_moves > 32) return hipErrorInvalidValue;
     for (int i = 0; i < a.n_moves; ++i)
         if (a.src[i] < 0 || a.src[i] >= a.max_seq || a.dst[i] < 0 || a.dst[i] >= a.max_seq) return hipErrorInvalidValue;
-    dim3 grid(a.n_kv_heads, a.n_planes), block(a.head_dim < 64 ? 64 : a.head_dim > 256 ? 256 : a.head_dim);
+    dim3 grid(a.n_kv_heads, 2 * a.n_layers), block(a.head_dim < 64 ? 64 : a.head_dim > 256 ? 256 : a.head_dim);
     if (dtype == F32)
         hipLaunchKernelGGL(k_kv_move<F32T>, grid, block, 0, s, a);
     else
         hipLaunchKernelGGL(k_kv_move<BF16T>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// the transposed value layout (bf16; kv_vt_index): test and debug helpers
+// ------------------------------------------------------------------------------------------
+// NaN-fills every value of slots >= first_slot of every kv head of one layer's value plane.
+__global__ void k_vt_poison(uint16_t *plane, int n_kv, int nb32, int d, int first_slot) {
+    const int64_t per_head = (int64_t)nb32 * d * 32;
+    const int64_t first = (int64_t)(first_slot >> 5) * d * 32;  // blocks below hold committed slots only
+    const int64_t n = (int64_t)n_kv * (per_head - first);
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t h = i / (per_head - first), r = first + i % (per_head - first);
+        const int slot = (int)(r / ((int64_t)d * 32)) * 32 + (int)(r & 31);
+        if (slot >= first_slot) plane[h * per_head + r] = 0x7fc0;
+    }
+}
+hipError_t launch_vt_poison(void *plane, int n_kv, int nb32, int d, int first_slot, hipStream_t s) {
+    hipLaunchKernelGGL(k_vt_poison, dim3(1024), dim3(256), 0, s, (uint16_t *)plane, n_kv, nb32, d, first_slot);
+    return hipGetLastError();
+}
+// dst[h * d + e] = value element e of slot `slot` of kv head h
+__global__ void k_vt_read(const uint16_t *plane, int n_kv, int nb32, int d, int slot, float *dst) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_kv * d) dst[i] = __uint_as_float((uint32_t)plane[kv_vt_index(i / d, nb32, d, slot, i % d)] << 16);
+}
+hipError_t launch_vt_read(const void *plane, int n_kv, int nb32, int d, int slot, float *dst, hipStream_t s) {
+    hipLaunchKernelGGL(k_vt_read, dim3((n_kv * d + 255) / 256), dim3(256), 0, s, (const uint16_t *)plane, n_kv, nb32, d, slot, dst);
     return hipGetLastError();
 }
 

@@ -77,6 +77,10 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                         kc[0] = f32_to_bf16_rne(qa);
                         kc[half] = f32_to_bf16_rne(qb);
                     }
+                } else if (a.nb32 > 0) {  // values transposed in blocks of 32 slots
+                    uint16_t *vc = (uint16_t *)a.vcache + kv_vt_index(hh - nq - nkv, a.nb32, d, pos, i);
+                    vc[0] = f32_to_bf16_rne(ya);
+                    vc[half * 32] = f32_to_bf16_rne(yb);
                 } else {
                     uint16_t *vc = (uint16_t *)a.vcache + ((size_t)(hh - nq - nkv) * a.max_seq + pos) * d + i;
                     vc[0] = f32_to_bf16_rne(ya);

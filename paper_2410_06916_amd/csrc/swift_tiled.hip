@@ -267,14 +267,15 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         if (p < 0) return;
         const size_t head_units = (size_t)a.max_seq * a.head_dim / 8;  // 16-byte units of one head
         const int n_units = a.pf_rows * a.head_dim / 8;
+        // (values in transposed blocks of 32 slots: the blocks that hold rows [0, pf_rows) are contiguous too)
+        const size_t v_head_units = a.nb32 > 0 ? (size_t)a.nb32 * 32 * a.head_dim / 8 : head_units;
+        const int v_units = a.nb32 > 0 ? (a.pf_rows + 31) / 32 * 32 * a.head_dim / 8 : n_units;
         u32x4 x = {0u, 0u, 0u, 0u};
         for (int gh = p; gh < a.pf_heads; gh += a.pf_wgs) {
             const u32x4 *kp = (const u32x4 *)a.kcache + (size_t)gh * head_units;
-            const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * head_units;
-            for (int i = tid; i < n_units; i += 512) {
-                x ^= kp[i];
-                x ^= vp[i];
-            }
+            const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * v_head_units;
+            for (int i = tid; i < n_units; i += 512) x ^= kp[i];
+            for (int i = tid; i < v_units; i += 512) x ^= vp[i];
         }
         // (keeps the loads alive; the flag word is never all ones)
         if ((x.x & x.y & x.z & x.w) == 0xffffffffu && a.pf_rows < 0) ((volatile uint32_t *)smem)[0] = x.x;

@@ -725,15 +725,16 @@ def test_other_widths_narrow_depth_against_oracle(oracle_lib, width, scenario):
 
 
 # attention kernel instance per block size that each case of the bit-for-bit test is meant to reach
+_MFMA_7B = "mfma<d 128, group 1, 8 wavefronts, range 256, tiles 1>"      # one workgroup per kv head, no second launch
+_MFMA_LONG = "mfma<d 128, group 1, 4 wavefronts, range 128, tiles 1>"    # the cache cut into ranges + merge launch
 _EXPECTED_ATTN_PATHS = {
+    # heads of 16: the row-at-a-time kernels (vector arithmetic), rows sharing loads two by two
     "small-gqa-bf16": {1: "split<bf16, group 2, rows 1>", 2: "split<bf16, group 2, rows 2>",
                        16: "split<bf16, group 2, rows 2>"},
     "small-gqa-bf16-long-cache": {1: "split<bf16, group 2, rows 1>", 9: "split<bf16, group 2, rows 2>"},
-    "7b-width-2-layers": {1: "head<bf16, group 1, rows 1>", 5: "head<bf16, group 1, rows 1>",
-                          9: "head<bf16, group 1, rows 2>", 16: "head<bf16, group 1, rows 2>"},
-    "d128-mha": {1: "split<bf16, group 1, rows 1>", 2: "split<bf16, group 1, rows 2>",
-                 3: "split<bf16, group 1, rows 3>", 5: "split<bf16, group 1, rows 4>",
-                 16: "split<bf16, group 1, rows 4>"},
+    # heads of 128: the matrix-core kernel, every row of the block a column of one tile
+    "7b-width-2-layers": {1: _MFMA_7B, 5: _MFMA_7B, 9: _MFMA_7B, 16: _MFMA_7B},
+    "d128-mha": {1: _MFMA_LONG, 2: _MFMA_LONG, 3: _MFMA_LONG, 16: _MFMA_LONG},
 }
 
 
