@@ -74,6 +74,7 @@ struct Layout {
     uint64_t kv_k_bytes, kv_v_bytes;  // one layer's key plane, value plane (the value plane follows the key plane)
     int nb32;                         // > 0: values transposed in blocks of 32 slots, nb32 blocks per kv head
     bool mfma_attn;                   // decode / draft / verify attention on the matrix cores (bf16, heads of 64 or 128)
+    uint64_t q_s;  // queries as two bf16 terms (matrix-core attention)
     uint64_t x, q, att, h, logits, part_o, part_ml, out_tok, out_conf, out_topk;
     uint64_t samp_q, samp_p, samp_out;  // speculative sampling: draft and target distributions [16][V], results
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
@@ -130,6 +131,7 @@ Layout make_layout(const swift_model_config &c) {
     L.x = take(kMaxBlockRows * H * 4);
     L.q = take(kMaxBlockRows * Q * 4);
     L.att = take(kMaxBlockRows * Q * 4);
+    L.q_s = take(kMaxBlockRows * Q * 2 * 2);
     L.h = take(kMaxBlockRows * F * 4);
     L.logits = take(kMaxBlockRows * V * 4);
     L.part_o = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * c.head_dim * 4);
@@ -514,6 +516,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.kcache = kv_base(x, l, 0);
             m.vcache = kv_base(x, l, 1);
             m.nb32 = L.nb32;
+            m.q_s = L.mfma_attn ? dptr<uint16_t>(x, L.q_s) : nullptr;
             if (tree) {
                 m.tree = 1;
                 m.depth4 = tree->depth4;
@@ -544,6 +547,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             a.part_ml = x->scr.part_ml;
             a.max_split = L.n_split_max;
             a.nb32 = L.nb32;
+            a.q_s = dptr<uint16_t>(x, L.q_s);
             a.out = nullptr;
             a.out_s = as_;
             if (tree) {

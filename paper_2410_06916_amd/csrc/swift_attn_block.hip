@@ -2,8 +2,8 @@
 // the blocks of candidate evaluation; paper Section 3.1: the verify / prefill pass processes its rows as
 // one causal block).  One workgroup per (query head, range of cache slots): its four wavefronts take 16
 // block rows each and share every 64-slot chunk of keys and values through LDS, so a chunk is read once
-// for all 64 rows instead of once per group of rows.  The values come from a cache that stores them transposed
-// in blocks of 32 slots, so they reach LDS as V^T with plain 16-byte copies.
+// for all 64 rows instead of once per group of rows.  The values come from a cache that stores eight slots of
+// an element together, so they reach LDS as V^T with plain 16-byte copies.
 //
 // Arithmetic.  Scores: S^T = K Q^T with the fp32 query rows as three bf16 terms (the products are
 // exact, the sums fp32).  The transposed form leaves a row's scores in one lane column, so its
@@ -75,17 +75,17 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
 
     u32x4 kr[NPC], vr[NPC];
     // Keys: piece p = (slot p / PPR, 8 elements).  Slots past the longest row's range are replaced by its last
-    // slot (an unwritten slot may hold anything).  Values come from the transposed cache (blocks of 32 slots,
-    // kv_vt_index): piece p = (element p / 8, 8 slots of the chunk); slots past the range are zeroed in the
+    // slot (an unwritten slot may hold anything).  Values come from the cache that groups eight slots per element
+    // (kv_vt_index): piece p = (8-slot group p / D of the chunk, element p % D); slots past the range are zeroed in the
     // registers (0 x NaN is NaN in the second product).
     auto load_chunk = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < NPC; ++u) {
             const int p = tid + 256 * u, key = p / PPR, dj = p - key * PPR;
             kr[u] = *(const u32x4 *)(kc + (size_t)min(k0 + key, hi_all - 1) * D + 8 * dj);
-            const int dd = p >> 3, sg = p & 7;
-            const int blk = min((k0 >> 5) + (sg >> 2), a.nb32 - 1);
-            u32x4 v = *(const u32x4 *)(vt + ((size_t)blk * D + dd) * 32 + 8 * (sg & 3));
+            const int sg = p / D, dd = p - sg * D;
+            const int grp = min((k0 >> 3) + sg, 4 * a.nb32 - 1);
+            u32x4 v = *(const u32x4 *)(vt + ((size_t)grp * D + dd) * 8);
             const int n_ok = hi_all - (k0 + 8 * sg);  // slots of this piece inside the range
             if (n_ok < 8) {
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
         for (int u = 0; u < NPC; ++u) {
             const int p = tid + 256 * u, key = p / PPR, dj = p - key * PPR;
             *(u32x4 *)(Ks + key * KP + 8 * dj) = kr[u];
-            const int dd = p >> 3, sg = p & 7;
+            const int sg = p / D, dd = p - sg * D;
             *(u32x4 *)(Vt + dd * VP + 8 * (sg ^ ((dd >> 3) & 7))) = vr[u];
         }
     };

@@ -6,16 +6,16 @@
 // tile, so a workgroup reads every key/value chunk of its cache range once for up to 16 members -- once
 // per block for a block of up to 16 rows on one kv head per query head.  The operands come straight from
 // global memory in MFMA layout with 128-bit loads: the keys as stored, the values from a cache that holds
-// them transposed in blocks of 32 slots (kv_vt_index), so nothing is transposed or staged on the way.
+// eight slots of an element together (kv_vt_index), so nothing is transposed or staged on the way.
 //
 // What a row computes (the same for a row decoded alone, a row of a chain block and a row of a tree, bit for
 // bit, because every step below is per member and its order does not depend on the other members):
 //  * the row's prefix -- logical slots [0, P), P = its position -- is walked in chunks of 32 slots.  A
 //    workgroup owns a range of the cache capacity fixed by the configuration alone; its wavefronts take the
 //    range's chunks round-robin, each folding its chunks in order into a running (max, sum, weighted values)
-//    with S^T = K Q^T (query as three bf16 terms: exact products, fp32 sums) and O^T += V^T P^T
-//    (probabilities as two bf16 terms); the wavefronts' results are merged in wavefront order, the ranges'
-//    in range order (k_attn_mfma_combine);
+//    with S^T = K Q^T and O^T += V^T P^T (queries and probabilities as two bf16 terms each: relative error
+//    2^-17 against the 2^-9 of the bf16 keys and values; fp32 sums); the wavefronts' results are merged in
+//    wavefront order, the ranges' in range order (k_attn_mfma_combine);
 //  * the row's own slot (its key and value, written to the cache by the projection kernel of the same pass)
 //    is merged last, in fp32 vector arithmetic.  For a tree row the prefix beyond the committed slots is
 //    the first candidates of the levels above it: one mapping for all rows, so tree rows share the loads
@@ -103,7 +103,7 @@ __device__ inline void am_write(const AttnArgs &a, int row, int e, float y) {
 // that a lane's eight probabilities are slots 8 g .. 8 g + 7: the k range of its B operand in O^T = V^T P^T.
 //
 // Workgroup (kv head, cache range sp, member tile z), blockDim.x / 64 wavefronts.  range: slots per workgroup, a
-// multiple of 32 x wavefronts.  hi_all: end of the longest prefix of the block.
+// multiple of 32.  hi_all: end of the longest prefix of the block.
 template <int D, bool TREE>
 __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi_all) {
     constexpr int DC = D / 32;      // k steps of a score tile
@@ -127,26 +127,12 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
     const bool mem_ok = mem < M_total;
     const int mrow = mem_ok ? mem / group : 0, mhead = mem_ok ? mem - mrow * group : 0;
     const int lim = mem_ok ? min(am_prefix_end<TREE>(a, mrow), lo + range) : 0;  // the prefix slots it sees here
-    bf16x8 qop[DC][3];
-    {
-        const float *qp = a.q + ((size_t)mrow * nq + kvh * group + mhead) * D + 8 * g;
-#pragma unroll
-        for (int c = 0; c < DC; ++c) {
-            uint16_t h[8], m[8], l[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) split3(qp[32 * c + j], h[j], m[j], l[j]);
-            qop[c][0] = am_pack(h);
-            qop[c][1] = am_pack(m);
-            qop[c][2] = am_pack(l);
-        }
-    }
-
     // ---- operands of a chunk, straight from the cache in MFMA A layout
     // Chunks that lie below safe_end hold 32 prefix slots that sit where their numbers say: keys as stored,
-    // values one 16-byte load per eight slots.  The others (the chunk in which the longest prefix ends; in a
-    // tree, every chunk that reaches beyond the committed slots) go slot by slot through the mapping, with
-    // slots past the longest prefix replaced by its last slot (an unwritten slot may hold anything, and
-    // 0 x NaN is NaN in an MFMA).
+    // values one 16-byte load per eight slots.  In the chunk in which the longest prefix ends, the keys of the
+    // slots past it are replaced by its last slot's and their values by zeros (an unwritten slot may hold
+    // anything, and 0 x NaN is NaN in an MFMA); a tree's chunks beyond the committed slots go slot by slot
+    // through the mapping.
     const int safe_end = TREE ? min(a.n_base, hi_all) : hi_all;
     auto load_keys = [&](int c, u32x4(&kA)[2][DC]) {
         const bool plain = 32 * (c + 1) <= safe_end;
@@ -160,11 +146,28 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
         }
     };
     auto load_values = [&](int c, u32x4(&vA)[DT]) {
-        if (32 * (c + 1) <= safe_end) {
-            const uint16_t *vp = vt + ((size_t)c * D + col) * 32 + 8 * g;
+        const bool plain = 32 * (c + 1) <= safe_end;
+        if (!TREE || plain) {
+            const uint16_t *vp = vt + ((size_t)(4 * c + g) * D + col) * 8;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) vA[dt] = *(const u32x4 *)(vp + dt * (16 * 32));
+            for (int dt = 0; dt < DT; ++dt) vA[dt] = *(const u32x4 *)(vp + dt * (16 * 8));
+            if (!plain) {
+                // the chunk in which the longest prefix ends: the slots past it are zeroed in the registers
+                const int n_ok = hi_all - (32 * c + 8 * g);  // slots of this lane's eight that belong to the prefix
+                const uint32_t m0 = n_ok >= 2 ? 0xffffffffu : n_ok == 1 ? 0x0000ffffu : 0u;
+                const uint32_t m1 = n_ok >= 4 ? 0xffffffffu : n_ok == 3 ? 0x0000ffffu : 0u;
+                const uint32_t m2 = n_ok >= 6 ? 0xffffffffu : n_ok == 5 ? 0x0000ffffu : 0u;
+                const uint32_t m3 = n_ok >= 8 ? 0xffffffffu : n_ok == 7 ? 0x0000ffffu : 0u;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    vA[dt].x &= m0;
+                    vA[dt].y &= m1;
+                    vA[dt].z &= m2;
+                    vA[dt].w &= m3;
+                }
+            }
         } else {
+            // a tree's chunks beyond the committed slots: slot by slot through the mapping
             int ps[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) ps[j] = am_phys<TREE>(a, min(32 * c + 8 * g + j, hi_all - 1));
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
             for (int dt = 0; dt < DT; ++dt) {
                 uint16_t e[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) e[j] = vt[((size_t)(ps[j] >> 5) * D + 16 * dt + col) * 32 + (ps[j] & 31)];
+                for (int j = 0; j < 8; ++j) e[j] = vt[((size_t)(ps[j] >> 3) * D + 16 * dt + col) * 8 + (ps[j] & 7)];
                 vA[dt] = __builtin_bit_cast(u32x4, am_pack(e));
             }
         }
@@ -183,65 +186,108 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- this wavefront's chunks: every NW-th of the range.  The key operands are dead once the scores are
-    // done and the value operands once they are multiplied, so the next chunk's keys are requested right
-    // after the scores and its values right after the second product: the loads of one chunk are in flight
-    // while the other half of the previous one is worked on, with one chunk's worth of registers.
+    const int c_end = (hi + 31) >> 5;
+    u32x4 kA[2][DC], kB[2][DC], vA[DT];
+    int c = (lo >> 5) + wave;
+    // the first chunk's operands are requested before anything else, so that the set-up below (query operands,
+    // own slots) runs while they are on their way
+    if (c < c_end) {
+        load_keys(c, kA);
+        load_values(c, vA);
+    }
+
+    // query operands: two bf16 terms per value (relative error 2^-17; the keys they meet are bf16), written in
+    // this form by the projection kernel
+    bf16x8 qop[DC][2];
     {
-        const int c_end = (hi + 31) >> 5;
-        u32x4 kA[2][DC], vA[DT];
-        int c = (lo >> 5) + wave;
-        if (c < c_end) {
-            load_keys(c, kA);
-            load_values(c, vA);
+        const uint16_t *qp = a.q_s + ((size_t)(mrow * nq + kvh * group + mhead) * 2) * D + 8 * g;
+#pragma unroll
+        for (int c = 0; c < DC; ++c)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) qop[c][t] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + t * D + 32 * c));
+    }
+    // ---- the own slots of the rows that are finished here (prefix inside the first range), requested before
+    // the prefix is walked so that their latency is not paid at the end: scores by whole wavefronts into LDS,
+    // the value elements each thread will need in the last phase into registers
+    constexpr int kOwnMax = 16 * D / 256;  // elements per thread in the last phase with four wavefronts
+    float *s_own = am_sh + (size_t)NW * (16 * (MP + 2));
+    float v_own[kOwnMax];
+    if (sp == 0) {
+        // (member mm by wavefront NW - 1 - mm % NW: the last wavefronts have the fewest chunks to walk)
+        for (int mm = NW - 1 - wave; mm < 16; mm += NW) {
+            const int m = m0 + mm;
+            if (m >= M_total) continue;
+            const int row = m / group, head = m - row * group;
+            if (am_prefix_end<TREE>(a, row) > range) continue;  // finished by the combine kernel
+            const float sc = am_own_score(a.q + ((size_t)row * nq + kvh * group + head) * D,
+                                          kc + (size_t)am_own_slot<TREE>(a, row) * D, D, lane, scale);
+            if (lane == 0) s_own[mm] = sc;
         }
-        for (; c < c_end; c += NW) {
-            const bool more = c + NW < c_end;  // wavefront-uniform
-            float s[8];
-            float mx = -INFINITY;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int cc = 0; cc < DC; ++cc)
-#pragma unroll
-                    for (int t = 0; t < 3; ++t)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kA[tt][cc]), qop[cc][t], acc, 0, 0, 0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int slot = 32 * c + 8 * g + 4 * tt + i;
-                    const float v = slot < lim ? acc[i] * scale : -INFINITY;
-                    s[4 * tt + i] = v;
-                    mx = fmaxf(mx, v);
-                }
+        for (int u = 0; u < kOwnMax; ++u) {
+            const int idx = tid + u * (int)blockDim.x, mm = idx / D, dd = idx - mm * D, m = m0 + mm;
+            v_own[u] = 0.f;
+            if (idx < 16 * D && m < M_total && am_prefix_end<TREE>(a, m / group) <= range) {
+                const int own = am_own_slot<TREE>(a, m / group);
+                v_own[u] = am_bf(vt[((size_t)(own >> 3) * D + dd) * 8 + (own & 7)]);
             }
-            if (more) load_keys(c + NW, kA);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float mn = fmaxf(m_run, mx);
-            const float ms = mn == -INFINITY ? 0.f : mn;  // nothing live yet: every exponential below is 0
-            const float corr = __expf(m_run - ms);
-            float ps = 0.f;
-            uint16_t ph[8], pl[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float p = __expf(s[j] - ms);
-                ps += p;
-                const uint32_t hb = f32_to_bf16_rne_finite(p);
-                ph[j] = (uint16_t)hb;
-                pl[j] = (uint16_t)f32_to_bf16_rne_finite(p - __uint_as_float(hb << 16));
-            }
-            const bf16x8 phi = am_pack(ph), plo = am_pack(pl);
-            l_run = l_run * corr + ps;
-            m_run = mn;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                o[dt] *= corr;
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vA[dt]), phi, o[dt], 0, 0, 0);
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vA[dt]), plo, o[dt], 0, 0, 0);
-            }
-            if (more) load_values(c + NW, vA);
         }
+    }
+
+    // ---- this wavefront's chunks: every NW-th of the range, folded in order.  The keys of the next chunk are
+    // requested before the current chunk's scores are computed (two sets of key registers, used in turn); the
+    // value operands are dead once they are multiplied, so the next chunk's values are requested right after
+    // the second product, into the same registers.
+    auto step = [&](int c, const u32x4(&kCur)[2][DC], u32x4(&kNxt)[2][DC]) {
+        const bool more = c + NW < c_end;  // wavefront-uniform
+        if (more) load_keys(c + NW, kNxt);
+        float s[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int cc = 0; cc < DC; ++cc)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kCur[tt][cc]), qop[cc][t], acc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int slot = 32 * c + 8 * g + 4 * tt + i;
+                const float v = slot < lim ? acc[i] * scale : -INFINITY;
+                s[4 * tt + i] = v;
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mn = fmaxf(m_run, mx);
+        const float ms = mn == -INFINITY ? 0.f : mn;  // nothing live yet: every exponential below is 0
+        const float corr = __expf(m_run - ms);
+        float ps = 0.f;
+        uint16_t ph[8], pl[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float p = __expf(s[j] - ms);
+            ps += p;
+            const uint32_t hb = f32_to_bf16_rne_finite(p);
+            ph[j] = (uint16_t)hb;
+            pl[j] = (uint16_t)f32_to_bf16_rne_finite(p - __uint_as_float(hb << 16));
+        }
+        const bf16x8 phi = am_pack(ph), plo = am_pack(pl);
+        l_run = l_run * corr + ps;
+        m_run = mn;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            o[dt] *= corr;
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vA[dt]), phi, o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vA[dt]), plo, o[dt], 0, 0, 0);
+        }
+        if (more) load_values(c + NW, vA);
+    };
+    for (; c < c_end; c += 2 * NW) {
+        step(c, kA, kB);
+        if (c + NW < c_end) step(c + NW, kB, kA);
     }
 
     // ---- merge the wavefronts (in wavefront order), then finish the rows whose prefix ends in the first
@@ -257,21 +303,11 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) wbase[32 + col * MP + 16 * dt + 4 * g + i] = o[dt][i];
-    float *s_own = am_sh + (size_t)NW * (16 * (MP + 2));
     __syncthreads();
-    if (sp == 0) {
-        for (int mm = wave; mm < 16; mm += NW) {
-            const int m = m0 + mm;
-            if (m >= M_total) continue;
-            const int row = m / group, head = m - row * group;
-            if (am_prefix_end<TREE>(a, row) > range) continue;  // finished by the combine kernel
-            const float sc = am_own_score(a.q + ((size_t)row * nq + kvh * group + head) * D,
-                                          kc + (size_t)am_own_slot<TREE>(a, row) * D, D, lane, scale);
-            if (lane == 0) s_own[mm] = sc;
-        }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < 16 * D; idx += blockDim.x) {
+#pragma unroll
+    for (int u = 0; u < kOwnMax; ++u) {
+        const int idx = tid + u * (int)blockDim.x;
+        if (idx >= 16 * D) break;
         const int mm = idx / D, dd = idx - mm * D;
         const int m = m0 + mm;
         if (m >= M_total) continue;
@@ -291,9 +327,7 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
         }
         const int qh = kvh * group + head;
         if (nsr <= 1) {
-            const int own = am_own_slot<TREE>(a, row);
-            const float v_own = am_bf(vt[((size_t)(own >> 5) * D + dd) * 32 + (own & 31)]);
-            am_write(a, row, qh * D + dd, am_finish(mn, ls, os, s_own[mm], v_own));
+            am_write(a, row, qh * D + dd, am_finish(mn, ls, os, s_own[mm], v_own[u]));
         } else {
             const size_t slot = ((size_t)row * nq + qh) * n_split + sp;
             a.part_o[slot * D + dd] = os;
@@ -306,10 +340,12 @@ __global__ __launch_bounds__(512) void k_attn_mfma(AttnArgs a, int range, int hi
 }
 
 // Rows whose prefix spans several ranges: merges the ranges' partial results in range order, then the own
-// slot.  One wavefront per (query head, row).
+// slot.  One workgroup of two wavefronts per (query head, row): thread t owns value element t; the first
+// wavefront also computes the own slot's score.
 template <bool TREE>
-__global__ __launch_bounds__(64) void k_attn_mfma_combine(AttnArgs a, int range, int n_split) {
-    const int head = blockIdx.x, row = blockIdx.y, lane = threadIdx.x, d = a.head_dim;
+__global__ __launch_bounds__(128) void k_attn_mfma_combine(AttnArgs a, int range, int n_split) {
+    __shared__ float sh_own;
+    const int head = blockIdx.x, row = blockIdx.y, tid = threadIdx.x, d = a.head_dim;
     const int pe = am_prefix_end<TREE>(a, row);
     const int nsr = (pe + range - 1) / range;
     if (nsr <= 1) return;  // finished by the attention kernel itself
@@ -317,22 +353,42 @@ __global__ __launch_bounds__(64) void k_attn_mfma_combine(AttnArgs a, int range,
     const uint16_t *kc = (const uint16_t *)a.kcache + (size_t)kvh * a.max_seq * d;
     const uint16_t *vt = (const uint16_t *)a.vcache + (size_t)kvh * a.nb32 * d * 32;
     const int own = am_own_slot<TREE>(a, row);
-    const float s_own = am_own_score(a.q + ((size_t)row * a.n_q_heads + head) * d, kc + (size_t)own * d, d, lane,
-                                     1.0f / sqrtf((float)d));
     const size_t base = ((size_t)row * a.n_q_heads + head) * n_split;
-    float mn = -INFINITY;
-    for (int s = 0; s < nsr; ++s) mn = fmaxf(mn, a.part_ml[(base + s) * 2]);
-    for (int dd = lane; dd < d; dd += 64) {
-        float ls = 0.f, os = 0.f;
-        for (int s = 0; s < nsr; ++s) {
-            const float ms = a.part_ml[(base + s) * 2];
-            const float c = ms == -INFINITY ? 0.f : __expf(ms - mn);
-            ls += a.part_ml[(base + s) * 2 + 1] * c;
-            os += a.part_o[(base + s) * d + dd] * c;
+    const float *__restrict__ ml = a.part_ml + base * 2;
+    const float *__restrict__ po = a.part_o + base * d + tid;
+    // everything this thread needs, requested together: the ranges' (max, sum) pairs and its element of their
+    // weighted values, eight ranges at a time
+    const bool live = tid < d;
+    const float v_own = live ? am_bf(vt[((size_t)(own >> 3) * d + tid) * 8 + (own & 7)]) : 0.f;
+    float mn = -INFINITY, ls = 0.f, os = 0.f;
+    for (int s0 = 0; s0 < nsr; s0 += 8) {
+        float m8[8], l8[8], o8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int sidx = min(s0 + u, nsr - 1);
+            m8[u] = ml[2 * sidx];
+            l8[u] = ml[2 * sidx + 1];
+            o8[u] = live ? po[(size_t)sidx * d] : 0.f;
         }
-        const float v_own = am_bf(vt[((size_t)(own >> 5) * d + dd) * 32 + (own & 31)]);
-        am_write(a, row, head * d + dd, am_finish(mn, ls, os, s_own, v_own));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (s0 + u >= nsr) break;
+            // running merge in range order (a range's maximum is -inf only if its rows see nothing there)
+            const float m2 = fmaxf(mn, m8[u]);
+            const float c1 = mn == -INFINITY ? 0.f : __expf(mn - m2);
+            const float c2 = m8[u] == -INFINITY ? 0.f : __expf(m8[u] - m2);
+            ls = ls * c1 + l8[u] * c2;
+            os = os * c1 + o8[u] * c2;
+            mn = m2;
+        }
     }
+    if (tid < 64) {
+        const float sc = am_own_score(a.q + ((size_t)row * a.n_q_heads + head) * d, kc + (size_t)own * d, d, tid,
+                                      1.0f / sqrtf((float)d));
+        if (tid == 0) sh_own = sc;
+    }
+    __syncthreads();
+    if (live) am_write(a, row, head * d + tid, am_finish(mn, ls, os, sh_own, v_own));
 }
 
 // The launch shape.  Everything that shapes a row's arithmetic (wavefronts per workgroup, slots per range)
@@ -354,8 +410,8 @@ AmPlan am_plan(const AttnArgs &a, int n_cu) {
     int want = single ? 1 : (2 * n_cu + a.n_kv_heads - 1) / a.n_kv_heads;
     if (want > a.max_split) want = a.max_split;
     if (want < 1) want = 1;
-    const int gran = 32 * p.nw;
-    p.range = ((a.max_seq + want - 1) / want + gran - 1) / gran * gran;
+    // (whole chunks; a range need not hold the same number of chunks for every wavefront)
+    p.range = std::max(32 * p.nw, ((a.max_seq + want - 1) / want + 31) / 32 * 32);
     if (a.tree) {
         int deepest = 0;
         for (int r = 0; r < a.rows; ++r) deepest = std::max(deepest, am_nibble(a.depth4, a.row_base + r));
@@ -384,7 +440,7 @@ int attn_mfma_path_name(const AttnArgs &a, int n_cu, char *out, int capacity) {
 
 hipError_t launch_attn_mfma(const AttnArgs &a, int n_cu, hipStream_t s) {
     if ((a.head_dim != 64 && a.head_dim != 128) || a.rows < 1 || a.rows > kAttnMfmaMaxRows || a.nb32 < (a.max_seq + 31) / 32 ||
-        a.n_kv_heads < 1 || a.n_q_heads % a.n_kv_heads != 0 || !a.q || !a.kcache || !a.vcache || (!a.out && !a.out_s) ||
+        a.n_kv_heads < 1 || a.n_q_heads % a.n_kv_heads != 0 || !a.q || !a.q_s || !a.kcache || !a.vcache || (!a.out && !a.out_s) ||
         !a.part_o || !a.part_ml)
         return hipErrorInvalidValue;
     if (a.tree ? (a.row_base < 0 || a.row_base + a.rows > 16 || a.n_base < 0 || a.n_base + a.row_base + a.rows > a.max_seq)
@@ -416,9 +472,9 @@ hipError_t launch_attn_mfma(const AttnArgs &a, int n_cu, hipStream_t s) {
     if (e != hipSuccess || p.n_split == 1) return e;
     const dim3 cgrid(a.n_q_heads, a.rows);
     if (a.tree)
-        hipLaunchKernelGGL(k_attn_mfma_combine<true>, cgrid, dim3(64), 0, s, a, p.range, p.n_split);
+        hipLaunchKernelGGL(k_attn_mfma_combine<true>, cgrid, dim3(128), 0, s, a, p.range, p.n_split);
     else
-        hipLaunchKernelGGL(k_attn_mfma_combine<false>, cgrid, dim3(64), 0, s, a, p.range, p.n_split);
+        hipLaunchKernelGGL(k_attn_mfma_combine<false>, cgrid, dim3(128), 0, s, a, p.range, p.n_split);
     return hipGetLastError();
 }
 

@@ -78,20 +78,22 @@ struct AttnArgs {
     // the same way, as a chain row at position n_base + depth, so the result is the chain's bit for bit.
     int tree, n_base, row_base;
     uint64_t depth4, spine4;
-    // Matrix-core attention (bf16 cache, heads of 64 or 128; attn_mfma_applies): the values are stored
-    // transposed in blocks of 32 slots (see kv_vt_index), nb32 blocks per kv head.
+    // Matrix-core attention (bf16 cache, heads of 64 or 128; attn_mfma_applies): the values are stored in
+    // groups of eight slots (see kv_vt_index), nb32 chunks of 32 slots per kv head.
     int nb32;
+    const uint16_t *q_s;          // matrix-core attention: the query rows as two bf16 terms, [rows][n_q][2][d]
 };
 // ------------------------------------------------------------------------------------------
 // key/value cache layouts
 // ------------------------------------------------------------------------------------------
 // Keys: [kv head][slot][d].  Values: the same, except for bf16 caches with heads of 64 or 128, whose
 // attention runs on the matrix cores and wants eight consecutive slots of one value element in one 16-byte
-// load: there the values are stored transposed in blocks of 32 slots, [kv head][slot / 32][element][slot % 32]
-// (nb32 = ceil(max_seq / 32) blocks per head).
+// load: there the values are stored in groups of eight slots, [kv head][slot / 8][element][slot % 8], with
+// 4 * nb32 groups per head (nb32 = ceil(max_seq / 32): whole 32-slot chunks).  A token's values then land 16
+// bytes apart inside one 16 * d byte region, and the 32 slots of a chunk are one contiguous 64 * d bytes.
 inline bool attn_mfma_applies(int dtype, int head_dim) { return dtype == 1 /* BF16 */ && (head_dim == 64 || head_dim == 128); }
 __host__ __device__ inline size_t kv_vt_index(int kv_head, int nb32, int d, int slot, int elem) {
-    return (((size_t)kv_head * nb32 + (slot >> 5)) * d + elem) * 32 + (slot & 31);
+    return (((size_t)kv_head * nb32 * 4 + (slot >> 3)) * d + elem) * 8 + (slot & 7);
 }
 // Rows one launch of the matrix-core attention kernel takes (two tiles of 16 members for one kv head per
 // workgroup; more members go to further workgroups)
@@ -230,7 +232,9 @@ struct MvArgs {
     // of a token tree (tree != 0, R <= 16), for position pos0 + nibble r of depth4 (the row's level)
     int tree;
     uint64_t depth4;
-    int nb32;              // QKV: > 0: the values go to the transposed layout (kv_vt_index) with nb32 blocks per head
+    int nb32;              // QKV: > 0: the values go to the grouped layout (kv_vt_index), nb32 32-slot chunks per head
+    uint16_t *q_s;         // QKV: nullptr, or [R][n_q][2][d]: the rotated queries once more, as two bf16 terms (hi, then
+                           // what is left of the fp32 value after hi), the operand form of the matrix-core attention
     // multi-row kernel only: split-K scratch
     float *part;           // [k splits][row group][R][16] fp32 partial results
     int *counters;         // one per 8-row-group block, zero between launches

@@ -708,12 +708,12 @@ hipError_t launch_kv_move(int dtype, const KvMoveArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 // NaN-fills every value of slots >= first_slot of every kv head of one layer's value plane.
 __global__ void k_vt_poison(uint16_t *plane, int n_kv, int nb32, int d, int first_slot) {
-    const int64_t per_head = (int64_t)nb32 * d * 32;
-    const int64_t first = (int64_t)(first_slot >> 5) * d * 32;  // blocks below hold committed slots only
+    const int64_t per_head = (int64_t)nb32 * 32 * d;
+    const int64_t first = (int64_t)(first_slot >> 3) * d * 8;  // groups below hold committed slots only
     const int64_t n = (int64_t)n_kv * (per_head - first);
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t h = i / (per_head - first), r = first + i % (per_head - first);
-        const int slot = (int)(r / ((int64_t)d * 32)) * 32 + (int)(r & 31);
+        const int slot = (int)(r / ((int64_t)d * 8)) * 8 + (int)(r & 7);
         if (slot >= first_slot) plane[h * per_head + r] = 0x7fc0;
     }
 }

@@ -7,6 +7,22 @@
 
 namespace swift {
 
+// Values in the grouped layout (kv_vt_index) are written two bytes at a time into 128-byte lines that the
+// pass fills only partly, and such a store completes only once the rest of the line has been fetched.  The
+// projection kernel therefore touches the lines its epilogue will write while the weights stream: lane
+// (block row r, half) of the calling wavefront reads one word of the line that holds elements 8 g .. 8 g + 7
+// (+ d/2) of row r's slot; rg is a row group of the value part of the fused q|k|v matrix (else nothing
+// happens).  The loaded word is only kept alive, never used.
+__device__ inline void mv_touch_value_lines(const MvArgs &a, int rg, int lane) {
+    const int d = a.head_dim, half = d >> 1, gph = half >> 3;
+    const int hh = rg / gph, head = hh - a.n_q_heads - a.n_kv_heads;
+    const int r = lane >> 1;
+    if (a.nb32 <= 0 || head < 0 || head >= a.n_kv_heads || r >= a.R) return;
+    const int i = 8 * (rg - hh * gph) + (lane & 1) * half;
+    const uint32_t w = *(const volatile uint32_t *)((const uint16_t *)a.vcache + (kv_vt_index(head, a.nb32, d, a.pos0 + r, i) & ~(size_t)1));
+    asm volatile("" ::"v"(w));
+}
+
 // What follows the dot products of one 16-row group, run by one whole wavefront.
 // Y(r, j): finished dot product of block row r and tile row j (before the norm scale).
 // rot: optional LDS copy of the rotary rows, [R][d/2 cos | d/2 sin]; nullptr = read the tables.
@@ -72,15 +88,23 @@ __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const floa
                         float *qp = a.out_f32 + (size_t)r * a.ld_out + hh * d + i;
                         qp[0] = qa;
                         qp[half] = qb;
+                        if (a.q_s) {
+                            uint16_t *qs = a.q_s + ((size_t)(r * nq + hh) * 2) * d + i;
+                            const uint32_t ha = f32_to_bf16_rne_finite(qa), hb = f32_to_bf16_rne_finite(qb);
+                            qs[0] = (uint16_t)ha;
+                            qs[half] = (uint16_t)hb;
+                            qs[d] = (uint16_t)f32_to_bf16_rne_finite(qa - __uint_as_float(ha << 16));
+                            qs[d + half] = (uint16_t)f32_to_bf16_rne_finite(qb - __uint_as_float(hb << 16));
+                        }
                     } else {
                         uint16_t *kc = (uint16_t *)a.kcache + ((size_t)(hh - nq) * a.max_seq + pos) * d + i;
                         kc[0] = f32_to_bf16_rne(qa);
                         kc[half] = f32_to_bf16_rne(qb);
                     }
-                } else if (a.nb32 > 0) {  // values transposed in blocks of 32 slots
+                } else if (a.nb32 > 0) {  // values in groups of eight slots
                     uint16_t *vc = (uint16_t *)a.vcache + kv_vt_index(hh - nq - nkv, a.nb32, d, pos, i);
                     vc[0] = f32_to_bf16_rne(ya);
-                    vc[half * 32] = f32_to_bf16_rne(yb);
+                    vc[half * 8] = f32_to_bf16_rne(yb);
                 } else {
                     uint16_t *vc = (uint16_t *)a.vcache + ((size_t)(hh - nq - nkv) * a.max_seq + pos) * d + i;
                     vc[0] = f32_to_bf16_rne(ya);

@@ -267,15 +267,25 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         if (p < 0) return;
         const size_t head_units = (size_t)a.max_seq * a.head_dim / 8;  // 16-byte units of one head
         const int n_units = a.pf_rows * a.head_dim / 8;
-        // (values in transposed blocks of 32 slots: the blocks that hold rows [0, pf_rows) are contiguous too)
+        // (values in groups of eight slots: the groups that hold rows [0, pf_rows) are contiguous too)
         const size_t v_head_units = a.nb32 > 0 ? (size_t)a.nb32 * 32 * a.head_dim / 8 : head_units;
         const int v_units = a.nb32 > 0 ? (a.pf_rows + 31) / 32 * 32 * a.head_dim / 8 : n_units;
         u32x4 x = {0u, 0u, 0u, 0u};
         for (int gh = p; gh < a.pf_heads; gh += a.pf_wgs) {
             const u32x4 *kp = (const u32x4 *)a.kcache + (size_t)gh * head_units;
             const u32x4 *vp = (const u32x4 *)a.vcache + (size_t)gh * v_head_units;
-            for (int i = tid; i < n_units; i += 512) x ^= kp[i];
-            for (int i = tid; i < v_units; i += 512) x ^= vp[i];
+            // (eight steps' loads requested together: one step at a time, the loop is a chain of memory latencies)
+            for (int i0 = tid; i0 < v_units; i0 += 8 * 512) {  // (v_units >= n_units)
+                u32x4 t[16];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = i0 + 512 * u;
+                    t[2 * u] = i < n_units ? kp[i] : u32x4{0u, 0u, 0u, 0u};  // (plain loads: the lines are meant to stay in L2)
+                    t[2 * u + 1] = i < v_units ? vp[i] : u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) x ^= t[u];
+            }
         }
         // (keeps the loads alive; the flag word is never all ones)
         if ((x.x & x.y & x.z & x.w) == 0xffffffffu && a.pf_rows < 0) ((volatile uint32_t *)smem)[0] = x.x;
@@ -322,6 +332,9 @@ __global__ __launch_bounds__(512, 4) void k_mv1(MvArgs a) {  // 4 wavefronts per
         auto side_loads = [&]() {
             if (tid < 4) ((uint32_t *)smem)[tid] = 0u;
             if (EPI == EPI_QKV) {
+                // the lines the epilogues of this workgroup's rounds will write values into (wavefront s: round s)
+                if (wave < a.S)
+                    for (int gg = 0; gg < G; ++gg) mv_touch_value_lines(a, min((wave * W + (int)blockIdx.x) * G + gg, last_rg), lane);
                 const int d = a.head_dim, half = d >> 1;
                 for (int i = tid; i < R * half; i += 512) {
                     const int r = i / half, e = i - r * half;
@@ -613,6 +626,10 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
 #pragma unroll
     for (int g = 0; g < RG; ++g)  // row groups past the end repeat the last one; their results are dropped
         base[g] = (const u32x4 *)a.Wt + ((size_t)min(rg0 + g, a.n_rg - 1) * T + tb) * 64 + lane;
+    if (EPI == EPI_QKV && active) {  // the lines this wavefront's epilogue will write values into
+#pragma unroll
+        for (int g = 0; g < RG; ++g) mv_touch_value_lines(a, min(rg0 + g, a.n_rg - 1), lane);
+    }
     const u32x4 *bsrc = (const u32x4 *)a.in_s;
     const int real_units = (a.K >> 3) * NC;
     const int chunk_units = 4 * CT * NC;  // 16-byte units of one B chunk (<= 512 NQ)
