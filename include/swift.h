@@ -32,7 +32,7 @@
  *
  * Guarantee: a token's logits, and the keys and values it leaves in the cache, do
  * not depend on how many rows share its pass (one-row decoding, a draft pass, a
- * verify block of 2..16 rows): every kernel adds a row's products in the same
+ * verify block or token tree of 2..32 rows): every kernel adds a row's products in the same
  * order.  Speculative greedy decoding therefore reproduces plain greedy decoding
  * of the same context exactly (paper Sections 1 and 3.1), not just up to
  * rounding.  Prefill blocks use an order of their own; both decoding modes share
@@ -56,8 +56,9 @@ extern "C" {
 #define SWIFT_F32 0
 #define SWIFT_BF16 1
 
-/* Largest number of rows one verify block may hold (pending token + k drafts): k <= SWIFT_MAX_BLOCK - 1. */
-#define SWIFT_MAX_BLOCK 16
+/* Largest number of rows one verify block or token tree may hold (pending token + k drafts): k <=
+ * SWIFT_MAX_BLOCK - 1.  The paper's maximum draft length is 25 (Appendix B.2): a chain block of 26 rows. */
+#define SWIFT_MAX_BLOCK 32
 /* Longest context window of a candidate evaluation (gamma of Section 4.1.2; Table 9 goes up to 128). */
 #define SWIFT_MAX_WINDOW 128
 
@@ -226,7 +227,7 @@ int swift_verify(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_t
  * All contexts of a process share one array per GPU, and it keeps the last call's contents: calls that
  * overlap on one GPU (two streams, two threads) race; one call at a time per GPU.
  * State changes, errors and the following swift_accept are exactly those of swift_verify. */
-#define SWIFT_STATIC_SCRATCH_BYTES (24u << 20)
+#define SWIFT_STATIC_SCRATCH_BYTES (32u << 20)
 int swift_verify_static(swift_ctx *ctx, const int32_t *tokens, int k, int32_t *target_tokens, float *logits_out);
 
 /* Acceptance + roll-back after a swift_verify: m = swift_match_prefix(tokens[1..k], targets);
@@ -247,11 +248,12 @@ int swift_accept(swift_ctx *ctx, int32_t *emitted, int *n_emitted);
 int swift_topk_width(float p);
 
 /* swift_draft_step that also keeps candidates: position j = 1..*k_out gets width[j-1] =
- * min(swift_topk_width(p_j), max_width, rows still free in the block) tokens in
+ * min(swift_topk_width(p_j), max_width, rows still free in the block) tokens (a block holds at most
+ * min(SWIFT_MAX_BLOCK, max_seq - n) rows: every row takes a cache slot of its own) in
  * tokens[(j-1)*SWIFT_TOPK ..] (host, [max_k][SWIFT_TOPK]; largest logit first, equal logits in id order;
  * the first is the draft token the next position continues from).  Drafting ends as in swift_draft_step, or
  * when the block is full.  draft_conf, width: host, max_k entries.  max_width >= 1 (1: the plain chain).
- * Needs 0 <= max_k <= SWIFT_MAX_BLOCK - 1 and n + SWIFT_MAX_BLOCK <= max_seq (SWIFT_ECAPACITY). */
+ * Needs 0 <= max_k <= SWIFT_MAX_BLOCK - 1 and n < max_seq (SWIFT_ECAPACITY). */
 int swift_draft_step_topk(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float conf_threshold, int max_width,
                           int32_t *tokens, float *draft_conf, int *width, int *k_out);
 

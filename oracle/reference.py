@@ -343,7 +343,7 @@ class Oracle:
                                  C.byref(nm), _p(lg, C.c_double) if want_logits else None), "ora_eval_mask")
         return (pred, nm.value, lg) if want_logits else (pred, nm.value)
 
-    TREE_ROWS = 16
+    TREE_ROWS = 32
     TOPK = 10
 
     def draft_step_topk(self, skip: np.ndarray, max_k: int, conf_threshold: float, max_width: int = 10):

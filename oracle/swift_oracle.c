@@ -87,7 +87,8 @@
 #define ORA_F32 0
 #define ORA_BF16 1
 #define ORA_MAX_BLOCK 64
-#define ORA_TREE_ROWS 16 /* rows of a token tree block: the pending token + all candidates */
+#define ORA_TREE_ROWS 32 /* rows of a token tree block: the pending token + all candidates (room for the
+                            paper's maximum draft length of 25, Appendix B.2) */
 #define ORA_TOPK 10      /* widest candidate set of one draft position */
 
 typedef struct {
@@ -838,17 +839,18 @@ void ora_topk(const double *logits, int n, int k, int32_t *tokens) {
 /* Drafting as in ora_draft_step, keeping for every draft position j its top candidates
  * tokens[j][0..width[j]) (tokens[j][0] is the draft token the next position continues from) with
  * width[j] = min(ora_topk_width(p_j), max_width, rows left), where a block holds at most
- * ORA_TREE_ROWS rows (the pending token and all candidates); drafting also stops when no row is
- * left.  tokens: [max_k][ORA_TOPK]. */
+ * min(ORA_TREE_ROWS, max_seq - n) rows (the pending token and all candidates; every row needs a cache
+ * slot of its own); drafting also stops when no row is left.  tokens: [max_k][ORA_TOPK]. */
 int ora_draft_step_topk(ora_model *m, const uint8_t *skip, int max_k, double conf_threshold, int max_width,
                         int32_t *tokens, double *draft_conf, int *width, int *k_out) {
     if (!m || !skip || !tokens || !width || max_k < 0 || max_k > ORA_TREE_ROWS - 1 || max_width < 1) return ORA_EINVAL;
     if (m->pending < 0) return ORA_ESTATE;
-    if (m->n + ORA_TREE_ROWS > m->c.max_seq) return ORA_ECAPACITY;
+    const int cap_rows = m->c.max_seq - m->n < ORA_TREE_ROWS ? m->c.max_seq - m->n : ORA_TREE_ROWS;
+    if (cap_rows < 1) return ORA_ECAPACITY;
     double *lg = (double *)malloc(sizeof(double) * (size_t)m->c.vocab);
     int32_t prev = m->pending;
     int k = 0, rows = 1;
-    for (int j = 1; j <= max_k && rows < ORA_TREE_ROWS; ++j) {
+    for (int j = 1; j <= max_k && rows < cap_rows; ++j) {
         int rc = ora_forward_row(m, prev, m->n + j - 1, skip, lg);
         if (rc) {
             free(lg);
@@ -860,7 +862,7 @@ int ora_draft_step_topk(ora_model *m, const uint8_t *skip, int max_k, double con
         m->n_draft_passes++;
         int w = ora_topk_width(p);
         if (w > max_width) w = max_width;
-        if (w > ORA_TREE_ROWS - rows) w = ORA_TREE_ROWS - rows;
+        if (w > cap_rows - rows) w = cap_rows - rows;
         if (w > m->c.vocab) w = m->c.vocab;
         ora_topk(lg, m->c.vocab, w, tokens + (size_t)k * ORA_TOPK);
         width[k] = w;

@@ -10,7 +10,7 @@ import numpy as np
 from . import build as _build
 
 F32, BF16 = 0, 1
-MAX_BLOCK = 16
+MAX_BLOCK = 32
 MAX_WINDOW = 128   # longest candidate-evaluation window (SWIFT_MAX_WINDOW)
 TOPK = 10
 KERNEL_CLASSES = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lmhead": 5, "other": 6}

@@ -332,12 +332,9 @@ char *kv_base(swift_ctx *x, int layer, int which) {
     return x->base + x->L.kv + (uint64_t)layer * (x->L.kv_k_bytes + x->L.kv_v_bytes) + (which ? x->L.kv_k_bytes : 0);
 }
 
-// The rows of a token tree: level of each block row, block row of the first candidate of each level
-// (the only one with children), both also packed as 4-bit fields for the kernels.
-struct TreeRows {
-    int depth[kMaxRows], spine[kMaxRows];
-    uint64_t depth4, spine4;
-};
+// The rows of a token tree: level of each block row, block row of the first candidate of each level (the only
+// one with children).
+typedef TreeTab TreeRows;
 
 // ---- storage-generic path: one token through the network at position `pos`; row = which row of
 // the activation / logits buffers to use.  skip == nullptr: full model.  want_logits: run the LM
@@ -410,8 +407,7 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
                 a.tree = 1;
                 a.n_base = tree_base;
                 a.row_base = row;
-                a.depth4 = tree->depth4;
-                a.spine4 = tree->spine4;
+                a.tt = *tree;
             }
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * eb * (pos + 1),
                           [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
@@ -435,8 +431,11 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
 // network in one sweep over the weights.  Row r attends cache slots [0, pos0 + r].
 // tree: the rows are those of a token tree (R <= 16): row r goes to slot pos0 + r, is rotated for position
 // pos0 + its level, and attends the committed slots and the rows on its path from the root.
+// exact: the block's rows must come out as they would from any other block size (draft, verify and tree
+// passes: the exact layouts, up to kMaxRows rows); otherwise blocks of more than 16 rows take the bulk layouts.
 int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
-                        bool reuse_kv = false, const TreeRows *tree = nullptr) {
+                        bool reuse_kv, const TreeRows *tree, bool exact) {
+    const int RLC = block_row_layout(R, exact);  // layout code of every split activation of this pass
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -469,8 +468,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.T = (K + 31) / 32;
         m.n_rg = n_rg;
         m.R = R;
-        m.RL = block_row_layout(R);
-        m.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
+        m.RL = RLC;
+        m.rp = block_row_pitch(R);
         m.eps = c.rms_eps;
         m.norm_dim = H;
         m.pos0 = pos0;
@@ -519,7 +518,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.q_s = L.mfma_attn ? dptr<uint16_t>(x, L.q_s) : nullptr;
             if (tree) {
                 m.tree = 1;
-                m.depth4 = tree->depth4;
+                memcpy(m.depth, tree->depth, sizeof(m.depth));
             }
             // the committed keys/values the attention launch will read: warmed into L2 by spare workgroups of
             // this launch (one-workgroup-per-head attention only: its workgroup-to-head mapping is what the
@@ -554,8 +553,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                 a.tree = 1;
                 a.n_base = pos0;
                 a.row_base = 0;
-                a.depth4 = tree->depth4;
-                a.spine4 = tree->spine4;
+                a.tt = *tree;
             }
             list.push_back(at);
 
@@ -603,8 +601,8 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     ea.xs = xs;
     ea.gain_next = gain_of(0);
     ea.pss = pss;
-    ea.rp = R <= kMaxRows ? 16 : kMaxBlockRows;
-    ea.RL = block_row_layout(R);
+    ea.rp = block_row_pitch(R);
+    ea.RL = RLC;
     HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
 
     // ---- one launch per stage
@@ -612,24 +610,24 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         const int kc = list[i].kc;
         if (list[i].epi < 0 && attn_block_applies(c.dtype, list[i].at)) {
             AttnArgs a = list[i].at;
-            a.out_rows = block_row_layout(R);
+            a.out_rows = RLC;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
                           [&] { return launch_attn_block(a, x->n_cu, s); }));
         } else if (list[i].epi < 0 && L.mfma_attn) {
             AttnArgs a = list[i].at;
-            a.out_rows = block_row_layout(R);
+            a.out_rows = RLC;
             HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R), [&] { return launch_attn_mfma(a, x->n_cu, s); }));
         } else if (list[i].epi < 0) {
-            // a launch of the split kernel covers up to 16 rows of the block (its partial buffers)
+            // a launch of the split kernel covers up to kMaxRows rows of the block (its partial buffers)
             const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
             for (int row0 = 0; row0 < R; row0 += per_launch) {
                 AttnArgs a = list[i].at;
                 a.q += (size_t)row0 * Q;
                 a.n_ctx += row0;
-                a.row_base = row0;  // (a tree has at most 16 rows: one part)
+                a.row_base = row0;  // (a tree has at most kMaxRows rows: one part)
                 a.rows = std::min(per_launch, R - row0);
-                a.out_s += 8 * block_terms(block_row_layout(R)) * row0;  // first of this part's term columns
-                a.out_rows = block_row_layout(R);
+                a.out_s += 8 * block_terms(RLC) * row0;  // first of this part's term columns
+                a.out_rows = RLC;
                 HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
                               [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
             }
@@ -652,9 +650,10 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
 // reuse_kv: the rows' keys and values are not computed; every row attends what the cache already holds
 // for slots up to its own position (candidate evaluation).
 int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
-                  bool reuse_kv = false, const TreeRows *tree = nullptr) {
-    if (tree && R > kMaxRows) return fail(SWIFT_EINVAL, "a token tree has at most 16 rows");
-    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits, reuse_kv, tree);
+                  bool reuse_kv = false, const TreeRows *tree = nullptr, bool exact = true) {
+    if (tree && R > kMaxRows) return fail(SWIFT_EINVAL, "a token tree has at most SWIFT_MAX_BLOCK rows");
+    if (exact && R > kMaxRows) return fail(SWIFT_EINVAL, "a verify block has at most SWIFT_MAX_BLOCK rows");
+    if (x->L.tiled) return forward_block_tiled(x, tokens, R, pos0, skip, want_logits, reuse_kv, tree, exact);
     for (int r = 0; r < R; ++r) {
         int rc = forward_row(x, tokens[r], pos0 + r, skip, r, want_logits, reuse_kv, tree, pos0);
         if (rc) return rc;
@@ -888,7 +887,7 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     const int block = x->L.tiled ? kMaxBlockRows : kMaxRows;
     for (int i = 0; i < n_prompt; i += block) {
         last_rows = std::min(block, n_prompt - i);
-        int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt);
+        int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt, false, nullptr, false);
         if (rc) return rc;
     }
     int rc = read_results(x, last_rows);
@@ -917,7 +916,7 @@ extern "C" int swift_eval_mask(swift_ctx *x, const uint8_t *skip_mask, const int
     int m = 0;
     for (int r0 = 0; r0 < gamma; r0 += kMaxBlockRows) {
         const int rows = std::min(kMaxBlockRows, gamma - r0);
-        int rc = forward_block(x, window + r0, rows, x->n - gamma + r0, skip_mask, true, true);
+        int rc = forward_block(x, window + r0, rows, x->n - gamma + r0, skip_mask, true, true, nullptr, false);
         if (rc) return rc;
         rc = read_results(x, rows);
         if (rc) return rc;
@@ -1039,7 +1038,7 @@ extern "C" int swift_verify_static(swift_ctx *x, const int32_t *tokens, int k, i
             m.T = (mt.K + 31) / 32;
             m.n_rg = mt.n_rg;
             m.R = R;
-            m.RL = block_row_layout(R);
+            m.RL = block_row_layout(R, true);
             m.head_dim = d;
             m.part_capacity = x->L.mv_part_capacity;
             const int slots = mv_split_slots(m, x->n_cu);
@@ -1099,13 +1098,15 @@ extern "C" int swift_draft_step_topk(swift_ctx *x, const uint8_t *skip_mask, int
     if (max_width < 1) return fail(SWIFT_EINVAL, "max_width must be at least 1");
     if (max_k > 0 && (!tokens || !draft_conf || !width)) return fail(SWIFT_EINVAL, "null output array");
     if (x->pending < 0) return fail(SWIFT_ESTATE, "draft before prefill");
-    if (x->n + SWIFT_MAX_BLOCK > x->c.max_seq) return fail(SWIFT_ECAPACITY, "a full tree block would run past the cache capacity");
+    // every row of the block needs a cache slot of its own
+    const int cap_rows = std::min(SWIFT_MAX_BLOCK, x->c.max_seq - x->n);
+    if (cap_rows < 1) return fail(SWIFT_ECAPACITY, "no cache slot left for the pending token");
     int32_t prev = x->pending;
     int k = 0, rows = 1;
     x->k_verify = -1;     // the draft overwrites slots an outstanding verification wrote: its accept must fail
     x->tree_levels = -1;
     x->k_sampled = -1;
-    for (int j = 1; j <= max_k && rows < SWIFT_MAX_BLOCK; ++j) {
+    for (int j = 1; j <= max_k && rows < cap_rows; ++j) {
         x->want_topk = true;
         int rc = forward_block(x, &prev, 1, x->n + j - 1, skip_mask, true);
         x->want_topk = false;
@@ -1116,7 +1117,7 @@ extern "C" int swift_draft_step_topk(swift_ctx *x, const uint8_t *skip_mask, int
         const float p = x->h_conf[0];
         int w = swift_topk_width(p);
         w = std::min(w, max_width);
-        w = std::min(w, SWIFT_MAX_BLOCK - rows);
+        w = std::min(w, cap_rows - rows);
         w = std::min(w, x->c.vocab);
         for (int i = 0; i < w; ++i) tokens[(size_t)k * SWIFT_TOPK + i] = x->h_topk[i];
         width[k] = w;
@@ -1142,15 +1143,12 @@ extern "C" int swift_verify_tree(swift_ctx *x, const int32_t *tokens, const int 
     for (int j = 1; j <= levels; ++j) {
         const int w = width[j - 1];
         if (w < 1 || w > SWIFT_TOPK) return fail(SWIFT_EINVAL, "level width out of range (1..10)");
-        if (rows + w > SWIFT_MAX_BLOCK) return fail(SWIFT_EINVAL, "more than 16 rows in the tree");
-        t.spine[j] = rows;
-        for (int i = 0; i < w; ++i) t.depth[rows++] = j;
+        if (rows + w > SWIFT_MAX_BLOCK) return fail(SWIFT_EINVAL, "more than SWIFT_MAX_BLOCK rows in the tree");
+        t.spine[j] = (uint8_t)rows;
+        for (int i = 0; i < w; ++i) t.depth[rows++] = (uint8_t)j;
     }
-    for (int r = 0; r < rows; ++r) {
+    for (int r = 0; r < rows; ++r)
         if (tokens[r] < 0 || tokens[r] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
-        t.depth4 |= (uint64_t)t.depth[r] << (4 * r);
-    }
-    for (int j = 0; j <= levels; ++j) t.spine4 |= (uint64_t)t.spine[j] << (4 * j);
     if (x->n + rows > x->c.max_seq) return fail(SWIFT_ECAPACITY, "block would run past the cache capacity");
     int rc = forward_block(x, tokens, rows, x->n, nullptr, true, false, &t);
     if (rc) return rc;
@@ -1466,7 +1464,7 @@ extern "C" int swift_debug_attn_path(swift_ctx *x, int rows, int tree, char *out
     a.n_base = x->n;
     a.nb32 = x->L.nb32;
     if (tree)  // (a chain of `rows` levels: the deepest tree of that many rows)
-        for (int r = 0; r < rows; ++r) a.depth4 |= (uint64_t)r << (4 * r);
+        for (int r = 0; r < rows; ++r) a.tt.depth[r] = a.tt.spine[r] = (uint8_t)r;
     if (x->L.tiled && attn_block_applies(c.dtype, a))
         snprintf(out, (size_t)capacity, "block<bf16, d %d>", c.head_dim);
     else if (x->L.mfma_attn)

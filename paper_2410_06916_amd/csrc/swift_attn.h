@@ -79,7 +79,7 @@ __device__ inline void attn_batch(const u32x4 (&kv)[NB], const u32x4 (&vv)[NB], 
 template <bool TREE>
 __device__ inline int attn_row_ctx(const AttnArgs &a, int row) {
     if constexpr (TREE)
-        return a.n_base + (int)((a.depth4 >> (4 * ((a.row_base + row) & 15))) & 15) + 1;
+        return a.n_base + (int)a.tt.depth[(a.row_base + row) & (kMaxRows - 1)] + 1;
     else
         return a.n_ctx + row;
 }
@@ -91,8 +91,8 @@ __device__ inline int attn_phys_slot(const AttnArgs &a, int row, int p) {
     if constexpr (TREE) {
         const int lvl = p - a.n_base;
         if (lvl < 0) return p;
-        const int depth = (int)((a.depth4 >> (4 * ((a.row_base + row) & 15))) & 15);
-        return a.n_base + (lvl < depth ? (int)((a.spine4 >> (4 * (lvl & 15))) & 15) : a.row_base + row);
+        const int depth = (int)a.tt.depth[(a.row_base + row) & (kMaxRows - 1)];
+        return a.n_base + (lvl < depth ? (int)a.tt.spine[lvl & (kMaxRows - 1)] : a.row_base + row);
     } else {
         return p;
     }
@@ -208,7 +208,7 @@ __device__ inline void attn_head_unit(const AttnArgs &a, int g, int row0, float 
         if (a.out_s) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
-            const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+            const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode), nt = block_terms(ocode);
             uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
                 split3(y, hi[i], mid[i], lw[i]);
             }
             if (a.out_s) {
-                const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+                const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode), nt = block_terms(ocode);
                 uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {

@@ -43,12 +43,10 @@ __device__ inline bf16x8 am_pack(const uint16_t (&v)[8]) {
     return __builtin_bit_cast(bf16x8, u);
 }
 
-__host__ __device__ inline int am_nibble(uint64_t t, int i) { return (int)((t >> (4 * (i & 15))) & 15); }
-
 // Logical slots [0, this) are launch row r's prefix; its own slot holds the row's key and value.
 template <bool TREE>
 __device__ inline int am_prefix_end(const AttnArgs &a, int r) {
-    return TREE ? a.n_base + am_nibble(a.depth4, a.row_base + r) : a.n_ctx - 1 + r;
+    return TREE ? a.n_base + (int)a.tt.depth[(a.row_base + r) & (kMaxRows - 1)] : a.n_ctx - 1 + r;
 }
 template <bool TREE>
 __device__ inline int am_own_slot(const AttnArgs &a, int r) {
@@ -58,7 +56,7 @@ __device__ inline int am_own_slot(const AttnArgs &a, int r) {
 // first row, then the first candidates of the levels in between.
 template <bool TREE>
 __device__ inline int am_phys(const AttnArgs &a, int p) {
-    if (TREE && p >= a.n_base) return a.n_base + am_nibble(a.spine4, p - a.n_base);
+    if (TREE && p >= a.n_base) return a.n_base + (int)a.tt.spine[(p - a.n_base) & (kMaxRows - 1)];
     return p;
 }
 
@@ -88,7 +86,7 @@ __device__ inline void am_write(const AttnArgs &a, int row, int e, float y) {
     if (a.out_s) {
         uint16_t hi, mid, lo;
         split3(y, hi, mid, lo);
-        const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+        const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode), nt = block_terms(ocode);
         uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
         p[0] = hi;
         p[8] = mid;
@@ -414,7 +412,7 @@ AmPlan am_plan(const AttnArgs &a, int n_cu) {
     p.range = std::max(32 * p.nw, ((a.max_seq + want - 1) / want + 31) / 32 * 32);
     if (a.tree) {
         int deepest = 0;
-        for (int r = 0; r < a.rows; ++r) deepest = std::max(deepest, am_nibble(a.depth4, a.row_base + r));
+        for (int r = 0; r < a.rows; ++r) deepest = std::max(deepest, (int)a.tt.depth[(a.row_base + r) & (kMaxRows - 1)]);
         p.hi_all = a.n_base + deepest;
     } else {
         p.hi_all = a.n_ctx - 1 + a.rows - 1;
@@ -443,7 +441,7 @@ hipError_t launch_attn_mfma(const AttnArgs &a, int n_cu, hipStream_t s) {
         a.n_kv_heads < 1 || a.n_q_heads % a.n_kv_heads != 0 || !a.q || !a.q_s || !a.kcache || !a.vcache || (!a.out && !a.out_s) ||
         !a.part_o || !a.part_ml)
         return hipErrorInvalidValue;
-    if (a.tree ? (a.row_base < 0 || a.row_base + a.rows > 16 || a.n_base < 0 || a.n_base + a.row_base + a.rows > a.max_seq)
+    if (a.tree ? (a.row_base < 0 || a.row_base + a.rows > kMaxRows || a.n_base < 0 || a.n_base + a.row_base + a.rows > a.max_seq)
                : (a.n_ctx < 1 || a.n_ctx - 1 + a.rows > a.max_seq))
         return hipErrorInvalidValue;
     const AmPlan p = am_plan(a, n_cu);

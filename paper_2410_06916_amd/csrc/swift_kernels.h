@@ -8,17 +8,28 @@
 
 namespace swift {
 
-constexpr int kMaxRows = 16;       // rows of one verify block (SWIFT_MAX_BLOCK)
+constexpr int kMaxRows = 32;       // rows of one verify block or token tree (SWIFT_MAX_BLOCK)
 constexpr int kMaxBlockRows = 64;  // rows of one prefill block
-// Rows the split-activation layouts of a block of R rows are pitched for: R itself up to 16 rows (verify
-// blocks), else 32 or 64 (prefill blocks, candidate evaluation windows).
-inline int block_row_layout(int R) { return R <= kMaxRows ? R : R <= 32 ? 32 : kMaxBlockRows; }
-// bf16 terms an fp32 activation is split into, by the layout's row count RL.  Up to 16 rows: three
-// (hi + mid + lo is the value exactly), so that a row's result does not depend on the rows it shares
-// a pass with.  Blocks of more than 16 rows (prefill, candidate evaluation) make no such promise and
-// carry the first two terms only (relative error 2^-17 per element): a third less to stage, read and
-// multiply.  Term t of row r is column terms * r + t.
-__host__ __device__ inline int block_terms(int RL) { return RL > kMaxRows ? 2 : 3; }
+// How the split activations of a block are laid out: a code that holds the rows the layout is pitched for and
+// how many bf16 terms an fp32 activation is split into.
+//  * exact layouts (draft, verify and tree blocks of up to kMaxRows rows; any block of up to 16 rows): pitched for
+//    the block's own row count, three terms (hi + mid + lo is the value exactly) and one fixed summation order,
+//    so that a row's result does not depend on the rows it shares a pass with;
+//  * bulk layouts (prefill blocks and candidate evaluation windows of more than 16 rows): pitched for 32 or 64
+//    rows, the first two terms only (relative error 2^-17 per element): a third less to stage, read and
+//    multiply, and no promise about the order.
+// Term t of row r is column terms * r + t.
+constexpr int kBulkLayout = 0x100;
+__host__ __device__ inline int layout_rows(int RL) { return RL & 0xff; }
+__host__ __device__ inline int block_terms(int RL) { return (RL & kBulkLayout) ? 2 : 3; }
+inline int block_row_layout(int R, bool exact) { return (exact || R <= 16) ? R : ((R <= 32 ? 32 : kMaxBlockRows) | kBulkLayout); }
+// Row pitch of the per-row-group partial sums of squares (pss): 16 for blocks of up to 16 rows, else 64.
+inline int block_row_pitch(int R) { return R <= 16 ? 16 : kMaxBlockRows; }
+// The rows of a token tree (block rows 0 .. rows-1): level of each row; block row of the first candidate of each
+// level (the only one with children; spine[0] = 0, the block's first row).
+struct TreeTab {
+    uint8_t depth[kMaxRows], spine[kMaxRows];
+};
 constexpr int kAttnMaxSplit = 64;  // most cache-length splits of one (row, kv head)
 constexpr int kGemvThreads = 256;  // 4 wavefronts of 64
 
@@ -67,17 +78,17 @@ struct AttnArgs {
     float *part_ml;               // [rows][n_q][n_split][2]   running max, running sum
     int max_split;                // splits the partial buffers can hold
     float *out;                   // fp32 [rows][n_q][d], or nullptr
-    uint16_t *out_s;              // bf16 term split [n_q*d/8][block_terms(out_rows)*out_rows][8], or nullptr
-    int out_rows;                 // rows of the block out_s belongs to (0: rows); a launch may cover a
-                                  // 16-row part of a larger block: out_s then points at its first column
-    // Token tree instead of a chain (tree != 0; at most 16 block rows).  Launch row r is block row
-    // row_base + r and sits at level depth(row) of the tree (nibble `row` of depth4); the block's
-    // keys/values sit in slots n_base + block row.  The row attends, in this order, the committed slots
-    // [0, n_base), then for level i = 0 .. depth-1 the slot of block row spine(i) (nibble i of spine4;
-    // spine(0) = 0, the block's first row), then its own slot: the same sequence of keys/values, batched
+    uint16_t *out_s;              // bf16 term split [n_q*d/8][terms * layout rows][8], or nullptr
+    int out_rows;                 // layout code (block_row_layout) of the block out_s belongs to (0: an exact layout
+                                  // of `rows` rows); a launch may cover a part of a larger block: out_s then points
+                                  // at its first column
+    // Token tree instead of a chain (tree != 0; at most kMaxRows block rows).  Launch row r is block row
+    // row_base + r and sits at level tt.depth[row] of the tree; the block's keys/values sit in slots
+    // n_base + block row.  The row attends, in this order, the committed slots [0, n_base), then for level
+    // i = 0 .. depth-1 the slot of block row tt.spine[i], then its own slot: the same sequence of keys/values, batched
     // the same way, as a chain row at position n_base + depth, so the result is the chain's bit for bit.
     int tree, n_base, row_base;
-    uint64_t depth4, spine4;
+    TreeTab tt;
     // Matrix-core attention (bf16 cache, heads of 64 or 128; attn_mfma_applies): the values are stored in
     // groups of eight slots (see kv_vt_index), nb32 chunks of 32 slots per kv head.
     int nb32;
@@ -203,8 +214,8 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s);
 
 // Activations between the tiled kernels.  An fp32 activation vector of R rows (tokens) that
 // feeds a projection is kept as three bf16 terms per value (value = hi + mid + lo exactly), laid
-// out as the MFMA B operand: [K/8 chunks][NC = 3R columns][8 k] bf16, column 3r + term (blocks of
-// more than 16 rows: the first two terms, NC = 2 RL columns, column 2r + term; block_terms).  The
+// out as the MFMA B operand: [K/8 chunks][NC = 3R columns][8 k] bf16, column 3r + term (bulk
+// layouts: the first two terms, NC = 2 x 32 or 2 x 64 columns, column 2r + term; block_terms).  The
 // residual stream itself stays fp32 [R][H]; the kernel that updates it also writes the split of
 // (x * gain of the next consumer) and, per 16-row group, the partial sums of squares of x, so the
 // consumer only adds up the partials (fixed order) to get the RMSNorm scale 1/sqrt(mean x^2 + eps)
@@ -213,7 +224,7 @@ struct MvArgs {
     const void *Wt;        // tiled weights
     int O, K, T, n_rg;     // real rows / depth, k-tiles, row groups
     int R;                 // activation rows, 1..64
-    int RL;                // rows the split layouts (in_s, out_s) are pitched for: block_row_layout(R)
+    int RL;                // layout code of the split layouts (in_s, out_s): block_row_layout
                            // (columns of rows that do not exist hold garbage that no result depends on)
     const uint16_t *in_s;  // split input [K/8][3 RL][8]
     const float *pss;      // [n_pss][rp] partial sums of squares of the producer, or nullptr: no norm
@@ -229,9 +240,9 @@ struct MvArgs {
     const float *cos_tab, *sin_tab;  // QKV: [max_seq][d/2]
     int pos0, max_seq, head_dim, n_q_heads, n_kv_heads;
     // QKV: row r's keys/values go to slot pos0 + r; it is rotated for position pos0 + r, or, for the rows
-    // of a token tree (tree != 0, R <= 16), for position pos0 + nibble r of depth4 (the row's level)
+    // of a token tree (tree != 0, R <= kMaxRows), for position pos0 + depth[r] (the row's level)
     int tree;
-    uint64_t depth4;
+    uint8_t depth[kMaxRows];
     int nb32;              // QKV: > 0: the values go to the grouped layout (kv_vt_index), nb32 32-slot chunks per head
     uint16_t *q_s;         // QKV: nullptr, or [R][n_q][2][d]: the rotated queries once more, as two bf16 terms (hi, then
                            // what is left of the fp32 value after hi), the operand form of the matrix-core attention
@@ -249,7 +260,7 @@ struct MvArgs {
 };
 // position block row r of a QKV pass is rotated for
 __host__ __device__ inline int mv_rope_pos(const MvArgs &a, int r) {
-    return a.pos0 + (a.tree ? (int)((a.depth4 >> (4 * (r & 15))) & 15) : r);
+    return a.pos0 + (a.tree ? (int)a.depth[r & (kMaxRows - 1)] : r);
 }
 constexpr size_t kMvMaxLds = 150 * 1024;
 // Rows the LDS-resident kernel takes (3R term columns must fit one MFMA column block)
@@ -272,7 +283,7 @@ int mv_split_slots(const MvArgs &a, int n_cu);
 struct EmbedRowsArgs {
     const uint16_t *E;  // [V][H] bf16 row-major
     int H, R;
-    int RL;             // rows the split layout xs is pitched for: block_row_layout(R)
+    int RL;             // layout code of xs: block_row_layout
     int32_t tokens[kMaxBlockRows];
     float *x;           // [R][H]
     uint16_t *xs;       // [H/8][3 RL][8]

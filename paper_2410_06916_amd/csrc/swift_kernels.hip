@@ -290,7 +290,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
     }
     __syncthreads();
 
-    const int orows = a.out_rows ? a.out_rows : a.rows;
+    const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode);
     for (int idx = tid; idx < M * d; idx += 256) {
         const int mm = idx / d, j = idx - mm * d;
         const int rr = mm / GROUP, h = mm - rr * GROUP;
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(256) void k_attn_split(AttnArgs a, int chunk) {
             if (a.out_s) {
                 uint16_t hi16, mid16, lo16;
                 split3(y, hi16, mid16, lo16);
-                const int nt = block_terms(orows);
+                const int nt = block_terms(ocode);
                 uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
                 p[0] = hi16;
                 p[8] = mid16;
@@ -355,7 +355,7 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
         if (a.out_s) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
-            const int orows = a.out_rows ? a.out_rows : a.rows, nt = block_terms(orows);
+            const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode), nt = block_terms(ocode);
             uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;
@@ -438,7 +438,7 @@ static AttnPlan attn_plan(const AttnArgs &a, int n_cu) {
 
 template <typename T>
 static hipError_t launch_attn_t(const AttnArgs &a, int n_cu, hipStream_t s) {
-    if (a.tree && (a.row_base < 0 || a.row_base + a.rows > 16)) return hipErrorInvalidValue;
+    if (a.tree && (a.row_base < 0 || a.row_base + a.rows > kMaxRows)) return hipErrorInvalidValue;
     const AttnPlan p = attn_plan<T>(a, n_cu);
     if (p.head) {
 #define SWIFT_HEAD_CASE(G)                                                            \

@@ -30,7 +30,7 @@ __device__ inline void mv_touch_value_lines(const MvArgs &a, int rg, int lane) {
 // (no loop around the loads and stores below).
 template <int EPI, bool ONE_PASS = false, typename YF>
 __device__ inline void mv_epilogue(const MvArgs &a, int rg, int lane, const float *rs, const float *rot, YF Y) {
-    const int R = a.R, NT = block_terms(a.RL), NC = NT * a.RL;  // NC: column pitch of the split outputs
+    const int R = a.R, NT = block_terms(a.RL), NC = NT * layout_rows(a.RL);  // NC: column pitch of the split outputs
     if (EPI == EPI_RESID || EPI == EPI_LOGITS) {
         const int iters = ONE_PASS ? 1 : (16 * R + 63) >> 6;
         for (int it = 0; it < iters; ++it) {

@@ -90,7 +90,7 @@ hipError_t launch_tile_weights(const TileArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_embed_rows(EmbedRowsArgs a) {
     // one thread per (row r, element i); 16 consecutive lanes share a 16-element group
-    const int NT = block_terms(a.RL), NC = NT * a.RL;
+    const int NT = block_terms(a.RL), NC = NT * layout_rows(a.RL);
     const int Hp = (a.H + 15) & ~15;
     const int total = a.R * Hp;
     for (int idx0 = blockIdx.x * 256; idx0 < total; idx0 += gridDim.x * 256) {
@@ -205,6 +205,46 @@ __device__ inline void mv_norm_rows64(const MvArgs &a, float *rs /* LDS [64] */,
     }
     // (no barrier here: the scales are read by the epilogue only, and every caller has a barrier between
     // this point and its epilogue)
+}
+
+// The same for exact layouts of 17..32 rows (row pitch 64), in the summation order of mv_norm_load /
+// mv_norm_finish -- a row's scale must not depend on the rows it shares a pass with: thread (row r, q) adds
+// the partials q + 32 u and q + 16 + 32 u, u = 0, 1, .., as two sums; then 32 threads add the 32 sums in
+// order.  One barrier, before the final sums.  scratch: LDS [1024].
+__device__ inline void mv_norm_rows32(const MvArgs &a, float *rs /* LDS [64] */, float *scratch) {
+    const int tid = threadIdx.x, r = tid & 31, q0 = tid >> 5;
+    if (a.pss) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int q = q0 + 16 * half;
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = q + 32 * u;
+                v[u] = p < a.n_pss ? a.pss[(size_t)p * a.rp + r] : 0.f;
+            }
+            float ss = 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) ss += v[u];
+            for (int p0 = 256; p0 < a.n_pss; p0 += 256) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int p = p0 + q + 32 * u;
+                    v[u] = p < a.n_pss ? a.pss[(size_t)p * a.rp + r] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) ss += v[u];
+            }
+            scratch[q * 32 + r] = ss;
+        }
+    }
+    __syncthreads();
+    if (tid < 32) {
+        float ss = 0.f;
+        if (a.pss)
+            for (int q2 = 0; q2 < 32; ++q2) ss += scratch[q2 * 32 + tid];
+        rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
+    }
 }
 
 // Slices (of the 8 K slices of a row group) whose sums are added first, in slice order, before the
@@ -583,23 +623,23 @@ static hipError_t launch_mv1(int epi, MvArgs a, int n_cu, int ks_override, int w
 // workgroup that arrives last at a counter adds the partials in split order (so the result does
 // not depend on arrival order) and runs the epilogue.
 //
-// NCB <= 3 (verify blocks of up to 16 rows) reproduces the LDS-resident kernel bit for bit: the K
-// range of a row group is cut into the same 8 slices of ceil(T/8) tiles, a slice is accumulated from
-// zero tile by tile, a workgroup covers a group of 8, 4, 2 or 1 whole slices (mv_slice_group: a
-// function of the matrix alone, not of the row count) and adds their sums per term in slice order,
-// combines the three terms, and the last workgroup adds the group results in order.  The
-// LDS-resident kernel adds its 8 slice sums in the same grouping.  NCB = 4 / 8 (blocks of 17-32 / 33-64 rows, two-term columns) keep their own
-// fixed order.
-template <int EPI, int NCB, int CT, int RG, bool DMA>
+// CANON (exact layouts: verify blocks of up to 32 rows, 1-6 column blocks) reproduces the LDS-resident kernel
+// bit for bit: the K range of a row group is cut into the same 8 slices of ceil(T/8) tiles, a slice is
+// accumulated from zero tile by tile, a workgroup covers a group of 8, 4, 2 or 1 whole slices (mv_slice_group: a
+// function of the matrix alone, not of the row count) and adds their sums per term in slice order, combines
+// the three terms, and the last workgroup adds the group results in order.  The LDS-resident kernel adds its 8
+// slice sums in the same grouping.  The bulk variants (NCB = 4 / 8: layouts of 32 / 64 rows, two-term columns)
+// keep their own fixed order.
+template <int EPI, int NCB, int CT, int RG, bool DMA, bool CANON>
 __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int R = a.R, NT = block_terms(a.RL), NC = NT * a.RL;  // NC: columns of the split input as laid out (= 16 NCB beyond 16 rows)
+    const int R = a.R, NT = block_terms(a.RL), NC = NT * layout_rows(a.RL);  // NC: columns of the split input as laid out
     const int buf_bytes = 4 * CT * NC * 16;
     // the result dump (NCB * 8 KB) reuses the B buffers, so the region is at least that large
     const int main_bytes = max(2 * buf_bytes, NCB * 8192);
     float *rs = (float *)(smem + 16 + (size_t)main_bytes);
     int *flag = (int *)(rs + 64);
-    float *nscratch = rs + 80;  // [512]
+    float *nscratch = rs + 80;  // [1024]
     float *dump = (float *)(smem + 16);  // reuses the B buffers after the last MFMA
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -611,7 +651,7 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     const int tb = (int)blockIdx.y * TS;
     const int nt = min(T, tb + TS) - tb;  // >= 1 (launcher)
     const int col = lane & 15, kg = lane >> 4;
-    constexpr bool kCanon = NCB <= 3;  // verify blocks; the variants for more than 16 rows keep their own order
+    constexpr bool kCanon = CANON;  // exact layouts (verify blocks); the bulk variants keep their own order
     // A slice is walked in chunks of CT tiles that do not run over its end (the last chunk of a slice
     // may be partial), so that slices end between chunks.  The prefill variant has one "slice": its
     // whole K range.
@@ -747,6 +787,8 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
         loadA(0, A0);
         if (a.rp == 16)
             mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+        else if (CANON)
+            mv_norm_rows32(a, rs, nscratch);
         else
             mv_norm_rows64(a, rs, nscratch);
         auto step = [&](int c, const u32x4(&Ac)[RG][CT], int bc, u32x4(&An)[RG][CT], int bn) {
@@ -775,6 +817,8 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
         if (nch > 1) loadB(1, tmp);
         if (a.rp == 16)
             mv_norm_finish(a, mv_norm_load(a), rs, nscratch);
+        else if (CANON)
+            mv_norm_rows32(a, rs, nscratch);
         else
             mv_norm_rows64(a, rs, nscratch);
 
@@ -859,18 +903,18 @@ __global__ __launch_bounds__(512) void k_mvN(MvArgs a, int TS, int rpw) {
     if (tid == 0) a.counters[blockIdx.x] = 0;
 }
 
-template <int EPI, int NCB, int CT, int RG, bool DMA>
+template <int EPI, int NCB, int CT, int RG, bool DMA, bool CANON>
 static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT, RG, DMA>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_mvN<EPI, NCB, CT, RG, DMA, CANON>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMvMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int NC = block_terms(a.RL) * a.RL;
+    const int NC = block_terms(a.RL) * layout_rows(a.RL);
     const size_t buf2 = 2 * (size_t)4 * CT * NC * 16;
-    const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 320 + 2048;
+    const size_t lds = 16 + (buf2 > (size_t)NCB * 8192 ? buf2 : (size_t)NCB * 8192) + 320 + 4096;
     const int n_rb = (a.n_rg + 8 * RG - 1) / (8 * RG);
     // split K over workgroups until about one workgroup per compute unit exists
     // (never more workgroups than compute units: one workgroup fills a compute unit's registers,
@@ -879,7 +923,7 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
     if (ksp < 1) ksp = 1;
     if (ksp > 8) ksp = 8;
     int TS;
-    if (NCB <= 3) {
+    if (CANON) {
         TS = ((a.T + 7) / 8) * mv_slice_group(a, n_cu);
     } else {
         while (ksp > 1 && ((a.T + ksp - 1) / ksp < 8 || (int64_t)a.n_rg * ksp > a.part_capacity)) --ksp;
@@ -896,36 +940,45 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
         if (rpw > 8) rpw = 8;
         grid_x = (a.n_rg + rpw * RG - 1) / (rpw * RG);
     }
-    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG, DMA>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
+    return launch_maybe_timed(k_mvN<EPI, NCB, CT, RG, DMA, CANON>, dim3(grid_x, ksp), dim3(512), lds, s, a, TS, rpw);
 }
 
 int mv_split_slots(const MvArgs &a, int n_cu) {
     if (a.R <= kMvSmallRows && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds) return 0;  // LDS-resident kernel
-    if (block_terms(a.RL) * a.RL > 48) return a.part_capacity;  // the variants for more than 16 rows: not needed by callers
+    if (a.RL & kBulkLayout) return a.part_capacity;  // (bulk layouts: not needed by callers)
     const int TS = ((a.T + 7) / 8) * mv_slice_group(a, n_cu);
     const int ksp = (a.T + TS - 1) / TS;
     return ksp > 1 ? ksp * a.n_rg : 0;
 }
 
 hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_override, hipStream_t s) {
-    if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp ||
-        a.RL != block_row_layout(a.R))
+    const bool bulk = (a.RL & kBulkLayout) != 0;
+    const int lrows = layout_rows(a.RL);
+    if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp || a.R > lrows ||
+        (bulk ? (lrows != 32 && lrows != 64) : (lrows != a.R || lrows > kMaxRows)))
         return hipErrorInvalidValue;
     // small blocks whose whole activation fits in LDS take the single-pass kernel
     if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
-    // up to 16 rows: 1-3 column blocks of three-term columns, K chunks of 8 tiles; 17-32 / 33-64 rows
-    // (prefill, candidate evaluation): 4 / 8 column blocks of two-term columns
-    const int ncb = (block_terms(a.RL) * a.RL + 15) / 16;
-#define SWIFT_MVN_CASE(E)                                               \
-    case E:                                                             \
-        switch (ncb) {                                                  \
-            case 1: return launch_mvN_t<E, 1, 8, 1, false>(a, n_cu, s);          \
-            case 2: return launch_mvN_t<E, 2, 8, 1, false>(a, n_cu, s);          \
-            case 3: return launch_mvN_t<E, 3, 8, 1, false>(a, n_cu, s);          \
-            case 4: return launch_mvN_t<E, 4, 8, 1, true>(a, n_cu, s);          \
-            case 8: return launch_mvN_t<E, 8, 8, 1, true>(a, n_cu, s);          \
-            default: return hipErrorInvalidValue;                        \
+    // exact layouts (up to 32 rows): 1-6 column blocks of three-term columns, K chunks of 8 tiles, the fixed
+    // summation order; bulk layouts of 32 / 64 rows (prefill, candidate evaluation): 4 / 8 column blocks of
+    // two-term columns
+    const int ncb = (block_terms(a.RL) * lrows + 15) / 16;
+#define SWIFT_MVN_CASE(E)                                                                \
+    case E:                                                                              \
+        if (bulk) switch (ncb) {                                                         \
+                case 4: return launch_mvN_t<E, 4, 8, 1, true, false>(a, n_cu, s);        \
+                case 8: return launch_mvN_t<E, 8, 8, 1, true, false>(a, n_cu, s);        \
+                default: return hipErrorInvalidValue;                                    \
+            }                                                                            \
+        switch (ncb) {                                                                   \
+            case 1: return launch_mvN_t<E, 1, 8, 1, false, true>(a, n_cu, s);            \
+            case 2: return launch_mvN_t<E, 2, 8, 1, false, true>(a, n_cu, s);            \
+            case 3: return launch_mvN_t<E, 3, 8, 1, false, true>(a, n_cu, s);            \
+            case 4: return launch_mvN_t<E, 4, 8, 1, false, true>(a, n_cu, s);            \
+            case 5: return launch_mvN_t<E, 5, 8, 1, false, true>(a, n_cu, s);            \
+            case 6: return launch_mvN_t<E, 6, 8, 1, false, true>(a, n_cu, s);            \
+            default: return hipErrorInvalidValue;                                        \
         }
     switch (epi) {
         SWIFT_MVN_CASE(EPI_QKV)

@@ -61,7 +61,7 @@ def lockstep_swift(o, g, prompt, n_new, mask, max_k, eps, tol, poison=False):
     emitted tokens and how often each kind of near tie occurred."""
     import numpy as np
     ties = dict(prefill=0, draft=0, stop=0, target=0)
-    rows_checked = max_rows = 0
+    rows_checked = max_rows = decisions = 0
     prompt = np.asarray(prompt, np.int32)
     emitted = []
 
@@ -85,6 +85,7 @@ def lockstep_swift(o, g, prompt, n_new, mask, max_k, eps, tol, poison=False):
         do = np.zeros(0, np.int32)
         if budget:
             do, co = o.draft_step(mask, budget, eps)
+            decisions += len(do)
             dg, cg = g.draft_step(mask, budget, eps)
             common = 0
             while common < min(len(do), len(dg)) and do[common] == dg[common]:
@@ -108,6 +109,7 @@ def lockstep_swift(o, g, prompt, n_new, mask, max_k, eps, tol, poison=False):
         err = rel_err_rowmax(lg, lo)
         assert np.all(err <= tol), ("verify logits", n0, err.max())
         rows_checked += len(block)
+        decisions += len(block)
         max_rows = max(max_rows, len(block))
         em = o.accept()
         if np.array_equal(tg, to):
@@ -123,4 +125,5 @@ def lockstep_swift(o, g, prompt, n_new, mask, max_k, eps, tol, poison=False):
             ids = np.concatenate((prompt, np.asarray(emitted[:-1], np.int32))).astype(np.int32)
             tok = prefill_both(ids, "target")
             assert tok == emitted[-1]   # (the oracle's block forward is its row forward: same token)
-    return dict(tokens=np.asarray(emitted[:n_new], np.int32), ties=ties, rows_checked=rows_checked, max_rows=max_rows)
+    return dict(tokens=np.asarray(emitted[:n_new], np.int32), ties=ties, rows_checked=rows_checked, max_rows=max_rows,
+                decisions=decisions)

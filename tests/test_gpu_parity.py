@@ -489,7 +489,8 @@ def test_tree_rows_equal_chain_rows_bit_for_bit(case):
     g.prefill(si.uniform_ids(4, n_prompt, shape.vocab))
     n0, t0 = g.cache_len, g.pending
     rng = np.random.default_rng(8)
-    for widths in ((3, 1, 5, 2), (10, 5), (1, 1, 1, 1, 1, 1, 1), (2, 2, 2, 2, 2, 2, 2, 1), (4,)):
+    for widths in ((3, 1, 5, 2), (10, 5), (1, 1, 1, 1, 1, 1, 1), (2, 2, 2, 2, 2, 2, 2, 1), (4,), (10, 10, 10, 1),
+                   (1,) * 25):
         g.rollback(n0, t0)
         levels = [rng.integers(0, shape.vocab, w).astype(np.int32) for w in widths]
         tgt, lg = g.verify_tree(levels, True)
@@ -555,7 +556,7 @@ def test_errors_and_state_machine_on_device(oracle_lib):
         g.verify([t + 1 if t + 1 < shape.vocab else 0])   # first row is not the pending token
     assert e.value.code == -1
     with pytest.raises(P.SwiftError) as e:
-        g.draft_step(np.zeros(2 * shape.n_layers, np.uint8), 16, 0.5)
+        g.draft_step(np.zeros(2 * shape.n_layers, np.uint8), 32, 0.5)   # more than SWIFT_MAX_BLOCK - 1 drafts
     assert e.value.code == -1
     n0 = g.cache_len
     with pytest.raises(P.SwiftError) as e:
@@ -625,7 +626,8 @@ def test_tree_errors_and_degenerate_trees_on_device(oracle_lib):
     import paper_2410_06916_amd as P
     shape = hp.SMALL_GQA
     weights = hp.shaped_weights(shape, seed=1)
-    o, g = _pair(oracle_lib, shape, weights, 40, threads=1)
+    MAXB = P.binding.MAX_BLOCK
+    o, g = _pair(oracle_lib, shape, weights, 40 + MAXB, threads=1)
     mask = np.zeros(2 * shape.n_layers, np.uint8)
     with pytest.raises(P.SwiftError) as e:
         g.draft_step_topk(mask, 3, 0.0)                        # before prefill
@@ -638,8 +640,8 @@ def test_tree_errors_and_degenerate_trees_on_device(oracle_lib):
     assert e.value.code == -3
     with pytest.raises(oracle_lib.OracleError):
         o.accept_tree()
-    for bad in ([np.arange(11)], [np.arange(10), np.arange(6)], [np.array([], np.int32)],
-                [np.array([shape.vocab])]):                    # too wide, too many rows, empty level, bad id
+    for bad in ([np.arange(11)], [np.arange(10)] * 3 + [np.arange(2)], [np.array([], np.int32)],
+                [np.array([shape.vocab])]):                    # too wide, too many rows (33), empty level, bad id
         with pytest.raises(P.SwiftError) as e:
             g.verify_tree([np.asarray(b, np.int32) for b in bad])
         assert e.value.code == -1
@@ -665,8 +667,23 @@ def test_tree_errors_and_degenerate_trees_on_device(oracle_lib):
     with pytest.raises(P.SwiftError):
         g.accept()
     g.accept_tree()
-    # capacity: a tree step needs room for a full block
-    while g.cache_len + 16 <= 40:
+    # capacity: the block is narrowed to the cache slots that are left (every row takes one); with none left the
+    # call is refused
+    cap = 40 + MAXB
+    while o.cache_len < g.cache_len:                   # (the oracle catches up with the steps above)
+        o.verify([o.pending]); o.accept()
+    assert o.pending == g.pending
+    while g.cache_len + 4 < cap:
+        to, _ = o.verify([o.pending]); o.accept()
+        tg, _ = g.verify([g.pending]); g.accept()
+        assert int(to[0]) == int(tg[0])
+    lo, _ = o.draft_step_topk(mask, 3, 0.0)
+    lg, _ = g.draft_step_topk(mask, 3, 0.0)
+    assert len(lo) == len(lg) and all(np.array_equal(a, b) for a, b in zip(lo, lg))
+    assert 1 + sum(len(l) for l in lg) == cap - g.cache_len == 4
+    g.verify_tree(lg)
+    g.rollback(g.cache_len, g.pending)
+    while g.cache_len < cap:
         g.verify([g.pending]); g.accept()
     with pytest.raises(P.SwiftError) as e:
         g.draft_step_topk(mask, 3, 0.0)
@@ -688,6 +705,32 @@ def test_full_width_narrow_depth(oracle_lib, base, n_layers):
     assert np.array_equal(got, want)
     _compare_traces(shape, to, tg)
     g.close()
+
+
+def test_paper_maximum_draft_length_at_7b_width(oracle_lib):
+    """Appendix B.2 sets the maximum draft length to 25: forced-length drafting of 25 tokens and 26-row verify
+    blocks at the 7B widths (two layers), step by step against the oracle, and the output equals the library's
+    own plain greedy decoding."""
+    import paper_2410_06916_amd as P
+    shape = si.LLAMA2_7B.with_layers(2)
+    g = P.SwiftModel(shape, 160)
+    o = oracle_lib.Oracle(shape, 160, threads=16)
+    for name, t in _gpu_weights(shape, 0):
+        g.load_tensor(name, t)
+        o.set_tensor(name, t.cpu())
+    prompt = si.uniform_ids(3, 40, shape.vocab)
+    mask = np.array([0, 1, 0, 0], np.uint8)
+    res = hp.lockstep_swift(o, g, prompt, 60, mask, 25, 0.0, TOL["bf16"])
+    # (random-init logits are nearly flat: with bf16 keys and values a few per cent of the arg-max decisions are
+    # near ties that may fall either way; each one was checked against the oracle's own margin)
+    assert res["max_rows"] == 26 and sum(res["ties"].values()) <= max(2, 0.05 * res["decisions"]), res
+    ar = P.generate_ar(g, prompt, 60)
+    out, trace = P.generate_swift(g, prompt, 60, mask, 25, 0.0)
+    assert np.array_equal(out, ar) and max(len(t["block"]) for t in trace) == 26
+    if sum(res["ties"].values()) == 0:
+        assert np.array_equal(out, res["tokens"])
+    g.close()
+    o.close()
 
 
 _WIDTHS = {"13b": si.LLAMA2_13B, "70b": si.LLAMA2_70B}
@@ -719,22 +762,22 @@ def test_other_widths_narrow_depth_against_oracle(oracle_lib, width, scenario):
     assert len(res["tokens"]) == n_new and res["rows_checked"] >= n_new
     # with forced-length drafts the verify blocks really had max_k + 1 rows
     assert res["max_rows"] == max_k + 1
-    assert sum(res["ties"].values()) <= 2, res["ties"]
+    assert sum(res["ties"].values()) <= max(2, 0.05 * res["decisions"]), res["ties"]
     g.close()
     o.close()
 
 
 # attention kernel instance per block size that each case of the bit-for-bit test is meant to reach
-_MFMA_7B = "mfma<d 128, group 1, 8 wavefronts, range 256, tiles 1>"      # one workgroup per kv head, no second launch
-_MFMA_LONG = "mfma<d 128, group 1, 4 wavefronts, range 128, tiles 1>"    # the cache cut into ranges + merge launch
+_MFMA_7B = "mfma<d 128, group 1, 8 wavefronts, range 256, tiles %d>"     # one workgroup per kv head, no second launch
+_MFMA_LONG = "mfma<d 128, group 1, 4 wavefronts, range 128, tiles %d>"   # the cache cut into ranges + merge launch
 _EXPECTED_ATTN_PATHS = {
     # heads of 16: the row-at-a-time kernels (vector arithmetic), rows sharing loads two by two
     "small-gqa-bf16": {1: "split<bf16, group 2, rows 1>", 2: "split<bf16, group 2, rows 2>",
                        16: "split<bf16, group 2, rows 2>"},
     "small-gqa-bf16-long-cache": {1: "split<bf16, group 2, rows 1>", 9: "split<bf16, group 2, rows 2>"},
     # heads of 128: the matrix-core kernel, every row of the block a column of one tile
-    "7b-width-2-layers": {1: _MFMA_7B, 5: _MFMA_7B, 9: _MFMA_7B, 16: _MFMA_7B},
-    "d128-mha": {1: _MFMA_LONG, 2: _MFMA_LONG, 3: _MFMA_LONG, 16: _MFMA_LONG},
+    "7b-width-2-layers": {1: _MFMA_7B % 1, 5: _MFMA_7B % 1, 9: _MFMA_7B % 1, 16: _MFMA_7B % 1, 26: _MFMA_7B % 2},
+    "d128-mha": {1: _MFMA_LONG % 1, 2: _MFMA_LONG % 1, 3: _MFMA_LONG % 1, 16: _MFMA_LONG % 1, 32: _MFMA_LONG % 2},
 }
 
 
@@ -742,7 +785,7 @@ _EXPECTED_ATTN_PATHS = {
 def test_block_rows_equal_single_rows_bit_for_bit(case):
     """What makes speculative output equal plain greedy output exactly rather than up to rounding
     (Sections 1 and 3.1: verification leaves the output unchanged): the logits of a token do not
-    depend on how many rows share its pass.  Rows of verify blocks of 2..16 tokens against the same
+    depend on how many rows share its pass.  Rows of verify blocks of 2..32 tokens against the same
     tokens decoded one at a time, compared bit for bit; both attention kernels, the LDS-resident and
     the block projection kernel, split K over 1..8 workgroups."""
     import paper_2410_06916_amd as P
@@ -769,12 +812,12 @@ def test_block_rows_equal_single_rows_bit_for_bit(case):
     g.prefill(si.uniform_ids(4, n_prompt, shape.vocab))
     n0, t0 = g.cache_len, g.pending
     toks, rows = [t0], []
-    for _ in range(16):
+    for _ in range(32):
         tgt, lg = g.verify([g.pending], True)
         g.accept()
         toks.append(int(tgt[0]))
         rows.append(lg[0].copy())
-    for R in (2, 3, 5, 6, 9, 16):
+    for R in (2, 3, 5, 6, 9, 16, 17, 26, 32):
         g.rollback(n0, t0)
         tgt, lg = g.verify(toks[:R], True)
         assert [int(x) for x in tgt] == toks[1:R + 1]

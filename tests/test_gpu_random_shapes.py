@@ -101,7 +101,7 @@ def _random_loop_case(seed, dtype):
     shape = si.ModelShape(f"loop-{seed}", n_layers, n_q * d, n_q, n_kv, d, ffn, vocab, dtype,
                           1e-6 if dtype == "fp32" else 1e-5)
     mask = (rng.random(2 * n_layers) < 0.35).astype(np.uint8)
-    max_k = int(rng.integers(1, 16))
+    max_k = int(rng.integers(1, 32))
     eps = float(rng.choice([0.0, 0.3, 0.8]))
     width = int(rng.choice([1, 3, 10]))
     return shape, max_seq, n_prompt, n_new, mask, max_k, eps, width

@@ -332,7 +332,7 @@ def test_topk_widths_and_selection(oracle_lib):
 def test_dynamic_verification_is_lossless(oracle_lib, small, max_k, eps):
     """Sections 1 and 3.1: whatever is drafted, and however widely it is verified, the output is the
     target model's greedy output.  Also: the cache that tree acceptance leaves behind (accepted rows
-    moved to consecutive slots) is the cache plain decoding builds; a block never exceeds 16 rows;
+    moved to consecutive slots) is the cache plain decoding builds; a block never exceeds 32 rows;
     the counters add up."""
     s, o, prompt, ar = small
     masks = _masks(s.n_layers)
@@ -345,7 +345,7 @@ def test_dynamic_verification_is_lossless(oracle_lib, small, max_k, eps):
         assert 1 + sum(t["m"] + 1 for t in trace) == 40
         for t in trace:
             rows = 1 + sum(len(l) for l in t["levels"])
-            assert rows <= 16 and len(t["levels"]) <= max_k
+            assert rows <= oracle_lib.Oracle.TREE_ROWS == 32 and len(t["levels"]) <= max_k
             for lev, p in zip(t["levels"], t["conf"]):
                 assert 1 <= len(lev) <= oracle_lib.lib().ora_topk_width(p) and len(set(lev.tolist())) == len(lev)
             # an accepted candidate beside the spine ends the path
@@ -427,7 +427,35 @@ def test_tree_acceptance_by_hand(oracle_lib, small):
     with pytest.raises(Exception):
         o.accept_tree()                                # no tree outstanding
     with pytest.raises(Exception):
-        o.verify_tree(o.pending, [np.arange(10, dtype=np.int32), np.arange(10, dtype=np.int32)])   # 21 rows
+        o.verify_tree(o.pending, [np.arange(10, dtype=np.int32)] * 3 + [np.arange(2, dtype=np.int32)])   # 33 rows
+
+
+def test_tree_blocks_shrink_to_the_cache_slots_left(oracle_lib, small):
+    """Every row of a tree block takes a cache slot of its own, so a block holds at most
+    min(32, capacity - cache length) rows: with a cache that has room for only a few slots beyond the
+    generated tokens the candidate sets are narrowed, never refused, and the output stays the target
+    model's greedy output (Sections 1 and 3.1); with no slot left drafting is refused."""
+    s, _, prompt, ar = small
+    n_new = 40
+    tight = oracle_lib.Oracle(s, len(prompt) + n_new + 2)
+    tight.set_weights(hp.shaped_weights(s, seed=21))
+    masks = _masks(s.n_layers)
+    narrowed = 0
+    for name in ("all", "rand0"):
+        out, trace = oracle_lib.generate_swift_tree(tight, prompt, n_new, masks[name], 8, 0.0)
+        assert np.array_equal(out, ar), name
+        for t in trace:
+            rows = 1 + sum(len(l) for l in t["levels"])
+            assert rows <= min(32, len(prompt) + n_new + 2 - t["n"])
+            narrowed += int(rows == len(prompt) + n_new + 2 - t["n"])
+    assert narrowed > 0
+    # fill the cache to the last slot: no room for the pending token's row
+    tight.prefill(prompt)
+    while tight.cache_len < len(prompt) + n_new + 2:
+        tight.verify([tight.pending]); tight.accept()
+    with pytest.raises(oracle_lib.OracleError):
+        tight.draft_step_topk(masks["all"], 3, 0.0)
+    tight.close()
 
 
 @pytest.mark.parametrize("tree_width", [0, 10])
