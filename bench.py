@@ -5,7 +5,9 @@ One "step" is one whole pass of the hot path over one synthetic input of the
 7B workload: prefill of the 512-token prompt, then 256 greedy new tokens through
 draft (skip mask, max 8 drafts, confidence stop 0.8) -> verify -> accept.
 `value` is decode throughput (new tokens after the prefill token / time from the
-end of prefill to the last token), inputs and weights resident in HBM.
+end of prefill to the last token), inputs and weights resident in HBM.  Steps are timed with
+the host clock between device synchronisations (every decoding step ends in one: the host
+reads the step's tokens); per-kernel figures come from HIP events on the library's stream.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -115,6 +117,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-modes", action="store_true")
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's number of new tokens")
+    ap.add_argument("--verify-rows", default="", help="comma-separated block sizes: time verify blocks of these many rows")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -135,7 +138,9 @@ def main():
     shape = w.shape
     mask = si.workload_mask(w)
     prompt = si.workload_prompt(w)
-    max_seq = w.n_prompt + w.n_new + w.max_k + 8
+    # room for the run itself, for the short measurement loops after it (up to ~100 tokens from the prompt's end)
+    # and for a verify block of the largest size
+    max_seq = w.n_prompt + max(w.n_new, 128) + max(w.max_k, 32) + 8
 
     t0 = time.perf_counter()
     g = P.SwiftModel(shape, max_seq, dev)
@@ -177,6 +182,8 @@ def main():
     per_launch_bytes = nbytes / max(n_l, 1)
     avg_us = ms * 1e3 / max(n_l, 1)
     achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if n_l else 0.0
+    # (HBM traffic needs the profiler's counters: the value is the one kept with the rocprofv3 summary, not
+    # measured in this run)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gateup_7b_hbm_traffic.json")
     if args.workload == "7b" and os.path.exists(tpath):
@@ -185,32 +192,47 @@ def main():
     roofline = {"bound": "hbm", "kernel": "k_mv1<SwiGLU> (RMSNorm scale + gate/up projection + SwiGLU, 1-2 rows)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": "stored: profiles/gateup_7b_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)"
+                if traffic is not None else None,
                 "launches": n_l, "avg_us": round(avg_us, 2), "bytes_per_launch": int(per_launch_bytes)}
     log(f"[bench] gate/up kernel: {n_l} launches, avg {avg_us:.2f} us, {achieved:.0f} GB/s")
 
+    # ---- every kernel class at the workload's context (the cache holds the whole prompt): 16 decoding steps of
+    # one one-row draft pass and one two-row verify pass each, the class's launches bracketed by HIP events
     per_class = {}
-    if not args.no_extra_modes:
-        for kc in ("qkv", "attn", "oproj", "down", "lmhead"):
-            g.profile_class(kc)
-            g.prefill(prompt[:8])
-            for _ in range(16):
-                d, _c = g.draft_step(mask, 1, 2.0)
-                g.verify(np.concatenate([[g.pending], d]).astype(np.int32))
-                g.accept()
-            n_l2, ms2, b2 = g.profile_read()
-            g.profile_class(None)
-            if n_l2:
-                per_class[kc] = {"avg_us": round(ms2 * 1e3 / n_l2, 2),
-                                 "GBps": round(b2 / max(ms2, 1e-9) / 1e6, 1), "launches": n_l2}
-        per_class["gateup"] = {"avg_us": roofline["avg_us"], "GBps": roofline["achieved"], "launches": n_l}
+    g.prefill(prompt)
+    n_ctx0, t_ctx0 = g.cache_len, g.pending
+    for kc in ("qkv", "attn", "oproj", "down", "lmhead"):
+        g.rollback(n_ctx0, t_ctx0)
+        g.profile_class(kc)
+        for _ in range(16):
+            d, _c = g.draft_step(mask, 1, 2.0)
+            g.verify(np.concatenate([[g.pending], d]).astype(np.int32))
+            g.accept()
+        n_l2, ms2, b2 = g.profile_read()
+        g.profile_class(None)
+        if n_l2:
+            gbps = b2 / max(ms2, 1e-9) / 1e6
+            per_class[kc] = {"avg_us": round(ms2 * 1e3 / n_l2, 2), "GBps": round(gbps, 1),
+                             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4), "launches": n_l2}
+    per_class["gateup"] = {"avg_us": roofline["avg_us"], "GBps": roofline["achieved"], "frac_of_hbm_peak": roofline["frac"],
+                           "launches": n_l}
+    per_class["note"] = ("event-bracketed launches (a few per cent above the kernel-trace durations); bytes = weights of the "
+                         "projection, or the keys and values of the slots read (attn: context %d)" % n_ctx0)
+    # the weight-streaming kernels side by side, worst first, and the whole one-row pass end to end
+    ws = sorted(((k, v["frac_of_hbm_peak"]) for k, v in per_class.items() if k in ("qkv", "oproj", "gateup", "down", "lmhead")),
+                key=lambda kv: kv[1])
+    roofline["weight_streaming_kernels_frac"] = {k: f for k, f in ws}
+    roofline["worst_weight_streaming_kernel"] = ws[0][0] if ws else None
 
     # ---- other modes (one step each): plain autoregressive, forced-length drafts
     modes = {"as_configured": {"tokens_per_s": round(value, 2),
                                "M": round(st["emitted_by_verify"] / max(st["verify_passes"], 1), 3),
                                "alpha": round(st["accepted"] / max(st["draft_passes"], 1), 4)}}
+    # plain autoregressive decoding of the target model: always measured (it is the metric's "decode tokens/s")
+    _, pf, dc, _ = run_generation(P, g, prompt, w.n_new, mask, 0, 0.0)
+    modes["autoregressive"] = {"tokens_per_s": round(n_after / dc, 2)}
     if not args.no_extra_modes:
-        _, pf, dc, _ = run_generation(P, g, prompt, w.n_new, mask, 0, 0.0)
-        modes["autoregressive"] = {"tokens_per_s": round(n_after / dc, 2)}
         _, pf, dc, tr = run_generation(P, g, prompt, w.n_new, mask, w.max_k, 0.0)
         s2 = g.stats()
         modes["forced_max_draft"] = {"tokens_per_s": round(n_after / dc, 2),
@@ -262,7 +284,7 @@ def main():
     passes = None
     projection = None
     prefill_info = None
-    if not args.no_extra_modes:
+    if True:
         draft_bytes_ = P.pass_bytes(g.cfg, mask, w.n_prompt, 1)
         full_bytes_ = P.pass_bytes(g.cfg, None, w.n_prompt, 1)
         torch.cuda.synchronize()
@@ -312,6 +334,8 @@ def main():
                         "mfma_frac_of_2500_TFLOPs": round(flops / t_pf / 2.5e15, 4),
                         "note": "64-row blocks (128 MFMA columns per weight tile with the two-term activations of such blocks); "
                                 "flops counted once per product, not per term"}
+        roofline["full_pass_1row_frac"] = passes["full_pass_hbm_frac"]
+        roofline["draft_pass_frac"] = passes["draft_pass_hbm_frac"]
         log(f"[bench] passes: {passes}")
 
     # ---- candidate evaluation of the optimisation phase (Section 4.1.2): one draft-model block pass
@@ -330,6 +354,25 @@ def main():
                 ts.append(time.perf_counter() - t0)
             cand[f"gamma_{gamma}"] = {"ms": round(float(np.median(ts)) * 1e3, 3), "n_match": int(n_match)}
         log(f"[bench] candidate evaluation: {cand}")
+
+    # ---- verify blocks of given row counts at the workload's context (forced-length verification: the block
+    # kernels at their real shapes; also what the rocprofv3 summaries of the verify kernels are made from)
+    verify_rows = None
+    if args.verify_rows:
+        g.prefill(prompt)
+        n0_, t0_ = g.cache_len, g.pending
+        rng = np.random.default_rng(7)
+        verify_rows = {"context": n0_, "note": "median of 8 calls, host clock around the synchronising call"}
+        for R in [int(v) for v in args.verify_rows.split(",")]:
+            block = np.concatenate(([t0_], rng.integers(0, shape.vocab, R - 1))).astype(np.int32)
+            ts = []
+            for _ in range(8):
+                g.rollback(n0_, t0_)
+                t0 = time.perf_counter()
+                g.verify(block)
+                ts.append(time.perf_counter() - t0)
+            verify_rows[f"rows_{R}"] = {"ms": round(float(np.median(ts)) * 1e3, 3)}
+        log(f"[bench] verify blocks: {verify_rows}")
 
     if args.pmc_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -367,6 +410,7 @@ def main():
         "projection": projection,
         "prefill": prefill_info,
         "candidate_evaluation": cand,
+        "verify_blocks": verify_rows,
     }
     print(json.dumps(result), flush=True)
 
