@@ -212,7 +212,7 @@ extern "C" int swift_pass_bytes(const swift_model_config *cfg, const uint8_t *sk
 // Layout of the array: [arrival counters][split-K partial sums][attention partials: part_ml | part_o].
 constexpr size_t kStaticCounterBytes = 4096 * 4;
 constexpr int kStaticPartSlots = 8192;  // row-group-splits of kMaxRows rows, as the arena's area holds for such blocks
-constexpr size_t kStaticPartBytes = (size_t)kStaticPartSlots * 16 * kMaxRows * 4;            // 8 MiB
+constexpr size_t kStaticPartBytes = (size_t)kStaticPartSlots * 16 * kMaxRows * 4;            // 16 MiB
 constexpr size_t kStaticAttnBytes = SWIFT_STATIC_SCRATCH_BYTES - kStaticCounterBytes - kStaticPartBytes;
 static __device__ __align__(256) unsigned char scratch[SWIFT_STATIC_SCRATCH_BYTES];
 // The array's address on each device (every GPU holds its own copy at its own address); set once per device.
