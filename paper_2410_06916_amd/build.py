@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswift_hip.so")
 SOURCES = ["swift_api.hip", "swift_kernels.hip", "swift_tiled.hip", "swift_opt.hip", "swift_sample.hip",
-           "swift_attn_block.hip", "swift_attn_mfma.hip"]
+           "swift_attn_block.hip", "swift_attn_mfma.hip", "swift_gemm.hip"]
 HEADERS = ["swift_kernels.h", "swift_device.h", "swift_attn.h", "swift_mv.h", os.path.join("..", "..", "include", "swift.h")]
 # digest of the sources the library was built from, written beside it (file times do not survive every copy)
 STAMP = os.path.join(HERE, "libswift_hip.srchash")

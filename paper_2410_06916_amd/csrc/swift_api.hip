@@ -79,6 +79,8 @@ struct Layout {
     uint64_t samp_q, samp_p, samp_out;  // speculative sampling: draft and target distributions [16][V], results
     // tiled path: split activations (three bf16 terms, MFMA B layout), RMSNorm partials, split-K scratch
     uint64_t xs, as_, hs, pss, mv_part, mv_counters;
+    // elements from one sub-block of a prompt macro block to the next, per activation buffer
+    uint64_t sub_x, sub_q, sub_q_s, sub_xs, sub_as, sub_hs, sub_pss;
     int mv_part_capacity;
     uint64_t stage, stage_bytes;  // staging for host tensors that are re-tiled on the device
     uint64_t total;
@@ -128,10 +130,20 @@ Layout make_layout(const swift_model_config &c) {
     L.kv_v_bytes = align_up(L.mfma_attn ? KV * (uint64_t)L.nb32 * 32 * eb : KV * c.max_seq * eb);
     L.kv = take((uint64_t)c.n_layers * (L.kv_k_bytes + L.kv_v_bytes));
     L.n_split_max = kAttnMaxSplit;
-    L.x = take(kMaxBlockRows * H * 4);
-    L.q = take(kMaxBlockRows * Q * 4);
+    // (tiled path: a prompt macro block holds kMacroSub sub-blocks of kMaxBlockRows rows, each with activation
+    // buffers of its own; every other pass uses the first sub-block's)
+    const uint64_t subs = L.tiled ? kMacroSub : 1;
+    L.sub_x = kMaxBlockRows * H;
+    L.sub_q = kMaxBlockRows * Q;
+    L.sub_q_s = kMaxBlockRows * Q * 2;
+    L.sub_xs = ceil_div(H, 32) * 4 * 3 * kMaxBlockRows * 8;
+    L.sub_as = ceil_div(Q, 32) * 4 * 3 * kMaxBlockRows * 8;
+    L.sub_hs = ceil_div(F, 32) * 4 * 3 * kMaxBlockRows * 8;
+    L.sub_pss = ceil_div(H, 16) * kMaxBlockRows;
+    L.x = take(subs * L.sub_x * 4);
+    L.q = take(subs * L.sub_q * 4);
     L.att = take(kMaxBlockRows * Q * 4);
-    L.q_s = take(kMaxBlockRows * Q * 2 * 2);
+    L.q_s = take(subs * L.sub_q_s * 2);
     L.h = take(kMaxBlockRows * F * 4);
     L.logits = take(kMaxBlockRows * V * 4);
     L.part_o = take((uint64_t)kMaxRows * c.n_q_heads * L.n_split_max * c.head_dim * 4);
@@ -142,10 +154,10 @@ Layout make_layout(const swift_model_config &c) {
     L.samp_q = take((uint64_t)kMaxRows * V * 4);
     L.samp_p = take((uint64_t)kMaxRows * V * 4);
     L.samp_out = take(256);
-    L.xs = take(ceil_div(H, 32) * 4 * 3 * kMaxBlockRows * 16);
-    L.as_ = take(ceil_div(Q, 32) * 4 * 3 * kMaxBlockRows * 16);
-    L.hs = take(ceil_div(F, 32) * 4 * 3 * kMaxBlockRows * 16);
-    L.pss = take(ceil_div(H, 16) * kMaxBlockRows * 4);
+    L.xs = take(subs * L.sub_xs * 2);
+    L.as_ = take(subs * L.sub_as * 2);
+    L.hs = take(subs * L.sub_hs * 2);
+    L.pss = take(subs * L.sub_pss * 4);
     L.mv_part_capacity = 8192;
     L.mv_part = take((uint64_t)L.mv_part_capacity * 16 * kMaxBlockRows * 4);
     L.mv_counters = take(4096 * 4);
@@ -282,6 +294,7 @@ struct swift_ctx {
     swift_stats st;
     // launch-shape overrides per kernel class (0 = automatic); measurement hook
     int tune_ks[SWIFT_KC_COUNT], tune_wg[SWIFT_KC_COUNT];
+    int prefill_sub, gemm_rgw;  // swift_debug_prefill
     // profiling
     int prof_class;
     std::vector<ProfRec> prof;
@@ -427,15 +440,55 @@ int forward_row(swift_ctx *x, int32_t token, int pos, const uint8_t *skip, int r
     return SWIFT_OK;
 }
 
+// Attention of a block of a.rows chain or tree rows whose first row attends a.n_ctx slots; RLC: layout code of the
+// block a.out_s belongs to.  The kernel is chosen from the configuration and the block's kind alone.
+int block_attention(swift_ctx *x, const AttnArgs &at, int RLC) {
+    const swift_model_config &c = x->c;
+    const Layout &L = x->L;
+    hipStream_t s = x->stream;
+    const int R = at.rows, Q = c.n_q_heads * c.head_dim, KV = c.n_kv_heads * c.head_dim, ctx0 = at.n_ctx - 1;
+    if (attn_block_applies(c.dtype, at)) {
+        AttnArgs a = at;
+        a.out_rows = RLC;
+        HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (ctx0 + R), [&] { return launch_attn_block(a, x->n_cu, s); }));
+    } else if (L.mfma_attn) {
+        AttnArgs a = at;
+        a.out_rows = RLC;
+        HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (ctx0 + R), [&] { return launch_attn_mfma(a, x->n_cu, s); }));
+    } else {
+        // a launch of the split kernel covers up to kMaxRows rows of the block (its partial buffers)
+        const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
+        for (int row0 = 0; row0 < R; row0 += per_launch) {
+            AttnArgs a = at;
+            a.q += (size_t)row0 * Q;
+            a.n_ctx += row0;
+            a.row_base = row0;  // (a tree has at most kMaxRows rows: one part)
+            a.rows = std::min(per_launch, R - row0);
+            a.out_s += 8 * block_terms(RLC) * row0;  // first of this part's term columns
+            a.out_rows = RLC;
+            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (ctx0 + row0 + a.rows),
+                          [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+        }
+    }
+    return SWIFT_OK;
+}
+
 // ---- tiled bf16 path: a block of R rows (tokens[0..R) at positions pos0..pos0+R-1) through the
 // network in one sweep over the weights.  Row r attends cache slots [0, pos0 + r].
 // tree: the rows are those of a token tree (R <= 16): row r goes to slot pos0 + r, is rotated for position
 // pos0 + its level, and attends the committed slots and the rows on its path from the root.
 // exact: the block's rows must come out as they would from any other block size (draft, verify and tree
 // passes: the exact layouts, up to kMaxRows rows); otherwise blocks of more than 16 rows take the bulk layouts.
+//
+// n_sub > 0: a prompt macro block instead: n_sub sub-blocks of kMaxBlockRows rows, the last one with R rows, at
+// positions pos0 .. (tokens holds all their rows).  Every projection is one launch of the blocked matrix product
+// over all sub-blocks; attention, the embedding and the LM head (last sub-block only: results land in rows
+// [0, R)) go sub-block by sub-block.  Bulk layouts; neither reuse_kv nor tree.
 int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
-                        bool reuse_kv, const TreeRows *tree, bool exact) {
-    const int RLC = block_row_layout(R, exact);  // layout code of every split activation of this pass
+                        bool reuse_kv, const TreeRows *tree, bool exact, int n_sub = 0) {
+    if (n_sub > 0 && (reuse_kv || tree || exact || n_sub > kMacroSub)) return fail(SWIFT_EINVAL, "bad macro block");
+    // layout code of every split activation of this pass
+    const int RLC = n_sub > 0 ? (kMaxBlockRows | kBulkLayout) : block_row_layout(R, exact);
     const swift_model_config &c = x->c;
     const Layout &L = x->L;
     const int H = c.hidden, d = c.head_dim, Q = c.n_q_heads * d, KV = c.n_kv_heads * d, F = c.ffn, V = c.vocab;
@@ -469,7 +522,7 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
         m.n_rg = n_rg;
         m.R = R;
         m.RL = RLC;
-        m.rp = block_row_pitch(R);
+        m.rp = n_sub > 0 ? kMaxBlockRows : block_row_pitch(R);
         m.eps = c.rms_eps;
         m.norm_dim = H;
         m.pos0 = pos0;
@@ -582,55 +635,62 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             push_mv(SWIFT_KC_DOWN, EPI_RESID, w);
         }
     }
+    // (macro block: the LM head reads the last sub-block's buffers)
+    const int last = n_sub > 0 ? n_sub - 1 : 0;
     if (want_logits) {
         MvArgs m = base_args(L.lm_head, V, H, (V + 15) / 16);
-        m.in_s = xs;
-        m.pss = pss;
+        m.in_s = xs + last * L.sub_xs;
+        m.pss = pss + last * L.sub_pss;
         m.n_pss = n_pss;
         m.out_f32 = dptr<float>(x, L.logits);
         m.ld_out = V;
         push_mv(SWIFT_KC_LMHEAD, EPI_LOGITS, m);
     }
 
-    EmbedRowsArgs ea{};
-    ea.E = dptr<uint16_t>(x, L.embed);
-    ea.H = H;
-    ea.R = R;
-    for (int r = 0; r < R; ++r) ea.tokens[r] = tokens[r];
-    ea.x = xf;
-    ea.xs = xs;
-    ea.gain_next = gain_of(0);
-    ea.pss = pss;
-    ea.rp = block_row_pitch(R);
-    ea.RL = RLC;
-    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * H * 2, [&] { return launch_embed_rows(ea, s); }));
+    MacroArgs ma{};
+    ma.S = n_sub;
+    ma.rows_last = R;
+    auto sub_rows = [&](int sb) { return sb == last ? R : kMaxBlockRows; };
+    for (int sb = 0; sb <= last; ++sb) {
+        EmbedRowsArgs ea{};
+        ea.E = dptr<uint16_t>(x, L.embed);
+        ea.H = H;
+        ea.R = sub_rows(sb);
+        for (int r = 0; r < ea.R; ++r) ea.tokens[r] = tokens[sb * kMaxBlockRows + r];
+        ea.x = xf + sb * L.sub_x;
+        ea.xs = xs + sb * L.sub_xs;
+        ea.gain_next = gain_of(0);
+        ea.pss = pss + sb * L.sub_pss;
+        ea.rp = n_sub > 0 ? kMaxBlockRows : block_row_pitch(R);
+        ea.RL = RLC;
+        HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)ea.R * H * 2, [&] { return launch_embed_rows(ea, s); }));
+    }
 
     // ---- one launch per stage
     for (size_t i = 0; i < list.size(); ++i) {
         const int kc = list[i].kc;
-        if (list[i].epi < 0 && attn_block_applies(c.dtype, list[i].at)) {
-            AttnArgs a = list[i].at;
-            a.out_rows = RLC;
-            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R),
-                          [&] { return launch_attn_block(a, x->n_cu, s); }));
-        } else if (list[i].epi < 0 && L.mfma_attn) {
-            AttnArgs a = list[i].at;
-            a.out_rows = RLC;
-            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + R), [&] { return launch_attn_mfma(a, x->n_cu, s); }));
-        } else if (list[i].epi < 0) {
-            // a launch of the split kernel covers up to kMaxRows rows of the block (its partial buffers)
-            const int per_launch = attn_uses_head_kernel(c.max_seq, c.n_kv_heads) ? R : kMaxRows;
-            for (int row0 = 0; row0 < R; row0 += per_launch) {
+        if (list[i].epi < 0) {
+            for (int sb = 0; sb <= last; ++sb) {
                 AttnArgs a = list[i].at;
-                a.q += (size_t)row0 * Q;
-                a.n_ctx += row0;
-                a.row_base = row0;  // (a tree has at most kMaxRows rows: one part)
-                a.rows = std::min(per_launch, R - row0);
-                a.out_s += 8 * block_terms(RLC) * row0;  // first of this part's term columns
-                a.out_rows = RLC;
-                HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + row0 + a.rows),
-                              [&] { return launch_attn_decode(c.dtype, a, x->n_cu, s); }));
+                a.rows = sub_rows(sb);
+                a.n_ctx += sb * kMaxBlockRows;
+                a.q += sb * L.sub_q;
+                a.q_s += sb * L.sub_q_s;
+                a.out_s += sb * L.sub_as;
+                int rc = block_attention(x, a, RLC);
+                if (rc) return rc;
             }
+        } else if (n_sub > 0 && list[i].epi != EPI_LOGITS) {
+            // (sub-block strides: which buffers a launch reads and writes follows from its epilogue)
+            const MvArgs &m = list[i].mv;
+            const int epi = list[i].epi;
+            ma.in_s = kc == SWIFT_KC_OPROJ ? L.sub_as : kc == SWIFT_KC_DOWN ? L.sub_hs : L.sub_xs;
+            ma.pss = L.sub_pss;
+            ma.out_f32 = epi == EPI_QKV ? L.sub_q : L.sub_x;
+            ma.out_s = epi == EPI_SWIGLU ? L.sub_hs : L.sub_xs;
+            ma.pss_out = L.sub_pss;
+            ma.q_s = L.sub_q_s;
+            HIP_TRY(timed(x, kc, (uint64_t)m.O * m.K * 2, [&] { return launch_gemm(epi, m, ma, x->n_cu, x->gemm_rgw, s); }));
         } else {
             const MvArgs &m = list[i].mv;
             const int epi = list[i].epi;
@@ -780,6 +840,8 @@ extern "C" int swift_create(const swift_model_config *cfg, void *device_mem, uin
     x->prof_class = -1;
     memset(x->tune_ks, 0, sizeof(x->tune_ks));
     memset(x->tune_wg, 0, sizeof(x->tune_wg));
+    x->prefill_sub = 0;
+    x->gemm_rgw = 0;
     x->h_tok = nullptr;
     x->h_conf = nullptr;
     hipError_t e = hipHostMalloc((void **)&x->h_tok, (2 * kMaxBlockRows + 4 + kTopK) * 4, hipHostMallocDefault);
@@ -883,12 +945,27 @@ extern "C" int swift_prefill(swift_ctx *x, const int32_t *prompt, int n_prompt, 
     for (int i = 0; i < n_prompt; ++i)
         if (prompt[i] < 0 || prompt[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
     int last_rows = 0;
-    // (bf16 models: blocks of up to 64 rows stream the weights once per block)
-    const int block = x->L.tiled ? kMaxBlockRows : kMaxRows;
-    for (int i = 0; i < n_prompt; i += block) {
-        last_rows = std::min(block, n_prompt - i);
-        int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt, false, nullptr, false);
-        if (rc) return rc;
+    if (x->L.tiled) {
+        // bf16 models: macro blocks of up to kMacroSub sub-blocks of 64 rows share one sweep over the weights (a
+        // blocked matrix product per projection); what is left at the end, if it fits one sub-block, goes through
+        // the block kernels
+        const int subs = x->prefill_sub > 0 ? x->prefill_sub : kMacroSub;
+        for (int i = 0; i < n_prompt;) {
+            const int rows = std::min(subs * kMaxBlockRows, n_prompt - i);
+            const bool macro = x->prefill_sub >= 0 && rows > kMaxBlockRows;
+            const int n_blk = std::min(rows, kMaxBlockRows * (macro ? subs : 1));
+            const int n_sub = macro ? (n_blk + kMaxBlockRows - 1) / kMaxBlockRows : 0;
+            last_rows = macro ? n_blk - (n_sub - 1) * kMaxBlockRows : n_blk;
+            int rc = forward_block_tiled(x, prompt + i, last_rows, i, nullptr, i + n_blk == n_prompt, false, nullptr, false, n_sub);
+            if (rc) return rc;
+            i += n_blk;
+        }
+    } else {
+        for (int i = 0; i < n_prompt; i += kMaxRows) {
+            last_rows = std::min((int)kMaxRows, n_prompt - i);
+            int rc = forward_block(x, prompt + i, last_rows, i, nullptr, i + last_rows == n_prompt, false, nullptr, false);
+            if (rc) return rc;
+        }
     }
     int rc = read_results(x, last_rows);
     if (rc) return rc;
@@ -1482,6 +1559,14 @@ extern "C" int swift_debug_tune(swift_ctx *x, int kernel_class, int waves_per_ro
         return fail(SWIFT_EINVAL, "bad argument");
     x->tune_ks[kernel_class] = waves_per_row_group;
     x->tune_wg[kernel_class] = workgroups;
+    return SWIFT_OK;
+}
+
+extern "C" int swift_debug_prefill(swift_ctx *x, int sub_blocks, int row_groups_per_wavefront) {
+    if (!x || sub_blocks < -1 || sub_blocks > kMacroSub || row_groups_per_wavefront < 0 || row_groups_per_wavefront > 4)
+        return fail(SWIFT_EINVAL, "bad argument");
+    x->prefill_sub = sub_blocks;
+    x->gemm_rgw = row_groups_per_wavefront;
     return SWIFT_OK;
 }
 

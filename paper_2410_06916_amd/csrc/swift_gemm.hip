@@ -1,0 +1,314 @@
+// Projections of a prompt macro block: up to kMacroSub sub-blocks of 64 rows through one weight matrix in
+// one launch, as a blocked matrix product on the matrix cores (paper Section 4.2: the pass over the input
+// that fills the cache before drafting starts; Section 3.1: the rows of a block are independent given the
+// cache, so any number of them may share one sweep over the weights).
+//
+// A workgroup of 8 wavefronts owns a tile of 4 RGW 16-row groups of W times two sub-blocks (2 x 64 rows x 2
+// bf16 terms = 256 columns).  Wavefront (wm, wn) = (w & 3, w >> 2) owns RGW row groups times the 128 columns
+// of sub-block wn: 8 RGW accumulator tiles.  Both operands reach LDS straight from global memory (no
+// registers in between) through a ring of kStages stages of one 32-deep k tile each: 4 RGW weight tiles of
+// 1 KB (already in A-operand order) and the two sub-blocks' 8 KB of split activations (already in B-operand
+// order).  While stage c is multiplied, stages c+1 .. c+kStages-2 are on their way and the loads of stage
+// c+kStages-1 are issued: what a compute unit can take in is bounded by the bytes it keeps in flight, and
+// the ring is what keeps most of LDS in flight.  One barrier per stage.
+//
+// The workgroups that share a weight tile (the other sub-block pairs of the macro block) and those that
+// share activations (the other row tiles) are given consecutive positions on one die, so that what one of
+// them pulls from memory the others find in that die's L2.
+//
+// The epilogue is the block kernel's (mv_epilogue), run per (row group, sub-block) on that sub-block's
+// buffers: every sub-block ends up exactly as laid out for a 64-row block of the bulk layout.
+#include <math.h>
+
+#include <type_traits>
+
+#include "swift_device.h"
+#include "swift_kernels.h"
+#include "swift_mv.h"
+
+namespace swift {
+
+namespace {
+
+constexpr int kRingBytes = 144 * 1024;   // most of LDS: what is in flight bounds what a compute unit takes in
+constexpr int kNormFloats = 2 * 16 * 64;  // scratch of gemm_norm_scales
+
+// RMSNorm scales of the workgroup's two sub-blocks: rs[64 wn + r].  Thread (wn, q, r4) adds the partials q, q + 16,
+// .. of rows 4 r4 .. 4 r4 + 3 of sub-block wn (16 loads of 16 bytes in flight at a time); then one thread per row
+// adds the sixteen sums in order.
+__device__ inline void gemm_norm_scales(const MvArgs &a, const MacroArgs &ma, int sub0, float *rs, float *scratch) {
+    const int tid = threadIdx.x, r4 = tid & 15, q = (tid >> 4) & 15, wn = tid >> 8;
+    const int sub = min(sub0 + wn, ma.S - 1);
+    if (a.pss) {
+        const float *p = a.pss + (size_t)sub * ma.pss + 4 * r4;
+        f32x4 ss = {0.f, 0.f, 0.f, 0.f};
+        for (int p0 = 0; p0 < a.n_pss; p0 += 256) {
+            f32x4 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int i = p0 + q + 16 * u;
+                v[u] = i < a.n_pss ? *(const f32x4 *)(p + (size_t)i * a.rp) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) ss += v[u];
+        }
+        *(f32x4 *)(scratch + (wn * 16 + q) * 64 + 4 * r4) = ss;
+    }
+    __syncthreads();
+    if (tid < 128) {
+        const int w2 = tid >> 6, r2 = tid & 63;
+        float ss = 0.f;
+        if (a.pss)
+            for (int q2 = 0; q2 < 16; ++q2) ss += scratch[(w2 * 16 + q2) * 64 + r2];
+        rs[tid] = a.pss ? 1.0f / sqrtf(ss / (float)a.norm_dim + a.eps) : 1.0f;
+    }
+}
+
+template <int RGW>
+struct GemmOperands {
+    u32x4 av[RGW], bv[8];
+};
+
+template <int EPI, int RGW>
+__global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, int NN) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int A_BYTES = 4 * RGW * 1024;
+    constexpr int ST_BYTES = A_BYTES + 2 * 8192;
+    constexpr int NST = kRingBytes / ST_BYTES;   // stages of the ring
+    constexpr int NP = 4 * RGW + 16;              // 1 KB pieces of a stage
+    constexpr int PW = (NP + 7) / 8;              // pieces a wavefront copies per stage (PW - 1 past the remainder)
+    static_assert(NST >= 3 && NST * PW < 64, "ring depth against the load counter");
+    unsigned char *ring = smem;
+    float *rs = (float *)(smem + kRingBytes);     // [2][64]
+    float *nscratch = rs + 128;                   // [kNormFloats]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 3, wn = wave >> 2;
+    // workgroup -> tile: the NN column tiles of a row tile sit next to each other on one die (consecutive
+    // workgroup ids go round the 8 dies)
+    const int id = blockIdx.x, die = id & 7, qd = id >> 3;
+    const int nt = qd % NN, mt = (qd / NN) * 8 + die;
+    if (mt >= MT) return;
+    const int sub0 = 2 * nt;
+    const int T = a.T;
+    const int col = lane & 15, kg = lane >> 4;
+
+    // ---- what this wavefront copies per stage: pieces p = wave + 8 i, each 64 lanes x 16 bytes from a
+    // wavefront-uniform address
+    const unsigned char *src[PW];   // the piece in the next stage to be issued (tile 0 at first)
+    int stride[PW];                 // bytes from one k tile to the next
+    int seg64[PW];                  // B pieces: first 16-byte unit of the piece inside its tile (A pieces: -1)
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+        const int p = wave + 8 * i;
+        if (p < 4 * RGW) {
+            const int rg = min(mt * 4 * RGW + p, a.n_rg - 1);  // row groups past the end repeat the last one
+            src[i] = (const unsigned char *)a.Wt + (size_t)rg * T * 1024;
+            stride[i] = 1024;
+            seg64[i] = -1;
+        } else {
+            const int q = min(p, NP - 1) - 4 * RGW, sb = min(sub0 + (q >> 3), ma.S - 1), seg = q & 7;
+            src[i] = (const unsigned char *)(a.in_s + (size_t)sb * ma.in_s) + seg * 1024;
+            stride[i] = 8192;
+            seg64[i] = seg * 64;
+        }
+    }
+    const bool full_share = (NP % 8 == 0) || wave < NP % 8;  // this wavefront copies PW pieces (else PW - 1)
+    int issue_slot = 0;  // ring slot of the next stage to be issued
+    auto issue = [&]() {
+        unsigned char *dst = ring + issue_slot * ST_BYTES + wave * 1024;
+        issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
+#pragma unroll
+        for (int i = 0; i < PW; ++i) {
+            if (i < PW - 1 || full_share)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + lane * 16),
+                                                 (__attribute__((address_space(3))) void *)(dst + i * 8192), 16, 0, 0);
+            src[i] += stride[i];
+        }
+    };
+    // waits until at most `stages` stages' worth of this wavefront's loads are in flight (loads complete in order;
+    // every stage is the same number of loads per lane)
+    auto wait_all_but = [&](auto stages) {
+        constexpr int n = decltype(stages)::value;
+        if (full_share) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * PW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (PW - 1)) : "memory");
+    };
+    // (the wait as a builtin: the compiler follows it, unlike one inside inline assembly, and so does not add a
+    // wait of its own for the operand reads of the previous step in front of the matrix instructions)
+    auto lds_sync = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wavefront's LDS reads and writes are done
+        asm volatile("s_barrier" ::: "memory");
+    };
+
+    f32x4 acc[RGW][8];
+#pragma unroll
+    for (int g = 0; g < RGW; ++g)
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) acc[g][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // A ragged last k tile (depth not a multiple of 32) is not part of the pipeline: it is handled at the end.
+    const int TF = (a.K & 31) ? T - 1 : T;
+    // ---- prologue: the ring filled with the first NST stages, then the norm scales (whose barrier waits for
+    // everything in flight)
+#pragma unroll
+    for (int t = 0; t < NST; ++t)
+        if (t < TF) issue();
+    gemm_norm_scales(a, ma, sub0, rs, nscratch);
+
+    const unsigned char *a_base = ring + (wm * RGW) * 1024 + lane * 16;
+    const unsigned char *b_base = ring + A_BYTES + wn * 8192 + (kg * 128 + col) * 16;
+    int read_slot = 0;  // ring slot of the next stage to be read
+    // (wavefronts without a sub-block -- an odd sub-block count leaves half of the last column tile empty -- go
+    // through the motions on the last sub-block's data; their results are dropped)
+    auto read_operands = [&](GemmOperands<RGW> &o) {
+        const int off = read_slot * ST_BYTES;
+        read_slot = read_slot + 1 == NST ? 0 : read_slot + 1;
+#pragma unroll
+        for (int g = 0; g < RGW; ++g) o.av[g] = *(const u32x4 *)(a_base + off + g * 1024);
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) o.bv[cb] = *(const u32x4 *)(b_base + off + cb * 256);
+    };
+    auto multiply = [&](const GemmOperands<RGW> &o) {
+#pragma unroll
+        for (int g = 0; g < RGW; ++g)
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb)
+                acc[g][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, o.av[g]),
+                                                                     __builtin_bit_cast(bf16x8, o.bv[cb]), acc[g][cb], 0, 0, 0);
+    };
+    // Step t: the operands of stage t are in registers (read during step t - 1).  Once stage t + 1 has landed for
+    // everybody -- and everybody's reads of stage t have completed: the barrier waits for them -- stage t + NST is
+    // requested into the slot stage t leaves, the operands of stage t + 1 are read into the other register set, and
+    // the matrix cores work on stage t meanwhile.  (The last step reads a slot nobody needs: no harm.)
+    auto step = [&](int t, const GemmOperands<RGW> &cur, GemmOperands<RGW> &nxt) {
+        if (t + NST < TF)
+            wait_all_but(std::integral_constant<int, NST - 2>());  // stages t + 2 .. t + NST - 1 may stay in flight
+        else
+            wait_all_but(std::integral_constant<int, 0>());
+        lds_sync();
+        if (t + NST < TF) issue();
+        read_operands(nxt);
+        // (the reads stay in front of the matrix instructions: left alone, the scheduler sinks them behind to save
+        // registers, and LDS and the matrix cores then take turns instead of working side by side)
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(cur);
+    };
+    GemmOperands<RGW> o0, o1;
+    if (TF > 0) {
+        wait_all_but(std::integral_constant<int, 0>());
+        lds_sync();
+        read_operands(o0);
+        for (int t = 0; t < TF; t += 2) {
+            step(t, o0, o1);
+            if (t + 1 < TF) step(t + 1, o1, o0);
+        }
+    }
+    if (TF < T) {
+        // the ragged tile: copied with ordinary loads, zeros past the real depth (a piece lies wholly inside or
+        // wholly outside it), into the first ring slot
+        const int real_units = (a.K >> 3) * 128;  // 16-byte units of a sub-block's split activation
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PW; ++i) {
+            if (i < PW - 1 || full_share) {
+                const bool past = seg64[i] >= 0 && seg64[i] + TF * 512 >= real_units;
+                const unsigned char *sp = src[i];  // (every full tile has been issued: the piece's next tile is this one)
+                const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : *(const u32x4 *)(sp + lane * 16);
+                *(u32x4 *)(ring + wave * 1024 + i * 8192 + lane * 16) = v;
+            }
+        }
+        __syncthreads();
+        read_slot = 0;
+        read_operands(o0);
+        multiply(o0);
+    }
+
+    // ---- epilogue per row group: results to LDS (dump[wave][column][tile row]), then the block kernel's epilogue
+    // on the sub-block's own buffers
+    const int sub = min(sub0 + wn, ma.S - 1);
+    MvArgs as = a;
+    as.R = sub == ma.S - 1 ? ma.rows_last : 64;
+    as.pos0 = a.pos0 + 64 * sub;
+    as.in_s = a.in_s + (size_t)sub * ma.in_s;
+    if (a.out_f32) as.out_f32 = a.out_f32 + (size_t)sub * ma.out_f32;
+    if (a.out_s) as.out_s = a.out_s + (size_t)sub * ma.out_s;
+    if (a.pss_out) as.pss_out = a.pss_out + (size_t)sub * ma.pss_out;
+    if (a.q_s) as.q_s = a.q_s + (size_t)sub * ma.q_s;
+    float *dw = (float *)ring + (size_t)wave * 2048;
+    const bool wave_live = sub0 + wn < ma.S;
+    const float *rsw = rs + 64 * wn;
+#pragma unroll
+    for (int g = 0; g < RGW; ++g) {
+        const int rg = (mt * 4 + wm) * RGW + g;
+        __syncthreads();  // the ring / the previous dump is no longer read
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) dw[(16 * cb + col) * 16 + 4 * kg + r4] = acc[g][cb][r4];
+        __syncthreads();
+        if (wave_live && rg < a.n_rg)
+            mv_epilogue<EPI>(as, rg, lane, rsw, nullptr,
+                             [&](int r, int j) { return dw[(2 * r) * 16 + j] + dw[(2 * r + 1) * 16 + j]; });
+    }
+}
+
+template <int EPI, int RGW>
+hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, hipStream_t s) {
+    static bool attr_set = false;
+    const size_t lds = kRingBytes + 128 * 4 + kNormFloats * 4;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI, RGW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int MT = (a.n_rg + 4 * RGW - 1) / (4 * RGW), NN = (ma.S + 1) / 2;
+    const int grid = ((MT + 7) / 8) * 8 * NN;
+    hipLaunchKernelGGL((k_gemm<EPI, RGW>), dim3(grid), dim3(512), lds, s, a, ma, MT, NN);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int gemm_row_groups_per_wave(const MvArgs &a, const MacroArgs &ma, int n_cu) {
+    // The tile height that finishes first by a simple count: rounds of workgroups (one per compute unit) times
+    // the longer of a stage's multiply time and the time to take its bytes in.
+    const int NN = (ma.S + 1) / 2;
+    int best = 1;
+    double best_t = 1e30;
+    for (int rgw = 1; rgw <= 4; ++rgw) {
+        const int MT = (a.n_rg + 4 * rgw - 1) / (4 * rgw);
+        const int rounds = (MT * NN + n_cu - 1) / n_cu;
+        const double mfma = 256.0 * rgw, intake = (4.0 * rgw + 16.0) * 1024.0 / 28.0;  // cycles per stage
+        const double t = rounds * (mfma > intake ? mfma : intake);
+        if (t < best_t) {
+            best_t = t;
+            best = rgw;
+        }
+    }
+    return best;
+}
+
+hipError_t launch_gemm(int epi, const MvArgs &a, const MacroArgs &ma, int n_cu, int rgw_override, hipStream_t s) {
+    if (ma.S < 1 || ma.S > kMacroSub || ma.rows_last < 1 || ma.rows_last > 64 || a.RL != (64 | kBulkLayout) || a.rp != 64 ||
+        (a.K & 7) != 0 || a.T != (a.K + 31) / 32 || a.n_rg < 1 || !a.Wt || !a.in_s || a.tree)
+        return hipErrorInvalidValue;
+    const int rgw = (rgw_override >= 1 && rgw_override <= 4) ? rgw_override : gemm_row_groups_per_wave(a, ma, n_cu);
+#define SWIFT_GEMM_CASE(E)                                                \
+    case E:                                                               \
+        switch (rgw) {                                                    \
+            case 1: return launch_gemm_t<E, 1>(a, ma, s);                 \
+            case 2: return launch_gemm_t<E, 2>(a, ma, s);                 \
+            case 3: return launch_gemm_t<E, 3>(a, ma, s);                 \
+            default: return launch_gemm_t<E, 4>(a, ma, s);                \
+        }
+    switch (epi) {
+        SWIFT_GEMM_CASE(EPI_QKV)
+        SWIFT_GEMM_CASE(EPI_RESID)
+        SWIFT_GEMM_CASE(EPI_SWIGLU)
+    }
+#undef SWIFT_GEMM_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace swift

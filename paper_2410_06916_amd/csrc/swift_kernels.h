@@ -279,6 +279,20 @@ hipError_t launch_mv(int epilogue, MvArgs a, int n_cu, int ks_override, int wg_o
 // described by `a` (0: the launch splits K inside workgroups only and uses neither `part` nor `counters`).
 int mv_split_slots(const MvArgs &a, int n_cu);
 
+// Prompt macro blocks: up to kMacroSub consecutive sub-blocks of 64 rows (the last one may hold fewer) go through a
+// projection in one launch.  Each sub-block has buffers of its own, laid out as for a 64-row block in the bulk
+// layout; sub-block s is found at the given element strides from sub-block 0's pointers in MvArgs, its rows sit at
+// positions pos0 + 64 s ..
+constexpr int kMacroSub = 8;
+struct MacroArgs {
+    int S;          // sub-blocks, 1..kMacroSub
+    int rows_last;  // rows of the last one, 1..64 (the others hold 64)
+    int64_t in_s, pss, out_f32, out_s, pss_out, q_s;  // strides, in elements of the respective buffer
+};
+// epilogue: EPI_QKV, EPI_RESID or EPI_SWIGLU; a.R is ignored, a.RL must be the 64-row bulk layout, a.rp = 64, a.K a
+// multiple of 8.  rgw_override: 0 = automatic, else 1..4 row groups per wavefront (tuning runs).
+hipError_t launch_gemm(int epilogue, const MvArgs &a, const MacroArgs &ma, int n_cu, int rgw_override, hipStream_t s);
+
 // x[r] = E[token r] (fp32), split of x * gain_next, partial sums of squares per 16 elements.
 struct EmbedRowsArgs {
     const uint16_t *E;  // [V][H] bf16 row-major

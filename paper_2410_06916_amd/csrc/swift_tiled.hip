@@ -944,8 +944,8 @@ static hipError_t launch_mvN_t(const MvArgs &a, int n_cu, hipStream_t s) {
 }
 
 int mv_split_slots(const MvArgs &a, int n_cu) {
-    if (a.R <= kMvSmallRows && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds) return 0;  // LDS-resident kernel
     if (a.RL & kBulkLayout) return a.part_capacity;  // (bulk layouts: not needed by callers)
+    if (a.R <= kMvSmallRows && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds) return 0;  // LDS-resident kernel
     const int TS = ((a.T + 7) / 8) * mv_slice_group(a, n_cu);
     const int ksp = (a.T + TS - 1) / TS;
     return ksp > 1 ? ksp * a.n_rg : 0;
@@ -957,8 +957,8 @@ hipError_t launch_mv(int epi, MvArgs a, int n_cu, int ks_override, int wg_overri
     if (a.R < 1 || a.R > kMaxBlockRows || (a.rp != 16 && a.rp != 64) || a.R > a.rp || a.R > lrows ||
         (bulk ? (lrows != 32 && lrows != 64) : (lrows != a.R || lrows > kMaxRows)))
         return hipErrorInvalidValue;
-    // small blocks whose whole activation fits in LDS take the single-pass kernel
-    if (a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
+    // small blocks (in their own exact layout) whose whole activation fits in LDS take the single-pass kernel
+    if (!bulk && a.R <= kMvSmallRows && ks_override != 16 && mv1_lds_bytes(a.K, a.R, a.head_dim) <= kMvMaxLds)
         return launch_mv1(epi, a, n_cu, ks_override, wg_override, s);
     // exact layouts (up to 32 rows): 1-6 column blocks of three-term columns, K chunks of 8 tiles, the fixed
     // summation order; bulk layouts of 32 / 64 rows (prefill, candidate evaluation): 4 / 8 column blocks of
