@@ -96,9 +96,10 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 
     // ---- what this wavefront copies per stage: pieces p = wave + 8 i, each 64 lanes x 16 bytes from a
     // wavefront-uniform address
-    const unsigned char *src[PW];   // the piece in the next stage to be issued (tile 0 at first)
+    const unsigned char *src[PW];   // tile 0 of the piece (wavefront-uniform)
     int stride[PW];                 // bytes from one k tile to the next
     int seg64[PW];                  // B pieces: first 16-byte unit of the piece inside its tile (A pieces: -1)
+    uint32_t voff[PW];              // this lane's byte offset from src[i] in the next stage to be issued
 #pragma unroll
     for (int i = 0; i < PW; ++i) {
         const int p = wave + 8 * i;
@@ -113,26 +114,24 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
             stride[i] = 8192;
             seg64[i] = seg * 64;
         }
+        voff[i] = lane * 16;
     }
     const bool full_share = (NP % 8 == 0) || wave < NP % 8;  // this wavefront copies PW pieces (else PW - 1)
-    int issue_slot = 0;  // ring slot of the next stage to be issued
-    auto issue = [&]() {
-        unsigned char *dst = ring + issue_slot * ST_BYTES + wave * 1024;
-        issue_slot = issue_slot + 1 == NST ? 0 : issue_slot + 1;
+    // FULL: whether this wavefront copies PW pieces (a compile-time copy of full_share)
+    auto issue = [&](int slot_bytes, auto FULL) {
+        unsigned char *dst = ring + slot_bytes + wave * 1024;
 #pragma unroll
         for (int i = 0; i < PW; ++i) {
-            if (i < PW - 1 || full_share)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + lane * 16),
+            if (i < PW - 1 || decltype(FULL)::value)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (size_t)voff[i]),
                                                  (__attribute__((address_space(3))) void *)(dst + i * 8192), 16, 0, 0);
-            src[i] += stride[i];
+            voff[i] += stride[i];
         }
     };
-    // waits until at most `stages` stages' worth of this wavefront's loads are in flight (loads complete in order;
-    // every stage is the same number of loads per lane)
-    auto wait_all_but = [&](auto stages) {
-        constexpr int n = decltype(stages)::value;
-        if (full_share) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * PW) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (PW - 1)) : "memory");
+    // waits until at most N stages' worth of this wavefront's loads are in flight (loads complete in order; every
+    // stage is the same number of loads per lane)
+    auto wait_all_but = [&](auto N, auto FULL) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(N)::value * (decltype(FULL)::value ? PW : PW - 1)) : "memory");
     };
     // (the wait as a builtin: the compiler follows it, unlike one inside inline assembly, and so does not add a
     // wait of its own for the operand reads of the previous step in front of the matrix instructions)
@@ -149,25 +148,15 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 
     // A ragged last k tile (depth not a multiple of 32) is not part of the pipeline: it is handled at the end.
     const int TF = (a.K & 31) ? T - 1 : T;
-    // ---- prologue: the ring filled with the first NST stages, then the norm scales (whose barrier waits for
-    // everything in flight)
-#pragma unroll
-    for (int t = 0; t < NST; ++t)
-        if (t < TF) issue();
-    gemm_norm_scales(a, ma, sub0, rs, nscratch);
-
     const unsigned char *a_base = ring + (wm * RGW) * 1024 + lane * 16;
     const unsigned char *b_base = ring + A_BYTES + wn * 8192 + (kg * 128 + col) * 16;
-    int read_slot = 0;  // ring slot of the next stage to be read
     // (wavefronts without a sub-block -- an odd sub-block count leaves half of the last column tile empty -- go
     // through the motions on the last sub-block's data; their results are dropped)
-    auto read_operands = [&](GemmOperands<RGW> &o) {
-        const int off = read_slot * ST_BYTES;
-        read_slot = read_slot + 1 == NST ? 0 : read_slot + 1;
+    auto read_operands = [&](int slot_bytes, GemmOperands<RGW> &o) {
 #pragma unroll
-        for (int g = 0; g < RGW; ++g) o.av[g] = *(const u32x4 *)(a_base + off + g * 1024);
+        for (int g = 0; g < RGW; ++g) o.av[g] = *(const u32x4 *)(a_base + slot_bytes + g * 1024);
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) o.bv[cb] = *(const u32x4 *)(b_base + off + cb * 256);
+        for (int cb = 0; cb < 8; ++cb) o.bv[cb] = *(const u32x4 *)(b_base + slot_bytes + cb * 256);
     };
     auto multiply = [&](const GemmOperands<RGW> &o) {
 #pragma unroll
@@ -177,33 +166,67 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
                 acc[g][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, o.av[g]),
                                                                      __builtin_bit_cast(bf16x8, o.bv[cb]), acc[g][cb], 0, 0, 0);
     };
-    // Step t: the operands of stage t are in registers (read during step t - 1).  Once stage t + 1 has landed for
-    // everybody -- and everybody's reads of stage t have completed: the barrier waits for them -- stage t + NST is
-    // requested into the slot stage t leaves, the operands of stage t + 1 are read into the other register set, and
-    // the matrix cores work on stage t meanwhile.  (The last step reads a slot nobody needs: no harm.)
-    auto step = [&](int t, const GemmOperands<RGW> &cur, GemmOperands<RGW> &nxt) {
-        if (t + NST < TF)
-            wait_all_but(std::integral_constant<int, NST - 2>());  // stages t + 2 .. t + NST - 1 may stay in flight
-        else
-            wait_all_but(std::integral_constant<int, 0>());
+
+    // The pipeline.  Step t: the operands of stage t are in registers (read during step t - 1).  Once stage t + 1
+    // has landed for everybody -- and everybody's reads of stage t have completed: the barrier waits for them --
+    // stage t + NST is requested into the slot stage t leaves, the operands of stage t + 1 are read into the other
+    // register set, and the matrix cores work on stage t meanwhile.  `slot`: byte offset of stage t's ring slot.
+    // The loop body is kept free of conditions: a wavefront issues at most one scalar instruction every few cycles,
+    // and whatever the loop needs beyond the matrix instructions is paid for in full.
+    auto pipeline = [&](auto FULL) {
+        constexpr auto ALL = std::integral_constant<int, 0>();
+        constexpr auto AHEAD = std::integral_constant<int, NST - 2>();  // stages t + 2 .. t + NST - 1 may stay in flight
+#pragma unroll
+        for (int t = 0; t < NST; ++t)
+            if (t < TF) issue(t * ST_BYTES, FULL);
+        gemm_norm_scales(a, ma, sub0, rs, nscratch);
+        if (TF == 0) return;
+        GemmOperands<RGW> o0, o1;
+        wait_all_but(ALL, FULL);
         lds_sync();
-        if (t + NST < TF) issue();
-        read_operands(nxt);
-        // (the reads stay in front of the matrix instructions: left alone, the scheduler sinks them behind to save
-        // registers, and LDS and the matrix cores then take turns instead of working side by side)
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(cur);
-    };
-    GemmOperands<RGW> o0, o1;
-    if (TF > 0) {
-        wait_all_but(std::integral_constant<int, 0>());
-        lds_sync();
-        read_operands(o0);
-        for (int t = 0; t < TF; t += 2) {
-            step(t, o0, o1);
-            if (t + 1 < TF) step(t + 1, o1, o0);
+        read_operands(0, o0);
+        int t = 0, slot = 0;
+        auto next_slot = [&](int sl) { return sl + ST_BYTES == NST * ST_BYTES ? 0 : sl + ST_BYTES; };
+        auto steady = [&](const GemmOperands<RGW> &cur, GemmOperands<RGW> &nxt) {
+            const int nslot = next_slot(slot);
+            wait_all_but(AHEAD, FULL);
+            lds_sync();
+            issue(slot, FULL);
+            read_operands(nslot, nxt);
+            // (the reads stay in front of the matrix instructions: left alone, the scheduler sinks them behind to
+            // save registers, and LDS and the matrix cores then take turns instead of working side by side)
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(cur);
+            slot = nslot;
+        };
+        // (the last step reads a slot nobody needs: no harm)
+        auto drain = [&](const GemmOperands<RGW> &cur, GemmOperands<RGW> &nxt) {
+            const int nslot = next_slot(slot);
+            wait_all_but(ALL, FULL);
+            lds_sync();
+            read_operands(nslot, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(cur);
+            slot = nslot;
+        };
+        for (; t + NST + 1 < TF; t += 2) {  // both steps issue a stage
+            steady(o0, o1);
+            steady(o1, o0);
         }
-    }
+        if (t + NST < TF) {  // an odd number of issuing steps: one more, then the operands sit in the other set
+            steady(o0, o1);
+            drain(o1, o0);
+            t += 2;
+        }
+        for (; t < TF; t += 2) {
+            drain(o0, o1);
+            if (t + 1 < TF) drain(o1, o0);
+        }
+    };
+    if (full_share)
+        pipeline(std::true_type());
+    else
+        pipeline(std::false_type());
     if (TF < T) {
         // the ragged tile: copied with ordinary loads, zeros past the real depth (a piece lies wholly inside or
         // wholly outside it), into the first ring slot
@@ -213,15 +236,15 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
         for (int i = 0; i < PW; ++i) {
             if (i < PW - 1 || full_share) {
                 const bool past = seg64[i] >= 0 && seg64[i] + TF * 512 >= real_units;
-                const unsigned char *sp = src[i];  // (every full tile has been issued: the piece's next tile is this one)
+                const unsigned char *sp = src[i] + (size_t)TF * stride[i];
                 const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : *(const u32x4 *)(sp + lane * 16);
                 *(u32x4 *)(ring + wave * 1024 + i * 8192 + lane * 16) = v;
             }
         }
         __syncthreads();
-        read_slot = 0;
-        read_operands(o0);
-        multiply(o0);
+        GemmOperands<RGW> o;
+        read_operands(0, o);
+        multiply(o);
     }
 
     // ---- epilogue per row group: results to LDS (dump[wave][column][tile row]), then the block kernel's epilogue
