@@ -669,7 +669,16 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
     // ---- one launch per stage
     for (size_t i = 0; i < list.size(); ++i) {
         const int kc = list[i].kc;
-        if (list[i].epi < 0) {
+        if (list[i].epi < 0 && n_sub > 0 && L.mfma_attn) {
+            // (the block attention kernel takes the whole macro block in one launch)
+            AttnArgs a = list[i].at;
+            a.rows = last * kMaxBlockRows + R;
+            a.sub_rows = kMaxBlockRows;
+            a.sub_q = L.sub_q;
+            a.sub_out_s = L.sub_as;
+            a.out_rows = RLC;
+            HIP_TRY(timed(x, SWIFT_KC_ATTN, (uint64_t)2 * KV * 2 * (pos0 + a.rows), [&] { return launch_attn_block(a, x->n_cu, s); }));
+        } else if (list[i].epi < 0) {
             for (int sb = 0; sb <= last; ++sb) {
                 AttnArgs a = list[i].at;
                 a.rows = sub_rows(sb);

@@ -35,8 +35,10 @@ __device__ inline bf16x8 pack_bf16x8(const uint16_t (&v)[8]) {
 // Scores of one half chunk (32 slots) are two MFMA tiles tt = 0, 1; tile row 4 g + i is slot
 // 8 g + 4 tt + i of the half, so that a lane's eight probabilities of the half are slots 8 g .. 8 g + 7:
 // the k range of its B operand in the second product.
+// A prompt macro block (a.sub_rows = 64) is one launch too: blockIdx.z is the sub-block, which is treated as a block
+// of its own whose partial results sit at the macro block's row numbers.
 template <int D>
-__global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
+__global__ __launch_bounds__(256) void k_attn_block(AttnArgs am, int chunk) {
     constexpr int DC = D / 32;   // k steps of a score tile
     constexpr int DT = D / 16;   // 16-row tiles of O^T
     constexpr int PPR = D / 8;   // 16-byte pieces per cache row
@@ -46,6 +48,14 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
     __shared__ __align__(16) uint16_t Ks[64 * KP];
     __shared__ __align__(16) uint16_t Vt[D * VP];
 
+    AttnArgs a = am;
+    const int row_base = (int)blockIdx.z * 64;  // first row of this sub-block in the macro block
+    if (am.sub_rows) {
+        a.rows = min(64, am.rows - row_base);
+        a.n_ctx = am.n_ctx + row_base;
+        a.q = am.q + (size_t)blockIdx.z * am.sub_q;
+        if (am.out_s) a.out_s = am.out_s + (size_t)blockIdx.z * am.sub_out_s;
+    }
     const int head = blockIdx.x, sp = blockIdx.y, n_split = gridDim.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 15, g = lane >> 4;
     const int nq = a.n_q_heads, kvh = head / (nq / a.n_kv_heads);
@@ -211,7 +221,7 @@ __global__ __launch_bounds__(256) void k_attn_block(AttnArgs a, int chunk) {
             }
         }
     } else {  // partial result of this range; k_attn_combine merges the ranges in order
-        const size_t base = ((size_t)row * nq + head) * n_split + sp;
+        const size_t base = ((size_t)(row_base + row) * nq + head) * n_split + sp;
         if (g == 0) {
             a.part_ml[base * 2] = m_run;
             a.part_ml[base * 2 + 1] = l_run;
@@ -230,7 +240,9 @@ bool attn_block_applies(int dtype, const AttnArgs &a) {
 }
 
 hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s) {
-    if (a.tree || a.rows < 1 || a.rows > 64 || (a.head_dim != 64 && a.head_dim != 128) || a.n_ctx < 1 ||
+    const int n_sub = a.sub_rows ? (a.rows + 63) / 64 : 1;
+    if (a.tree || a.rows < 1 || a.rows > 64 * n_sub || (a.sub_rows != 0 && a.sub_rows != 64) || n_sub > kMacroSub ||
+        (a.sub_rows && a.out) || (a.head_dim != 64 && a.head_dim != 128) || a.n_ctx < 1 ||
         a.n_kv_heads < 1 || a.n_q_heads % a.n_kv_heads != 0 || a.n_ctx + a.rows - 1 > a.max_seq || (!a.out && !a.out_s) ||
         a.nb32 < (a.max_seq + 31) / 32 ||
         !a.part_o || !a.part_ml)
@@ -238,7 +250,7 @@ hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s) {
     const int ctx = a.n_ctx + a.rows - 1;
     // ranges: about two workgroups per compute unit, at least two chunks each, and no more partial results
     // than the buffers hold (they are sized for kMaxRows rows times max_split ranges)
-    int want = (2 * n_cu + a.n_q_heads - 1) / a.n_q_heads;
+    int want = (2 * n_cu + a.n_q_heads * n_sub - 1) / (a.n_q_heads * n_sub);
     const int cap = kMaxRows * a.max_split / a.rows;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
@@ -246,7 +258,7 @@ hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s) {
     if (chunk < 128) chunk = 128;
     const int n_split = (ctx + chunk - 1) / chunk;
     if ((int64_t)n_split * a.rows > (int64_t)kMaxRows * a.max_split) return hipErrorInvalidValue;
-    const dim3 grid(a.n_q_heads, n_split), block(256);
+    const dim3 grid(a.n_q_heads, n_split, n_sub), block(256);
     if (a.head_dim == 128)
         hipLaunchKernelGGL(k_attn_block<128>, grid, block, 0, s, a, chunk);
     else

@@ -93,6 +93,11 @@ struct AttnArgs {
     // groups of eight slots (see kv_vt_index), nb32 chunks of 32 slots per kv head.
     int nb32;
     const uint16_t *q_s;          // matrix-core attention: the query rows as two bf16 terms, [rows][n_q][2][d]
+    // Prompt macro block (block attention kernel only): the rows come in sub-blocks of sub_rows rows (0: one block),
+    // sub-block z with buffers of its own at q + z * sub_q and out_s + z * sub_out_s (elements); row r of the macro
+    // block is row r % sub_rows of sub-block r / sub_rows and attends n_ctx + r slots as in any chain block.
+    int sub_rows;
+    int64_t sub_q, sub_out_s;
 };
 // ------------------------------------------------------------------------------------------
 // key/value cache layouts
@@ -126,7 +131,8 @@ size_t attn_partial_floats(int dtype, const AttnArgs &a, int n_cu);
 // Merges the partial results of n_split cache ranges of `chunk` slots, per (row, query head), in range order.
 hipError_t launch_attn_combine(const AttnArgs &a, int chunk, int n_split, hipStream_t s);
 // Blocks of 17..64 chain rows over a bf16 cache with head_dim 64 or 128: the whole block in one launch on the
-// matrix cores (all rows share every key/value load).  `a` describes the whole block (rows, out_rows).
+// matrix cores (all rows share every key/value load).  `a` describes the whole block (rows, out_rows), or a prompt
+// macro block of up to kMacroSub such blocks (sub_rows = 64).
 bool attn_block_applies(int dtype, const AttnArgs &a);
 hipError_t launch_attn_block(const AttnArgs &a, int n_cu, hipStream_t s);
 

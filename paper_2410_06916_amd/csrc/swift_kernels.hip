@@ -356,7 +356,9 @@ __global__ void k_attn_combine(AttnArgs a, int chunk, int n_split) {
             uint16_t hi, mid, lo;
             split3(y, hi, mid, lo);
             const int ocode = a.out_rows ? a.out_rows : a.rows, orows = layout_rows(ocode), nt = block_terms(ocode);
-            uint16_t *p = a.out_s + ((size_t)(e >> 3) * (nt * orows) + nt * row) * 8 + (e & 7);
+            // (a prompt macro block: the row's sub-block has an output buffer of its own)
+            const int z = a.sub_rows ? row / a.sub_rows : 0, r = row - z * a.sub_rows;
+            uint16_t *p = a.out_s + (size_t)z * a.sub_out_s + ((size_t)(e >> 3) * (nt * orows) + nt * r) * 8 + (e & 7);
             p[0] = hi;
             p[8] = mid;
             if (nt == 3) p[16] = lo;
