@@ -332,7 +332,7 @@ def main():
         prefill_info = {"ms": round(t_pf * 1e3, 2), "tokens_per_s": round(w.n_prompt / t_pf, 1),
                         "algorithmic_TFLOPs": round(flops / t_pf / 1e12, 2),
                         "mfma_frac_of_2500_TFLOPs": round(flops / t_pf / 2.5e15, 4),
-                        "note": "64-row blocks (128 MFMA columns per weight tile with the two-term activations of such blocks); "
+                        "note": "macro blocks of up to 512 rows per sweep over the weights (blocked matrix product, two-term activations); "
                                 "flops counted once per product, not per term"}
         roofline["full_pass_1row_frac"] = passes["full_pass_hbm_frac"]
         roofline["draft_pass_frac"] = passes["draft_pass_hbm_frac"]
