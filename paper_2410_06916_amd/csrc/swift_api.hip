@@ -568,7 +568,9 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
             m.kcache = kv_base(x, l, 0);
             m.vcache = kv_base(x, l, 1);
             m.nb32 = L.nb32;
-            m.q_s = L.mfma_attn ? dptr<uint16_t>(x, L.q_s) : nullptr;
+            // (the two-term copy of the queries is the operand of the matrix-core attention of blocks of up to 32 rows;
+            // a macro block's attention takes the fp32 queries)
+            m.q_s = L.mfma_attn && n_sub == 0 ? dptr<uint16_t>(x, L.q_s) : nullptr;
             if (tree) {
                 m.tree = 1;
                 memcpy(m.depth, tree->depth, sizeof(m.depth));

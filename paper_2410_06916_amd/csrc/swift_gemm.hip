@@ -291,8 +291,6 @@ hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, hipStream_t s) {
     return hipGetLastError();
 }
 
-}  // namespace
-
 int gemm_row_groups_per_wave(const MvArgs &a, const MacroArgs &ma, int n_cu) {
     // The tile height that finishes first by a simple count: rounds of workgroups (one per compute unit) times
     // the longer of a stage's multiply time and the time to take its bytes in.
@@ -311,6 +309,8 @@ int gemm_row_groups_per_wave(const MvArgs &a, const MacroArgs &ma, int n_cu) {
     }
     return best;
 }
+
+}  // namespace
 
 hipError_t launch_gemm(int epi, const MvArgs &a, const MacroArgs &ma, int n_cu, int rgw_override, hipStream_t s) {
     if (ma.S < 1 || ma.S > kMacroSub || ma.rows_last < 1 || ma.rows_last > 64 || a.RL != (64 | kBulkLayout) || a.rp != 64 ||
