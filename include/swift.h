@@ -352,8 +352,9 @@ int swift_debug_tune(swift_ctx *ctx, int kernel_class, int waves_per_row_group, 
 /* How swift_prefill walks a prompt on bf16 models (tuning and test runs; every setting gives results within the
  * library's tolerance, not the same bits).  sub_blocks: 0 = the default (macro blocks of up to 8 sub-blocks of 64
  * rows per sweep over the weights), 1..8 = macro blocks of at most that many sub-blocks, -1 = one 64-row block per
- * sweep.  row_groups_per_wavefront: 0 = automatic, 1..4 = tile height of the blocked matrix product. */
-int swift_debug_prefill(swift_ctx *ctx, int sub_blocks, int row_groups_per_wavefront);
+ * sweep.  tiling: 0 = automatic, else the workgroup tile of the blocked matrix product: 1..4 = 64, 128, 192 or 256
+ * weight rows x two sub-blocks, 5 / 6 = 128 / 256 weight rows x one sub-block. */
+int swift_debug_prefill(swift_ctx *ctx, int sub_blocks, int tiling);
 
 /* Turns per-launch timing of one kernel class on (kernel_class in [0, SWIFT_KC_COUNT)) or off (-1).
  * While on, every launch of that class is bracketed by HIP events on the context's stream. */

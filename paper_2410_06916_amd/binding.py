@@ -380,10 +380,11 @@ class SwiftModel:
     def tune(self, name: str, waves_per_row_group: int = 0, workgroups: int = 0):
         _chk(lib().swift_debug_tune(self._h, KERNEL_CLASSES[name], waves_per_row_group, workgroups), "swift_debug_tune")
 
-    def prefill_blocks(self, sub_blocks: int = 0, row_groups_per_wavefront: int = 0):
+    def prefill_blocks(self, sub_blocks: int = 0, tiling: int = 0):
         """How prefill walks a prompt (bf16 models): 0 = default macro blocks, 1..8 = at most that many 64-row
-        sub-blocks per sweep over the weights, -1 = one 64-row block per sweep."""
-        _chk(lib().swift_debug_prefill(self._h, sub_blocks, row_groups_per_wavefront), "swift_debug_prefill")
+        sub-blocks per sweep over the weights, -1 = one 64-row block per sweep; tiling: 0 = automatic, 1..6 = the
+        workgroup tile of the blocked matrix product (see swift_debug_prefill)."""
+        _chk(lib().swift_debug_prefill(self._h, sub_blocks, tiling), "swift_debug_prefill")
 
     def profile_class(self, name: Optional[str]):
         _chk(lib().swift_profile_class(self._h, -1 if name is None else KERNEL_CLASSES[name]), "swift_profile_class")

@@ -1573,11 +1573,11 @@ extern "C" int swift_debug_tune(swift_ctx *x, int kernel_class, int waves_per_ro
     return SWIFT_OK;
 }
 
-extern "C" int swift_debug_prefill(swift_ctx *x, int sub_blocks, int row_groups_per_wavefront) {
-    if (!x || sub_blocks < -1 || sub_blocks > kMacroSub || row_groups_per_wavefront < 0 || row_groups_per_wavefront > 4)
+extern "C" int swift_debug_prefill(swift_ctx *x, int sub_blocks, int tiling) {
+    if (!x || sub_blocks < -1 || sub_blocks > kMacroSub || tiling < 0 || tiling > 6)
         return fail(SWIFT_EINVAL, "bad argument");
     x->prefill_sub = sub_blocks;
-    x->gemm_rgw = row_groups_per_wavefront;
+    x->gemm_rgw = tiling;
     return SWIFT_OK;
 }
 

@@ -69,13 +69,15 @@ struct GemmOperands {
     u32x4 av[RGW], bv[8];
 };
 
-template <int EPI, int RGW>
+template <int EPI, int WN, int RGW>
 __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, int NN) {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int A_BYTES = 4 * RGW * 1024;
-    constexpr int ST_BYTES = A_BYTES + 2 * 8192;
+    constexpr int WM = 8 / WN;                    // wavefronts along the rows; WN sub-blocks side by side
+    constexpr int TRG = WM * RGW;                 // row groups of the workgroup's tile
+    constexpr int A_BYTES = TRG * 1024;
+    constexpr int ST_BYTES = A_BYTES + WN * 8192;
     constexpr int NST = kRingBytes / ST_BYTES;   // stages of the ring
-    constexpr int NP = 4 * RGW + 16;              // 1 KB pieces of a stage
+    constexpr int NP = TRG + 8 * WN;              // 1 KB pieces of a stage
     constexpr int PW = (NP + 7) / 8;              // pieces a wavefront copies per stage (PW - 1 past the remainder)
     static_assert(NST >= 3 && NST * PW < 64, "ring depth against the load counter");
     unsigned char *ring = smem;
@@ -84,13 +86,13 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 3, wn = wave >> 2;
+    const int wm = wave % WM, wn = wave / WM;
     // workgroup -> tile: the NN column tiles of a row tile sit next to each other on one die (consecutive
     // workgroup ids go round the 8 dies)
     const int id = blockIdx.x, die = id & 7, qd = id >> 3;
     const int nt = qd % NN, mt = (qd / NN) * 8 + die;
     if (mt >= MT) return;
-    const int sub0 = 2 * nt;
+    const int sub0 = WN * nt;
     const int T = a.T;
     const int col = lane & 15, kg = lane >> 4;
 
@@ -103,13 +105,13 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 #pragma unroll
     for (int i = 0; i < PW; ++i) {
         const int p = wave + 8 * i;
-        if (p < 4 * RGW) {
-            const int rg = min(mt * 4 * RGW + p, a.n_rg - 1);  // row groups past the end repeat the last one
+        if (p < TRG) {
+            const int rg = min(mt * TRG + p, a.n_rg - 1);  // row groups past the end repeat the last one
             src[i] = (const unsigned char *)a.Wt + (size_t)rg * T * 1024;
             stride[i] = 1024;
             seg64[i] = -1;
         } else {
-            const int q = min(p, NP - 1) - 4 * RGW, sb = min(sub0 + (q >> 3), ma.S - 1), seg = q & 7;
+            const int q = min(p, NP - 1) - TRG, sb = min(sub0 + (q >> 3), ma.S - 1), seg = q & 7;
             src[i] = (const unsigned char *)(a.in_s + (size_t)sb * ma.in_s) + seg * 1024;
             stride[i] = 8192;
             seg64[i] = seg * 64;
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
     const float *rsw = rs + 64 * wn;
 #pragma unroll
     for (int g = 0; g < RGW; ++g) {
-        const int rg = (mt * 4 + wm) * RGW + g;
+        const int rg = (mt * WM + wm) * RGW + g;
         __syncthreads();  // the ring / the previous dump is no longer read
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb)
@@ -276,35 +278,45 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
     }
 }
 
-template <int EPI, int RGW>
+template <int EPI, int WN, int RGW>
 hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, hipStream_t s) {
     static bool attr_set = false;
     const size_t lds = kRingBytes + 128 * 4 + kNormFloats * 4;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI, RGW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI, WN, RGW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int MT = (a.n_rg + 4 * RGW - 1) / (4 * RGW), NN = (ma.S + 1) / 2;
+    constexpr int TRG = (8 / WN) * RGW;
+    const int MT = (a.n_rg + TRG - 1) / TRG, NN = (ma.S + WN - 1) / WN;
     const int grid = ((MT + 7) / 8) * 8 * NN;
-    hipLaunchKernelGGL((k_gemm<EPI, RGW>), dim3(grid), dim3(512), lds, s, a, ma, MT, NN);
+    hipLaunchKernelGGL((k_gemm<EPI, WN, RGW>), dim3(grid), dim3(512), lds, s, a, ma, MT, NN);
     return hipGetLastError();
 }
 
-int gemm_row_groups_per_wave(const MvArgs &a, const MacroArgs &ma, int n_cu) {
-    // The tile height that finishes first by a simple count: rounds of workgroups (one per compute unit) times
-    // the longer of a stage's multiply time and the time to take its bytes in.
-    const int NN = (ma.S + 1) / 2;
+// Tilings: code 1..4 = two sub-blocks side by side (workgroup tile 64 RGW rows x 256 columns, RGW = the code),
+// 5, 6 = one sub-block (tile 128 or 256 rows x 128 columns: for matrices with few rows, where the narrower tile
+// gives as many workgroups with fewer bytes to copy per product).
+struct GemmTiling {
+    int wn, rgw;
+};
+constexpr GemmTiling kGemmTilings[7] = {{0, 0}, {2, 1}, {2, 2}, {2, 3}, {2, 4}, {1, 1}, {1, 2}};
+
+int gemm_tiling(const MvArgs &a, const MacroArgs &ma, int n_cu) {
+    // The one that finishes first by a simple count: rounds of workgroups (one per compute unit) times the longer
+    // of a stage's multiply time and the time to take its bytes in (about 21 bytes per cycle and compute unit when
+    // the units of a die stream the same data: measured).
     int best = 1;
     double best_t = 1e30;
-    for (int rgw = 1; rgw <= 4; ++rgw) {
-        const int MT = (a.n_rg + 4 * rgw - 1) / (4 * rgw);
+    for (int code = 1; code <= 6; ++code) {
+        const int wn = kGemmTilings[code].wn, rgw = kGemmTilings[code].rgw, trg = (8 / wn) * rgw;
+        const int MT = (a.n_rg + trg - 1) / trg, NN = (ma.S + wn - 1) / wn;
         const int rounds = (MT * NN + n_cu - 1) / n_cu;
-        const double mfma = 256.0 * rgw, intake = (4.0 * rgw + 16.0) * 1024.0 / 28.0;  // cycles per stage
+        const double mfma = 256.0 * rgw, intake = (trg + 8.0 * wn) * 1024.0 / 21.0;  // cycles per stage
         const double t = rounds * (mfma > intake ? mfma : intake);
         if (t < best_t) {
             best_t = t;
-            best = rgw;
+            best = code;
         }
     }
     return best;
@@ -312,18 +324,20 @@ int gemm_row_groups_per_wave(const MvArgs &a, const MacroArgs &ma, int n_cu) {
 
 }  // namespace
 
-hipError_t launch_gemm(int epi, const MvArgs &a, const MacroArgs &ma, int n_cu, int rgw_override, hipStream_t s) {
+hipError_t launch_gemm(int epi, const MvArgs &a, const MacroArgs &ma, int n_cu, int tiling_override, hipStream_t s) {
     if (ma.S < 1 || ma.S > kMacroSub || ma.rows_last < 1 || ma.rows_last > 64 || a.RL != (64 | kBulkLayout) || a.rp != 64 ||
         (a.K & 7) != 0 || a.T != (a.K + 31) / 32 || a.n_rg < 1 || !a.Wt || !a.in_s || a.tree)
         return hipErrorInvalidValue;
-    const int rgw = (rgw_override >= 1 && rgw_override <= 4) ? rgw_override : gemm_row_groups_per_wave(a, ma, n_cu);
+    const int code = (tiling_override >= 1 && tiling_override <= 6) ? tiling_override : gemm_tiling(a, ma, n_cu);
 #define SWIFT_GEMM_CASE(E)                                                \
     case E:                                                               \
-        switch (rgw) {                                                    \
-            case 1: return launch_gemm_t<E, 1>(a, ma, s);                 \
-            case 2: return launch_gemm_t<E, 2>(a, ma, s);                 \
-            case 3: return launch_gemm_t<E, 3>(a, ma, s);                 \
-            default: return launch_gemm_t<E, 4>(a, ma, s);                \
+        switch (code) {                                                   \
+            case 1: return launch_gemm_t<E, 2, 1>(a, ma, s);              \
+            case 2: return launch_gemm_t<E, 2, 2>(a, ma, s);              \
+            case 3: return launch_gemm_t<E, 2, 3>(a, ma, s);              \
+            case 4: return launch_gemm_t<E, 2, 4>(a, ma, s);              \
+            case 5: return launch_gemm_t<E, 1, 1>(a, ma, s);              \
+            default: return launch_gemm_t<E, 1, 2>(a, ma, s);             \
         }
     switch (epi) {
         SWIFT_GEMM_CASE(EPI_QKV)

@@ -296,8 +296,9 @@ struct MacroArgs {
     int64_t in_s, pss, out_f32, out_s, pss_out, q_s;  // strides, in elements of the respective buffer
 };
 // epilogue: EPI_QKV, EPI_RESID or EPI_SWIGLU; a.R is ignored, a.RL must be the 64-row bulk layout, a.rp = 64, a.K a
-// multiple of 8.  rgw_override: 0 = automatic, else 1..4 row groups per wavefront (tuning runs).
-hipError_t launch_gemm(int epilogue, const MvArgs &a, const MacroArgs &ma, int n_cu, int rgw_override, hipStream_t s);
+// multiple of 8.  tiling_override: 0 = automatic, else the tile shape (tuning runs): 1..4 = that many row groups per
+// wavefront on two sub-blocks side by side, 5 / 6 = one / two row groups per wavefront on one sub-block.
+hipError_t launch_gemm(int epilogue, const MvArgs &a, const MacroArgs &ma, int n_cu, int tiling_override, hipStream_t s);
 
 // x[r] = E[token r] (fp32), split of x * gain_next, partial sums of squares per 16 elements.
 struct EmbedRowsArgs {

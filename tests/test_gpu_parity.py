@@ -173,10 +173,10 @@ def test_prefill_block_sizes_against_oracle(oracle_lib):
     g.close()
 
 
-@pytest.mark.parametrize("subs,rgw", [(-1, 0)] + [(s_, r_) for s_ in (2, 3, 8) for r_ in (1, 2, 3, 4)])
+@pytest.mark.parametrize("subs,rgw", [(-1, 0)] + [(s_, r_) for s_ in (2, 3, 8) for r_ in (1, 2, 3, 4, 5, 6)])
 def test_prefill_tilings_against_oracle(oracle_lib, subs, rgw):
-    """Every tile height of the blocked matrix product (1..4 row groups per wavefront: another ring depth and
-    another share of the copies per wavefront each) and macro blocks of 2, 3 and 8 sub-blocks, against the one
+    """Every tile shape of the blocked matrix product (1..4 row groups per wavefront on two sub-blocks, 1 or 2 on
+    one: another ring depth and another share of the copies per wavefront each) and macro blocks of 2, 3 and 8 sub-blocks, against the one
     64-row block per sweep that the same prompts take with subs = -1; heads of 64 (attention on the matrix
     cores inside the macro block), a row count that leaves row groups past the end of every tile height."""
     shape = si.ModelShape("macro-d64", 2, 224, 4, 2, 64, 344, 300, "bf16", 1e-5)
