@@ -582,6 +582,10 @@ def test_errors_and_state_machine_on_device(oracle_lib):
     with pytest.raises(P.SwiftError) as e:
         g.prefill([1, 2, shape.vocab])             # id out of range
     assert e.value.code == -1
+    for bad in ((-2, 0), (9, 0), (0, -1), (0, 7)):
+        with pytest.raises(P.SwiftError) as e:
+            g.prefill_blocks(*bad)                 # block count / tile shape out of range
+        assert e.value.code == -1
     t = g.prefill([1, 2, 3])
     with pytest.raises(P.SwiftError) as e:
         g.accept()                                 # nothing verified

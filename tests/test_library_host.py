@@ -113,6 +113,7 @@ def test_null_and_range_arguments_are_rejected_without_a_device(P):
     assert L.swift_rollback(None, 0, 0) == -1
     assert L.swift_get_stats(None, None) == -1
     assert L.swift_load_tensor(None, b"embed", None, 0, 0) == -1
+    assert L.swift_debug_prefill(None, 0, 0) == -1
     out = vp()
     from paper_2410_06916_amd import binding as B
     cfg = B.make_config(si.TINY, 64)
