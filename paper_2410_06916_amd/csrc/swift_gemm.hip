@@ -3,16 +3,17 @@
 // that fills the cache before drafting starts; Section 3.1: the rows of a block are independent given the
 // cache, so any number of them may share one sweep over the weights).
 //
-// A workgroup of 8 wavefronts owns a tile of 4 RGW 16-row groups of W times two sub-blocks (2 x 64 rows x 2
-// bf16 terms = 256 columns).  Wavefront (wm, wn) = (w & 3, w >> 2) owns RGW row groups times the 128 columns
-// of sub-block wn: 8 RGW accumulator tiles.  Both operands reach LDS straight from global memory (no
-// registers in between) through a ring of kStages stages of one 32-deep k tile each: 4 RGW weight tiles of
-// 1 KB (already in A-operand order) and the two sub-blocks' 8 KB of split activations (already in B-operand
-// order).  While stage c is multiplied, stages c+1 .. c+kStages-2 are on their way and the loads of stage
-// c+kStages-1 are issued: what a compute unit can take in is bounded by the bytes it keeps in flight, and
-// the ring is what keeps most of LDS in flight.  One barrier per stage.
+// A workgroup of 8 wavefronts owns a tile of WM RGW 16-row groups of W times WN sub-blocks (WN x 64 rows x 2
+// bf16 terms = 128 WN columns; WM WN = 8, WN = 2 or 1).  Wavefront (wm, wn) = (w % WM, w / WM) owns RGW row groups
+// times the 128 columns of sub-block wn: 8 RGW accumulator tiles.  Both operands reach LDS straight from global
+// memory (no registers in between) through a ring of NST stages of one 32-deep k tile each: WM RGW weight tiles
+// of 1 KB (already in A-operand order) and the sub-blocks' 8 KB of split activations each (already in B-operand
+// order).  In step t the operands of stage t + 1 are read from LDS and stage t is multiplied while stages
+// t + 2 .. t + NST - 1 are on their way and stage t + NST is requested: what a compute unit can take in is
+// bounded by the bytes it keeps in flight, and the ring is what keeps most of LDS in flight.  One barrier per
+// stage.
 //
-// The workgroups that share a weight tile (the other sub-block pairs of the macro block) and those that
+// The workgroups that share a weight tile (the other column tiles of the macro block) and those that
 // share activations (the other row tiles) are given consecutive positions on one die, so that what one of
 // them pulls from memory the others find in that die's L2.
 //
