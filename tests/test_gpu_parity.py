@@ -782,7 +782,8 @@ def test_other_widths_narrow_depth_against_oracle(oracle_lib, width, scenario):
     targets exact -- a differing token must be a near tie of the oracle's own logits -- and every verify row's
     logits within the bf16 tolerance.  short-cache: 12-token prompt, drafts of up to 3 tokens, the attention
     sublayer of layer 1 and the MLP of layer 0 skipped.  long-cache: a cache capacity beyond the short-context
-    attention kernel's, a 70-token prompt (a 64-row prefill block and a tail), drafts of up to 12 tokens
+    attention kernel's, a 70-token prompt (one macro block of two sub-blocks, 64 and 6 rows, through the blocked
+    matrix product at these widths), drafts of up to 12 tokens
     (13-row verify blocks), both sublayers of layer 0 skipped."""
     import paper_2410_06916_amd as P
     shape = _WIDTHS[width].with_layers(2)
