@@ -734,8 +734,10 @@ int forward_block(swift_ctx *x, const int32_t *tokens, int R, int pos0, const ui
 
 // Copies rows [0, rows) of the token / confidence results to the pinned staging area and waits.
 int read_results(swift_ctx *x, int rows) {
-    HIP_TRY(hipMemcpyAsync(x->h_tok, dptr<int32_t>(x, x->L.out_tok), rows * 4, hipMemcpyDeviceToHost, x->stream));
-    HIP_TRY(hipMemcpyAsync(x->h_conf, dptr<float>(x, x->L.out_conf), rows * 4, hipMemcpyDeviceToHost, x->stream));
+    // (tokens and confidences lie kMaxBlockRows words apart on the device and in the staging area alike: one copy)
+    if (x->L.out_conf != x->L.out_tok + kMaxBlockRows * 4 || (char *)x->h_conf != (char *)x->h_tok + kMaxBlockRows * 4)
+        return fail(SWIFT_EINVAL, "result areas are not adjacent");
+    HIP_TRY(hipMemcpyAsync(x->h_tok, dptr<int32_t>(x, x->L.out_tok), (kMaxBlockRows + rows) * 4, hipMemcpyDeviceToHost, x->stream));
     HIP_TRY(hipStreamSynchronize(x->stream));
     // a token id is fed back as an embedding row index: never pass on one outside the vocabulary
     for (int i = 0; i < rows; ++i)
