@@ -160,8 +160,9 @@ int swift_draft_step(swift_ctx *ctx, const uint8_t *skip_mask, int max_k, float 
  * 0 .. n - gamma + i as they are (nothing is written; keys and values of the rows are not computed);
  * predicted[i] (host, gamma ids, may be NULL) = its arg-max, the prediction of window[i + 1].
  * *n_match = number of i with predicted[i] == window[i + 1]; matchness = *n_match / gamma.
- * 1 <= gamma <= SWIFT_MAX_WINDOW (the largest context window of the paper's Table 9; windows of more
- * than 64 tokens run as blocks of 64 rows) and gamma <= n, else SWIFT_EINVAL / SWIFT_ESTATE.  Cache, cache length, pending
+ * 1 <= gamma <= SWIFT_MAX_WINDOW (the largest context window of the paper's Table 9; a window of more
+ * than 64 tokens runs as one macro block of two 64-row sub-blocks on bf16 models, as two blocks
+ * otherwise) and gamma <= n, else SWIFT_EINVAL / SWIFT_ESTATE.  Cache, cache length, pending
  * token, outstanding draft/verify state and statistics are left unchanged. */
 int swift_eval_mask(swift_ctx *ctx, const uint8_t *skip_mask, const int32_t *window, int gamma,
                     int32_t *predicted, int *n_match);

@@ -483,10 +483,11 @@ int block_attention(swift_ctx *x, const AttnArgs &at, int RLC) {
 // n_sub > 0: a prompt macro block instead: n_sub sub-blocks of kMaxBlockRows rows, the last one with R rows, at
 // positions pos0 .. (tokens holds all their rows).  Every projection is one launch of the blocked matrix product
 // over all sub-blocks; attention, the embedding and the LM head (last sub-block only: results land in rows
-// [0, R)) go sub-block by sub-block.  Bulk layouts; neither reuse_kv nor tree.
+// [0, R)) go sub-block by sub-block.  Bulk layouts; no tree.  With reuse_kv (a candidate-evaluation window of more
+// than one sub-block) the caller asks for every sub-block's predictions afterwards (macro_sub_logits).
 int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, const uint8_t *skip, bool want_logits,
                         bool reuse_kv, const TreeRows *tree, bool exact, int n_sub = 0) {
-    if (n_sub > 0 && (reuse_kv || tree || exact || n_sub > kMacroSub)) return fail(SWIFT_EINVAL, "bad macro block");
+    if (n_sub > 0 && (tree || exact || n_sub > kMacroSub)) return fail(SWIFT_EINVAL, "bad macro block");
     // layout code of every split activation of this pass
     const int RLC = n_sub > 0 ? (kMaxBlockRows | kBulkLayout) : block_row_layout(R, exact);
     const swift_model_config &c = x->c;
@@ -714,6 +715,44 @@ int forward_block_tiled(swift_ctx *x, const int32_t *tokens, int R, int pos0, co
                       x->want_topk ? dptr<int32_t>(x, L.out_topk) : nullptr, kTopK};
         HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)R * V * 4, [&] { return launch_argmax_conf(am, s); }));
     }
+    return SWIFT_OK;
+}
+
+// After a macro block pass: LM head and arg-max over the `rows` rows of sub-block sb, whose final residual stream the
+// pass left in that sub-block's buffers; results land in rows [0, rows).
+int macro_sub_logits(swift_ctx *x, int sb, int rows) {
+    const swift_model_config &c = x->c;
+    const Layout &L = x->L;
+    if (!L.tiled || sb < 0 || sb >= kMacroSub || rows < 1 || rows > kMaxBlockRows) return fail(SWIFT_EINVAL, "bad sub-block");
+    hipStream_t s = x->stream;
+    MvArgs m{};
+    m.Wt = x->base + L.lm_head;
+    m.O = c.vocab;
+    m.K = c.hidden;
+    m.T = (c.hidden + 31) / 32;
+    m.n_rg = (c.vocab + 15) / 16;
+    m.R = rows;
+    m.RL = kMaxBlockRows | kBulkLayout;
+    m.rp = kMaxBlockRows;
+    m.eps = c.rms_eps;
+    m.norm_dim = c.hidden;
+    m.max_seq = c.max_seq;
+    m.head_dim = c.head_dim;
+    m.n_q_heads = c.n_q_heads;
+    m.n_kv_heads = c.n_kv_heads;
+    m.part = x->scr.mv_part;
+    m.counters = x->scr.mv_counters;
+    m.part_capacity = L.mv_part_capacity;
+    m.in_s = dptr<uint16_t>(x, L.xs) + sb * L.sub_xs;
+    m.pss = dptr<float>(x, L.pss) + sb * L.sub_pss;
+    m.n_pss = (c.hidden + 15) / 16;
+    m.out_f32 = dptr<float>(x, L.logits);
+    m.ld_out = c.vocab;
+    HIP_TRY(timed(x, SWIFT_KC_LMHEAD, (uint64_t)m.O * m.K * 2,
+                  [&] { return launch_mv(EPI_LOGITS, m, x->n_cu, x->tune_ks[SWIFT_KC_LMHEAD], x->tune_wg[SWIFT_KC_LMHEAD], s); }, true));
+    ArgmaxArgs am{dptr<float>(x, L.logits), c.vocab, rows, dptr<int32_t>(x, L.out_tok), dptr<float>(x, L.out_conf),
+                  x->want_topk ? dptr<int32_t>(x, L.out_topk) : nullptr, kTopK};
+    HIP_TRY(timed(x, SWIFT_KC_OTHER, (uint64_t)rows * c.vocab * 4, [&] { return launch_argmax_conf(am, s); }));
     return SWIFT_OK;
 }
 
@@ -1001,9 +1040,28 @@ extern "C" int swift_eval_mask(swift_ctx *x, const uint8_t *skip_mask, const int
     if (gamma > x->n) return fail(SWIFT_ESTATE, "window longer than the cache");
     for (int i = 0; i <= gamma; ++i)
         if (window[i] < 0 || window[i] >= x->c.vocab) return fail(SWIFT_EINVAL, "token id out of range");
-    // Rows read the target's cache and write nothing, so a window longer than a block is evaluated
-    // block by block.
     int m = 0;
+    if (x->L.tiled && x->prefill_sub >= 0 && gamma > kMaxBlockRows) {
+        // bf16 models: a window of more than one 64-row block is one macro block (one sweep over the weights of
+        // the candidate's sublayers for all its rows), then the LM head and the arg-max sub-block by sub-block
+        const int n_sub = (gamma + kMaxBlockRows - 1) / kMaxBlockRows;
+        int rc = forward_block_tiled(x, window, gamma - (n_sub - 1) * kMaxBlockRows, x->n - gamma, skip_mask, false, true,
+                                     nullptr, false, n_sub);
+        if (rc) return rc;
+        for (int sb = 0; sb < n_sub; ++sb) {
+            const int r0 = sb * kMaxBlockRows, rows = std::min(kMaxBlockRows, gamma - r0);
+            if ((rc = macro_sub_logits(x, sb, rows))) return rc;
+            if ((rc = read_results(x, rows))) return rc;
+            for (int i = 0; i < rows; ++i) {
+                if (predicted) predicted[r0 + i] = x->h_tok[i];
+                if (x->h_tok[i] == window[r0 + i + 1]) ++m;
+            }
+        }
+        *n_match = m;
+        return SWIFT_OK;
+    }
+    // Rows read the target's cache and write nothing, so a longer window can also be evaluated block by block
+    // (fp32 models; bf16 models when macro blocks are switched off).
     for (int r0 = 0; r0 < gamma; r0 += kMaxBlockRows) {
         const int rows = std::min(kMaxBlockRows, gamma - r0);
         int rc = forward_block(x, window + r0, rows, x->n - gamma + r0, skip_mask, true, true, nullptr, false);

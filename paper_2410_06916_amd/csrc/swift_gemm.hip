@@ -19,6 +19,11 @@
 //
 // The epilogue is the block kernel's (mv_epilogue), run per (row group, sub-block) on that sub-block's
 // buffers: every sub-block ends up exactly as laid out for a 64-row block of the bulk layout.
+//
+// Where the tiles alone would leave compute units idle -- a matrix of few rows (o_proj, down_proj) under a macro
+// block of two to four sub-blocks: a prompt of 65-256 tokens, a candidate-evaluation window of more than 64 -- the
+// depth is split over two or four workgroups per tile as well (gridDim.y): each publishes its results, the
+// workgroup that arrives last at the tile's counter adds them in part order and runs the epilogue.
 #include <math.h>
 
 #include <type_traits>
@@ -71,7 +76,7 @@ struct GemmOperands {
 };
 
 template <int EPI, int WN, int RGW>
-__global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, int NN) {
+__global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, int NN, int TS) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int WM = 8 / WN;                    // wavefronts along the rows; WN sub-blocks side by side
     constexpr int TRG = WM * RGW;                 // row groups of the workgroup's tile
@@ -96,6 +101,10 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
     const int sub0 = WN * nt;
     const int T = a.T;
     const int col = lane & 15, kg = lane >> 4;
+    // gridDim.y > 1: the depth is split over workgroups, TS k tiles each (matrices of few rows under a macro block of
+    // few sub-blocks would otherwise leave most compute units idle); the parts' results are added at the end
+    const int KSP = gridDim.y, kz = blockIdx.y;
+    const int t_lo = kz * TS, t_hi = min(T, t_lo + TS);  // (every part holds tiles: the launcher)
 
     // ---- what this wavefront copies per stage: pieces p = wave + 8 i, each 64 lanes x 16 bytes from a
     // wavefront-uniform address
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
             stride[i] = 8192;
             seg64[i] = seg * 64;
         }
-        voff[i] = lane * 16;
+        voff[i] = lane * 16 + t_lo * stride[i];
     }
     const bool full_share = (NP % 8 == 0) || wave < NP % 8;  // this wavefront copies PW pieces (else PW - 1)
     // FULL: whether this wavefront copies PW pieces (a compile-time copy of full_share)
@@ -149,8 +158,10 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[g][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // A ragged last k tile (depth not a multiple of 32) is not part of the pipeline: it is handled at the end.
-    const int TF = (a.K & 31) ? T - 1 : T;
+    // A ragged last k tile (depth not a multiple of 32) is not part of the pipeline: it is handled at the end (by
+    // the part that holds it).  TF: full tiles of this workgroup's part; TR: the ragged tile's number, if it is here.
+    const bool ragged = (a.K & 31) != 0 && t_hi == T;
+    const int TF = t_hi - t_lo - (ragged ? 1 : 0), TR = T - 1;
     const unsigned char *a_base = ring + (wm * RGW) * 1024 + lane * 16;
     const unsigned char *b_base = ring + A_BYTES + wn * 8192 + (kg * 128 + col) * 16;
     // (wavefronts without a sub-block -- an odd sub-block count leaves half of the last column tile empty -- go
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
         pipeline(std::true_type());
     else
         pipeline(std::false_type());
-    if (TF < T) {
+    if (ragged) {
         // the ragged tile: copied with ordinary loads, zeros past the real depth (a piece lies wholly inside or
         // wholly outside it), into the first ring slot
         const int real_units = (a.K >> 3) * 128;  // 16-byte units of a sub-block's split activation
@@ -238,8 +249,8 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
 #pragma unroll
         for (int i = 0; i < PW; ++i) {
             if (i < PW - 1 || full_share) {
-                const bool past = seg64[i] >= 0 && seg64[i] + TF * 512 >= real_units;
-                const unsigned char *sp = src[i] + (size_t)TF * stride[i];
+                const bool past = seg64[i] >= 0 && seg64[i] + TR * 512 >= real_units;
+                const unsigned char *sp = src[i] + (size_t)TR * stride[i];
                 const u32x4 v = past ? u32x4{0u, 0u, 0u, 0u} : *(const u32x4 *)(sp + lane * 16);
                 *(u32x4 *)(ring + wave * 1024 + i * 8192 + lane * 16) = v;
             }
@@ -264,23 +275,83 @@ __global__ __launch_bounds__(512) void k_gemm(MvArgs a, MacroArgs ma, int MT, in
     float *dw = (float *)ring + (size_t)wave * 2048;
     const bool wave_live = sub0 + wn < ma.S;
     const float *rsw = rs + 64 * wn;
-#pragma unroll
-    for (int g = 0; g < RGW; ++g) {
-        const int rg = (mt * WM + wm) * RGW + g;
+    auto dump = [&](int g) {
         __syncthreads();  // the ring / the previous dump is no longer read
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) dw[(16 * cb + col) * 16 + 4 * kg + r4] = acc[g][cb][r4];
         __syncthreads();
-        if (wave_live && rg < a.n_rg)
-            mv_epilogue<EPI>(as, rg, lane, rsw, nullptr,
-                             [&](int r, int j) { return dw[(2 * r) * 16 + j] + dw[(2 * r + 1) * 16 + j]; });
+    };
+    if (KSP == 1) {
+#pragma unroll
+        for (int g = 0; g < RGW; ++g) {
+            const int rg = (mt * WM + wm) * RGW + g;
+            dump(g);
+            if (wave_live && rg < a.n_rg)
+                mv_epilogue<EPI>(as, rg, lane, rsw, nullptr,
+                                 [&](int r, int j) { return dw[(2 * r) * 16 + j] + dw[(2 * r + 1) * 16 + j]; });
+        }
+        return;
     }
+    // ---- depth split over workgroups: every part publishes its results, the two terms combined, as
+    // part[(kz n_rg + rg) S + sub][row][tile row]; the workgroup that arrives last at the tile's counter adds the
+    // parts in part order (so the result does not depend on who is last) and runs the epilogue.
+    // (device-scope atomic stores write through, so thread 0's release has nothing to flush; the barrier orders every
+    // wavefront's stores before it)
+    const size_t pslot = 1024;
+#pragma unroll
+    for (int g = 0; g < RGW; ++g) {
+        const int rg = (mt * WM + wm) * RGW + g;
+        dump(g);
+        if (wave_live && rg < a.n_rg) {
+            float *pp = a.part + (((size_t)kz * a.n_rg + rg) * ma.S + sub) * pslot;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int idx = lane + 64 * i, r = idx >> 4, j = idx & 15;
+                __hip_atomic_store(pp + idx, dw[(2 * r) * 16 + j] + dw[(2 * r + 1) * 16 + j], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    int *flag = (int *)nscratch;
+    __syncthreads();
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(a.counters + mt * NN + nt, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = (old == KSP - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (*flag == 0) return;
+    // (plain loads below: ordered after thread 0's acquire by the barrier)
+#pragma unroll
+    for (int g = 0; g < RGW; ++g) {
+        const int rg = (mt * WM + wm) * RGW + g;
+        const bool live = wave_live && rg < a.n_rg;
+        __syncthreads();  // the previous dump is no longer read
+        if (live) {
+            const float *p0 = a.part + ((size_t)rg * ma.S + sub) * pslot + lane * 4;
+            const size_t kstride = (size_t)a.n_rg * ma.S * pslot;
+            f32x4 sum[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sum[q] = *(const f32x4 *)(p0 + 256 * q);
+            for (int k2 = 1; k2 < KSP; ++k2) {
+                f32x4 v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = *(const f32x4 *)(p0 + k2 * kstride + 256 * q);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sum[q] += v[q];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) *(f32x4 *)(dw + lane * 4 + 256 * q) = sum[q];
+        }
+        __syncthreads();
+        if (live) mv_epilogue<EPI>(as, rg, lane, rsw, nullptr, [&](int r, int j) { return dw[r * 16 + j]; });
+    }
+    if (tid == 0) a.counters[mt * NN + nt] = 0;
 }
 
 template <int EPI, int WN, int RGW>
-hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, hipStream_t s) {
+hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, int ksp, hipStream_t s) {
     static bool attr_set = false;
     const size_t lds = kRingBytes + 128 * 4 + kNormFloats * 4;
     if (!attr_set) {
@@ -291,7 +362,11 @@ hipError_t launch_gemm_t(const MvArgs &a, const MacroArgs &ma, hipStream_t s) {
     constexpr int TRG = (8 / WN) * RGW;
     const int MT = (a.n_rg + TRG - 1) / TRG, NN = (ma.S + WN - 1) / WN;
     const int grid = ((MT + 7) / 8) * 8 * NN;
-    hipLaunchKernelGGL((k_gemm<EPI, WN, RGW>), dim3(grid), dim3(512), lds, s, a, ma, MT, NN);
+    const int TS = (a.T + ksp - 1) / ksp;
+    ksp = (a.T + TS - 1) / TS;  // parts that hold tiles
+    if (ksp > 1 && (!a.part || !a.counters || (int64_t)ksp * a.n_rg * ma.S > a.part_capacity || MT * NN > 4096))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_gemm<EPI, WN, RGW>), dim3(grid, ksp), dim3(512), lds, s, a, ma, MT, NN, TS);
     return hipGetLastError();
 }
 
@@ -303,18 +378,34 @@ struct GemmTiling {
 };
 constexpr GemmTiling kGemmTilings[7] = {{0, 0}, {2, 1}, {2, 2}, {2, 3}, {2, 4}, {1, 1}, {1, 2}};
 
+// Depth parts for a tiling: 1 unless the tiles leave compute units idle; then the largest of 2, 4 that still gives
+// at most one workgroup per compute unit, parts of at least 16 k tiles, and partial results that fit the scratch.
+int gemm_depth_parts(const MvArgs &a, const MacroArgs &ma, int n_cu, int code) {
+    const int wn = kGemmTilings[code].wn, rgw = kGemmTilings[code].rgw, trg = (8 / wn) * rgw;
+    const int MT = (a.n_rg + trg - 1) / trg, NN = (ma.S + wn - 1) / wn;
+    int ksp = 1;
+    while (ksp < 4 && MT * NN * ksp * 2 <= n_cu && a.T / (ksp * 2) >= 16 && a.part && a.counters &&
+           (int64_t)ksp * 2 * a.n_rg * ma.S <= a.part_capacity && MT * NN <= 4096)
+        ksp *= 2;
+    return ksp;
+}
+
 int gemm_tiling(const MvArgs &a, const MacroArgs &ma, int n_cu) {
-    // The one that finishes first by a simple count: rounds of workgroups (one per compute unit) times the longer
-    // of a stage's multiply time and the time to take its bytes in (about 21 bytes per cycle and compute unit when
-    // the units of a die stream the same data: measured).
+    // The one that finishes first by a simple count: rounds of workgroups (one per compute unit) times the k tiles
+    // of a workgroup times the longer of a stage's multiply time and the time to take its bytes in (about 21 bytes
+    // per cycle and compute unit when the units of a die stream the same data: measured), plus, with the depth
+    // split, what publishing and adding the parts costs (measured: about 20 us, and the parts' bytes written and read
+    // at about 3 TB/s).
     int best = 1;
     double best_t = 1e30;
     for (int code = 1; code <= 6; ++code) {
         const int wn = kGemmTilings[code].wn, rgw = kGemmTilings[code].rgw, trg = (8 / wn) * rgw;
         const int MT = (a.n_rg + trg - 1) / trg, NN = (ma.S + wn - 1) / wn;
-        const int rounds = (MT * NN + n_cu - 1) / n_cu;
+        const int ksp = gemm_depth_parts(a, ma, n_cu, code);
+        const int rounds = (MT * NN * ksp + n_cu - 1) / n_cu;
         const double mfma = 256.0 * rgw, intake = (trg + 8.0 * wn) * 1024.0 / 21.0;  // cycles per stage
-        const double t = rounds * (mfma > intake ? mfma : intake);
+        const double parts = ksp > 1 ? 45000.0 + 2.0 * ksp * a.n_rg * ma.S * 4096.0 * 0.0007 : 0.0;
+        const double t = rounds * ((a.T + ksp - 1) / ksp) * (mfma > intake ? mfma : intake) + parts;
         if (t < best_t) {
             best_t = t;
             best = code;
@@ -330,15 +421,16 @@ hipError_t launch_gemm(int epi, const MvArgs &a, const MacroArgs &ma, int n_cu, 
         (a.K & 7) != 0 || a.T != (a.K + 31) / 32 || a.n_rg < 1 || !a.Wt || !a.in_s || a.tree)
         return hipErrorInvalidValue;
     const int code = (tiling_override >= 1 && tiling_override <= 6) ? tiling_override : gemm_tiling(a, ma, n_cu);
+    const int ksp = gemm_depth_parts(a, ma, n_cu, code);
 #define SWIFT_GEMM_CASE(E)                                                \
     case E:                                                               \
         switch (code) {                                                   \
-            case 1: return launch_gemm_t<E, 2, 1>(a, ma, s);              \
-            case 2: return launch_gemm_t<E, 2, 2>(a, ma, s);              \
-            case 3: return launch_gemm_t<E, 2, 3>(a, ma, s);              \
-            case 4: return launch_gemm_t<E, 2, 4>(a, ma, s);              \
-            case 5: return launch_gemm_t<E, 1, 1>(a, ma, s);              \
-            default: return launch_gemm_t<E, 1, 2>(a, ma, s);             \
+            case 1: return launch_gemm_t<E, 2, 1>(a, ma, ksp, s);         \
+            case 2: return launch_gemm_t<E, 2, 2>(a, ma, ksp, s);         \
+            case 3: return launch_gemm_t<E, 2, 3>(a, ma, ksp, s);         \
+            case 4: return launch_gemm_t<E, 2, 4>(a, ma, ksp, s);         \
+            case 5: return launch_gemm_t<E, 1, 1>(a, ma, ksp, s);         \
+            default: return launch_gemm_t<E, 1, 2>(a, ma, ksp, s);        \
         }
     switch (epi) {
         SWIFT_GEMM_CASE(EPI_QKV)

@@ -276,16 +276,21 @@ def test_prefill_at_7b_width_against_oracle(oracle_lib, blocks):
     g.close()
 
 
-@pytest.mark.parametrize("case", ["small-gqa", "small-gqa-bf16", "7b-width-2-layers"])
+@pytest.mark.parametrize("case", ["small-gqa", "small-gqa-bf16", "7b-width-2-layers", "7b-width-long-window"])
 def test_candidate_evaluation_against_oracle(oracle_lib, case):
     """Section 4.1.2, Eq. 3-4: predictions of candidate draft models over the last gamma generated
     tokens (block pass with the skip mask, target cache reused, nothing written) and the match
-    count, for windows of 1..128 tokens (more than 64: two blocks); the decoding state is untouched."""
+    count, for windows of 1..128 tokens (more than 64: two blocks for fp32 models, one macro block of two
+    sub-blocks through the blocked matrix product for bf16 models; the long-window case takes that path at
+    the 7B width, heads of 128); the decoding state is untouched."""
     import paper_2410_06916_amd as P
-    if case == "7b-width-2-layers":
+    if case.startswith("7b-width"):
         shape = si.LLAMA2_7B.with_layers(2)
         weights = si.make_weights(shape, 0)
-        n_prompt, n_gen, gammas, threads = 10, 24, (1, 5, 17, 32), 8
+        if case == "7b-width-2-layers":
+            n_prompt, n_gen, gammas, threads = 10, 24, (1, 5, 17, 32), 8
+        else:
+            n_prompt, n_gen, gammas, threads = 10, 104, (65, 100), 8
         masks = [np.zeros(4, np.uint8), np.array([0, 1, 1, 0], np.uint8)]
     else:
         shape = hp.SMALL_GQA if case == "small-gqa" else hp.SMALL_GQA_BF16
@@ -307,6 +312,12 @@ def test_candidate_evaluation_against_oracle(oracle_lib, case):
             po, mo = o.eval_mask(mask, seq[-(gamma + 1):])
             pg, mg = g.eval_mask(mask, seq[-(gamma + 1):])
             assert np.array_equal(pg, po) and mg == mo, (case, gamma, mi)
+            if shape.dtype == "bf16" and gamma > 64:
+                # the same window block by block (macro blocks switched off): the same predictions
+                g.prefill_blocks(-1)
+                pb, mb = g.eval_mask(mask, seq[-(gamma + 1):])
+                g.prefill_blocks(0)
+                assert np.array_equal(pb, po) and mb == mo, (case, gamma, mi, "64-row blocks")
             if mi == 0 and gamma + 1 <= n_gen:
                 assert mg == gamma      # nothing skipped, window inside the target model's own output
     assert (g.cache_len, g.pending) == (n, pend)
