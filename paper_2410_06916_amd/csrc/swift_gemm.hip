@@ -380,11 +380,13 @@ constexpr GemmTiling kGemmTilings[7] = {{0, 0}, {2, 1}, {2, 2}, {2, 3}, {2, 4}, 
 
 // Depth parts for a tiling: 1 unless the tiles leave compute units idle; then the largest of 2, 4 that still gives
 // at most one workgroup per compute unit, parts of at least 16 k tiles, and partial results that fit the scratch.
+// Only for macro blocks of up to four sub-blocks: with more, the parts' results are too many bytes (measured at
+// eight sub-blocks, same machine: down_proj 128-131 us with four parts against 113 us unsplit).
 int gemm_depth_parts(const MvArgs &a, const MacroArgs &ma, int n_cu, int code) {
     const int wn = kGemmTilings[code].wn, rgw = kGemmTilings[code].rgw, trg = (8 / wn) * rgw;
     const int MT = (a.n_rg + trg - 1) / trg, NN = (ma.S + wn - 1) / wn;
     int ksp = 1;
-    while (ksp < 4 && MT * NN * ksp * 2 <= n_cu && a.T / (ksp * 2) >= 16 && a.part && a.counters &&
+    while (ma.S <= 4 && ksp < 4 && MT * NN * ksp * 2 <= n_cu && a.T / (ksp * 2) >= 16 && a.part && a.counters &&
            (int64_t)ksp * 2 * a.n_rg * ma.S <= a.part_capacity && MT * NN <= 4096)
         ksp *= 2;
     return ksp;
