@@ -318,6 +318,14 @@ def test_candidate_evaluation_against_oracle(oracle_lib, case):
                 pb, mb = g.eval_mask(mask, seq[-(gamma + 1):])
                 g.prefill_blocks(0)
                 assert np.array_equal(pb, po) and mb == mo, (case, gamma, mi, "64-row blocks")
+                if case == "7b-width-long-window":
+                    # every tile shape of the blocked matrix product (with two sub-blocks the matrices of few rows
+                    # split the depth over workgroups under each of them)
+                    for tiling in range(1, 7):
+                        g.prefill_blocks(0, tiling)
+                        pt, mt = g.eval_mask(mask, seq[-(gamma + 1):])
+                        assert np.array_equal(pt, po) and mt == mo, (case, gamma, mi, "tiling", tiling)
+                    g.prefill_blocks(0)
             if mi == 0 and gamma + 1 <= n_gen:
                 assert mg == gamma      # nothing skipped, window inside the target model's own output
     assert (g.cache_len, g.pending) == (n, pend)
