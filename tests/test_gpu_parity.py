@@ -250,9 +250,9 @@ def test_block_attention_on_matrix_cores_against_oracle(oracle_lib, case):
 @pytest.mark.parametrize("blocks", ["macro-block", "64-row-blocks"])
 def test_prefill_at_7b_width_against_oracle(oracle_lib, blocks):
     """The 7B workload's widths (hidden 4096, 32 heads of 128, ffn 11008), two layers deep, a 200-token prompt.
-    macro-block: one macro block of four sub-blocks (64, 64, 64 and 8 rows) through the blocked matrix product at the
-    tile heights this shape takes (three row groups per wavefront for q|k|v and gate/up, one for o_proj and
-    down_proj) and the macro block's attention in one launch.  64-row-blocks: three 64-row blocks through the block
+    macro-block: one macro block of four sub-blocks (64, 64, 64 and 8 rows) through the blocked matrix product with
+    the tiles this shape takes at four sub-blocks (o_proj and down_proj, with few rows, split their depth over
+    workgroups) and the macro block's attention in one launch.  64-row-blocks: three 64-row blocks through the block
     kernels (the third one's attention over two cache ranges) and an 8-row tail."""
     shape = si.LLAMA2_7B.with_layers(2)
     weights = si.make_weights(shape, 0)
